@@ -1,0 +1,234 @@
+"""Seeded synthetic inputs for the block-quantised matmul workloads.
+
+This module only draws random numbers and lists shapes.  It holds none of the
+method's arithmetic (no unpacking, no dequantisation, no matmul): the CPU
+oracle and the HIP library both receive exactly the arrays produced here and
+each does its own work on them.
+
+Interchange ("canonical") form of one quantised matrix W[N, K] with bit-width
+b and blocks of 32 along K (the block format of Eq. 1, Section 3):
+
+  codes  : uint8 [N, K/32, 4*b]  -- per block a little-endian bitstream of
+           32 b-bit codes.  Codes are iid uniform on {0..2^b-1}, so the
+           bitstream is simply iid uniform bytes and is drawn as such.
+  scales : uint16 [N, K/32]      -- fp16 bit patterns of d = fp16(|g| * 0.02),
+           g ~ N(0, 1) drawn in fp32.
+
+Activations are N(0, 1) drawn in fp32 and rounded (nearest-even) to fp16 or
+bf16; they are carried as uint16 bit patterns so numpy needs no bf16 type.
+
+The shapes stand in for the LLaMA-2-7B backbone of OpenVLA-OFT and for a
+Gemma-2B-shaped backbone; no real checkpoint or benchmark item is used.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Iterator, List, Sequence, Tuple
+
+import numpy as np
+
+BLOCK = 32
+BASE_SEED = 0
+
+# (name, N, K) of the seven matrices of one transformer layer, in layer order.
+LLAMA2_7B_LAYER: Tuple[Tuple[str, int, int], ...] = (
+    ("q", 4096, 4096),
+    ("k", 4096, 4096),
+    ("v", 4096, 4096),
+    ("o", 4096, 4096),
+    ("gate", 11008, 4096),
+    ("up", 11008, 4096),
+    ("down", 4096, 11008),
+)
+LLAMA2_7B_LAYERS = 32
+
+GEMMA_2B_LAYER: Tuple[Tuple[str, int, int], ...] = (
+    ("q", 2048, 2048),
+    ("k", 256, 2048),
+    ("v", 256, 2048),
+    ("o", 2048, 2048),
+    ("gate", 16384, 2048),
+    ("up", 16384, 2048),
+    ("down", 2048, 16384),
+)
+GEMMA_2B_LAYERS = 18
+
+PREFILL_M = 300          # 256 image-patch rows followed by 44 text rows
+PREFILL_IMAGE_ROWS = 256
+PREFILL_IMAGE_GAIN = 3.0
+
+
+@dataclasses.dataclass(frozen=True)
+class MatrixSpec:
+    """One matrix of a backbone-shaped stream."""
+    index: int      # position in the stream
+    layer: int
+    name: str
+    N: int
+    K: int
+    bits: int
+
+    @property
+    def weights(self) -> int:
+        return self.N * self.K
+
+
+def _rng(*key: int) -> np.random.Generator:
+    """Counter-based generator keyed by a tuple of small integers."""
+    ss = np.random.SeedSequence([int(k) & 0xFFFFFFFF for k in key])
+    return np.random.Generator(np.random.Philox(ss))
+
+
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to bf16 (nearest, ties to even); returns uint16 bit patterns."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return u.astype(np.uint16)
+
+
+def f32_to_f16_bits(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to fp16 (nearest-even, numpy's cast); returns uint16 bit patterns."""
+    return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def draw_codes(N: int, K: int, bits: int, *key: int) -> np.ndarray:
+    """Canonical code bitstream uint8[N, K/32, 4*bits] of iid uniform codes."""
+    assert K % BLOCK == 0 and bits in (2, 3, 4)
+    nb = K // BLOCK
+    g = _rng(101, *key)
+    return g.integers(0, 256, size=(N, nb, 4 * bits), dtype=np.uint8)
+
+
+def draw_scales(N: int, K: int, *key: int) -> np.ndarray:
+    """fp16 bit patterns uint16[N, K/32] of d = fp16(|N(0,1)| * 0.02)."""
+    nb = K // BLOCK
+    g = _rng(202, *key)
+    d = np.abs(g.standard_normal(size=(N, nb), dtype=np.float32)) * np.float32(0.02)
+    return f32_to_f16_bits(d)
+
+
+def draw_activations(M: int, K: int, dtype: str, *key: int,
+                     image_rows: int = 0, image_gain: float = 1.0) -> np.ndarray:
+    """Activations uint16[M, K] (bit patterns of `dtype`, "f16" or "bf16"), N(0,1);
+    the first `image_rows` rows are multiplied by `image_gain` before rounding."""
+    g = _rng(303, *key)
+    x = g.standard_normal(size=(M, K), dtype=np.float32)
+    if image_rows:
+        x[:image_rows] *= np.float32(image_gain)
+    if dtype == "f16":
+        return f32_to_f16_bits(x)
+    if dtype == "bf16":
+        return f32_to_bf16_bits(x)
+    raise ValueError(dtype)
+
+
+def draw_matrix(N: int, K: int, bits: int, *key: int) -> Tuple[np.ndarray, np.ndarray]:
+    return draw_codes(N, K, bits, *key), draw_scales(N, K, *key)
+
+
+# ----------------------------------------------------------------------------
+# exact-arithmetic inputs: integer activations and power-of-two scales, for
+# which every fp32 summation order gives the same bits.
+# ----------------------------------------------------------------------------
+def draw_pow2_scales(N: int, K: int, *key: int) -> np.ndarray:
+    """fp16 bit patterns of scales 2^e, e uniform in {-6..-1}."""
+    nb = K // BLOCK
+    g = _rng(404, *key)
+    e = g.integers(-6, 0, size=(N, nb))
+    return f32_to_f16_bits(np.ldexp(np.float32(1.0), e).astype(np.float32))
+
+
+def draw_int_activations(M: int, K: int, dtype: str, *key: int) -> np.ndarray:
+    """Integer-valued activations uniform in {-4..4}."""
+    g = _rng(505, *key)
+    x = g.integers(-4, 5, size=(M, K)).astype(np.float32)
+    return f32_to_f16_bits(x) if dtype == "f16" else f32_to_bf16_bits(x)
+
+
+# ----------------------------------------------------------------------------
+# backbone-shaped streams and the seeded bit allocation
+# ----------------------------------------------------------------------------
+def layer_shapes(model: str) -> Tuple[Tuple[Tuple[str, int, int], ...], int]:
+    if model == "llama2-7b":
+        return LLAMA2_7B_LAYER, LLAMA2_7B_LAYERS
+    if model == "gemma-2b":
+        return GEMMA_2B_LAYER, GEMMA_2B_LAYERS
+    raise ValueError(model)
+
+
+def seeded_allocation(shapes: Sequence[Tuple[int, int]], mean_code_bits: float,
+                      seed: int = BASE_SEED) -> List[int]:
+    """One bit-width from {2,3,4} per matrix with an element-weighted mean of
+    code bits not above `mean_code_bits`.
+
+    Deterministic: every matrix starts at 2 bits; a seeded permutation is walked
+    cyclically; at each matrix still below 4 bits a seeded step of +1 or +2
+    (clamped to 4) is applied if the remaining bit budget allows it; the walk
+    ends after a full pass without an upgrade.
+    """
+    g = _rng(606, seed)
+    n = len(shapes)
+    sizes = [int(a) * int(b) for a, b in shapes]
+    total = sum(sizes)
+    bits = [2] * n
+    budget = int(round(mean_code_bits * total)) - 2 * total
+    order = list(g.permutation(n))
+    changed = True
+    while changed:
+        changed = False
+        for i in order:
+            if bits[i] >= 4:
+                continue
+            step = min(int(g.integers(1, 3)), 4 - bits[i])
+            cost = step * sizes[i]
+            if cost <= budget:
+                bits[i] += step
+                budget -= cost
+                changed = True
+    return bits
+
+
+def backbone_stream(model: str, allocation: str = "mixed", seed: int = BASE_SEED,
+                    layers: int | None = None) -> List[MatrixSpec]:
+    """The matrices of a backbone-shaped stream in layer order.
+
+    allocation:
+      "b2" / "b3" / "b4" : uniform bit-width;
+      "mixed"            : seeded {2,3,4} allocation whose element-weighted mean of
+                           code bits is 2.5 (3.0 bits per weight stored, scales included);
+      "floor"            : every matrix at 2 bits = 2.5 bits per weight stored.
+    """
+    shp, L = layer_shapes(model)
+    if layers is not None:
+        L = layers
+    flat = [(l, nm, N, K) for l in range(L) for (nm, N, K) in shp]
+    if allocation in ("b2", "b3", "b4"):
+        bits = [int(allocation[1])] * len(flat)
+    elif allocation == "floor":
+        bits = [2] * len(flat)
+    elif allocation == "mixed":
+        bits = seeded_allocation([(N, K) for (_, _, N, K) in flat], 2.5, seed)
+    else:
+        raise ValueError(allocation)
+    return [MatrixSpec(i, l, nm, N, K, b) for i, ((l, nm, N, K), b) in enumerate(zip(flat, bits))]
+
+
+def stored_bits_per_weight(stream: Sequence[MatrixSpec]) -> float:
+    """Bits per weight of the canonical form, fp16 block scales included."""
+    tot = sum(m.weights for m in stream)
+    return sum(m.weights * (m.bits + 16.0 / BLOCK) for m in stream) / tot
+
+
+def iter_stream_inputs(stream: Sequence[MatrixSpec], M: int, dtype: str, seed: int = BASE_SEED,
+                       prefill_profile: bool = False
+                       ) -> Iterator[Tuple[MatrixSpec, np.ndarray, np.ndarray, np.ndarray]]:
+    """Yield (spec, codes, scales, activations) per matrix; activations are independent
+    per matrix (the stream is a weight-matmul proxy, not a dependent forward pass)."""
+    for m in stream:
+        codes, scales = draw_matrix(m.N, m.K, m.bits, seed, 3, m.index)
+        if prefill_profile:
+            x = draw_activations(M, m.K, dtype, seed, 3, m.index,
+                                 image_rows=min(PREFILL_IMAGE_ROWS, M), image_gain=PREFILL_IMAGE_GAIN)
+        else:
+            x = draw_activations(M, m.K, dtype, seed, 3, m.index)
+        yield m, codes, scales, x
