@@ -1,0 +1,129 @@
+/*
+ * aq.h -- C ABI of the block-quantised matmul library for AMD MI355X (gfx950).
+ *
+ * The library multiplies activations by a weight matrix W[N, K] (N output
+ * features, K input features, y = x W^T) that is stored in the block
+ * quantisation format of Eq. 1 (Section 3, "Weight quantization"), with one
+ * bit-width per matrix (Section 1 and Section 4.1: the bit-width varies across
+ * matrices and is uniform inside each, so one dense kernel serves a matrix):
+ *
+ *     w_hat[n, k] = d[n, k/32] * (q[n, k] - 2^(bits-1)),
+ *
+ *   bits  in {2, 3, 4}         -- the matrix's bit-width (n of Eq. 1's n-bit quantiser)
+ *   block =  32                -- B of Eq. 1; blocks run along K inside a row of W
+ *   q     in {0 .. 2^bits - 1} -- the codes (uniform codebook Q_n)
+ *   d                          -- s_b of Eq. 1, one IEEE binary16 value per block
+ *   z_b   = 2^(bits-1)         -- fixed, not stored
+ *
+ * Canonical ("interchange") form handed to aq_pack_weights:
+ *   codes  uint8  [N][K/32][4*bits] : per block one little-endian bitstream; code i
+ *          of the block occupies stream bits i*bits .. i*bits+bits-1, stream bit t is
+ *          bit (t % 8) of byte (t / 8).  4-bit: two codes per byte, low nibble first;
+ *          3-bit: 12 bytes per block, codes straddle bytes; blocks never share a byte.
+ *   scales uint16 [N][K/32]         : binary16 bit patterns.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE are device (HBM) addresses, 16-byte aligned; pointers
+ *     marked HOST are ordinary host memory.  The caller owns every buffer; the library
+ *     allocates and frees nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work on it and never synchronise.
+ *   - Return value: AQ_OK (0) or a negative AQ_E* code.  Arguments are validated on
+ *     the host before anything is launched; on error nothing has been enqueued.
+ *   - Activations are half precision (Appendix "Limitations": weight-only quantisation,
+ *     activations stay at half precision): AQ_F16 or AQ_BF16 bit patterns.  Outputs are
+ *     fp32.  Accumulation is fp32.
+ */
+#ifndef AQ_H
+#define AQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AQ_OK        0
+#define AQ_EINVAL   (-1)  /* bits not in {2,3,4}; block != 32; N, K or M < 1; K % 32 != 0; ld too small; count < 1 */
+#define AQ_ENULL    (-2)  /* a required pointer is NULL */
+#define AQ_EALIGN   (-3)  /* a device pointer is not 16-byte aligned */
+#define AQ_ESIZE    (-4)  /* a caller-provided buffer is too small */
+#define AQ_EDTYPE   (-5)  /* activation dtype is neither AQ_F16 nor AQ_BF16 */
+#define AQ_ELAUNCH  (-6)  /* the HIP runtime reported an error at launch */
+
+#define AQ_F16   1
+#define AQ_BF16  2
+
+/* Text for a status code (static storage, never NULL). */
+const char* aq_status_string(int status);
+
+/* Bytes of the packed device blob of an N x K matrix, 0 if the arguments are invalid.
+ * The blob stores exactly the canonical information (bits/8 + 1/16 bytes per weight)
+ * re-tiled for the kernels, with N rounded up to 16 and K to 512; its layout is
+ * private to this build of the library. */
+size_t aq_packed_size(int64_t N, int64_t K, int bits, int block);
+
+/* Eq. 1's stored form -> device blob (re-tiling only, no value changes).
+ *   codes   DEVICE uint8  [N][K/32][4*bits]   canonical bitstream (see above)
+ *   scales  DEVICE uint16 [N][K/32]           binary16 bit patterns
+ *   packed  DEVICE, packed_bytes >= aq_packed_size(N, K, bits, block); written entirely.
+ * One-off per matrix (the serialisation step of Appendix D), not on the timed path. */
+int aq_pack_weights(const uint8_t* codes, const uint16_t* scales,
+                    int64_t N, int64_t K, int bits, int block,
+                    void* packed, size_t packed_bytes, void* stream);
+
+/* Decode (batch 1): y[n] = sum_k x[k] * w_hat[n, k], unpack + dequantise fused into the
+ * product ("dequantize on the fly inside a hand-written kernel", Appendix D; Eq. 1).
+ *   packed  DEVICE blob from aq_pack_weights with the same (N, K, bits, block)
+ *   x       DEVICE uint16 [K]  activations, x_dtype = AQ_F16 or AQ_BF16
+ *   y       DEVICE float  [N]  overwritten */
+int aq_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block,
+             const void* x, int x_dtype, float* y, void* stream);
+
+/* A stream of independent decode products in ONE launch: the per-matrix bit-width of
+ * Section 4.1 selects the code path per descriptor ("every matmul dispatches to one
+ * dense kernel", Section 1); used for a whole backbone pass (7 matrices x L layers).
+ * Step 1 (host only): aq_qgemv_batch_plan turns `count` descriptors into a plan image
+ *   of aq_qgemv_batch_plan_size(count) bytes in HOST memory `plan_host`.
+ * Step 2: the caller copies that image to 16-byte-aligned DEVICE memory `plan_dev`.
+ * Step 3: aq_qgemv_batch(plan_host, plan_dev, stream) launches; it may be repeated. */
+typedef struct aq_gemv_desc {
+    const void* packed;   /* DEVICE blob */
+    const void* x;        /* DEVICE uint16 [K] */
+    float*      y;        /* DEVICE float [N] */
+    int64_t     N, K;
+    int32_t     bits;     /* 2, 3 or 4 */
+    int32_t     x_dtype;  /* AQ_F16 or AQ_BF16 */
+} aq_gemv_desc;
+
+size_t aq_qgemv_batch_plan_size(int count);
+int aq_qgemv_batch_plan(const aq_gemv_desc* descs /*HOST*/, int count, int block,
+                        void* plan_host, size_t plan_bytes);
+int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
+
+/* Prefill: Y[m, n] = sum_k X[m, k] * w_hat[n, k] for M rows of activations; code tiles are
+ * unpacked to exact small integers (q - 2^(bits-1)) in LDS, multiplied on the matrix cores,
+ * and the fp16 block scale d is applied in fp32 to each block's partial sum (Eq. 1 with the
+ * factor d taken out of the block's sum), fp32 accumulation.
+ *   X   DEVICE uint16 [M][ldx], ldx >= K, x_dtype = AQ_BF16 (AQ_F16 also accepted)
+ *   Y   DEVICE float  [M][ldy], ldy >= N, overwritten for m < M, n < N
+ *   workspace DEVICE, workspace_bytes >= aq_qgemm_workspace_size(M, N, K, bits); may be
+ *       NULL when that size is 0.  Contents need no initialisation. */
+size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits);
+int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block,
+             const void* X, int64_t M, int64_t ldx, int x_dtype,
+             float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Parity / debug: the blob decoded back to what Eq. 1 defines.
+ *   codes_u8 DEVICE uint8 [N][K]  one code per byte
+ *   W        DEVICE float [N][K]  d * (q - 2^(bits-1)); exact in fp32 (11-bit x 4-bit significands) */
+int aq_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block,
+                    uint8_t* codes_u8, void* stream);
+int aq_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int block,
+                   float* W, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AQ_H */

@@ -1,0 +1,169 @@
+"""Python binding of libaq.so -- block-quantised matmul kernels for MI355X (gfx950).
+
+Argument marshalling only: every function below forwards torch tensors' device pointers
+to the C entry point of the same name (see include/aq.h); nothing is computed in Python
+and there is no CPU fallback.  If libaq.so has not been built (paper_2605_24011_amd/build.py)
+importing a function raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Sequence
+
+AQ_OK = 0
+AQ_EINVAL, AQ_ENULL, AQ_EALIGN, AQ_ESIZE, AQ_EDTYPE, AQ_ELAUNCH = -1, -2, -3, -4, -5, -6
+AQ_F16, AQ_BF16 = 1, 2
+BLOCK = 32
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaq.so")
+_lib = None
+
+_i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+
+
+class AqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class aq_gemv_desc(ctypes.Structure):
+    _fields_ = [("packed", _p), ("x", _p), ("y", _p), ("N", _i64), ("K", _i64),
+                ("bits", ctypes.c_int32), ("x_dtype", ctypes.c_int32)]
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2605_24011_amd.build` "
+                              "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.aq_status_string.restype = ctypes.c_char_p
+        L.aq_status_string.argtypes = [_int]
+        L.aq_packed_size.restype = _sz
+        L.aq_packed_size.argtypes = [_i64, _i64, _int, _int]
+        L.aq_pack_weights.argtypes = [_p, _p, _i64, _i64, _int, _int, _p, _sz, _p]
+        L.aq_qgemv.argtypes = [_p, _i64, _i64, _int, _int, _p, _int, _p, _p]
+        L.aq_qgemv_batch_plan_size.restype = _sz
+        L.aq_qgemv_batch_plan_size.argtypes = [_int]
+        L.aq_qgemv_batch_plan.argtypes = [ctypes.POINTER(aq_gemv_desc), _int, _int, _p, _sz]
+        L.aq_qgemv_batch.argtypes = [_p, _p, _p]
+        L.aq_qgemm_workspace_size.restype = _sz
+        L.aq_qgemm_workspace_size.argtypes = [_i64, _i64, _i64, _int]
+        L.aq_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
+        L.aq_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
+        L.aq_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().aq_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != AQ_OK:
+        raise AqError(status, where)
+
+
+def _stream(stream=None) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float16:
+        return AQ_F16
+    if t.dtype == torch.bfloat16:
+        return AQ_BF16
+    raise AqError(AQ_EDTYPE, "activation dtype")
+
+
+def aq_packed_size(N: int, K: int, bits: int, block: int = BLOCK) -> int:
+    return int(lib().aq_packed_size(N, K, bits, block))
+
+
+def aq_pack_weights(codes, scales, N: int, K: int, bits: int, block: int = BLOCK, stream=None):
+    """codes: cuda uint8 [N, K/32, 4*bits]; scales: cuda int16/uint16/float16 [N, K/32] -> uint8 blob."""
+    import torch
+    size = aq_packed_size(N, K, bits, block)
+    if size == 0:
+        raise AqError(AQ_EINVAL, "aq_packed_size")
+    packed = torch.empty(size, dtype=torch.uint8, device=codes.device)
+    _check(lib().aq_pack_weights(codes.data_ptr(), scales.data_ptr(), N, K, bits, block,
+                                 packed.data_ptr(), size, _stream(stream)), "aq_pack_weights")
+    return packed
+
+
+def aq_qgemv(packed, N: int, K: int, bits: int, x, y=None, block: int = BLOCK, stream=None):
+    """x: cuda float16/bfloat16 [K] -> y: cuda float32 [N]."""
+    import torch
+    if y is None:
+        y = torch.empty(N, dtype=torch.float32, device=x.device)
+    _check(lib().aq_qgemv(packed.data_ptr(), N, K, bits, block, x.data_ptr(), _dtype_code(x),
+                          y.data_ptr(), _stream(stream)), "aq_qgemv")
+    return y
+
+
+class GemvBatch:
+    """A planned stream of decode products (one launch).  Holds references to every tensor."""
+
+    def __init__(self, items: Sequence[tuple], block: int = BLOCK):
+        """items: (packed, N, K, bits, x, y) per matrix."""
+        import torch
+        n = len(items)
+        descs = (aq_gemv_desc * n)()
+        for d, (packed, N, K, bits, x, y) in zip(descs, items):
+            d.packed, d.x, d.y = packed.data_ptr(), x.data_ptr(), y.data_ptr()
+            d.N, d.K, d.bits, d.x_dtype = N, K, bits, _dtype_code(x)
+        size = int(lib().aq_qgemv_batch_plan_size(n))
+        self.plan_host = torch.empty(size, dtype=torch.uint8)
+        _check(lib().aq_qgemv_batch_plan(descs, n, block, self.plan_host.data_ptr(), size), "aq_qgemv_batch_plan")
+        self.plan_dev = self.plan_host.to(items[0][0].device)
+        self.items = list(items)
+
+    def run(self, stream=None) -> None:
+        _check(lib().aq_qgemv_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), _stream(stream)),
+               "aq_qgemv_batch")
+
+
+def aq_qgemm_workspace_size(M: int, N: int, K: int, bits: int) -> int:
+    return int(lib().aq_qgemm_workspace_size(M, N, K, bits))
+
+
+def aq_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None):
+    """X: cuda bfloat16/float16 [M, K] (row stride = X.stride(0)) -> Y: cuda float32 [M, N]."""
+    import torch
+    M = X.shape[0]
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    need = aq_qgemm_workspace_size(M, N, K, bits)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().aq_qgemm(packed.data_ptr(), N, K, bits, block, X.data_ptr(), M, X.stride(0), _dtype_code(X),
+                          Y.data_ptr(), Y.stride(0), ws_ptr, ws_bytes, _stream(stream)), "aq_qgemm")
+    return Y
+
+
+def aq_unpack_codes(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):
+    import torch
+    out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(lib().aq_unpack_codes(packed.data_ptr(), N, K, bits, block, out.data_ptr(), _stream(stream)),
+           "aq_unpack_codes")
+    return out
+
+
+def aq_dequant_f32(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):
+    import torch
+    out = torch.empty((N, K), dtype=torch.float32, device=packed.device)
+    _check(lib().aq_dequant_f32(packed.data_ptr(), N, K, bits, block, out.data_ptr(), _stream(stream)),
+           "aq_dequant_f32")
+    return out

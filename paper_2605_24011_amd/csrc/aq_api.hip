@@ -1,0 +1,213 @@
+// C-ABI shim: host-side argument validation and dispatch.  Nothing here touches the GPU
+// before every argument has been checked, so the error paths can be tested on a machine
+// without one.
+#include <hip/hip_runtime.h>
+#include <cstring>
+#include "../../include/aq.h"
+#include "aq_layout.h"
+#include "aq_kernels.h"
+
+namespace {
+
+constexpr int64_t AQ_MAX_K = 16384;          // x (fp16) must fit the decode kernel's LDS stage
+constexpr int64_t AQ_MAX_N = (int64_t)1 << 24;
+constexpr int64_t AQ_MAX_M = (int64_t)1 << 20;
+
+struct PlanHeader {                          // first 64 bytes of a batch plan image
+    uint32_t magic;
+    int32_t count;
+    int32_t total_wgs;
+    int32_t tiles_per_wg;
+    int32_t max_K;
+    int32_t reserved[11];
+};
+static_assert(sizeof(PlanHeader) == 64, "PlanHeader must stay 64 bytes");
+constexpr uint32_t PLAN_MAGIC = 0x41515031u;  // "AQP1"
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_matrix(int64_t N, int64_t K, int bits, int block)
+{
+    if (bits != 2 && bits != 3 && bits != 4) return AQ_EINVAL;
+    if (block != AQ_BLOCK) return AQ_EINVAL;
+    if (N < 1 || K < 1 || N > AQ_MAX_N || K > AQ_MAX_K) return AQ_EINVAL;
+    if (K % AQ_BLOCK != 0) return AQ_EINVAL;
+    return AQ_OK;
+}
+
+int check_dtype(int dt) { return (dt == AQ_F16 || dt == AQ_BF16) ? AQ_OK : AQ_EDTYPE; }
+
+AqGemvTask make_task(const void* packed, int64_t N, int64_t K, int bits, const void* x, int dt, float* y)
+{
+    AqGemvTask t;
+    std::memset(&t, 0, sizeof(t));
+    t.blob = static_cast<const uint8_t*>(packed);
+    t.x = static_cast<const uint16_t*>(x);
+    t.y = y;
+    t.N = N;
+    t.K = (int32_t)K;
+    t.bits = bits;
+    t.x_dtype = dt;
+    t.nchunks = (int32_t)aq_num_chunks(K);
+    return t;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* aq_status_string(int status)
+{
+    switch (status) {
+        case AQ_OK: return "ok";
+        case AQ_EINVAL: return "invalid argument (bits must be 2, 3 or 4; block 32; K a multiple of 32 and <= 16384; sizes >= 1)";
+        case AQ_ENULL: return "null pointer";
+        case AQ_EALIGN: return "device pointer not 16-byte aligned";
+        case AQ_ESIZE: return "buffer too small";
+        case AQ_EDTYPE: return "activation dtype must be AQ_F16 or AQ_BF16";
+        case AQ_ELAUNCH: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+size_t aq_packed_size(int64_t N, int64_t K, int bits, int block)
+{
+    if (check_matrix(N, K, bits, block) != AQ_OK) return 0;
+    return (size_t)aq_blob_bytes(N, K, bits);
+}
+
+int aq_pack_weights(const uint8_t* codes, const uint16_t* scales, int64_t N, int64_t K, int bits, int block,
+                    void* packed, size_t packed_bytes, void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if (!codes || !scales || !packed) return AQ_ENULL;
+    if (!aligned16(codes) || !aligned16(scales) || !aligned16(packed)) return AQ_EALIGN;
+    if (packed_bytes < (size_t)aq_blob_bytes(N, K, bits)) return AQ_ESIZE;
+    return aqk_pack(codes, scales, N, K, bits, packed, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
+int aq_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, const void* x, int x_dtype,
+             float* y, void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if ((rc = check_dtype(x_dtype)) != AQ_OK) return rc;
+    if (!packed || !x || !y) return AQ_ENULL;
+    if (!aligned16(packed) || !aligned16(x) || !aligned16(y)) return AQ_EALIGN;
+    AqGemvTask t = make_task(packed, N, K, bits, x, x_dtype, y);
+    int rt = aqk_gemv_tiles_per_wg(N, false);
+    t.wg_begin = 0;
+    t.wg_count = aqk_gemv_wg_count(N, rt);
+    return aqk_gemv(nullptr, 0, t, rt, t.wg_count, (int)K, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
+size_t aq_qgemv_batch_plan_size(int count)
+{
+    if (count < 1) return 0;
+    return sizeof(PlanHeader) + (size_t)count * sizeof(AqGemvTask);
+}
+
+int aq_qgemv_batch_plan(const aq_gemv_desc* descs, int count, int block, void* plan_host, size_t plan_bytes)
+{
+    if (count < 1) return AQ_EINVAL;
+    if (!descs || !plan_host) return AQ_ENULL;
+    if (plan_bytes < aq_qgemv_batch_plan_size(count)) return AQ_ESIZE;
+    const int rt = aqk_gemv_tiles_per_wg(0, true);
+    int64_t wgs = 0;
+    int max_K = 0;
+    for (int i = 0; i < count; ++i) {
+        const aq_gemv_desc& d = descs[i];
+        int rc = check_matrix(d.N, d.K, d.bits, block);
+        if (rc != AQ_OK) return rc;
+        if ((rc = check_dtype(d.x_dtype)) != AQ_OK) return rc;
+        if (!d.packed || !d.x || !d.y) return AQ_ENULL;
+        if (!aligned16(d.packed) || !aligned16(d.x) || !aligned16(d.y)) return AQ_EALIGN;
+        wgs += aqk_gemv_wg_count(d.N, rt);
+        if (wgs > 0x7FFFFFFF) return AQ_EINVAL;
+        if (d.K > max_K) max_K = (int)d.K;
+    }
+    PlanHeader h;
+    std::memset(&h, 0, sizeof(h));
+    h.magic = PLAN_MAGIC;
+    h.count = count;
+    h.tiles_per_wg = rt;
+    h.max_K = max_K;
+    AqGemvTask* tasks = reinterpret_cast<AqGemvTask*>(static_cast<uint8_t*>(plan_host) + sizeof(PlanHeader));
+    int32_t begin = 0;
+    for (int i = 0; i < count; ++i) {
+        const aq_gemv_desc& d = descs[i];
+        AqGemvTask t = make_task(d.packed, d.N, d.K, d.bits, d.x, d.x_dtype, d.y);
+        t.wg_begin = begin;
+        t.wg_count = aqk_gemv_wg_count(d.N, rt);
+        begin += t.wg_count;
+        std::memcpy(&tasks[i], &t, sizeof(t));
+    }
+    h.total_wgs = begin;
+    std::memcpy(plan_host, &h, sizeof(h));
+    return AQ_OK;
+}
+
+int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream)
+{
+    if (!plan_host || !plan_dev) return AQ_ENULL;
+    if (!aligned16(plan_dev)) return AQ_EALIGN;
+    PlanHeader h;
+    std::memcpy(&h, plan_host, sizeof(h));
+    if (h.magic != PLAN_MAGIC || h.count < 1 || h.total_wgs < 1) return AQ_EINVAL;
+    const AqGemvTask* tasks =
+        reinterpret_cast<const AqGemvTask*>(static_cast<const uint8_t*>(plan_dev) + sizeof(PlanHeader));
+    AqGemvTask none;
+    std::memset(&none, 0, sizeof(none));
+    return aqk_gemv(tasks, h.count, none, h.tiles_per_wg, h.total_wgs, h.max_K,
+                    static_cast<hipStream_t>(stream)) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+}
+
+size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits)
+{
+    if (check_matrix(N, K, bits, AQ_BLOCK) != AQ_OK || M < 1 || M > AQ_MAX_M) return 0;
+    return aqk_gemm_workspace(M, N, K, bits);
+}
+
+int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M,
+             int64_t ldx, int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes,
+             void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if (M < 1 || M > AQ_MAX_M || ldx < K || ldy < N) return AQ_EINVAL;
+    if (ldx % 8 != 0) return AQ_EINVAL;      // rows of X must keep 16-byte alignment
+    if ((rc = check_dtype(x_dtype)) != AQ_OK) return rc;
+    if (!packed || !X || !Y) return AQ_ENULL;
+    size_t need = aqk_gemm_workspace(M, N, K, bits);
+    if (need > 0 && !workspace) return AQ_ENULL;
+    if (!aligned16(packed) || !aligned16(X) || !aligned16(Y) || (workspace && !aligned16(workspace)))
+        return AQ_EALIGN;
+    if (workspace_bytes < need) return AQ_ESIZE;
+    return aqk_gemm(packed, N, K, bits, X, M, ldx, x_dtype, Y, ldy, workspace,
+                    static_cast<hipStream_t>(stream)) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+}
+
+int aq_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if (!packed || !codes_u8) return AQ_ENULL;
+    if (!aligned16(packed) || !aligned16(codes_u8)) return AQ_EALIGN;
+    return aqk_unpack_codes(packed, N, K, bits, codes_u8, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
+int aq_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int block, float* W, void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if (!packed || !W) return AQ_ENULL;
+    if (!aligned16(packed) || !aligned16(W)) return AQ_EALIGN;
+    return aqk_dequant(packed, N, K, bits, W, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
+}  // extern "C"

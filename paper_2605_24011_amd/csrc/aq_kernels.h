@@ -1,0 +1,36 @@
+// Internal launch interface between the C-ABI shim (aq_api.hip) and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+// One decode product y = x W^T as the kernels see it (device-visible, 64 bytes).
+struct AqGemvTask {
+    const uint8_t* blob;
+    const uint16_t* x;
+    float* y;
+    int64_t N;
+    int32_t K;
+    int32_t bits;
+    int32_t x_dtype;
+    int32_t nchunks;    // ceil(K / 256)
+    int32_t wg_begin;   // first workgroup of this task inside a batched launch
+    int32_t wg_count;
+    int64_t pad;
+};
+static_assert(sizeof(AqGemvTask) == 64, "AqGemvTask must stay 64 bytes");
+
+hipError_t aqk_pack(const uint8_t* codes, const uint16_t* scales, int64_t N, int64_t K, int bits,
+                    void* blob, hipStream_t s);
+hipError_t aqk_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, uint8_t* out, hipStream_t s);
+hipError_t aqk_dequant(const void* blob, int64_t N, int64_t K, int bits, float* out, hipStream_t s);
+
+// tiles (of 16 rows) per workgroup used by the decode kernel for a matrix of N rows
+int aqk_gemv_tiles_per_wg(int64_t N, bool batched);
+int aqk_gemv_wg_count(int64_t N, int tiles_per_wg);
+// tasks == nullptr: run `single`; else run `count` tasks from device memory, `total_wgs` workgroups
+hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int tiles_per_wg,
+                    int total_wgs, int max_K, hipStream_t s);
+
+size_t aqk_gemm_workspace(int64_t M, int64_t N, int64_t K, int bits);
+hipError_t aqk_gemm(const void* blob, int64_t N, int64_t K, int bits, const void* X, int64_t M, int64_t ldx,
+                    int x_dtype, float* Y, int64_t ldy, void* ws, hipStream_t s);

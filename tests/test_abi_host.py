@@ -1,0 +1,84 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol
+include/aq.h declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_24011_amd as aq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(aq.LIB_PATH):
+        from paper_2605_24011_amd import build
+        build.build()
+    return aq.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "aq.h")).read()
+    names = set(re.findall(r"\b(aq_[a-z0-9_]+)\s*\(", header))
+    assert {"aq_pack_weights", "aq_qgemv", "aq_qgemm", "aq_packed_size", "aq_qgemv_batch"} <= names
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_packed_size_is_canonical_bytes_on_aligned_shapes(L):
+    # bits/8 + 1/16 bytes per weight when N % 128 == 0 and K % 256 == 0
+    for b, want in ((2, 5_242_880), (3, 7_340_032), (4, 9_437_184)):
+        assert aq.aq_packed_size(4096, 4096, b) == want
+    assert aq.aq_packed_size(11008, 4096, 4) == 25_362_432
+    assert aq.aq_packed_size(4096, 11008, 2) == 14_090_240
+    assert aq.aq_packed_size(16384, 2048, 3) == 14_680_064
+    # padded shapes are never smaller than the canonical form
+    assert aq.aq_packed_size(17, 96, 3) >= 17 * 96 * 3 // 8 + 17 * 3 * 2
+    # invalid arguments give 0
+    for bad in ((0, 32, 4, 32), (4, 33, 4, 32), (4, 32, 5, 32), (4, 32, 4, 64), (4, 32768, 4, 32)):
+        assert aq.aq_packed_size(*bad) == 0
+
+
+def test_argument_validation_without_a_gpu(L):
+    A = 4096   # any 16-byte aligned non-null fake address: validation must fail before it is used
+    assert L.aq_pack_weights(A, A, 16, 64, 7, 32, A, 1 << 20, None) == aq.AQ_EINVAL
+    assert L.aq_pack_weights(A, A, 16, 48, 4, 32, A, 1 << 20, None) == aq.AQ_EINVAL
+    assert L.aq_pack_weights(None, A, 16, 64, 4, 32, A, 1 << 20, None) == aq.AQ_ENULL
+    assert L.aq_pack_weights(A + 4, A, 16, 64, 4, 32, A, 1 << 20, None) == aq.AQ_EALIGN
+    assert L.aq_pack_weights(A, A, 16, 64, 4, 32, A, 100, None) == aq.AQ_ESIZE
+    assert L.aq_qgemv(A, 16, 64, 4, 32, A, 7, A, None) == aq.AQ_EDTYPE
+    assert L.aq_qgemv(A, 16, 64, 4, 32, None, aq.AQ_F16, A, None) == aq.AQ_ENULL
+    assert L.aq_qgemv(A, 16, 64, 4, 32, A, aq.AQ_F16, A + 8, None) == aq.AQ_EALIGN
+    assert L.aq_qgemv(A, 0, 64, 4, 32, A, aq.AQ_F16, A, None) == aq.AQ_EINVAL
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 0, 64, aq.AQ_BF16, A, 16, None, 0, None) == aq.AQ_EINVAL
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 32, aq.AQ_BF16, A, 16, None, 0, None) == aq.AQ_EINVAL   # ldx < K
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, aq.AQ_BF16, A, 8, None, 0, None) == aq.AQ_EINVAL    # ldy < N
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, 9, A, 16, None, 0, None) == aq.AQ_EDTYPE
+    assert L.aq_unpack_codes(None, 16, 64, 4, 32, A, None) == aq.AQ_ENULL
+    assert L.aq_dequant_f32(A, 16, 64, 3, 32, A + 2, None) == aq.AQ_EALIGN
+    for s in (0, -1, -2, -3, -4, -5, -6, -99):
+        assert aq.status_string(s)
+
+
+def test_batch_plan_validation(L):
+    A = 4096
+    n = 3
+    descs = (aq.aq_gemv_desc * n)()
+    for i, d in enumerate(descs):
+        d.packed, d.x, d.y, d.N, d.K, d.bits, d.x_dtype = A, A, A, 256 * (i + 1), 512, 2 + i, aq.AQ_F16
+    size = L.aq_qgemv_batch_plan_size(n)
+    assert size >= n * 64
+    buf = ctypes.create_string_buffer(size)
+    assert L.aq_qgemv_batch_plan(descs, n, 32, buf, size) == aq.AQ_OK
+    assert L.aq_qgemv_batch_plan(descs, n, 32, buf, size - 1) == aq.AQ_ESIZE
+    assert L.aq_qgemv_batch_plan(descs, 0, 32, buf, size) == aq.AQ_EINVAL
+    descs[1].bits = 5
+    assert L.aq_qgemv_batch_plan(descs, n, 32, buf, size) == aq.AQ_EINVAL
+    descs[1].bits = 3
+    descs[2].x = None
+    assert L.aq_qgemv_batch_plan(descs, n, 32, buf, size) == aq.AQ_ENULL
+    bad = ctypes.create_string_buffer(size)
+    assert L.aq_qgemv_batch(bad, A, None) == aq.AQ_EINVAL     # not a plan image
+    assert L.aq_qgemv_batch(buf, None, None) == aq.AQ_ENULL

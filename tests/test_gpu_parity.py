@@ -1,0 +1,238 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Bars: codes and dequantised weights bit-exact; outputs
+relative L2 <= 1e-3 against the fp64 oracle (fp32 accumulation), and exact on inputs
+where every summation order gives the same fp32 bits."""
+import numpy as np
+import pytest
+
+import aq_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+REL_L2_BAR = 1e-3        # the acceptance bar
+REL_L2_EXPECTED = 2e-4   # fp32-accumulation error model: anything above this hints at a bug
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    import paper_2605_24011_amd as aq
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    aq.lib()
+    return torch, aq
+
+
+def _dev(torch, a, kind=None):
+    t = torch.from_numpy(np.ascontiguousarray(a).view(np.int16) if a.dtype == np.uint16 else np.ascontiguousarray(a))
+    t = t.cuda()
+    if kind == "f16":
+        t = t.view(torch.float16)
+    elif kind == "bf16":
+        t = t.view(torch.bfloat16)
+    return t
+
+
+def _pack(torch, aq, codes, scales, N, K, bits):
+    return aq.aq_pack_weights(_dev(torch, codes), _dev(torch, scales), N, K, bits)
+
+
+SHAPES = [  # several tiles, ragged N (not a multiple of 16 / 128), K not a multiple of 256
+    (8, 32), (16, 256), (17, 96), (200, 1056), (128, 512), (300, 4096), (131, 2048),
+]
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K", SHAPES)
+def test_codes_and_dequant_bit_exact(gpu, oracle, bits, N, K):
+    torch, aq = gpu
+    codes, scales = wl.draw_matrix(N, K, bits, 1, N, K)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    q = aq.aq_unpack_codes(packed, N, K, bits).cpu().numpy()
+    assert np.array_equal(q, oracle.unpack(codes, N, K, bits))
+    W = aq.aq_dequant_f32(packed, N, K, bits).cpu().numpy()
+    want = oracle.dequant(codes, scales, N, K, bits)
+    assert np.array_equal(W.astype(np.float64), want)     # -0.0 == 0.0 compares equal
+
+
+def test_subnormal_and_zero_scales_are_exact(gpu, oracle):
+    torch, aq = gpu
+    N, K, bits = 32, 256, 4
+    codes = wl.draw_codes(N, K, bits, 2)
+    scales = wl.draw_scales(N, K, 2)
+    scales[0, :] = 0x0000                  # zero scale: all-zero block
+    scales[1, :] = 0x0001                  # smallest subnormal
+    scales[2, :] = 0x03FF                  # largest subnormal
+    scales[3, :] = 0x0400                  # smallest normal
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    W = aq.aq_dequant_f32(packed, N, K, bits).cpu().numpy()
+    assert np.array_equal(W.astype(np.float64), oracle.dequant(codes, scales, N, K, bits))
+    x = wl.draw_activations(1, K, "f16", 2)
+    y = aq.aq_qgemv(packed, N, K, bits, _dev(torch, x[0], "f16")).cpu().numpy()
+    ref = oracle.qmatmul(codes, scales, N, K, bits, x, "f16")[0]
+    assert oracle.rel_l2(y, ref) <= REL_L2_EXPECTED
+    assert np.all(y[0] == 0.0)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K", SHAPES + [(4096, 4096), (256, 2048), (1000, 11008)])
+def test_qgemv_matches_oracle(gpu, oracle, bits, N, K, dtype):
+    torch, aq = gpu
+    codes, scales = wl.draw_matrix(N, K, bits, 3, N, K)
+    x = wl.draw_activations(1, K, dtype, 3, N, K)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    y = aq.aq_qgemv(packed, N, K, bits, _dev(torch, x[0], dtype)).cpu().numpy()
+    ref = oracle.qmatmul(codes, scales, N, K, bits, x, dtype)[0]
+    err = oracle.rel_l2(y, ref)
+    assert err <= REL_L2_BAR
+    assert err <= REL_L2_EXPECTED, err
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_qgemv_exact_on_integer_inputs(gpu, oracle, bits, dtype):
+    """Integer activations in [-4, 4] and power-of-two scales: all partial sums are exact in
+    fp32 whatever the order, so the GPU must equal the oracle bit for bit."""
+    torch, aq = gpu
+    N, K = 300, 11008
+    codes = wl.draw_codes(N, K, bits, 4, bits)
+    scales = wl.draw_pow2_scales(N, K, 4, bits)
+    x = wl.draw_int_activations(1, K, dtype, 4, bits)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    y = aq.aq_qgemv(packed, N, K, bits, _dev(torch, x[0], dtype)).cpu().numpy()
+    ref = oracle.qmatmul(codes, scales, N, K, bits, x, dtype)[0]
+    assert np.array_equal(y.astype(np.float64), ref)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_qgemv_one_hot_reads_dequantised_weights(gpu, oracle, bits):
+    """x = e_k: y[n] = w_hat[n, k] exactly, for k at every position class of a block."""
+    torch, aq = gpu
+    N, K = 48, 512
+    codes, scales = wl.draw_matrix(N, K, bits, 5, bits)
+    W = oracle.dequant(codes, scales, N, K, bits)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    for k in list(range(0, 64)) + [255, 256, 300, 511]:
+        x = np.zeros(K, dtype=np.uint16)
+        x[k] = 0x3C00
+        y = aq.aq_qgemv(packed, N, K, bits, _dev(torch, x, "f16")).cpu().numpy()
+        assert np.array_equal(y.astype(np.float64), W[:, k]), k
+
+
+def test_qgemv_zero_activations_and_scaling(gpu, oracle):
+    torch, aq = gpu
+    N, K, bits = 64, 1024, 3
+    codes, scales = wl.draw_matrix(N, K, bits, 6)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    y0 = aq.aq_qgemv(packed, N, K, bits, torch.zeros(K, dtype=torch.float16, device="cuda")).cpu().numpy()
+    assert not y0.any()
+    x = wl.draw_activations(1, K, "bf16", 6)
+    # huge and tiny bf16 activations (outside fp16's range) keep the accuracy
+    for shift in (-60, 0, 40):
+        xs = (x[0].astype(np.int32) + (shift << 7)).astype(np.uint16)      # multiply by 2^shift
+        y = aq.aq_qgemv(packed, N, K, bits, _dev(torch, xs, "bf16")).cpu().numpy()
+        ref = oracle.qmatmul(codes, scales, N, K, bits, xs[None], "bf16")[0]
+        assert oracle.rel_l2(y, ref) <= REL_L2_EXPECTED
+
+
+def test_qgemv_batch_matches_single_calls(gpu, oracle):
+    """A mixed-bit stream in one launch gives what the per-matrix calls give, and the oracle's."""
+    torch, aq = gpu
+    specs = [(256, 512, 2, "f16"), (130, 2048, 3, "bf16"), (512, 1056, 4, "f16"), (16, 32, 2, "f16"),
+             (384, 11008, 3, "f16"), (1000, 4096, 4, "bf16")]
+    items, refs, singles = [], [], []
+    for i, (N, K, bits, dt) in enumerate(specs):
+        codes, scales = wl.draw_matrix(N, K, bits, 7, i)
+        x = wl.draw_activations(1, K, dt, 7, i)
+        packed = _pack(torch, aq, codes, scales, N, K, bits)
+        xd = _dev(torch, x[0], dt)
+        y = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, xd, y))
+        refs.append(oracle.qmatmul(codes, scales, N, K, bits, x, dt)[0])
+        singles.append(aq.aq_qgemv(packed, N, K, bits, xd).cpu().numpy())
+    batch = aq.GemvBatch(items)
+    batch.run()
+    batch.run()          # a plan can be replayed
+    torch.cuda.synchronize()
+    for (packed, N, K, bits, xd, y), ref, single in zip(items, refs, singles):
+        got = y.cpu().numpy()
+        assert oracle.rel_l2(got, ref) <= REL_L2_EXPECTED
+        assert oracle.rel_l2(got, single) <= 1e-5
+
+
+GEMM_CASES = [  # (N, K, M)
+    (64, 256, 16), (17, 96, 1), (200, 1056, 7), (256, 2048, 64), (512, 512, 300), (130, 4096, 81),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K,M", GEMM_CASES)
+def test_qgemm_matches_oracle(gpu, oracle, bits, N, K, M, dtype):
+    torch, aq = gpu
+    codes, scales = wl.draw_matrix(N, K, bits, 8, N, K)
+    X = wl.draw_activations(M, K, dtype, 8, N, K, image_rows=min(256, M) if M >= 256 else 0, image_gain=3.0)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, dtype)).cpu().numpy()
+    ref = oracle.qmatmul(codes, scales, N, K, bits, X, dtype)
+    err = oracle.rel_l2(Y, ref)
+    assert err <= REL_L2_BAR
+    assert err <= REL_L2_EXPECTED, err
+    # per-row too: a wrong row hides in the global norm when image rows are 3x larger
+    for m in range(M):
+        assert oracle.rel_l2(Y[m], ref[m]) <= REL_L2_BAR
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_qgemm_exact_on_integer_inputs_and_one_hot(gpu, oracle, bits):
+    torch, aq = gpu
+    N, K, M = 96, 1056, 40
+    codes = wl.draw_codes(N, K, bits, 9, bits)
+    scales = wl.draw_pow2_scales(N, K, 9, bits)
+    X = wl.draw_int_activations(M, K, "bf16", 9, bits)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16")).cpu().numpy()
+    assert np.array_equal(Y.astype(np.float64), oracle.qmatmul(codes, scales, N, K, bits, X, "bf16"))
+    # one-hot rows read dequantised weights through the public entry point, with random scales
+    codes, scales = wl.draw_matrix(N, K, bits, 10, bits)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    ks = [0, 1, 31, 32, 33, 255, 256, 700, K - 1]
+    X = np.zeros((len(ks), K), dtype=np.uint16)
+    for m, k in enumerate(ks):
+        X[m, k] = 0x3F80          # bf16 1.0
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16")).cpu().numpy()
+    W = oracle.dequant(codes, scales, N, K, bits)
+    assert np.array_equal(Y.astype(np.float64), W[:, ks].T)
+
+
+def test_qgemm_row_equals_qgemv_and_strides(gpu, oracle):
+    torch, aq = gpu
+    N, K, M, bits = 192, 2048, 5, 3
+    codes, scales = wl.draw_matrix(N, K, bits, 11)
+    X = wl.draw_activations(M, K, "bf16", 11)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    Xd = _dev(torch, X, "bf16")
+    # padded leading dimensions on both sides
+    Xp = torch.zeros((M, K + 64), dtype=torch.bfloat16, device="cuda")
+    Xp[:, :K] = Xd
+    Yp = torch.full((M, N + 8), -7.0, dtype=torch.float32, device="cuda")
+    aq.aq_qgemm(packed, N, K, bits, Xp[:, :K], Y=Yp[:, :N])
+    Y = Yp.cpu().numpy()
+    assert np.all(Y[:, N:] == -7.0)
+    ref = oracle.qmatmul(codes, scales, N, K, bits, X, "bf16")
+    assert oracle.rel_l2(Y[:, :N], ref) <= REL_L2_EXPECTED
+    for m in range(M):
+        yv = aq.aq_qgemv(packed, N, K, bits, Xd[m].contiguous()).cpu().numpy()
+        assert oracle.rel_l2(yv, Y[m, :N]) <= 1e-5
+
+
+def test_errors_raise_through_the_binding(gpu):
+    torch, aq = gpu
+    x = torch.zeros(64, dtype=torch.float32, device="cuda")
+    p = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    with pytest.raises(aq.AqError):
+        aq.aq_qgemv(p, 16, 64, 4, x)                       # fp32 activations
+    with pytest.raises(aq.AqError):
+        aq.aq_qgemv(p, 16, 64, 5, x.half())                # bad bit-width
+    with pytest.raises(aq.AqError):
+        aq.aq_qgemv(p, 16, 64, 4, x.half()[1:])            # misaligned pointer
