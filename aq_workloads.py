@@ -96,7 +96,9 @@ def draw_codes(N: int, K: int, bits: int, *key: int) -> np.ndarray:
     assert K % BLOCK == 0 and bits in (2, 3, 4)
     nb = K // BLOCK
     g = _rng(101, *key)
-    return g.integers(0, 256, size=(N, nb, 4 * bits), dtype=np.uint8)
+    n = N * nb * 4 * bits
+    raw = g.integers(0, 0xFFFFFFFFFFFFFFFF, size=(n + 7) // 8, dtype=np.uint64, endpoint=True)
+    return raw.view(np.uint8)[:n].reshape(N, nb, 4 * bits).copy()
 
 
 def draw_scales(N: int, K: int, *key: int) -> np.ndarray:
@@ -232,3 +234,38 @@ def iter_stream_inputs(stream: Sequence[MatrixSpec], M: int, dtype: str, seed: i
         else:
             x = draw_activations(M, m.K, dtype, seed, 3, m.index)
         yield m, codes, scales, x
+
+
+# ----------------------------------------------------------------------------
+# the same distributions drawn on the GPU (torch's seeded Philox generator), for the
+# bench, where drawing gigabytes on the host would hold the GPU idle.  Values differ
+# from the numpy draws (another generator) but follow the same recipe; the bench
+# copies what the oracle needs back to the host.
+# ----------------------------------------------------------------------------
+def _torch_gen(device, *key: int):
+    import torch
+    g = torch.Generator(device=device)
+    seed = int(np.random.SeedSequence([int(k) & 0xFFFFFFFF for k in key]).generate_state(1, np.uint64)[0])
+    g.manual_seed(seed & 0x7FFFFFFFFFFFFFFF)
+    return g
+
+
+def draw_matrix_torch(N: int, K: int, bits: int, device, *key: int):
+    """(codes uint8 [N, K/32, 4*bits], scales float16 [N, K/32]) on `device`."""
+    import torch
+    nb = K // BLOCK
+    g = _torch_gen(device, 101, *key)
+    codes = torch.randint(0, 256, (N, nb, 4 * bits), dtype=torch.uint8, device=device, generator=g)
+    d = torch.randn((N, nb), dtype=torch.float32, device=device, generator=g).abs_().mul_(0.02)
+    return codes, d.to(torch.float16)
+
+
+def draw_activations_torch(M: int, K: int, dtype: str, device, *key: int,
+                           image_rows: int = 0, image_gain: float = 1.0):
+    """Activations [M, K] of torch.float16 / torch.bfloat16 on `device`."""
+    import torch
+    g = _torch_gen(device, 303, *key)
+    x = torch.randn((M, K), dtype=torch.float32, device=device, generator=g)
+    if image_rows:
+        x[:image_rows] *= image_gain
+    return x.to(torch.float16 if dtype == "f16" else torch.bfloat16)

@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-quantised matmul hot path on one MI355X.
+
+A step is one decode token through a whole LLaMA-2-7B-shaped backbone: the batch-1
+product y = x W^T over all 224 block-quantised matrices (32 layers x q,k,v,o,gate,up,down)
+with the seeded mixed {2,3,4}-bit allocation, issued as ONE batched launch.  Inputs are
+synthetic, drawn on the GPU before the timed region, and stay resident in HBM.
+
+Printed JSON line (rank 0): metric/value = algorithmic GB/s of that decode pass (packed codes
++ fp16 scales + activations + outputs, divided by wall time); `roofline` = the decode kernel
+against the 8 TB/s HBM peak from HIP-event launch durations; `by_bits` = the same pass at a
+uniform 2, 3 and 4 bits; `prefill` = the M = 300 prefill GEMM over the same matrices in
+TFLOP/s against the dense bf16 MFMA peak; `cpu_baseline` = the CPU oracle timed on a bounded
+sample of the same workload on this host's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16/fp16 matrix rate
+
+
+def stored_bytes(N, K, bits):
+    return N * K * bits // 8 + N * (K // 32) * 2
+
+
+def gemv_bytes(N, K, bits):
+    """Algorithmic bytes of one decode product: packed weights + x (2 B each) + y (4 B each)."""
+    return stored_bytes(N, K, bits) + 2 * K + 4 * N
+
+
+def build_stream(aq, wl, torch, specs, x_dtype, seed_tag):
+    """Pack every matrix of `specs` on the GPU; returns batch items and keeps tensors alive."""
+    items = []
+    for m in specs:
+        codes, scales = wl.draw_matrix_torch(m.N, m.K, m.bits, "cuda", seed_tag, m.index)
+        packed = aq.aq_pack_weights(codes, scales, m.N, m.K, m.bits)
+        x = wl.draw_activations_torch(1, m.K, x_dtype, "cuda", seed_tag, m.index)[0].contiguous()
+        y = torch.empty(m.N, dtype=torch.float32, device="cuda")
+        items.append((packed, m.N, m.K, m.bits, x, y))
+        del codes, scales
+    torch.cuda.synchronize()
+    return items
+
+
+def time_launches(torch, fn, steps, warmup):
+    """Per-launch durations (ms) from HIP events on the launch stream, plus wall time of all steps."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    durs = [a.elapsed_time(b) for a, b in evs]
+    return durs, wall
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--skip-by-bits", action="store_true")
+    ap.add_argument("--skip-prefill", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--prefill-steps", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import aq_workloads as wl
+    import paper_2605_24011_amd as aq
+    aq.lib()      # fail loudly if the HIP library is missing: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+
+    # ---- the timed workload: mixed-bit LLaMA-2-7B-shaped decode stream -----------------
+    specs = wl.backbone_stream("llama2-7b", "mixed")
+    items = build_stream(aq, wl, torch, specs, "f16", 3)
+    batch = aq.GemvBatch(items)
+    step_bytes = sum(gemv_bytes(m.N, m.K, m.bits) for m in specs)
+    weights = sum(m.weights for m in specs)
+    durs, wall = time_launches(torch, batch.run, args.steps, args.warmup)
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms = sum(durs) / len(durs)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = step_bytes / (kernel_ms * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "qgemv_stream_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "qGEMV HBM GB/s (decode, batch 1, algorithmic bytes / time)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "llama2-7b-shaped decode stream, 224 matrices, seeded mixed {2,3,4}-bit allocation "
+                        "(mean 2.5 code bits = %.3f bits/weight stored), fp16 activations, one batched launch per token"
+                        % wl.stored_bits_per_weight(specs),
+            "matrices": len(specs),
+            "weights": weights,
+            "bytes_per_step": step_bytes,
+            "bits_histogram": {str(b): sum(1 for m in specs if m.bits == b) for b in (2, 3, 4)},
+        },
+        "tokens_per_s": round(1e3 / ms_per_step, 1),
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "roofline": {
+            "kernel": "qgemv_kernel<8> (batched decode)",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": traffic,
+            "avg_launch_ms": round(kernel_ms, 4),
+        },
+    }
+
+    # ---- CPU oracle on a bounded sample of the same workload ----------------------------
+    if not args.skip_cpu:
+        from oracle import aq_oracle
+        aq_oracle.build()
+        sample = [0, 4]          # layer 0: q (4096x4096) and gate (11008x4096)
+        cpu_bytes, cpu_s, worst = 0, 0.0, 0.0
+        batch.run()
+        torch.cuda.synchronize()
+        for idx in sample:
+            m = specs[idx]
+            codes, scales = wl.draw_matrix_torch(m.N, m.K, m.bits, "cuda", 3, m.index)
+            c = codes.cpu().numpy()
+            s = scales.view(torch.int16).cpu().numpy().view(np.uint16)
+            x = items[idx][4].view(torch.int16).cpu().numpy().view(np.uint16)[None, :]
+            t0 = time.perf_counter()
+            ref = aq_oracle.qmatmul(c, s, m.N, m.K, m.bits, x, "f16")[0]
+            cpu_s += time.perf_counter() - t0
+            cpu_bytes += gemv_bytes(m.N, m.K, m.bits)
+            worst = max(worst, aq_oracle.rel_l2(items[idx][5].cpu().numpy(), ref))
+        out["cpu_baseline"] = {
+            "value": round(cpu_bytes / cpu_s / 1e9, 4),
+            "unit": "GB/s",
+            "cores": aq_oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "fp64 unpack+dequant+matmul of 2 of the 224 matrices (layer 0 q 4096x4096 and gate 11008x4096), "
+                      "%.1f s of CPU time" % cpu_s,
+            "gpu_vs_oracle_rel_l2": float("%.3g" % worst),
+        }
+
+    # ---- the same pass at a uniform bit-width (cold: 2.0 / 2.8 / 3.6 GB per pass) ----------
+    if not args.skip_by_bits:
+        by_bits = {}
+        for b in (2, 3, 4):
+            sp = wl.backbone_stream("llama2-7b", "b%d" % b)
+            its = build_stream(aq, wl, torch, sp, "f16", 20 + b)
+            bt = aq.GemvBatch(its)
+            nbytes = sum(gemv_bytes(m.N, m.K, m.bits) for m in sp)
+            d, w = time_launches(torch, bt.run, max(10, args.steps // 2), 3)
+            ms = sum(d) / len(d)
+            by_bits[str(b)] = {"GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                               "pct_hbm_peak": round(100 * nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+                               "ms": round(ms, 4), "tokens_per_s": round(1e3 / ms, 1), "bytes": nbytes}
+            del its, bt
+            torch.cuda.empty_cache()
+        out["by_bits"] = by_bits
+
+    # ---- prefill: M = 300 over the same mixed stream -------------------------------------
+    if not args.skip_prefill:
+        M = wl.PREFILL_M
+        Xs = {}
+        for K in sorted({m.K for m in specs}):
+            Xs[K] = wl.draw_activations_torch(M, K, "bf16", "cuda", 4, K, image_rows=wl.PREFILL_IMAGE_ROWS,
+                                              image_gain=wl.PREFILL_IMAGE_GAIN)
+        Ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({m.N for m in specs})}
+
+        def prefill_pass():
+            for (packed, N, K, bits, _x, _y) in items:
+                aq.aq_qgemm(packed, N, K, bits, Xs[K], Y=Ys[N])
+
+        d, w = time_launches(torch, prefill_pass, args.prefill_steps, 1)
+        ms = sum(d) / len(d)
+        flops = 2.0 * M * weights
+        out["prefill"] = {
+            "workload": "M=300 (256 image rows x3 + 44 text rows, bf16) over the same 224 matrices",
+            "ms": round(ms, 3),
+            "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
+            "mfma_frac_of_bf16_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+            "prefill_tokens_per_s": round(M / (ms * 1e-3), 1),
+        }
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -23,6 +23,7 @@
 // A batched launch runs many matrices (each with its own bit-width) in one grid.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <cstdlib>
 #include "aq_layout.h"
 #include "aq_kernels.h"
 
@@ -33,6 +34,7 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 half4v __attribute__((ext_vector_type(4)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 
 constexpr int WAVES = 4;
 constexpr int THREADS = WAVES * 64;
@@ -203,24 +205,55 @@ __device__ float stage_x(const AqGemvTask& t, uint16_t* xh, float* corr, float* 
         }
     }
     __syncthreads();
+    // corr[block] = sum_t (magic_t + z) (x[2t] + x[2t+1]): one 2-wide fp16 dot product (fp32
+    // accumulate) per pair; the constants are small integers, exact in fp16
     const float z = (float)(1 << (BITS - 1));
     for (int b = tid; b < t.nchunks * AQ_CHUNK_BLOCKS; b += THREADS) {
-        const __half* xb = reinterpret_cast<const __half*>(xh) + b * AQ_BLOCK;
+        const u32x4* xb = reinterpret_cast<const u32x4*>(xh + b * AQ_BLOCK);
         float s = 0.f;
 #pragma unroll
-        for (int p = 0; p < 16; ++p)
-            s += (Codec<BITS>::offset(p) + z) * (__half2float(xb[2 * p]) + __half2float(xb[2 * p + 1]));
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const u32x4 v = xb[q4];
+            const uint32_t ws[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const _Float16 k = (_Float16)(Codec<BITS>::offset(4 * q4 + j) + z);
+                s = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, ws[j]), half2v{k, k}, s, false);
+            }
+        }
         corr[b] = s;
     }
     __syncthreads();
     return unscale;
 }
 
+#ifndef AQ_GEMV_MIN_WAVES
+#define AQ_GEMV_MIN_WAVES 3
+#endif
 template <int BITS, int RT>
-__device__ void gemv_body(const AqGemvTask& t, int wg, uint8_t* smem)
+__global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES) void qgemv_kernel(const AqGemvTask* __restrict__ tasks, int count,
+                                                        AqGemvTask single)
 {
+    extern __shared__ __align__(16) uint8_t smem[];
     constexpr int WORDS = Codec<BITS>::WORDS;
     constexpr int UNIT = 512 * BITS + 256;
+    constexpr int DEPTH = RT < 4 ? RT : 4;          // units of loads kept in flight per wavefront
+
+    AqGemvTask t;
+    int wg = blockIdx.x;
+    if (count == 0) {
+        t = single;
+    } else {
+        int lo = 0, hi = count - 1;          // last task whose first workgroup is <= blockIdx.x
+        while (lo < hi) {
+            int mid = (lo + hi + 1) >> 1;
+            if (tasks[mid].wg_begin <= wg) lo = mid; else hi = mid - 1;
+        }
+        t = tasks[lo];
+        wg -= t.wg_begin;
+    }
+    if (wg >= t.wg_count) return;
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 4, c = lane & 15;
     const int nch = t.nchunks, Kpad = nch * AQ_CHUNK_K;
@@ -231,77 +264,91 @@ __device__ void gemv_body(const AqGemvTask& t, int wg, uint8_t* smem)
     uint32_t* zeros = reinterpret_cast<uint32_t*>(smem + Kpad * 2 + nch * 32 + WAVES * RT * 512);  // 16 words
     if (tid < 16) zeros[tid] = 0u;
 
-    const float unscale = stage_x<BITS>(t, xh, corr, red);
-
     const int subs = AQ_GROUP_TILES / RT;
     const int group = wg / subs, sub = wg % subs;
     const bool diag = (c < 8) && ((c >> 1) == g);
     const bool hi = (c & 1) != 0;
 
+    // Register ring of DEPTH units (raw code words + 4 scales per lane).  The wavefront walks its
+    // units in the order (chunk, tile); a slot is refilled with the unit DEPTH positions ahead as
+    // soon as its words have been unpacked, so DEPTH - 1 units of loads stay in flight.  The first
+    // fill is issued before x is staged, so that it overlaps the workgroup's start-up.
+    const uint8_t* gbase = t.blob + ((int64_t)group * nch * AQ_GROUP_TILES + sub * RT) * UNIT;
+    const int64_t chunk_stride = (int64_t)AQ_GROUP_TILES * UNIT;
+    const int sc_off = 512 * BITS + (g * 8 + (c & 7)) * 8;
+    uint32_t raw[DEPTH][WORDS];
+    u32x2 sc[DEPTH];
+    if (wave < nch) {
+        const uint8_t* ub = gbase + wave * chunk_stride;
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+            Codec<BITS>::load(ub + u * UNIT, lane, raw[u]);
+            sc[u] = __builtin_nontemporal_load(as_global<u32x2>(ub + u * UNIT + sc_off));
+        }
+    }
+
+    // Per-wavefront partial sums live in LDS (red[wave][tile][r][g*8 + c], read-modify-written by
+    // their owner only), which keeps the tile loop a real loop with a small body and few registers.
+    float* myred = red + wave * RT * 128 + g * 8 + (c & 7);
+    for (int i = tid; i < WAVES * RT * 128; i += THREADS) red[i] = 0.f;
+
+    const float unscale = stage_x<BITS>(t, xh, corr, reinterpret_cast<float*>(zeros + 16));
+
     const typename Codec<BITS>::Magic magic = Codec<BITS>::magic();
-    float acc[RT][4];
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[rt][r] = 0.f;
 
     for (int ch = wave; ch < nch; ch += WAVES) {
-        const uint8_t* ub = t.blob + ((int64_t)(group * nch + ch) * AQ_GROUP_TILES + sub * RT) * UNIT;
-        uint32_t raw[RT][WORDS];
-        u32x2 sc[RT];
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            Codec<BITS>::load(ub + rt * UNIT, lane, raw[rt]);
-            sc[rt] = __builtin_nontemporal_load(as_global<u32x2>(ub + rt * UNIT + 512 * BITS) + (g * 8 + (c & 7)));
-        }
-        // B operand: x of block c on the slots of block c, zero elsewhere
-        const uint32_t* xsrc = diag ? reinterpret_cast<const uint32_t*>(xh + (ch * AQ_CHUNK_BLOCKS + c) * AQ_BLOCK)
-                                    : zeros;
-        uint32_t xp[16];
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            u32x4 v = *reinterpret_cast<const u32x4*>(xsrc + (diag ? 4 * q4 : 0));
-            xp[4 * q4 + 0] = v.x; xp[4 * q4 + 1] = v.y; xp[4 * q4 + 2] = v.z; xp[4 * q4 + 3] = v.w;
-        }
+        const bool more = ch + WAVES < nch;                     // uniform per wavefront
+        const uint8_t* ub = gbase + ch * chunk_stride;
+        // B operand: x of block c goes to the k-slots of block c (the low two registers for even
+        // c, the high two for odd c); every other slot reads the 64-byte zero region
+        const uint32_t* xblk = reinterpret_cast<const uint32_t*>(xh + (ch * AQ_CHUNK_BLOCKS + (c & 7)) * AQ_BLOCK);
+        const u32x2* blo = reinterpret_cast<const u32x2*>((diag && !hi) ? xblk : zeros);
+        const u32x2* bhi = reinterpret_cast<const u32x2*>((diag && hi) ? xblk : zeros);
         half8 B[8];
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
-            u32x4 bv;
-            bv.x = hi ? 0u : xp[2 * m];
-            bv.y = hi ? 0u : xp[2 * m + 1];
-            bv.z = hi ? xp[2 * m] : 0u;
-            bv.w = hi ? xp[2 * m + 1] : 0u;
-            B[m] = __builtin_bit_cast(half8, bv);
+            const u32x2 l = blo[m], h = bhi[m];
+            B[m] = __builtin_bit_cast(half8, u32x4{l.x, l.y, h.x, h.y});
         }
         const float nc = -corr[ch * AQ_CHUNK_BLOCKS + (c & 7)];
         const float4v negc = {nc, nc, nc, nc};
 
+#pragma unroll 1
+        for (int rt0 = 0; rt0 < RT; rt0 += DEPTH) {
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            uint32_t a0[16], a1[16];
-            Codec<BITS>::unpack(&raw[rt][0], magic, a0);
-            Codec<BITS>::unpack(&raw[rt][BITS], magic, a1);
-            float4v D = negc;
+            for (int u = 0; u < DEPTH; ++u) {
+                uint32_t a0[16], a1[16];
+                Codec<BITS>::unpack(&raw[u][0], magic, a0);
+                Codec<BITS>::unpack(&raw[u][BITS], magic, a1);
+                const half4v d4 = __builtin_bit_cast(half4v, sc[u]);      // scales of rows 4g .. 4g+3
+                // refill: DEPTH positions ahead is tile rt0+u+DEPTH of this chunk, or tile
+                // rt0+u+DEPTH-RT of the wavefront's next chunk
+                const int nt = rt0 + u + DEPTH;
+                const bool same = nt < RT;                                 // uniform
+                if (same || more) {
+                    const uint8_t* un = same ? ub + nt * UNIT : ub + WAVES * chunk_stride + (nt - RT) * UNIT;
+                    Codec<BITS>::load(un, lane, raw[u]);
+                    sc[u] = __builtin_nontemporal_load(as_global<u32x2>(un + sc_off));
+                }
+                // running sums of this tile: read early, the MFMA chain hides the LDS latency
+                float* dst = myred + (rt0 + u) * 128;
+                float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+                if (c < 8) { o0 = dst[0]; o1 = dst[32]; o2 = dst[64]; o3 = dst[96]; }
+                float4v D = negc;
 #pragma unroll
-            for (int m = 0; m < 8; ++m) {
-                u32x4 av = {a0[2 * m], a0[2 * m + 1], a1[2 * m], a1[2 * m + 1]};
-                D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, av), B[m], D, 0, 0, 0);
+                for (int m = 0; m < 8; ++m) {
+                    u32x4 av = {a0[2 * m], a0[2 * m + 1], a1[2 * m], a1[2 * m + 1]};
+                    D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, av), B[m], D, 0, 0, 0);
+                }
+                o0 = fmaf(D[0], (float)d4.x, o0);
+                o1 = fmaf(D[1], (float)d4.y, o1);
+                o2 = fmaf(D[2], (float)d4.z, o2);
+                o3 = fmaf(D[3], (float)d4.w, o3);
+                if (c < 8) { dst[0] = o0; dst[32] = o1; dst[64] = o2; dst[96] = o3; }   // wave-private slots
             }
-            const half4v d4 = __builtin_bit_cast(half4v, sc[rt]);     // scales of rows 4g .. 4g+3
-            acc[rt][0] = fmaf(D[0], (float)d4.x, acc[rt][0]);
-            acc[rt][1] = fmaf(D[1], (float)d4.y, acc[rt][1]);
-            acc[rt][2] = fmaf(D[2], (float)d4.z, acc[rt][2]);
-            acc[rt][3] = fmaf(D[3], (float)d4.w, acc[rt][3]);
         }
     }
 
-    // meet in LDS: red[wave][rt][r][g][c<8]
-    if (c < 8) {
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) red[((wave * RT + rt) * 4 + r) * 32 + g * 8 + c] = acc[rt][r];
-    }
     __syncthreads();
     if (tid < RT * 16) {
         const int rt = tid >> 4, i = tid & 15, gg = i >> 2, r = i & 3;
@@ -317,43 +364,21 @@ __device__ void gemv_body(const AqGemvTask& t, int wg, uint8_t* smem)
     }
 }
 
-template <int RT>
-__global__ __launch_bounds__(THREADS) void qgemv_kernel(const AqGemvTask* __restrict__ tasks, int count,
-                                                        AqGemvTask single)
-{
-    extern __shared__ __align__(16) uint8_t smem[];
-    AqGemvTask t;
-    int wg = blockIdx.x;
-    if (count == 0) {
-        t = single;
-    } else {
-        int lo = 0, hi = count - 1;          // last task whose first workgroup is <= blockIdx.x
-        while (lo < hi) {
-            int mid = (lo + hi + 1) >> 1;
-            if (tasks[mid].wg_begin <= wg) lo = mid; else hi = mid - 1;
-        }
-        t = tasks[lo];
-        wg -= t.wg_begin;
-    }
-    if (wg >= t.wg_count) return;
-    switch (t.bits) {
-        case 2: gemv_body<2, RT>(t, wg, smem); break;
-        case 3: gemv_body<3, RT>(t, wg, smem); break;
-        default: gemv_body<4, RT>(t, wg, smem); break;
-    }
-}
-
 size_t gemv_lds_bytes(int max_K, int RT)
 {
     int nch = (max_K + AQ_CHUNK_K - 1) / AQ_CHUNK_K;
-    return (size_t)nch * AQ_CHUNK_K * 2 + (size_t)nch * 32 + (size_t)WAVES * RT * 512 + 64;
+    return (size_t)nch * AQ_CHUNK_K * 2 + (size_t)nch * 32 + (size_t)WAVES * RT * 512 + 64 + 16;
 }
 
 }  // namespace
 
 int aqk_gemv_tiles_per_wg(int64_t N, bool batched)
 {
-    if (batched) return 8;
+    if (batched) {
+        const char* e = getenv("AQ_BATCH_RT");
+        int v = e ? atoi(e) : 8;
+        return (v == 1 || v == 2 || v == 4 || v == 8) ? v : 8;
+    }
     // a lone matrix: keep at least ~1024 workgroups where the matrix allows it
     int64_t tiles = (N + AQ_TILE_ROWS - 1) / AQ_TILE_ROWS;
     if (tiles >= 8192) return 8;
@@ -367,16 +392,27 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg)
     return (int)(aq_num_groups(N) * (AQ_GROUP_TILES / tiles_per_wg));
 }
 
-hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int tiles_per_wg,
+template <int RT>
+static void launch_bits(int bits, dim3 grid, size_t lds, hipStream_t s, const AqGemvTask* tasks, int count,
+                        const AqGemvTask& single)
+{
+    dim3 block(THREADS);
+    if (bits == 2) hipLaunchKernelGGL((qgemv_kernel<2, RT>), grid, block, lds, s, tasks, count, single);
+    else if (bits == 3) hipLaunchKernelGGL((qgemv_kernel<3, RT>), grid, block, lds, s, tasks, count, single);
+    else hipLaunchKernelGGL((qgemv_kernel<4, RT>), grid, block, lds, s, tasks, count, single);
+}
+
+// all tasks of one launch share `bits`
+hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
                     int total_wgs, int max_K, hipStream_t s)
 {
     size_t lds = gemv_lds_bytes(max_K, tiles_per_wg);
-    dim3 grid((unsigned)total_wgs), block(THREADS);
+    dim3 grid((unsigned)total_wgs);
     switch (tiles_per_wg) {
-        case 1: hipLaunchKernelGGL(qgemv_kernel<1>, grid, block, lds, s, tasks_dev, count, single); break;
-        case 2: hipLaunchKernelGGL(qgemv_kernel<2>, grid, block, lds, s, tasks_dev, count, single); break;
-        case 4: hipLaunchKernelGGL(qgemv_kernel<4>, grid, block, lds, s, tasks_dev, count, single); break;
-        default: hipLaunchKernelGGL(qgemv_kernel<8>, grid, block, lds, s, tasks_dev, count, single); break;
+        case 1: launch_bits<1>(bits, grid, lds, s, tasks_dev, count, single); break;
+        case 2: launch_bits<2>(bits, grid, lds, s, tasks_dev, count, single); break;
+        case 4: launch_bits<4>(bits, grid, lds, s, tasks_dev, count, single); break;
+        default: launch_bits<8>(bits, grid, lds, s, tasks_dev, count, single); break;
     }
     return hipGetLastError();
 }

@@ -27,8 +27,9 @@ hipError_t aqk_dequant(const void* blob, int64_t N, int64_t K, int bits, float* 
 // tiles (of 16 rows) per workgroup used by the decode kernel for a matrix of N rows
 int aqk_gemv_tiles_per_wg(int64_t N, bool batched);
 int aqk_gemv_wg_count(int64_t N, int tiles_per_wg);
-// tasks == nullptr: run `single`; else run `count` tasks from device memory, `total_wgs` workgroups
-hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int tiles_per_wg,
+// count == 0: run `single`; else run `count` tasks from device memory, `total_wgs` workgroups.
+// Every task of one launch has the same bit-width `bits`.
+hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
                     int total_wgs, int max_K, hipStream_t s);
 
 size_t aqk_gemm_workspace(int64_t M, int64_t N, int64_t K, int bits);
