@@ -227,6 +227,60 @@ __device__ float stage_x(const AqGemvTask& t, uint16_t* xh, float* corr, float* 
     return unscale;
 }
 
+#ifndef AQ_GEMV_SCHED_FENCE
+#define AQ_GEMV_SCHED_FENCE 1
+#endif
+// One unit (16 rows x 8 blocks): unpack the ring slot, optionally refill it from `next`, run the
+// 8 MFMAs against the block-diagonal B and fold the block sums, times their fp16 scales, into the
+// tile's running sums at `sums` (LDS, owned by this lane).
+template <int BITS, bool REFILL>
+__device__ __forceinline__ void unit_step(uint32_t (&raw)[Codec<BITS>::WORDS], u32x2& sc,
+                                          const typename Codec<BITS>::Magic& magic, const half8 (&B)[8],
+                                          const float4v& negc, const uint8_t* next, int lane, int sc_off,
+                                          float* sums)
+{
+#if AQ_GEMV_SCHED_FENCE
+    // Pin this unit's unpack behind the previous unit's stores: without it the compiler hoists the
+    // unpack of every unit in flight to the top of the loop body and holds all of their operands
+    // live at once (2-3x the registers).  Other wavefronts on the SIMD fill the MFMA latency.
+#pragma unroll
+    for (int i = 0; i < Codec<BITS>::WORDS; ++i) asm volatile("" : "+v"(raw[i]) : : "memory");
+#endif
+    uint32_t a0[16], a1[16];
+    Codec<BITS>::unpack(&raw[0], magic, a0);
+    Codec<BITS>::unpack(&raw[BITS], magic, a1);
+    const half4v d4 = __builtin_bit_cast(half4v, sc);           // scales of rows 4g .. 4g+3
+    if (REFILL) {
+        Codec<BITS>::load(next, lane, raw);
+        sc = __builtin_nontemporal_load(as_global<u32x2>(next + sc_off));
+    }
+    float o0 = sums[0], o1 = sums[32], o2 = sums[64], o3 = sums[96];   // read early: the MFMAs hide it
+    float4v D = negc;
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+        u32x4 av = {a0[2 * m], a0[2 * m + 1], a1[2 * m], a1[2 * m + 1]};
+        D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, av), B[m], D, 0, 0, 0);
+    }
+    sums[0] = fmaf(D[0], (float)d4.x, o0);
+    sums[32] = fmaf(D[1], (float)d4.y, o1);
+    sums[64] = fmaf(D[2], (float)d4.z, o2);
+    sums[96] = fmaf(D[3], (float)d4.w, o3);
+}
+
+// DEPTH consecutive units of one chunk starting at tile rt0; slot u is refilled from refill + u*UNIT
+template <int BITS, int DEPTH, bool REFILL>
+__device__ __forceinline__ void unit_block(uint32_t (&raw)[DEPTH][Codec<BITS>::WORDS], u32x2 (&sc)[DEPTH],
+                                           const typename Codec<BITS>::Magic& magic, const half8 (&B)[8],
+                                           const float4v& negc, const uint8_t* refill, int lane, int sc_off,
+                                           float* sums, int tile_stride)
+{
+    constexpr int UNIT = 512 * BITS + 256;
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u)
+        unit_step<BITS, REFILL>(raw[u], sc[u], magic, B, negc, refill + u * UNIT, lane, sc_off,
+                                sums + u * tile_stride);
+}
+
 #ifndef AQ_GEMV_MIN_WAVES
 #define AQ_GEMV_MIN_WAVES 3
 #endif
@@ -254,14 +308,15 @@ __global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES) void qgemv_kernel(const
     }
     if (wg >= t.wg_count) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: keep it in an SGPR
     const int g = lane >> 4, c = lane & 15;
     const int nch = t.nchunks, Kpad = nch * AQ_CHUNK_K;
 
     uint16_t* xh = reinterpret_cast<uint16_t*>(smem);                       // Kpad fp16
     float* corr = reinterpret_cast<float*>(smem + Kpad * 2);                // nch * 8
-    float* red = reinterpret_cast<float*>(smem + Kpad * 2 + nch * 32);      // WAVES * RT * 128
-    uint32_t* zeros = reinterpret_cast<uint32_t*>(smem + Kpad * 2 + nch * 32 + WAVES * RT * 512);  // 16 words
+    float* red = reinterpret_cast<float*>(smem + Kpad * 2 + nch * 32);      // WAVES * (RT + 1) * 128
+    uint32_t* zeros = reinterpret_cast<uint32_t*>(smem + Kpad * 2 + nch * 32 + WAVES * (RT + 1) * 512);  // 16 words
     if (tid < 16) zeros[tid] = 0u;
 
     const int subs = AQ_GROUP_TILES / RT;
@@ -288,19 +343,36 @@ __global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES) void qgemv_kernel(const
     }
 
     // Per-wavefront partial sums live in LDS (red[wave][tile][r][g*8 + c], read-modify-written by
-    // their owner only), which keeps the tile loop a real loop with a small body and few registers.
-    float* myred = red + wave * RT * 128 + g * 8 + (c & 7);
-    for (int i = tid; i < WAVES * RT * 128; i += THREADS) red[i] = 0.f;
+    // their owner only), so the tile loop needs no accumulator registers.  Lanes c >= 8 hold no
+    // useful MFMA column; they update a private dummy block so that no lane ever branches.
+    float* mysum;
+    int tile_stride;
+    {
+        float* dummy = red + WAVES * RT * 128;                 // WAVES * 128 floats
+        const int idx = g * 8 + (c & 7);
+        mysum = (c < 8) ? red + wave * RT * 128 + idx : dummy + wave * 128 + idx;
+        tile_stride = (c < 8) ? 128 : 0;
+    }
+    for (int i = tid; i < WAVES * (RT + 1) * 128; i += THREADS) red[i] = 0.f;
 
     const float unscale = stage_x<BITS>(t, xh, corr, reinterpret_cast<float*>(zeros + 16));
 
     const typename Codec<BITS>::Magic magic = Codec<BITS>::magic();
 
-    for (int ch = wave; ch < nch; ch += WAVES) {
-        const bool more = ch + WAVES < nch;                     // uniform per wavefront
-        const uint8_t* ub = gbase + ch * chunk_stride;
-        // B operand: x of block c goes to the k-slots of block c (the low two registers for even
-        // c, the high two for odd c); every other slot reads the 64-byte zero region
+    // The wavefront's units in visiting order: chunk wave, wave + 4, ...; inside a chunk tiles
+    // 0 .. RT-1, taken DEPTH at a time ("blocks").  Block j + 1 refills the ring while block j is
+    // being consumed.
+    constexpr int NBLK = RT / DEPTH;
+    const int my_chunks = wave < nch ? (nch - wave + WAVES - 1) / WAVES : 0;
+    const int total = my_chunks * NBLK;
+#pragma unroll 1
+    for (int j = 0; j < total; ++j) {
+        const int cj = j / NBLK, rb = j % NBLK;
+        // B operand of the chunk: x of block c goes to the k-slots of block c (the low two registers
+        // for even c, the high two for odd c); every other slot reads the 64-byte zero region.  It
+        // is re-read from LDS for every block of tiles: that costs LDS reads only and keeps its 32
+        // registers from living across the loop.
+        const int ch = wave + cj * WAVES;
         const uint32_t* xblk = reinterpret_cast<const uint32_t*>(xh + (ch * AQ_CHUNK_BLOCKS + (c & 7)) * AQ_BLOCK);
         const u32x2* blo = reinterpret_cast<const u32x2*>((diag && !hi) ? xblk : zeros);
         const u32x2* bhi = reinterpret_cast<const u32x2*>((diag && hi) ? xblk : zeros);
@@ -312,40 +384,13 @@ __global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES) void qgemv_kernel(const
         }
         const float nc = -corr[ch * AQ_CHUNK_BLOCKS + (c & 7)];
         const float4v negc = {nc, nc, nc, nc};
-
-#pragma unroll 1
-        for (int rt0 = 0; rt0 < RT; rt0 += DEPTH) {
-#pragma unroll
-            for (int u = 0; u < DEPTH; ++u) {
-                uint32_t a0[16], a1[16];
-                Codec<BITS>::unpack(&raw[u][0], magic, a0);
-                Codec<BITS>::unpack(&raw[u][BITS], magic, a1);
-                const half4v d4 = __builtin_bit_cast(half4v, sc[u]);      // scales of rows 4g .. 4g+3
-                // refill: DEPTH positions ahead is tile rt0+u+DEPTH of this chunk, or tile
-                // rt0+u+DEPTH-RT of the wavefront's next chunk
-                const int nt = rt0 + u + DEPTH;
-                const bool same = nt < RT;                                 // uniform
-                if (same || more) {
-                    const uint8_t* un = same ? ub + nt * UNIT : ub + WAVES * chunk_stride + (nt - RT) * UNIT;
-                    Codec<BITS>::load(un, lane, raw[u]);
-                    sc[u] = __builtin_nontemporal_load(as_global<u32x2>(un + sc_off));
-                }
-                // running sums of this tile: read early, the MFMA chain hides the LDS latency
-                float* dst = myred + (rt0 + u) * 128;
-                float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
-                if (c < 8) { o0 = dst[0]; o1 = dst[32]; o2 = dst[64]; o3 = dst[96]; }
-                float4v D = negc;
-#pragma unroll
-                for (int m = 0; m < 8; ++m) {
-                    u32x4 av = {a0[2 * m], a0[2 * m + 1], a1[2 * m], a1[2 * m + 1]};
-                    D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, av), B[m], D, 0, 0, 0);
-                }
-                o0 = fmaf(D[0], (float)d4.x, o0);
-                o1 = fmaf(D[1], (float)d4.y, o1);
-                o2 = fmaf(D[2], (float)d4.z, o2);
-                o3 = fmaf(D[3], (float)d4.w, o3);
-                if (c < 8) { dst[0] = o0; dst[32] = o1; dst[64] = o2; dst[96] = o3; }   // wave-private slots
-            }
+        float* sums = mysum + rb * DEPTH * tile_stride;
+        if (j + 1 < total) {
+            const int cn = (j + 1) / NBLK, rn = (j + 1) % NBLK;
+            const uint8_t* nb = gbase + (int64_t)(wave + cn * WAVES) * chunk_stride + rn * DEPTH * UNIT;
+            unit_block<BITS, DEPTH, true>(raw, sc, magic, B, negc, nb, lane, sc_off, sums, tile_stride);
+        } else {
+            unit_block<BITS, DEPTH, false>(raw, sc, magic, B, negc, gbase, lane, sc_off, sums, tile_stride);
         }
     }
 
@@ -367,7 +412,7 @@ __global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES) void qgemv_kernel(const
 size_t gemv_lds_bytes(int max_K, int RT)
 {
     int nch = (max_K + AQ_CHUNK_K - 1) / AQ_CHUNK_K;
-    return (size_t)nch * AQ_CHUNK_K * 2 + (size_t)nch * 32 + (size_t)WAVES * RT * 512 + 64 + 16;
+    return (size_t)nch * AQ_CHUNK_K * 2 + (size_t)nch * 32 + (size_t)WAVES * (RT + 1) * 512 + 64 + 16;
 }
 
 }  // namespace
