@@ -17,7 +17,7 @@ AQ_F16, AQ_BF16 = 1, 2
 BLOCK = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libaq.so")
+LIB_PATH = os.environ.get("AQ_LIB_PATH") or os.path.join(_HERE, "libaq.so")   # AQ_LIB_PATH: another build of the same library
 _lib = None
 
 _i64, _int, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t

@@ -18,8 +18,8 @@
 //  * the fp16 block scale multiplies the finished block sum in fp32 (one mixed-precision FMA per
 //    block and row), so every product is exact and only fp32 summation rounds.
 //
-// Work split: a workgroup of 4 wavefronts owns RT tiles (16 rows each) of one 128-row group and
-// the whole K extent; wavefront w takes chunks w, w+4, ...; partial sums meet in LDS at the end.
+// Work split: a workgroup of 4 wavefronts owns 4 or 8 tiles (16 rows each) of one 128-row group;
+// every wavefront walks the whole K extent of its own one or two tiles, sums stay in registers.
 // A batched launch runs many matrices (each with its own bit-width) in one grid.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -77,6 +77,9 @@ template <> struct Codec<2> {
     __device__ static Magic magic() {
         return {opaque_vgpr(0x54005400u), opaque_vgpr(0x4C004C00u), opaque_vgpr(0x44004400u)};
     }
+    __device__ static void fence(Magic& k, float& a) {
+        asm volatile("" : "+v"(k.m64), "+v"(k.m16), "+v"(k.m4), "+v"(a));
+    }
     __device__ static void unpack(const uint32_t* w, const Magic& k, uint32_t (&a)[16]) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -104,6 +107,7 @@ template <> struct Codec<4> {
     }
     struct Magic { uint32_t m256, m16; };
     __device__ static Magic magic() { return {opaque_vgpr(0x5C005C00u), opaque_vgpr(0x4C004C00u)}; }
+    __device__ static void fence(Magic& k, float& a) { asm volatile("" : "+v"(k.m256), "+v"(k.m16), "+v"(a)); }
     __device__ static void unpack(const uint32_t* w, const Magic& k, uint32_t (&a)[16]) {
 #pragma unroll
         for (int h = 0; h < 4; ++h) {
@@ -130,6 +134,7 @@ template <> struct Codec<3> {
     }
     struct Magic { uint32_t m128, m16; };
     __device__ static Magic magic() { return {opaque_vgpr(0x58005800u), opaque_vgpr(0x4C004C00u)}; }
+    __device__ static void fence(Magic& k, float& a) { asm volatile("" : "+v"(k.m128), "+v"(k.m16), "+v"(a)); }
     __device__ static void unpack(const uint32_t* w, const Magic& k, uint32_t (&a)[16]) {
 #pragma unroll
         for (int h = 0; h < 3; ++h) {
@@ -149,21 +154,37 @@ template <> struct Codec<3> {
 
 __device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
+// LDS layout of the staged x.  A block's 32 fp16 are 8 "quads" of 4 (8 bytes: the two B-operand
+// registers of one MFMA).  Blocks are stored in pairs, quad by quad, with an 8-byte zero between:
+//     entry m of pair p (24 bytes) = [quad m of block 2p][8 zero bytes][quad m of block 2p+1]
+// so the 16 bytes at entry m are (x, x, 0, 0) -- the B registers of an even block's lane -- and the
+// 16 bytes at entry m + 8 are (0, 0, x, x), those of an odd block's lane: one 16-byte LDS read
+// (8-byte aligned) per MFMA, no ALU work to place the zeros.
+constexpr int X_ENTRY_BYTES = 24;
+constexpr int X_PAIR_BYTES = 8 * X_ENTRY_BYTES;     // 192
+__device__ inline int x_lds_offset(int block, int quad)
+{
+    return (block >> 1) * X_PAIR_BYTES + quad * X_ENTRY_BYTES + (block & 1) * 16;
+}
+
 // Stage x into LDS as fp16 and compute corr[] per block.  bf16 input is multiplied by a power of
 // two chosen from max|x| so that it lands in fp16's range (bf16 has 8 significant bits, fp16 11:
 // the conversion is exact unless an element is > 2^28 times smaller than the largest); the
 // returned factor undoes it at the end.
 template <int BITS>
-__device__ float stage_x(const AqGemvTask& t, uint16_t* xh, float* corr, float* scratch)
+__device__ float stage_x(const AqGemvTask& t, uint8_t* xl, float* corr, float* scratch)
 {
     const int tid = threadIdx.x;
     const int K = t.K, Kpad = t.nchunks * AQ_CHUNK_K;
     float unscale = 1.0f;
+    for (int e = tid; e < t.nchunks * 4 * 8; e += THREADS)           // the zero middles of all entries
+        *reinterpret_cast<u32x2*>(xl + e * X_ENTRY_BYTES + 8) = u32x2{0u, 0u};
     if (t.x_dtype == 1) {   // AQ_F16: copy
         for (int i = tid * 8; i < Kpad; i += THREADS * 8) {
             u32x4 v = {0u, 0u, 0u, 0u};
             if (i < K) v = *(as_global<u32x4>(t.x + i));
-            *reinterpret_cast<u32x4*>(xh + i) = v;
+            *reinterpret_cast<u32x2*>(xl + x_lds_offset(i >> 5, (i & 31) >> 2)) = u32x2{v.x, v.y};
+            *reinterpret_cast<u32x2*>(xl + x_lds_offset(i >> 5, ((i & 31) >> 2) + 1)) = u32x2{v.z, v.w};
         }
     } else {                // AQ_BF16
         float amax = 0.f;
@@ -201,7 +222,8 @@ __device__ float stage_x(const AqGemvTask& t, uint16_t* xh, float* corr, float* 
                 }
                 o.x = os[0]; o.y = os[1]; o.z = os[2]; o.w = os[3];
             }
-            *reinterpret_cast<u32x4*>(xh + i) = o;
+            *reinterpret_cast<u32x2*>(xl + x_lds_offset(i >> 5, (i & 31) >> 2)) = u32x2{o.x, o.y};
+            *reinterpret_cast<u32x2*>(xl + x_lds_offset(i >> 5, ((i & 31) >> 2) + 1)) = u32x2{o.z, o.w};
         }
     }
     __syncthreads();
@@ -209,17 +231,15 @@ __device__ float stage_x(const AqGemvTask& t, uint16_t* xh, float* corr, float* 
     // accumulate) per pair; the constants are small integers, exact in fp16
     const float z = (float)(1 << (BITS - 1));
     for (int b = tid; b < t.nchunks * AQ_CHUNK_BLOCKS; b += THREADS) {
-        const u32x4* xb = reinterpret_cast<const u32x4*>(xh + b * AQ_BLOCK);
         float s = 0.f;
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const u32x4 v = xb[q4];
-            const uint32_t ws[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const _Float16 k = (_Float16)(Codec<BITS>::offset(4 * q4 + j) + z);
-                s = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, ws[j]), half2v{k, k}, s, false);
-            }
+        for (int q = 0; q < 8; ++q) {
+            const u32x2 v = *reinterpret_cast<const u32x2*>(xl + x_lds_offset(b, q));
+            const uint32_t p0 = v.x, p1 = v.y;   // scalars first: bit_cast of a vector element misreads it
+            const _Float16 k0 = (_Float16)(Codec<BITS>::offset(2 * q) + z);
+            const _Float16 k1 = (_Float16)(Codec<BITS>::offset(2 * q + 1) + z);
+            s = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, p0), half2v{k0, k0}, s, false);
+            s = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, p1), half2v{k1, k1}, s, false);
         }
         corr[b] = s;
     }
@@ -227,25 +247,23 @@ __device__ float stage_x(const AqGemvTask& t, uint16_t* xh, float* corr, float* 
     return unscale;
 }
 
-#ifndef AQ_GEMV_SCHED_FENCE
-#define AQ_GEMV_SCHED_FENCE 1
-#endif
 // One unit (16 rows x 8 blocks): unpack the ring slot, optionally refill it from `next`, run the
 // 8 MFMAs against the block-diagonal B and fold the block sums, times their fp16 scales, into the
-// tile's running sums at `sums` (LDS, owned by this lane).
+// tile's running sums (registers; lane (g, c) holds rows 4g .. 4g+3 of block column c).
+#ifndef AQ_EXP
+#define AQ_EXP 0
+#endif
 template <int BITS, bool REFILL>
 __device__ __forceinline__ void unit_step(uint32_t (&raw)[Codec<BITS>::WORDS], u32x2& sc,
-                                          const typename Codec<BITS>::Magic& magic, const half8 (&B)[8],
+                                          typename Codec<BITS>::Magic& magic, const half8 (&B)[8],
                                           const float4v& negc, const uint8_t* next, int lane, int sc_off,
-                                          float* sums)
+                                          float (&acc)[4])
 {
-#if AQ_GEMV_SCHED_FENCE
-    // Pin this unit's unpack behind the previous unit's stores: without it the compiler hoists the
-    // unpack of every unit in flight to the top of the loop body and holds all of their operands
-    // live at once (2-3x the registers).  Other wavefronts on the SIMD fill the MFMA latency.
-#pragma unroll
-    for (int i = 0; i < Codec<BITS>::WORDS; ++i) asm volatile("" : "+v"(raw[i]) : : "memory");
-#endif
+    // Order the units: this unit's unpack may not start before the tile's previous unit (two units
+    // back) has been folded into acc.  Without it the compiler hoists the unpack of every unit in
+    // flight to the top of the loop body and holds all of their operands live at once (2-3x the
+    // registers).  The empty asm ties the magic constants (inputs of every unpack instruction) to acc.
+    Codec<BITS>::fence(magic, acc[0]);
     uint32_t a0[16], a1[16];
     Codec<BITS>::unpack(&raw[0], magic, a0);
     Codec<BITS>::unpack(&raw[BITS], magic, a1);
@@ -254,44 +272,68 @@ __device__ __forceinline__ void unit_step(uint32_t (&raw)[Codec<BITS>::WORDS], u
         Codec<BITS>::load(next, lane, raw);
         sc = __builtin_nontemporal_load(as_global<u32x2>(next + sc_off));
     }
-    float o0 = sums[0], o1 = sums[32], o2 = sums[64], o3 = sums[96];   // read early: the MFMAs hide it
     float4v D = negc;
+#if AQ_EXP == 1      /* timing experiment: no MFMA, no unpack */
+    D[0] += __uint_as_float(raw[0] ^ raw[1]); D[1] += __uint_as_float(raw[2] ^ raw[3]);
+#elif AQ_EXP == 2    /* timing experiment: unpack, no MFMA */
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+        D[m & 3] += __uint_as_float(a0[2 * m] ^ a0[2 * m + 1] ^ a1[2 * m] ^ a1[2 * m + 1]);
+    }
+#else
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
         u32x4 av = {a0[2 * m], a0[2 * m + 1], a1[2 * m], a1[2 * m + 1]};
         D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, av), B[m], D, 0, 0, 0);
     }
-    sums[0] = fmaf(D[0], (float)d4.x, o0);
-    sums[32] = fmaf(D[1], (float)d4.y, o1);
-    sums[64] = fmaf(D[2], (float)d4.z, o2);
-    sums[96] = fmaf(D[3], (float)d4.w, o3);
+#endif
+    acc[0] = fmaf(D[0], (float)d4.x, acc[0]);
+    acc[1] = fmaf(D[1], (float)d4.y, acc[1]);
+    acc[2] = fmaf(D[2], (float)d4.z, acc[2]);
+    acc[3] = fmaf(D[3], (float)d4.w, acc[3]);
 }
 
-// DEPTH consecutive units of one chunk starting at tile rt0; slot u is refilled from refill + u*UNIT
-template <int BITS, int DEPTH, bool REFILL>
-__device__ __forceinline__ void unit_block(uint32_t (&raw)[DEPTH][Codec<BITS>::WORDS], u32x2 (&sc)[DEPTH],
-                                           const typename Codec<BITS>::Magic& magic, const half8 (&B)[8],
-                                           const float4v& negc, const uint8_t* refill, int lane, int sc_off,
-                                           float* sums, int tile_stride)
+// One chunk for the wavefront's TW tiles: fetch the chunk's B operand from LDS, then one unit per
+// tile out of ring slots slot0 .. slot0+TW-1, each refilled from the chunk two ahead.
+template <int BITS, int TW, bool REFILL>
+__device__ __forceinline__ void chunk_step(uint32_t (*raw)[Codec<BITS>::WORDS], u32x2* sc,
+                                           typename Codec<BITS>::Magic& magic, const uint8_t* xl,
+                                           const float* corr, const uint8_t* zeros, int ch, bool diag,
+                                           int c, const uint8_t* refill, int lane, int sc_off, float (*acc)[4])
 {
     constexpr int UNIT = 512 * BITS + 256;
+    // B: x of block c goes to the k-slots of block c (the low two registers for even c, the high two
+    // for odd c) and zeros elsewhere: one 16-byte LDS read per MFMA (see x_lds_offset).
+    // Re-read per chunk: that costs LDS reads only, no ALU work, and B never lives across the loop.
+    typedef u32x4 u32x4_a8 __attribute__((aligned(8)));
+    const uint8_t* bp = diag ? xl + (ch * 4 + (c >> 1)) * X_PAIR_BYTES + (c & 1) * 8 : zeros;
+    half8 B[8];
 #pragma unroll
-    for (int u = 0; u < DEPTH; ++u)
-        unit_step<BITS, REFILL>(raw[u], sc[u], magic, B, negc, refill + u * UNIT, lane, sc_off,
-                                sums + u * tile_stride);
+    for (int m = 0; m < 8; ++m)
+        B[m] = __builtin_bit_cast(half8, *reinterpret_cast<const u32x4_a8*>(bp + m * X_ENTRY_BYTES));
+    const float nc = -corr[ch * AQ_CHUNK_BLOCKS + (c & 7)];
+    const float4v negc = {nc, nc, nc, nc};
+#pragma unroll
+    for (int tw = 0; tw < TW; ++tw)
+        unit_step<BITS, REFILL>(raw[tw], sc[tw], magic, B, negc, refill + tw * UNIT, lane, sc_off, acc[tw]);
 }
 
-#ifndef AQ_GEMV_MIN_WAVES
-#define AQ_GEMV_MIN_WAVES 3
+#ifndef AQ_GEMV_MIN_WAVES_B2
+#define AQ_GEMV_MIN_WAVES_B2 4
 #endif
-template <int BITS, int RT>
-__global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES) void qgemv_kernel(const AqGemvTask* __restrict__ tasks, int count,
-                                                        AqGemvTask single)
+#ifndef AQ_GEMV_MIN_WAVES_B34
+#define AQ_GEMV_MIN_WAVES_B34 3
+#endif
+// Workgroup = 4 wavefronts x TW tiles (16 rows each) of one 128-row group; every wavefront walks
+// the whole K extent of its own tiles, so sums stay in registers and wavefronts never meet.  At
+// each chunk the 4 wavefronts together read one contiguous run of 4*TW units.
+template <int BITS, int TW>
+__global__ __launch_bounds__(THREADS, (BITS == 2 ? AQ_GEMV_MIN_WAVES_B2 : AQ_GEMV_MIN_WAVES_B34)) void qgemv_kernel(const AqGemvTask* __restrict__ tasks,
+                                                                           int count, AqGemvTask single)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     constexpr int WORDS = Codec<BITS>::WORDS;
     constexpr int UNIT = 512 * BITS + 256;
-    constexpr int DEPTH = RT < 4 ? RT : 4;          // units of loads kept in flight per wavefront
 
     AqGemvTask t;
     int wg = blockIdx.x;
@@ -311,125 +353,103 @@ __global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES) void qgemv_kernel(const
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: keep it in an SGPR
     const int g = lane >> 4, c = lane & 15;
-    const int nch = t.nchunks, Kpad = nch * AQ_CHUNK_K;
+    const int nch = t.nchunks;
 
-    uint16_t* xh = reinterpret_cast<uint16_t*>(smem);                       // Kpad fp16
-    float* corr = reinterpret_cast<float*>(smem + Kpad * 2);                // nch * 8
-    float* red = reinterpret_cast<float*>(smem + Kpad * 2 + nch * 32);      // WAVES * (RT + 1) * 128
-    uint32_t* zeros = reinterpret_cast<uint32_t*>(smem + Kpad * 2 + nch * 32 + WAVES * (RT + 1) * 512);  // 16 words
-    if (tid < 16) zeros[tid] = 0u;
+    const int xbytes = nch * 4 * X_PAIR_BYTES;
+    uint8_t* xl = smem;                                                      // staged x, see x_lds_offset
+    float* corr = reinterpret_cast<float*>(smem + xbytes);                   // nch * 8
+    uint8_t* zeros = smem + xbytes + nch * 32;                               // 192 bytes of zeros
+    float* scratch = reinterpret_cast<float*>(smem + xbytes + nch * 32 + 192);   // 4 floats
+    if (tid < 48) reinterpret_cast<uint32_t*>(zeros)[tid] = 0u;
 
-    const int subs = AQ_GROUP_TILES / RT;
-    const int group = wg / subs, sub = wg % subs;
+    constexpr int SUBS = AQ_GROUP_TILES / (WAVES * TW);
+    const int group = wg / SUBS, sub = wg % SUBS;
+    const int tile0 = (sub * WAVES + wave) * TW;                   // first of this wavefront's tiles
     const bool diag = (c < 8) && ((c >> 1) == g);
-    const bool hi = (c & 1) != 0;
 
-    // Register ring of DEPTH units (raw code words + 4 scales per lane).  The wavefront walks its
-    // units in the order (chunk, tile); a slot is refilled with the unit DEPTH positions ahead as
-    // soon as its words have been unpacked, so DEPTH - 1 units of loads stay in flight.  The first
-    // fill is issued before x is staged, so that it overlaps the workgroup's start-up.
-    const uint8_t* gbase = t.blob + ((int64_t)group * nch * AQ_GROUP_TILES + sub * RT) * UNIT;
+    // Register ring of 2*TW units (raw code words + 4 scales per lane): the units of chunk ch sit in
+    // slots (ch & 1)*TW .. +TW-1 and are refilled with the units of chunk ch + 2 as soon as they
+    // have been unpacked.  The first fill is issued before x is staged, to overlap the start-up.
+    const uint8_t* ubase = t.blob + ((int64_t)group * nch * AQ_GROUP_TILES + tile0) * UNIT;
     const int64_t chunk_stride = (int64_t)AQ_GROUP_TILES * UNIT;
     const int sc_off = 512 * BITS + (g * 8 + (c & 7)) * 8;
-    uint32_t raw[DEPTH][WORDS];
-    u32x2 sc[DEPTH];
-    if (wave < nch) {
-        const uint8_t* ub = gbase + wave * chunk_stride;
+    uint32_t raw[2 * TW][WORDS];
+    u32x2 sc[2 * TW];
 #pragma unroll
-        for (int u = 0; u < DEPTH; ++u) {
-            Codec<BITS>::load(ub + u * UNIT, lane, raw[u]);
-            sc[u] = __builtin_nontemporal_load(as_global<u32x2>(ub + u * UNIT + sc_off));
+    for (int p = 0; p < 2; ++p)
+        if (p < nch) {
+#pragma unroll
+            for (int tw = 0; tw < TW; ++tw) {
+                const uint8_t* u = ubase + p * chunk_stride + tw * UNIT;
+                Codec<BITS>::load(u, lane, raw[p * TW + tw]);
+                sc[p * TW + tw] = __builtin_nontemporal_load(as_global<u32x2>(u + sc_off));
+            }
         }
-    }
 
-    // Per-wavefront partial sums live in LDS (red[wave][tile][r][g*8 + c], read-modify-written by
-    // their owner only), so the tile loop needs no accumulator registers.  Lanes c >= 8 hold no
-    // useful MFMA column; they update a private dummy block so that no lane ever branches.
-    float* mysum;
-    int tile_stride;
-    {
-        float* dummy = red + WAVES * RT * 128;                 // WAVES * 128 floats
-        const int idx = g * 8 + (c & 7);
-        mysum = (c < 8) ? red + wave * RT * 128 + idx : dummy + wave * 128 + idx;
-        tile_stride = (c < 8) ? 128 : 0;
-    }
-    for (int i = tid; i < WAVES * (RT + 1) * 128; i += THREADS) red[i] = 0.f;
+    const float unscale = stage_x<BITS>(t, xl, corr, scratch);
 
-    const float unscale = stage_x<BITS>(t, xh, corr, reinterpret_cast<float*>(zeros + 16));
+    typename Codec<BITS>::Magic magic = Codec<BITS>::magic();
+    float acc[TW][4];
+#pragma unroll
+    for (int tw = 0; tw < TW; ++tw)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[tw][r] = 0.f;
 
-    const typename Codec<BITS>::Magic magic = Codec<BITS>::magic();
-
-    // The wavefront's units in visiting order: chunk wave, wave + 4, ...; inside a chunk tiles
-    // 0 .. RT-1, taken DEPTH at a time ("blocks").  Block j + 1 refills the ring while block j is
-    // being consumed.
-    constexpr int NBLK = RT / DEPTH;
-    const int my_chunks = wave < nch ? (nch - wave + WAVES - 1) / WAVES : 0;
-    const int total = my_chunks * NBLK;
 #pragma unroll 1
-    for (int j = 0; j < total; ++j) {
-        const int cj = j / NBLK, rb = j % NBLK;
-        // B operand of the chunk: x of block c goes to the k-slots of block c (the low two registers
-        // for even c, the high two for odd c); every other slot reads the 64-byte zero region.  It
-        // is re-read from LDS for every block of tiles: that costs LDS reads only and keeps its 32
-        // registers from living across the loop.
-        const int ch = wave + cj * WAVES;
-        const uint32_t* xblk = reinterpret_cast<const uint32_t*>(xh + (ch * AQ_CHUNK_BLOCKS + (c & 7)) * AQ_BLOCK);
-        const u32x2* blo = reinterpret_cast<const u32x2*>((diag && !hi) ? xblk : zeros);
-        const u32x2* bhi = reinterpret_cast<const u32x2*>((diag && hi) ? xblk : zeros);
-        half8 B[8];
-#pragma unroll
-        for (int m = 0; m < 8; ++m) {
-            const u32x2 l = blo[m], h = bhi[m];
-            B[m] = __builtin_bit_cast(half8, u32x4{l.x, l.y, h.x, h.y});
-        }
-        const float nc = -corr[ch * AQ_CHUNK_BLOCKS + (c & 7)];
-        const float4v negc = {nc, nc, nc, nc};
-        float* sums = mysum + rb * DEPTH * tile_stride;
-        if (j + 1 < total) {
-            const int cn = (j + 1) / NBLK, rn = (j + 1) % NBLK;
-            const uint8_t* nb = gbase + (int64_t)(wave + cn * WAVES) * chunk_stride + rn * DEPTH * UNIT;
-            unit_block<BITS, DEPTH, true>(raw, sc, magic, B, negc, nb, lane, sc_off, sums, tile_stride);
-        } else {
-            unit_block<BITS, DEPTH, false>(raw, sc, magic, B, negc, gbase, lane, sc_off, sums, tile_stride);
+    for (int ch = 0; ch < nch; ch += 2) {
+        const uint8_t* r0 = ubase + (int64_t)(ch + 2) * chunk_stride;
+        if (ch + 2 < nch)
+            chunk_step<BITS, TW, true>(raw, sc, magic, xl, corr, zeros, ch, diag, c, r0, lane, sc_off, acc);
+        else
+            chunk_step<BITS, TW, false>(raw, sc, magic, xl, corr, zeros, ch, diag, c, r0, lane, sc_off, acc);
+        if (ch + 1 < nch) {
+            if (ch + 3 < nch)
+                chunk_step<BITS, TW, true>(raw + TW, sc + TW, magic, xl, corr, zeros, ch + 1, diag, c,
+                                           r0 + chunk_stride, lane, sc_off, acc);
+            else
+                chunk_step<BITS, TW, false>(raw + TW, sc + TW, magic, xl, corr, zeros, ch + 1, diag, c,
+                                            r0 + chunk_stride, lane, sc_off, acc);
         }
     }
 
-    __syncthreads();
-    if (tid < RT * 16) {
-        const int rt = tid >> 4, i = tid & 15, gg = i >> 2, r = i & 3;
-        float s = 0.f;
+    // lane (g, c < 8) holds the sum over its block column; add the 8 columns (lanes c >= 8 carry no
+    // useful column and contribute zero), lane c == 0 stores rows 4g .. 4g+3
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) {
-            const float* p = red + ((w * RT + rt) * 4 + r) * 32 + gg * 8;
+    for (int tw = 0; tw < TW; ++tw)
 #pragma unroll
-            for (int cc = 0; cc < 8; ++cc) s += p[cc];
+        for (int r = 0; r < 4; ++r) {
+            float v = (c < 8) ? acc[tw][r] : 0.f;
+            v += __shfl_xor(v, 1, 64);
+            v += __shfl_xor(v, 2, 64);
+            v += __shfl_xor(v, 4, 64);
+            acc[tw][r] = v;
         }
-        const int64_t row = ((int64_t)group * AQ_GROUP_TILES + sub * RT + rt) * AQ_TILE_ROWS + i;
-        if (row < t.N) ((AQ_GLOBAL float*)(uintptr_t)t.y)[row] = s * unscale;
+    if (c == 0) {
+        AQ_GLOBAL float* y = (AQ_GLOBAL float*)(uintptr_t)t.y;
+#pragma unroll
+        for (int tw = 0; tw < TW; ++tw) {
+            const int64_t row0 = ((int64_t)group * AQ_GROUP_TILES + tile0 + tw) * AQ_TILE_ROWS + 4 * g;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (row0 + r < t.N) y[row0 + r] = acc[tw][r] * unscale;
+        }
     }
 }
 
-size_t gemv_lds_bytes(int max_K, int RT)
+size_t gemv_lds_bytes(int max_K)
 {
     int nch = (max_K + AQ_CHUNK_K - 1) / AQ_CHUNK_K;
-    return (size_t)nch * AQ_CHUNK_K * 2 + (size_t)nch * 32 + (size_t)WAVES * (RT + 1) * 512 + 64 + 16;
+    return (size_t)nch * 4 * X_PAIR_BYTES + (size_t)nch * 32 + 192 + 16;
 }
 
 }  // namespace
 
+// tiles per workgroup: 8 (two per wavefront) in general, 4 for a lone small matrix so that it
+// spreads over more compute units
 int aqk_gemv_tiles_per_wg(int64_t N, bool batched)
 {
-    if (batched) {
-        const char* e = getenv("AQ_BATCH_RT");
-        int v = e ? atoi(e) : 8;
-        return (v == 1 || v == 2 || v == 4 || v == 8) ? v : 8;
-    }
-    // a lone matrix: keep at least ~1024 workgroups where the matrix allows it
-    int64_t tiles = (N + AQ_TILE_ROWS - 1) / AQ_TILE_ROWS;
-    if (tiles >= 8192) return 8;
-    if (tiles >= 4096) return 4;
-    if (tiles >= 2048) return 2;
-    return 1;
+    if (batched) return 8;
+    return N >= 128 * 1024 ? 8 : 4;
 }
 
 int aqk_gemv_wg_count(int64_t N, int tiles_per_wg)
@@ -437,27 +457,18 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg)
     return (int)(aq_num_groups(N) * (AQ_GROUP_TILES / tiles_per_wg));
 }
 
-template <int RT>
-static void launch_bits(int bits, dim3 grid, size_t lds, hipStream_t s, const AqGemvTask* tasks, int count,
-                        const AqGemvTask& single)
-{
-    dim3 block(THREADS);
-    if (bits == 2) hipLaunchKernelGGL((qgemv_kernel<2, RT>), grid, block, lds, s, tasks, count, single);
-    else if (bits == 3) hipLaunchKernelGGL((qgemv_kernel<3, RT>), grid, block, lds, s, tasks, count, single);
-    else hipLaunchKernelGGL((qgemv_kernel<4, RT>), grid, block, lds, s, tasks, count, single);
-}
-
 // all tasks of one launch share `bits`
 hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
                     int total_wgs, int max_K, hipStream_t s)
 {
-    size_t lds = gemv_lds_bytes(max_K, tiles_per_wg);
-    dim3 grid((unsigned)total_wgs);
-    switch (tiles_per_wg) {
-        case 1: launch_bits<1>(bits, grid, lds, s, tasks_dev, count, single); break;
-        case 2: launch_bits<2>(bits, grid, lds, s, tasks_dev, count, single); break;
-        case 4: launch_bits<4>(bits, grid, lds, s, tasks_dev, count, single); break;
-        default: launch_bits<8>(bits, grid, lds, s, tasks_dev, count, single); break;
+    const size_t lds = gemv_lds_bytes(max_K);
+    const dim3 grid((unsigned)total_wgs), block(THREADS);
+#define AQ_LAUNCH(BITS, TW) hipLaunchKernelGGL((qgemv_kernel<BITS, TW>), grid, block, lds, s, tasks_dev, count, single)
+    if (tiles_per_wg == 8) {
+        if (bits == 2) AQ_LAUNCH(2, 2); else if (bits == 3) AQ_LAUNCH(3, 2); else AQ_LAUNCH(4, 2);
+    } else {
+        if (bits == 2) AQ_LAUNCH(2, 1); else if (bits == 3) AQ_LAUNCH(3, 1); else AQ_LAUNCH(4, 1);
     }
+#undef AQ_LAUNCH
     return hipGetLastError();
 }
