@@ -87,7 +87,8 @@ int aq_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block,
  * Step 1 (host only): aq_qgemv_batch_plan turns `count` descriptors into a plan image
  *   of aq_qgemv_batch_plan_size(count) bytes in HOST memory `plan_host`.
  * Step 2: the caller copies that image to 16-byte-aligned DEVICE memory `plan_dev`.
- * Step 3: aq_qgemv_batch(plan_host, plan_dev, stream) launches; it may be repeated. */
+ * Step 3: aq_qgemv_batch(plan_host, plan_dev, stream) launches (one kernel launch); it may be
+ *   repeated. */
 typedef struct aq_gemv_desc {
     const void* packed;   /* DEVICE blob */
     const void* x;        /* DEVICE uint16 [K] */

@@ -13,18 +13,15 @@ constexpr int64_t AQ_MAX_K = 16384;          // x (fp16) must fit the decode ker
 constexpr int64_t AQ_MAX_N = (int64_t)1 << 24;
 constexpr int64_t AQ_MAX_M = (int64_t)1 << 20;
 
-// First 64 bytes of a batch plan image.  The task records that follow are grouped by bit-width
-// (all 2-bit tasks, then 3-bit, then 4-bit, each group in the caller's order): one kernel
-// instantiation serves one bit-width, so a plan runs as up to three launches.
+// First 64 bytes of a batch plan image; the task records follow in the caller's order.
 struct PlanHeader {
     uint32_t magic;
     int32_t count;
     int32_t tiles_per_wg;
     int32_t max_K;
-    int32_t first[3];        // index of the first task of the 2-, 3-, 4-bit group
-    int32_t ntasks[3];
-    int32_t wgs[3];          // workgroups of each group's launch
-    int32_t reserved[3];
+    int32_t bits;            // the common bit-width of all tasks, 0 if they differ
+    int32_t total_wgs;
+    int32_t reserved[10];
 };
 static_assert(sizeof(PlanHeader) == 64, "PlanHeader must stay 64 bytes");
 constexpr uint32_t PLAN_MAGIC = 0x41515031u;  // "AQP1"
@@ -141,23 +138,18 @@ int aq_qgemv_batch_plan(const aq_gemv_desc* descs, int count, int block, void* p
     h.tiles_per_wg = rt;
     h.max_K = max_K;
     AqGemvTask* tasks = reinterpret_cast<AqGemvTask*>(static_cast<uint8_t*>(plan_host) + sizeof(PlanHeader));
-    int out = 0;
-    for (int gi = 0; gi < 3; ++gi) {
-        const int bits = 2 + gi;
-        int32_t begin = 0;
-        h.first[gi] = out;
-        for (int i = 0; i < count; ++i) {
-            const aq_gemv_desc& d = descs[i];
-            if (d.bits != bits) continue;
-            AqGemvTask t = make_task(d.packed, d.N, d.K, d.bits, d.x, d.x_dtype, d.y);
-            t.wg_begin = begin;
-            t.wg_count = aqk_gemv_wg_count(d.N, rt);
-            begin += t.wg_count;
-            std::memcpy(&tasks[out++], &t, sizeof(t));
-        }
-        h.ntasks[gi] = out - h.first[gi];
-        h.wgs[gi] = begin;
+    int32_t begin = 0;
+    h.bits = descs[0].bits;
+    for (int i = 0; i < count; ++i) {
+        const aq_gemv_desc& d = descs[i];
+        if (d.bits != descs[0].bits) h.bits = 0;
+        AqGemvTask t = make_task(d.packed, d.N, d.K, d.bits, d.x, d.x_dtype, d.y);
+        t.wg_begin = begin;
+        t.wg_count = aqk_gemv_wg_count(d.N, rt);
+        begin += t.wg_count;
+        std::memcpy(&tasks[i], &t, sizeof(t));
     }
+    h.total_wgs = begin;
     std::memcpy(plan_host, &h, sizeof(h));
     return AQ_OK;
 }
@@ -168,20 +160,14 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream)
     if (!aligned16(plan_dev)) return AQ_EALIGN;
     PlanHeader h;
     std::memcpy(&h, plan_host, sizeof(h));
-    if (h.magic != PLAN_MAGIC || h.count < 1) return AQ_EINVAL;
+    if (h.magic != PLAN_MAGIC || h.count < 1 || h.total_wgs < 1 || (h.bits != 0 && (h.bits < 2 || h.bits > 4)))
+        return AQ_EINVAL;
     const AqGemvTask* tasks =
         reinterpret_cast<const AqGemvTask*>(static_cast<const uint8_t*>(plan_dev) + sizeof(PlanHeader));
     AqGemvTask none;
     std::memset(&none, 0, sizeof(none));
-    for (int gi = 0; gi < 3; ++gi) {
-        if (h.ntasks[gi] == 0) continue;
-        if (h.ntasks[gi] < 0 || h.wgs[gi] < 1 || h.first[gi] < 0 || h.first[gi] + h.ntasks[gi] > h.count)
-            return AQ_EINVAL;
-        if (aqk_gemv(tasks + h.first[gi], h.ntasks[gi], none, 2 + gi, h.tiles_per_wg, h.wgs[gi], h.max_K,
-                     static_cast<hipStream_t>(stream)) != hipSuccess)
-            return AQ_ELAUNCH;
-    }
-    return AQ_OK;
+    return aqk_gemv(tasks, h.count, none, h.bits, h.tiles_per_wg, h.total_wgs, h.max_K,
+                    static_cast<hipStream_t>(stream)) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
 }
 
 size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits)

@@ -23,7 +23,6 @@
 // A batched launch runs many matrices (each with its own bit-width) in one grid.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
-#include <cstdlib>
 #include "aq_layout.h"
 #include "aq_kernels.h"
 
@@ -250,9 +249,6 @@ __device__ float stage_x(const AqGemvTask& t, uint8_t* xl, float* corr, float* s
 // One unit (16 rows x 8 blocks): unpack the ring slot, optionally refill it from `next`, run the
 // 8 MFMAs against the block-diagonal B and fold the block sums, times their fp16 scales, into the
 // tile's running sums (registers; lane (g, c) holds rows 4g .. 4g+3 of block column c).
-#ifndef AQ_EXP
-#define AQ_EXP 0
-#endif
 template <int BITS, bool REFILL>
 __device__ __forceinline__ void unit_step(uint32_t (&raw)[Codec<BITS>::WORDS], u32x2& sc,
                                           typename Codec<BITS>::Magic& magic, const half8 (&B)[8],
@@ -273,20 +269,11 @@ __device__ __forceinline__ void unit_step(uint32_t (&raw)[Codec<BITS>::WORDS], u
         sc = __builtin_nontemporal_load(as_global<u32x2>(next + sc_off));
     }
     float4v D = negc;
-#if AQ_EXP == 1      /* timing experiment: no MFMA, no unpack */
-    D[0] += __uint_as_float(raw[0] ^ raw[1]); D[1] += __uint_as_float(raw[2] ^ raw[3]);
-#elif AQ_EXP == 2    /* timing experiment: unpack, no MFMA */
-#pragma unroll
-    for (int m = 0; m < 8; ++m) {
-        D[m & 3] += __uint_as_float(a0[2 * m] ^ a0[2 * m + 1] ^ a1[2 * m] ^ a1[2 * m + 1]);
-    }
-#else
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
         u32x4 av = {a0[2 * m], a0[2 * m + 1], a1[2 * m], a1[2 * m + 1]};
         D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, av), B[m], D, 0, 0, 0);
     }
-#endif
     acc[0] = fmaf(D[0], (float)d4.x, acc[0]);
     acc[1] = fmaf(D[1], (float)d4.y, acc[1]);
     acc[2] = fmaf(D[2], (float)d4.z, acc[2]);
@@ -327,112 +314,52 @@ __device__ __forceinline__ void chunk_step(uint32_t (*raw)[Codec<BITS>::WORDS], 
 // Workgroup = 4 wavefronts x TW tiles (16 rows each) of one 128-row group; every wavefront walks
 // the whole K extent of its own tiles, so sums stay in registers and wavefronts never meet.  At
 // each chunk the 4 wavefronts together read one contiguous run of 4*TW units.
+// The task of this workgroup: `single` when count == 0, else the last record whose first workgroup
+// is not above blockIdx.x (binary search over uniform scalar loads).  A macro, so that the record
+// stays a kernel-local value in scalar registers.
+#define AQ_FIND_TASK(t, wg)                                                       \
+    AqGemvTask t;                                                                 \
+    int wg = blockIdx.x;                                                          \
+    if (count == 0) {                                                             \
+        t = single;                                                               \
+    } else {                                                                      \
+        int lo = 0, hi = count - 1;                                               \
+        while (lo < hi) {                                                         \
+            int mid = (lo + hi + 1) >> 1;                                         \
+            if (tasks[mid].wg_begin <= wg) lo = mid; else hi = mid - 1;           \
+        }                                                                         \
+        t = tasks[lo];                                                            \
+        wg -= t.wg_begin;                                                         \
+    }                                                                             \
+    if (wg >= t.wg_count) return
+
+// one bit-width per launch: the registers, and with them the occupancy, fit that bit-width
 template <int BITS, int TW>
-__global__ __launch_bounds__(THREADS, (BITS == 2 ? AQ_GEMV_MIN_WAVES_B2 : AQ_GEMV_MIN_WAVES_B34)) void qgemv_kernel(const AqGemvTask* __restrict__ tasks,
-                                                                           int count, AqGemvTask single)
+__global__ __launch_bounds__(THREADS, (BITS == 2 ? AQ_GEMV_MIN_WAVES_B2 : AQ_GEMV_MIN_WAVES_B34))
+void qgemv_kernel(const AqGemvTask* __restrict__ tasks, int count, AqGemvTask single)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    constexpr int WORDS = Codec<BITS>::WORDS;
-    constexpr int UNIT = 512 * BITS + 256;
+    AQ_FIND_TASK(t, wg);
+#include "aq_gemv_body.inc"
+}
 
-    AqGemvTask t;
-    int wg = blockIdx.x;
-    if (count == 0) {
-        t = single;
+// matrices of different bit-widths in one launch (a mixed-precision backbone pass): each workgroup
+// branches once on its matrix's bit-width; one launch has one tail instead of three
+template <int TW>
+__global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES_B34)
+void qgemv_mixed_kernel(const AqGemvTask* __restrict__ tasks, int count, AqGemvTask single)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    AQ_FIND_TASK(t, wg);
+    if (t.bits == 2) {
+        constexpr int BITS = 2;
+#include "aq_gemv_body.inc"
+    } else if (t.bits == 3) {
+        constexpr int BITS = 3;
+#include "aq_gemv_body.inc"
     } else {
-        int lo = 0, hi = count - 1;          // last task whose first workgroup is <= blockIdx.x
-        while (lo < hi) {
-            int mid = (lo + hi + 1) >> 1;
-            if (tasks[mid].wg_begin <= wg) lo = mid; else hi = mid - 1;
-        }
-        t = tasks[lo];
-        wg -= t.wg_begin;
-    }
-    if (wg >= t.wg_count) return;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: keep it in an SGPR
-    const int g = lane >> 4, c = lane & 15;
-    const int nch = t.nchunks;
-
-    const int xbytes = nch * 4 * X_PAIR_BYTES;
-    uint8_t* xl = smem;                                                      // staged x, see x_lds_offset
-    float* corr = reinterpret_cast<float*>(smem + xbytes);                   // nch * 8
-    uint8_t* zeros = smem + xbytes + nch * 32;                               // 192 bytes of zeros
-    float* scratch = reinterpret_cast<float*>(smem + xbytes + nch * 32 + 192);   // 4 floats
-    if (tid < 48) reinterpret_cast<uint32_t*>(zeros)[tid] = 0u;
-
-    constexpr int SUBS = AQ_GROUP_TILES / (WAVES * TW);
-    const int group = wg / SUBS, sub = wg % SUBS;
-    const int tile0 = (sub * WAVES + wave) * TW;                   // first of this wavefront's tiles
-    const bool diag = (c < 8) && ((c >> 1) == g);
-
-    // Register ring of 2*TW units (raw code words + 4 scales per lane): the units of chunk ch sit in
-    // slots (ch & 1)*TW .. +TW-1 and are refilled with the units of chunk ch + 2 as soon as they
-    // have been unpacked.  The first fill is issued before x is staged, to overlap the start-up.
-    const uint8_t* ubase = t.blob + ((int64_t)group * nch * AQ_GROUP_TILES + tile0) * UNIT;
-    const int64_t chunk_stride = (int64_t)AQ_GROUP_TILES * UNIT;
-    const int sc_off = 512 * BITS + (g * 8 + (c & 7)) * 8;
-    uint32_t raw[2 * TW][WORDS];
-    u32x2 sc[2 * TW];
-#pragma unroll
-    for (int p = 0; p < 2; ++p)
-        if (p < nch) {
-#pragma unroll
-            for (int tw = 0; tw < TW; ++tw) {
-                const uint8_t* u = ubase + p * chunk_stride + tw * UNIT;
-                Codec<BITS>::load(u, lane, raw[p * TW + tw]);
-                sc[p * TW + tw] = __builtin_nontemporal_load(as_global<u32x2>(u + sc_off));
-            }
-        }
-
-    const float unscale = stage_x<BITS>(t, xl, corr, scratch);
-
-    typename Codec<BITS>::Magic magic = Codec<BITS>::magic();
-    float acc[TW][4];
-#pragma unroll
-    for (int tw = 0; tw < TW; ++tw)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[tw][r] = 0.f;
-
-#pragma unroll 1
-    for (int ch = 0; ch < nch; ch += 2) {
-        const uint8_t* r0 = ubase + (int64_t)(ch + 2) * chunk_stride;
-        if (ch + 2 < nch)
-            chunk_step<BITS, TW, true>(raw, sc, magic, xl, corr, zeros, ch, diag, c, r0, lane, sc_off, acc);
-        else
-            chunk_step<BITS, TW, false>(raw, sc, magic, xl, corr, zeros, ch, diag, c, r0, lane, sc_off, acc);
-        if (ch + 1 < nch) {
-            if (ch + 3 < nch)
-                chunk_step<BITS, TW, true>(raw + TW, sc + TW, magic, xl, corr, zeros, ch + 1, diag, c,
-                                           r0 + chunk_stride, lane, sc_off, acc);
-            else
-                chunk_step<BITS, TW, false>(raw + TW, sc + TW, magic, xl, corr, zeros, ch + 1, diag, c,
-                                            r0 + chunk_stride, lane, sc_off, acc);
-        }
-    }
-
-    // lane (g, c < 8) holds the sum over its block column; add the 8 columns (lanes c >= 8 carry no
-    // useful column and contribute zero), lane c == 0 stores rows 4g .. 4g+3
-#pragma unroll
-    for (int tw = 0; tw < TW; ++tw)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            float v = (c < 8) ? acc[tw][r] : 0.f;
-            v += __shfl_xor(v, 1, 64);
-            v += __shfl_xor(v, 2, 64);
-            v += __shfl_xor(v, 4, 64);
-            acc[tw][r] = v;
-        }
-    if (c == 0) {
-        AQ_GLOBAL float* y = (AQ_GLOBAL float*)(uintptr_t)t.y;
-#pragma unroll
-        for (int tw = 0; tw < TW; ++tw) {
-            const int64_t row0 = ((int64_t)group * AQ_GROUP_TILES + tile0 + tw) * AQ_TILE_ROWS + 4 * g;
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (row0 + r < t.N) y[row0 + r] = acc[tw][r] * unscale;
-        }
+        constexpr int BITS = 4;
+#include "aq_gemv_body.inc"
     }
 }
 
@@ -457,14 +384,16 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg)
     return (int)(aq_num_groups(N) * (AQ_GROUP_TILES / tiles_per_wg));
 }
 
-// all tasks of one launch share `bits`
+// bits == 0: the tasks have different bit-widths (one mixed launch); else all tasks share `bits`
 hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
                     int total_wgs, int max_K, hipStream_t s)
 {
     const size_t lds = gemv_lds_bytes(max_K);
     const dim3 grid((unsigned)total_wgs), block(THREADS);
 #define AQ_LAUNCH(BITS, TW) hipLaunchKernelGGL((qgemv_kernel<BITS, TW>), grid, block, lds, s, tasks_dev, count, single)
-    if (tiles_per_wg == 8) {
+    if (bits == 0) {
+        hipLaunchKernelGGL((qgemv_mixed_kernel<2>), grid, block, lds, s, tasks_dev, count, single);
+    } else if (tiles_per_wg == 8) {
         if (bits == 2) AQ_LAUNCH(2, 2); else if (bits == 3) AQ_LAUNCH(3, 2); else AQ_LAUNCH(4, 2);
     } else {
         if (bits == 2) AQ_LAUNCH(2, 1); else if (bits == 3) AQ_LAUNCH(3, 1); else AQ_LAUNCH(4, 1);

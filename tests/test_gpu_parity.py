@@ -236,3 +236,69 @@ def test_errors_raise_through_the_binding(gpu):
         aq.aq_qgemv(p, 16, 64, 5, x.half())                # bad bit-width
     with pytest.raises(aq.AqError):
         aq.aq_qgemv(p, 16, 64, 4, x.half()[1:])            # misaligned pointer
+
+
+# ---------------------------------------------------------------------------------------------
+# full-size matrices in the launch configuration bench.py times (one batched launch over the
+# seven LLaMA-2-7B-shaped matrices of a layer, mixed bit-widths), checked on sampled outputs
+# ---------------------------------------------------------------------------------------------
+def test_full_size_layer_batched_sampled_rows(gpu, oracle):
+    torch, aq = gpu
+    rng = np.random.default_rng(123)
+    bits_of = {"q": 2, "k": 3, "v": 4, "o": 2, "gate": 3, "up": 2, "down": 4}
+    items, host = [], []
+    for i, (name, N, K) in enumerate(wl.LLAMA2_7B_LAYER):
+        b = bits_of[name]
+        codes, scales = wl.draw_matrix(N, K, b, 12, i)
+        x = wl.draw_activations(1, K, "f16", 12, i)
+        packed = _pack(torch, aq, codes, scales, N, K, b)
+        y = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, b, _dev(torch, x[0], "f16"), y))
+        host.append((codes, scales, x, N, K, b))
+    aq.GemvBatch(items).run()
+    torch.cuda.synchronize()
+    for (packed, N, K, b, xd, y), (codes, scales, x, _, _, _) in zip(items, host):
+        got = y.cpu().numpy()
+        assert np.isfinite(got).all()
+        rows = np.unique(np.concatenate([[0, 15, 16, 127, 128, N - 1], rng.integers(0, N, 250)]))
+        ref = oracle.qmatmul_rows(codes, scales, rows, K, b, x, "f16")[0]
+        assert oracle.rel_l2(got[rows], ref) <= REL_L2_EXPECTED
+        # unpacked codes of the sampled rows are bit-exact at full size too
+        q = aq.aq_unpack_codes(packed, N, K, b)[torch.from_numpy(rows).cuda()].cpu().numpy()
+        assert np.array_equal(q, oracle.unpack(codes[rows], len(rows), K, b))
+
+
+@pytest.mark.parametrize("name,N,K", [("q", 2048, 2048), ("k", 256, 2048), ("gate", 16384, 2048), ("down", 2048, 16384)])
+def test_gemma_shapes_decode_and_prefill_sampled(gpu, oracle, name, N, K):
+    """Gemma-2B-shaped matrices at 3 bits, bf16 activations, M in {1, 16, 64}; sampled columns."""
+    torch, aq = gpu
+    rng = np.random.default_rng(7)
+    codes, scales = wl.draw_matrix(N, K, 3, 13, N, K)
+    packed = _pack(torch, aq, codes, scales, N, K, 3)
+    rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 120)]))
+    for M in (1, 16, 64):
+        X = wl.draw_activations(M, K, "bf16", 13, N, K, M)
+        ref = oracle.qmatmul_rows(codes, scales, rows, K, 3, X, "bf16")
+        Y = aq.aq_qgemm(packed, N, K, 3, _dev(torch, X, "bf16")).cpu().numpy()
+        assert oracle.rel_l2(Y[:, rows], ref) <= REL_L2_EXPECTED
+        if M == 1:
+            y = aq.aq_qgemv(packed, N, K, 3, _dev(torch, X[0], "bf16")).cpu().numpy()
+            assert oracle.rel_l2(y[rows], ref[0]) <= REL_L2_EXPECTED
+
+
+def test_full_size_prefill_m300_sampled(gpu, oracle):
+    """One 4096 x 4096 matrix per bit-width at M = 300 (256 image rows x3, 44 text rows), sampled columns."""
+    torch, aq = gpu
+    rng = np.random.default_rng(9)
+    N = K = 4096
+    X = wl.draw_activations(300, K, "bf16", 14, image_rows=256, image_gain=3.0)
+    Xd = _dev(torch, X, "bf16")
+    for bits in (2, 3, 4):
+        codes, scales = wl.draw_matrix(N, K, bits, 14, bits)
+        packed = _pack(torch, aq, codes, scales, N, K, bits)
+        Y = aq.aq_qgemm(packed, N, K, bits, Xd).cpu().numpy()
+        rows = np.unique(np.concatenate([[0, 63, 64, N - 1], rng.integers(0, N, 60)]))
+        ref = oracle.qmatmul_rows(codes, scales, rows, K, bits, X, "bf16")
+        assert oracle.rel_l2(Y[:, rows], ref) <= REL_L2_EXPECTED
+        for m in (0, 255, 256, 299):
+            assert oracle.rel_l2(Y[m, rows], ref[m]) <= REL_L2_EXPECTED
