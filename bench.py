@@ -77,7 +77,13 @@ def main():
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=3)
+    ap.add_argument("--decode-only", action="store_true",
+                    help="only the timed decode stream (short run for rocprofv3 --pmc passes)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy 5 times and exit: scales the FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
+    if args.decode_only:
+        args.skip_by_bits = args.skip_prefill = args.skip_cpu = True
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists).", file=sys.stderr)
         sys.exit(2)
@@ -89,6 +95,15 @@ def main():
     aq.lib()      # fail loudly if the HIP library is missing: there is no fallback
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 1 << 30, "bytes_written": 1 << 30, "copies": 5}))
+        return
 
     # ---- the timed workload: mixed-bit LLaMA-2-7B-shaped decode stream -----------------
     specs = wl.backbone_stream("llama2-7b", "mixed")
@@ -102,13 +117,14 @@ def main():
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = step_bytes / (kernel_ms * 1e-3) / 1e9
 
+    # HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
+    # plain copy of known size); the committed summary carries the figure
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "qgemv_stream_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "qgemv_mixed_kernel__llama2-7b_mixed_decode__hbm_traffic.md")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+        import re
+        m = re.search(r"hbm_bytes_per_launch\s*=\s*(\d+)", open(tpath).read())
+        traffic = int(m.group(1)) if m else None
 
     out = {
         "metric": "qGEMV HBM GB/s (decode, batch 1, algorithmic bytes / time)",
