@@ -116,6 +116,23 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block,
              const void* X, int64_t M, int64_t ldx, int x_dtype,
              float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
+/* A list of independent prefill products in ONE launch (a whole backbone pass; a lone 4096-row
+ * matrix fills only a quarter of the GPU).  Same three steps as aq_qgemv_batch: plan on the host,
+ * copy the plan image to DEVICE memory, launch.  All descriptors of a plan share x_dtype. */
+typedef struct aq_gemm_desc {
+    const void* packed;   /* DEVICE blob */
+    const void* X;        /* DEVICE uint16 [M][ldx] */
+    float*      Y;        /* DEVICE float [M][ldy] */
+    int64_t     N, K, M, ldx, ldy;
+    int32_t     bits;     /* 2, 3 or 4 */
+    int32_t     x_dtype;  /* AQ_F16 or AQ_BF16 */
+} aq_gemm_desc;
+
+size_t aq_qgemm_batch_plan_size(int count);
+int aq_qgemm_batch_plan(const aq_gemm_desc* descs /*HOST*/, int count, int block,
+                        void* plan_host, size_t plan_bytes);
+int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* stream);
+
 /* Parity / debug: the blob decoded back to what Eq. 1 defines.
  *   codes_u8 DEVICE uint8 [N][K]  one code per byte
  *   W        DEVICE float [N][K]  d * (q - 2^(bits-1)); exact in fp32 (11-bit x 4-bit significands) */

@@ -34,6 +34,11 @@ class aq_gemv_desc(ctypes.Structure):
                 ("bits", ctypes.c_int32), ("x_dtype", ctypes.c_int32)]
 
 
+class aq_gemm_desc(ctypes.Structure):
+    _fields_ = [("packed", _p), ("X", _p), ("Y", _p), ("N", _i64), ("K", _i64), ("M", _i64), ("ldx", _i64),
+                ("ldy", _i64), ("bits", ctypes.c_int32), ("x_dtype", ctypes.c_int32)]
+
+
 def lib() -> ctypes.CDLL:
     """The loaded C library; raises if it has not been built."""
     global _lib
@@ -55,6 +60,10 @@ def lib() -> ctypes.CDLL:
         L.aq_qgemm_workspace_size.restype = _sz
         L.aq_qgemm_workspace_size.argtypes = [_i64, _i64, _i64, _int]
         L.aq_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
+        L.aq_qgemm_batch_plan_size.restype = _sz
+        L.aq_qgemm_batch_plan_size.argtypes = [_int]
+        L.aq_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _p, _sz]
+        L.aq_qgemm_batch.argtypes = [_p, _p, _p]
         L.aq_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         _lib = L
@@ -151,6 +160,29 @@ def aq_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block
     _check(lib().aq_qgemm(packed.data_ptr(), N, K, bits, block, X.data_ptr(), M, X.stride(0), _dtype_code(X),
                           Y.data_ptr(), Y.stride(0), ws_ptr, ws_bytes, _stream(stream)), "aq_qgemm")
     return Y
+
+
+class GemmBatch:
+    """A planned list of prefill products (one launch).  Holds references to every tensor."""
+
+    def __init__(self, items: Sequence[tuple], block: int = BLOCK):
+        """items: (packed, N, K, bits, X, Y) per matrix; X [M, K] half/bfloat16, Y [M, N] float32."""
+        import torch
+        n = len(items)
+        descs = (aq_gemm_desc * n)()
+        for d, (packed, N, K, bits, X, Y) in zip(descs, items):
+            d.packed, d.X, d.Y = packed.data_ptr(), X.data_ptr(), Y.data_ptr()
+            d.N, d.K, d.M, d.ldx, d.ldy = N, K, X.shape[0], X.stride(0), Y.stride(0)
+            d.bits, d.x_dtype = bits, _dtype_code(X)
+        size = int(lib().aq_qgemm_batch_plan_size(n))
+        self.plan_host = torch.empty(size, dtype=torch.uint8)
+        _check(lib().aq_qgemm_batch_plan(descs, n, block, self.plan_host.data_ptr(), size), "aq_qgemm_batch_plan")
+        self.plan_dev = self.plan_host.to(items[0][0].device)
+        self.items = list(items)
+
+    def run(self, stream=None) -> None:
+        _check(lib().aq_qgemm_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), _stream(stream)),
+               "aq_qgemm_batch")
 
 
 def aq_unpack_codes(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):

@@ -39,6 +39,48 @@ int check_matrix(int64_t N, int64_t K, int bits, int block)
 
 int check_dtype(int dt) { return (dt == AQ_F16 || dt == AQ_BF16) ? AQ_OK : AQ_EDTYPE; }
 
+struct GemmPlanHeader {
+    uint32_t magic;
+    int32_t count;
+    int32_t bits;            // the common bit-width, 0 if the tasks differ
+    int32_t x_dtype;
+    int32_t mtiles;          // m-tiles per wavefront, from the largest M
+    int32_t total_wgs;
+    int32_t reserved[10];
+};
+static_assert(sizeof(GemmPlanHeader) == 64, "GemmPlanHeader must stay 64 bytes");
+constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514731u;  // "AQG1"
+
+int check_gemm(int64_t N, int64_t K, int bits, int block, int64_t M, int64_t ldx, int64_t ldy, int x_dtype,
+               const void* packed, const void* X, const void* Y)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if (M < 1 || M > AQ_MAX_M || ldx < K || ldy < N) return AQ_EINVAL;
+    if (ldx % 8 != 0) return AQ_EINVAL;      // rows of X must keep 16-byte alignment
+    if ((rc = check_dtype(x_dtype)) != AQ_OK) return rc;
+    if (!packed || !X || !Y) return AQ_ENULL;
+    if (!aligned16(packed) || !aligned16(X) || !aligned16(Y)) return AQ_EALIGN;
+    return AQ_OK;
+}
+
+AqGemmTask make_gemm_task(const void* packed, int64_t N, int64_t K, int bits, const void* X, int64_t M,
+                          int64_t ldx, float* Y, int64_t ldy, int A, int wg_begin)
+{
+    AqGemmTask t;
+    std::memset(&t, 0, sizeof(t));
+    t.blob = static_cast<const uint8_t*>(packed);
+    t.X = static_cast<const uint16_t*>(X);
+    t.Y = Y;
+    t.N = N; t.M = M; t.ldx = ldx; t.ldy = ldy;
+    t.K = (int32_t)K; t.bits = bits; t.nchunks = (int32_t)aq_num_chunks(K);
+    int slabs = 0;
+    t.wg_begin = wg_begin;
+    t.wg_count = aqk_gemm_wg_count(N, M, A, &slabs);
+    t.slabs = slabs;
+    return t;
+}
+
 AqGemvTask make_task(const void* packed, int64_t N, int64_t K, int bits, const void* x, int dt, float* y)
 {
     AqGemvTask t;
@@ -180,18 +222,73 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, cons
              int64_t ldx, int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes,
              void* stream)
 {
-    int rc = check_matrix(N, K, bits, block);
+    int rc = check_gemm(N, K, bits, block, M, ldx, ldy, x_dtype, packed, X, Y);
     if (rc != AQ_OK) return rc;
-    if (M < 1 || M > AQ_MAX_M || ldx < K || ldy < N) return AQ_EINVAL;
-    if (ldx % 8 != 0) return AQ_EINVAL;      // rows of X must keep 16-byte alignment
-    if ((rc = check_dtype(x_dtype)) != AQ_OK) return rc;
-    if (!packed || !X || !Y) return AQ_ENULL;
     size_t need = aqk_gemm_workspace(M, N, K, bits);
     if (need > 0 && !workspace) return AQ_ENULL;
-    if (!aligned16(packed) || !aligned16(X) || !aligned16(Y) || (workspace && !aligned16(workspace)))
-        return AQ_EALIGN;
+    if (workspace && !aligned16(workspace)) return AQ_EALIGN;
     if (workspace_bytes < need) return AQ_ESIZE;
-    return aqk_gemm(packed, N, K, bits, X, M, ldx, x_dtype, Y, ldy, workspace,
+    const int A = aqk_gemm_mtiles(M);
+    AqGemmTask t = make_gemm_task(packed, N, K, bits, X, M, ldx, Y, ldy, A, 0);
+    return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, t.wg_count, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
+size_t aq_qgemm_batch_plan_size(int count)
+{
+    if (count < 1) return 0;
+    return sizeof(GemmPlanHeader) + (size_t)count * sizeof(AqGemmTask);
+}
+
+int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, void* plan_host, size_t plan_bytes)
+{
+    if (count < 1) return AQ_EINVAL;
+    if (!descs || !plan_host) return AQ_ENULL;
+    if (plan_bytes < aq_qgemm_batch_plan_size(count)) return AQ_ESIZE;
+    int64_t max_M = 0;
+    for (int i = 0; i < count; ++i) {
+        const aq_gemm_desc& d = descs[i];
+        int rc = check_gemm(d.N, d.K, d.bits, block, d.M, d.ldx, d.ldy, d.x_dtype, d.packed, d.X, d.Y);
+        if (rc != AQ_OK) return rc;
+        if (d.x_dtype != descs[0].x_dtype) return AQ_EDTYPE;
+        if (d.M > max_M) max_M = d.M;
+    }
+    GemmPlanHeader h;
+    std::memset(&h, 0, sizeof(h));
+    h.magic = GEMM_PLAN_MAGIC;
+    h.count = count;
+    h.bits = descs[0].bits;
+    h.x_dtype = descs[0].x_dtype;
+    h.mtiles = aqk_gemm_mtiles(max_M);
+    AqGemmTask* tasks = reinterpret_cast<AqGemmTask*>(static_cast<uint8_t*>(plan_host) + sizeof(GemmPlanHeader));
+    int64_t begin = 0;
+    for (int i = 0; i < count; ++i) {
+        const aq_gemm_desc& d = descs[i];
+        if (d.bits != descs[0].bits) h.bits = 0;
+        AqGemmTask t = make_gemm_task(d.packed, d.N, d.K, d.bits, d.X, d.M, d.ldx, d.Y, d.ldy, h.mtiles, (int)begin);
+        begin += t.wg_count;
+        if (begin > 0x7FFFFFFF) return AQ_EINVAL;
+        std::memcpy(&tasks[i], &t, sizeof(t));
+    }
+    h.total_wgs = (int32_t)begin;
+    std::memcpy(plan_host, &h, sizeof(h));
+    return AQ_OK;
+}
+
+int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* stream)
+{
+    if (!plan_host || !plan_dev) return AQ_ENULL;
+    if (!aligned16(plan_dev)) return AQ_EALIGN;
+    GemmPlanHeader h;
+    std::memcpy(&h, plan_host, sizeof(h));
+    if (h.magic != GEMM_PLAN_MAGIC || h.count < 1 || h.total_wgs < 1 || (h.bits != 0 && (h.bits < 2 || h.bits > 4)) ||
+        check_dtype(h.x_dtype) != AQ_OK)
+        return AQ_EINVAL;
+    const AqGemmTask* tasks =
+        reinterpret_cast<const AqGemmTask*>(static_cast<const uint8_t*>(plan_dev) + sizeof(GemmPlanHeader));
+    AqGemmTask none;
+    std::memset(&none, 0, sizeof(none));
+    return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.total_wgs,
                     static_cast<hipStream_t>(stream)) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
 }
 

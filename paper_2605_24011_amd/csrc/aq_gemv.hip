@@ -25,131 +25,14 @@
 #include <hip/hip_fp16.h>
 #include "aq_layout.h"
 #include "aq_kernels.h"
+#include "aq_codec.h"
 
 namespace {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float float4v __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 half4v __attribute__((ext_vector_type(4)));
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+using namespace aqdev;
 
 constexpr int WAVES = 4;
 constexpr int THREADS = WAVES * 64;
-
-// pointers read from a task record are generic; the streams they point to are global memory
-#define AQ_GLOBAL __attribute__((address_space(1)))
-template <class T> __device__ inline const AQ_GLOBAL T* as_global(const void* p)
-{
-    return (const AQ_GLOBAL T*)(uintptr_t)p;
-}
-
-// (a & mask) | magic must be ONE VALU instruction (V_AND_OR_B32).  gfx950's VOP3 encoding takes no
-// literal and a single scalar operand, so with two compile-time constants the compiler falls back
-// to an AND and an OR with literals.  `opaque_vgpr` hides the magic's value behind an empty asm
-// statement (no instruction is emitted) which pins it in a VGPR; the mask then rides in an SGPR.
-// The AND-OR itself stays ordinary C so that the compiler's hazard handling sees a real
-// instruction next to the MFMAs.
-__device__ inline uint32_t opaque_vgpr(uint32_t v)
-{
-    asm volatile("" : "+v"(v));
-    return v;
-}
-__device__ inline uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic) { return (a & mask) | magic; }
-
-// ---- per-bit-width codec: raw words of a lane, magic offsets, unpack to fp16 pairs ----
-template <int BITS> struct Codec;
-
-template <> struct Codec<2> {
-    static constexpr int WORDS = 4;            // per lane and unit (2 blocks x 2 words)
-    __device__ static float offset(int t) {    // magic of pair t, per half-bit position
-        const float o[8] = {64.f, 16.f, 64.f, 16.f, 4.f, 64.f, 16.f, 4.f};
-        return o[t & 7];
-    }
-    __device__ static void load(const uint8_t* unit, int lane, uint32_t (&w)[WORDS]) {
-        u32x4 v = __builtin_nontemporal_load(as_global<u32x4>(unit) + lane);
-        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
-    }
-    // words of one block -> 16 pair registers (fp16x2 = magic + code)
-    struct Magic { uint32_t m64, m16, m4; };
-    __device__ static Magic magic() {
-        return {opaque_vgpr(0x54005400u), opaque_vgpr(0x4C004C00u), opaque_vgpr(0x44004400u)};
-    }
-    __device__ static void fence(Magic& k, float& a) {
-        asm volatile("" : "+v"(k.m64), "+v"(k.m16), "+v"(k.m4), "+v"(a));
-    }
-    __device__ static void unpack(const uint32_t* w, const Magic& k, uint32_t (&a)[16]) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            uint32_t u0 = w[h], u1 = u0 >> 6, u2 = u0 << 4;
-            a[8 * h + 0] = and_or(u2, 0x00300030u, k.m64);
-            a[8 * h + 1] = and_or(u2, 0x00C000C0u, k.m16);
-            a[8 * h + 2] = and_or(u0, 0x00300030u, k.m64);
-            a[8 * h + 3] = and_or(u0, 0x00C000C0u, k.m16);
-            a[8 * h + 4] = and_or(u0, 0x03000300u, k.m4);
-            a[8 * h + 5] = and_or(u1, 0x00300030u, k.m64);
-            a[8 * h + 6] = and_or(u1, 0x00C000C0u, k.m16);
-            a[8 * h + 7] = and_or(u1, 0x03000300u, k.m4);
-        }
-    }
-};
-
-template <> struct Codec<4> {
-    static constexpr int WORDS = 8;
-    __device__ static float offset(int t) { return (t & 1) ? 16.f : 256.f; }
-    __device__ static void load(const uint8_t* unit, int lane, uint32_t (&w)[WORDS]) {
-        u32x4 v0 = __builtin_nontemporal_load(as_global<u32x4>(unit) + lane);
-        u32x4 v1 = __builtin_nontemporal_load(as_global<u32x4>(unit + 1024) + lane);
-        w[0] = v0.x; w[1] = v0.y; w[2] = v0.z; w[3] = v0.w;
-        w[4] = v1.x; w[5] = v1.y; w[6] = v1.z; w[7] = v1.w;
-    }
-    struct Magic { uint32_t m256, m16; };
-    __device__ static Magic magic() { return {opaque_vgpr(0x5C005C00u), opaque_vgpr(0x4C004C00u)}; }
-    __device__ static void fence(Magic& k, float& a) { asm volatile("" : "+v"(k.m256), "+v"(k.m16), "+v"(a)); }
-    __device__ static void unpack(const uint32_t* w, const Magic& k, uint32_t (&a)[16]) {
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            uint32_t u0 = w[h] << 2, u1 = w[h] >> 6;
-            a[4 * h + 0] = and_or(u0, 0x003C003Cu, k.m256);
-            a[4 * h + 1] = and_or(u0, 0x03C003C0u, k.m16);
-            a[4 * h + 2] = and_or(u1, 0x003C003Cu, k.m256);
-            a[4 * h + 3] = and_or(u1, 0x03C003C0u, k.m16);
-        }
-    }
-};
-
-template <> struct Codec<3> {
-    static constexpr int WORDS = 6;
-    __device__ static float offset(int t) {
-        const float o[5] = {128.f, 128.f, 16.f, 128.f, 16.f};
-        return t < 15 ? o[t % 5] : 16.f;
-    }
-    __device__ static void load(const uint8_t* unit, int lane, uint32_t (&w)[WORDS]) {
-        u32x2 v0 = __builtin_nontemporal_load(as_global<u32x2>(unit) + lane);
-        u32x4 v1 = __builtin_nontemporal_load(as_global<u32x4>(unit + 512) + lane);
-        w[0] = v0.x; w[1] = v0.y;
-        w[2] = v1.x; w[3] = v1.y; w[4] = v1.z; w[5] = v1.w;
-    }
-    struct Magic { uint32_t m128, m16; };
-    __device__ static Magic magic() { return {opaque_vgpr(0x58005800u), opaque_vgpr(0x4C004C00u)}; }
-    __device__ static void fence(Magic& k, float& a) { asm volatile("" : "+v"(k.m128), "+v"(k.m16), "+v"(a)); }
-    __device__ static void unpack(const uint32_t* w, const Magic& k, uint32_t (&a)[16]) {
-#pragma unroll
-        for (int h = 0; h < 3; ++h) {
-            uint32_t u0 = w[h], u1 = u0 >> 6, u2 = u0 << 3;
-            a[5 * h + 0] = and_or(u2, 0x00380038u, k.m128);
-            a[5 * h + 1] = and_or(u0, 0x00380038u, k.m128);
-            a[5 * h + 2] = and_or(u0, 0x01C001C0u, k.m16);
-            a[5 * h + 3] = and_or(u1, 0x00380038u, k.m128);
-            a[5 * h + 4] = and_or(u1, 0x01C001C0u, k.m16);
-        }
-        // pair 15: bit h of its codes sits in bit 15 of the halves of word h
-        uint32_t r = and_or(w[0] >> 9, 0x00400040u, k.m16);
-        r = and_or(w[1] >> 8, 0x00800080u, r);
-        a[15] = and_or(w[2] >> 7, 0x01000100u, r);
-    }
-};
 
 __device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 

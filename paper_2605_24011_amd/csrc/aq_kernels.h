@@ -32,6 +32,25 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg);
 hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
                     int total_wgs, int max_K, hipStream_t s);
 
+// One prefill product Y = X W^T as the kernel sees it (device-visible, 96 bytes).
+struct AqGemmTask {
+    const uint8_t* blob;
+    const uint16_t* X;
+    float* Y;
+    int64_t N, M, ldx, ldy;
+    int32_t K;
+    int32_t bits;
+    int32_t nchunks;    // ceil(K / 256)
+    int32_t slabs;      // 64-row slabs of W (N rounded up to 128, / 64)
+    int32_t wg_begin;   // first workgroup of this task inside a batched launch
+    int32_t wg_count;   // slabs * m-tiles
+    int64_t pad[2];
+};
+static_assert(sizeof(AqGemmTask) == 96, "AqGemmTask must stay 96 bytes");
+
+int aqk_gemm_mtiles(int64_t M);
+int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int* slabs);
 size_t aqk_gemm_workspace(int64_t M, int64_t N, int64_t K, int bits);
-hipError_t aqk_gemm(const void* blob, int64_t N, int64_t K, int bits, const void* X, int64_t M, int64_t ldx,
-                    int x_dtype, float* Y, int64_t ldy, void* ws, hipStream_t s);
+// count == 0: run `single`; bits == 0: the tasks' bit-widths differ; x_dtype and A are per launch
+hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
+                    int total_wgs, hipStream_t s);

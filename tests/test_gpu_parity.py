@@ -302,3 +302,28 @@ def test_full_size_prefill_m300_sampled(gpu, oracle):
         assert oracle.rel_l2(Y[:, rows], ref) <= REL_L2_EXPECTED
         for m in (0, 255, 256, 299):
             assert oracle.rel_l2(Y[m, rows], ref[m]) <= REL_L2_EXPECTED
+
+
+def test_qgemm_batch_matches_single_calls(gpu, oracle):
+    """Mixed-bit list of prefill products in one launch == the per-matrix calls == the oracle."""
+    torch, aq = gpu
+    specs = [(256, 512, 2, 37), (130, 2048, 3, 300), (512, 1056, 4, 64), (16, 32, 2, 1), (1000, 4096, 4, 200)]
+    items, refs = [], []
+    for i, (N, K, bits, M) in enumerate(specs):
+        codes, scales = wl.draw_matrix(N, K, bits, 15, i)
+        X = wl.draw_activations(M, K, "bf16", 15, i)
+        packed = _pack(torch, aq, codes, scales, N, K, bits)
+        Xd = _dev(torch, X, "bf16")
+        Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, Xd, Y))
+        refs.append(oracle.qmatmul(codes, scales, N, K, bits, X, "bf16"))
+    batch = aq.GemmBatch(items)
+    batch.run()
+    batch.run()
+    torch.cuda.synchronize()
+    for (packed, N, K, bits, Xd, Y), ref in zip(items, refs):
+        got = Y.cpu().numpy()
+        assert np.isfinite(got).all()
+        assert oracle.rel_l2(got, ref) <= REL_L2_EXPECTED
+        single = aq.aq_qgemm(packed, N, K, bits, Xd).cpu().numpy()
+        assert oracle.rel_l2(got, single) <= 1e-5
