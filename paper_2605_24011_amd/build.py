@@ -15,6 +15,8 @@ HIPCC_FLAGS = [
     "-Wall", "-Wno-unused-result",
     # packed-fp32 VALU forms are kept out of the generated code on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results in ordinary VGPRs (no AGPR copies around the fp32 scaling of block sums)
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
 ]
 
 

@@ -9,8 +9,9 @@
 //
 // Workgroup = 4 wavefronts, tile = 64 n (4 row tiles of the blob, one unit per wavefront and chunk)
 // x MT m with MT = 64*A (A = 5: all 300 prefill rows in one workgroup, so every weight is unpacked
-// once).  Wavefront w owns m-tiles [w*A, (w+1)*A) x all 64 n: A*4 accumulator tiles.  X steps of
-// 32 k (one block) are prefetched into registers one step ahead, weights one chunk (256 k) ahead.
+// once).  Wavefront w owns m-tiles [w*A, (w+1)*A) x all 64 n: A*4 accumulator tiles.  Its rows of X
+// are private, so X goes global -> registers in MFMA layout (two 32-k steps ahead) and only the
+// unpacked weights pass through LDS, double-buffered per 256-k chunk: one barrier per chunk.
 // A batched launch runs a list of matrices in one grid (a lone 4096-row matrix fills 64 of 256 CUs).
 #include <hip/hip_runtime.h>
 #include "aq_layout.h"
@@ -25,7 +26,6 @@ typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 constexpr int GM_WAVES = 4;
 constexpr int GM_THREADS = GM_WAVES * 64;
 constexpr int GM_NT = 64;                          // n per workgroup
-constexpr int X_ROW = AQ_BLOCK * 2 + 16;           // LDS row stride of an X step (32 k + pad): 80 B
 constexpr int W_ROW = AQ_CHUNK_K * 2 + 16;         // LDS row stride of the W chunk tile: 528 B
 
 // words of one block -> 16 registers, each a pair of exact (q - z) in fp16 or bf16
@@ -130,7 +130,7 @@ size_t aqk_gemm_workspace(int64_t, int64_t, int64_t, int) { return 0; }
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
                     int total_wgs, hipStream_t s)
 {
-    const size_t lds = (size_t)GM_NT * W_ROW + (size_t)64 * A * X_ROW + GM_NT * 8 * sizeof(float);
+    const size_t lds = 2 * ((size_t)GM_NT * W_ROW + GM_NT * 8 * sizeof(float));     // two chunk buffers
     const dim3 grid((unsigned)total_wgs);
     const bool bf = (x_dtype == 2);
 #define AQ_GO(B)                                                                     \
