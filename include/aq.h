@@ -60,7 +60,7 @@ const char* aq_status_string(int status);
 
 /* Bytes of the packed device blob of an N x K matrix, 0 if the arguments are invalid.
  * The blob stores exactly the canonical information (bits/8 + 1/16 bytes per weight)
- * re-tiled for the kernels, with N rounded up to 16 and K to 512; its layout is
+ * re-tiled for the kernels, with N rounded up to 128 and K to 256; its layout is
  * private to this build of the library. */
 size_t aq_packed_size(int64_t N, int64_t K, int bits, int block);
 
@@ -107,18 +107,25 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
  * unpacked to exact small integers (q - 2^(bits-1)) in LDS, multiplied on the matrix cores,
  * and the fp16 block scale d is applied in fp32 to each block's partial sum (Eq. 1 with the
  * factor d taken out of the block's sum), fp32 accumulation.
- *   X   DEVICE uint16 [M][ldx], ldx >= K, x_dtype = AQ_BF16 (AQ_F16 also accepted)
+ *   X   DEVICE uint16 [M][ldx], ldx >= K and ldx % 8 == 0, x_dtype = AQ_BF16 (AQ_F16 also accepted)
  *   Y   DEVICE float  [M][ldy], ldy >= N, overwritten for m < M, n < N
- *   workspace DEVICE, workspace_bytes >= aq_qgemm_workspace_size(M, N, K, bits); may be
- *       NULL when that size is 0.  Contents need no initialisation. */
+ *   workspace DEVICE, 16-byte aligned, workspace_bytes >= aq_qgemm_workspace_size(M, N, K, bits)
+ *       (= 2 bytes per element of X with M rounded up to 16).  The call first copies X into it in
+ *       the order the matrix cores read their operands (a permutation, no value changes), then
+ *       runs the product from that copy.  Contents need no initialisation and are scratch: calls
+ *       that share a workspace must be ordered on one stream. */
 size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits);
 int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block,
              const void* X, int64_t M, int64_t ldx, int x_dtype,
              float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
-/* A list of independent prefill products in ONE launch (a whole backbone pass; a lone 4096-row
- * matrix fills only a quarter of the GPU).  Same three steps as aq_qgemv_batch: plan on the host,
- * copy the plan image to DEVICE memory, launch.  All descriptors of a plan share x_dtype. */
+/* A list of independent prefill products in TWO launches (a whole backbone pass; a lone 4096-row
+ * matrix fills only a quarter of the GPU): one that re-orders every distinct activation matrix of
+ * the list into the workspace (descriptors with equal X, M, K and ldx share one copy), one for all
+ * the products.  Steps: plan on the host (aq_qgemm_batch_plan writes aq_qgemm_batch_plan_size(count)
+ * bytes), copy the plan image to 16-byte-aligned DEVICE memory, provide a DEVICE workspace of
+ * aq_qgemm_batch_workspace_size(plan_host) bytes, launch; the launch may be repeated.  All
+ * descriptors of a plan share x_dtype. */
 typedef struct aq_gemm_desc {
     const void* packed;   /* DEVICE blob */
     const void* X;        /* DEVICE uint16 [M][ldx] */
@@ -131,7 +138,9 @@ typedef struct aq_gemm_desc {
 size_t aq_qgemm_batch_plan_size(int count);
 int aq_qgemm_batch_plan(const aq_gemm_desc* descs /*HOST*/, int count, int block,
                         void* plan_host, size_t plan_bytes);
-int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* stream);
+size_t aq_qgemm_batch_workspace_size(const void* plan_host);   /* 0 if the plan image is invalid */
+int aq_qgemm_batch(const void* plan_host, const void* plan_dev,
+                   void* workspace, size_t workspace_bytes, void* stream);
 
 /* Parity / debug: the blob decoded back to what Eq. 1 defines.
  *   codes_u8 DEVICE uint8 [N][K]  one code per byte

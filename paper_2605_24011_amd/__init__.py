@@ -63,7 +63,9 @@ def lib() -> ctypes.CDLL:
         L.aq_qgemm_batch_plan_size.restype = _sz
         L.aq_qgemm_batch_plan_size.argtypes = [_int]
         L.aq_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _p, _sz]
-        L.aq_qgemm_batch.argtypes = [_p, _p, _p]
+        L.aq_qgemm_batch_workspace_size.restype = _sz
+        L.aq_qgemm_batch_workspace_size.argtypes = [_p]
+        L.aq_qgemm_batch.argtypes = [_p, _p, _p, _sz, _p]
         L.aq_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         _lib = L
@@ -178,11 +180,13 @@ class GemmBatch:
         self.plan_host = torch.empty(size, dtype=torch.uint8)
         _check(lib().aq_qgemm_batch_plan(descs, n, block, self.plan_host.data_ptr(), size), "aq_qgemm_batch_plan")
         self.plan_dev = self.plan_host.to(items[0][0].device)
+        self.workspace_bytes = int(lib().aq_qgemm_batch_workspace_size(self.plan_host.data_ptr()))
+        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=items[0][0].device)
         self.items = list(items)
 
     def run(self, stream=None) -> None:
-        _check(lib().aq_qgemm_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), _stream(stream)),
-               "aq_qgemm_batch")
+        _check(lib().aq_qgemm_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), self.workspace.data_ptr(),
+                                    self.workspace_bytes, _stream(stream)), "aq_qgemm_batch")
 
 
 def aq_unpack_codes(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):

@@ -3,6 +3,7 @@
 // without one.
 #include <hip/hip_runtime.h>
 #include <cstring>
+#include <vector>
 #include "../../include/aq.h"
 #include "aq_layout.h"
 #include "aq_kernels.h"
@@ -46,10 +47,13 @@ struct GemmPlanHeader {
     int32_t x_dtype;
     int32_t mtiles;          // m-tiles per wavefront, from the largest M
     int32_t total_wgs;
-    int32_t reserved[10];
+    int32_t retile_count;    // distinct activation matrices
+    int32_t retile_max_blocks;
+    int64_t workspace_bytes;
+    int32_t reserved[6];
 };
 static_assert(sizeof(GemmPlanHeader) == 64, "GemmPlanHeader must stay 64 bytes");
-constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514731u;  // "AQG1"
+constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514732u;  // "AQG2"
 
 int check_gemm(int64_t N, int64_t K, int bits, int block, int64_t M, int64_t ldx, int64_t ldy, int x_dtype,
                const void* packed, const void* X, const void* Y)
@@ -64,21 +68,32 @@ int check_gemm(int64_t N, int64_t K, int bits, int block, int64_t M, int64_t ldx
     return AQ_OK;
 }
 
-AqGemmTask make_gemm_task(const void* packed, int64_t N, int64_t K, int bits, const void* X, int64_t M,
-                          int64_t ldx, float* Y, int64_t ldy, int A, int wg_begin)
+AqGemmTask make_gemm_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset,
+                          float* Y, int64_t ldy, int A, int wg_begin)
 {
     AqGemmTask t;
     std::memset(&t, 0, sizeof(t));
     t.blob = static_cast<const uint8_t*>(packed);
-    t.X = static_cast<const uint16_t*>(X);
     t.Y = Y;
-    t.N = N; t.M = M; t.ldx = ldx; t.ldy = ldy;
+    t.N = N; t.M = M; t.ldy = ldy;
+    t.xt_offset = xt_offset;
     t.K = (int32_t)K; t.bits = bits; t.nchunks = (int32_t)aq_num_chunks(K);
     int slabs = 0;
     t.wg_begin = wg_begin;
     t.wg_count = aqk_gemm_wg_count(N, M, A, &slabs);
     t.slabs = slabs;
     return t;
+}
+
+AqRetileTask make_retile_task(const void* X, int64_t M, int64_t K, int64_t ldx, int64_t xt_offset)
+{
+    AqRetileTask r;
+    std::memset(&r, 0, sizeof(r));
+    r.X = static_cast<const uint16_t*>(X);
+    r.M = M; r.ldx = ldx; r.xt_offset = xt_offset;
+    r.K = (int32_t)K;
+    r.blocks = aqk_retile_blocks(M, K);
+    return r;
 }
 
 AqGemvTask make_task(const void* packed, int64_t N, int64_t K, int bits, const void* x, int dt, float* y)
@@ -215,7 +230,7 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream)
 size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits)
 {
     if (check_matrix(N, K, bits, AQ_BLOCK) != AQ_OK || M < 1 || M > AQ_MAX_M) return 0;
-    return aqk_gemm_workspace(M, N, K, bits);
+    return aqk_retile_bytes(M, K);
 }
 
 int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M,
@@ -224,20 +239,22 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, cons
 {
     int rc = check_gemm(N, K, bits, block, M, ldx, ldy, x_dtype, packed, X, Y);
     if (rc != AQ_OK) return rc;
-    size_t need = aqk_gemm_workspace(M, N, K, bits);
-    if (need > 0 && !workspace) return AQ_ENULL;
-    if (workspace && !aligned16(workspace)) return AQ_EALIGN;
-    if (workspace_bytes < need) return AQ_ESIZE;
+    if (!workspace) return AQ_ENULL;
+    if (!aligned16(workspace)) return AQ_EALIGN;
+    if (workspace_bytes < aqk_retile_bytes(M, K)) return AQ_ESIZE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const AqRetileTask r = make_retile_task(X, M, K, ldx, 0);
+    if (aqk_retile(nullptr, 0, r, r.blocks, workspace, s) != hipSuccess) return AQ_ELAUNCH;
     const int A = aqk_gemm_mtiles(M);
-    AqGemmTask t = make_gemm_task(packed, N, K, bits, X, M, ldx, Y, ldy, A, 0);
-    return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, t.wg_count, static_cast<hipStream_t>(stream)) == hipSuccess
-               ? AQ_OK : AQ_ELAUNCH;
+    AqGemmTask t = make_gemm_task(packed, N, K, bits, M, 0, Y, ldy, A, 0);
+    return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
 }
 
+// plan image: header, `count` product tasks, then up to `count` re-tiling tasks
 size_t aq_qgemm_batch_plan_size(int count)
 {
     if (count < 1) return 0;
-    return sizeof(GemmPlanHeader) + (size_t)count * sizeof(AqGemmTask);
+    return sizeof(GemmPlanHeader) + (size_t)count * (sizeof(AqGemmTask) + sizeof(AqRetileTask));
 }
 
 int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, void* plan_host, size_t plan_bytes)
@@ -260,36 +277,72 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, void* p
     h.bits = descs[0].bits;
     h.x_dtype = descs[0].x_dtype;
     h.mtiles = aqk_gemm_mtiles(max_M);
-    AqGemmTask* tasks = reinterpret_cast<AqGemmTask*>(static_cast<uint8_t*>(plan_host) + sizeof(GemmPlanHeader));
-    int64_t begin = 0;
+    uint8_t* base = static_cast<uint8_t*>(plan_host);
+    uint8_t* tasks = base + sizeof(GemmPlanHeader);
+    uint8_t* rtasks = tasks + (size_t)count * sizeof(AqGemmTask);
+    // products that read the same activations (same pointer, shape and row stride) share one re-tiled copy
+    std::vector<AqRetileTask> rt;
+    int64_t begin = 0, ws = 0;
     for (int i = 0; i < count; ++i) {
         const aq_gemm_desc& d = descs[i];
         if (d.bits != descs[0].bits) h.bits = 0;
-        AqGemmTask t = make_gemm_task(d.packed, d.N, d.K, d.bits, d.X, d.M, d.ldx, d.Y, d.ldy, h.mtiles, (int)begin);
+        int64_t off = -1;
+        for (const AqRetileTask& r : rt)
+            if (r.X == d.X && r.M == d.M && r.K == d.K && r.ldx == d.ldx) { off = r.xt_offset; break; }
+        if (off < 0) {
+            off = ws;
+            rt.push_back(make_retile_task(d.X, d.M, d.K, d.ldx, off));
+            ws += (int64_t)aqk_retile_bytes(d.M, d.K);
+            if (rt.back().blocks > h.retile_max_blocks) h.retile_max_blocks = rt.back().blocks;
+        }
+        AqGemmTask t = make_gemm_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, h.mtiles, (int)begin);
         begin += t.wg_count;
         if (begin > 0x7FFFFFFF) return AQ_EINVAL;
-        std::memcpy(&tasks[i], &t, sizeof(t));
+        std::memcpy(tasks + (size_t)i * sizeof(AqGemmTask), &t, sizeof(t));
     }
+    std::memset(rtasks, 0, (size_t)count * sizeof(AqRetileTask));
+    std::memcpy(rtasks, rt.data(), rt.size() * sizeof(AqRetileTask));
     h.total_wgs = (int32_t)begin;
+    h.retile_count = (int32_t)rt.size();
+    h.workspace_bytes = ws;
     std::memcpy(plan_host, &h, sizeof(h));
     return AQ_OK;
 }
 
-int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* stream)
+static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
 {
-    if (!plan_host || !plan_dev) return AQ_ENULL;
-    if (!aligned16(plan_dev)) return AQ_EALIGN;
-    GemmPlanHeader h;
     std::memcpy(&h, plan_host, sizeof(h));
-    if (h.magic != GEMM_PLAN_MAGIC || h.count < 1 || h.total_wgs < 1 || (h.bits != 0 && (h.bits < 2 || h.bits > 4)) ||
-        check_dtype(h.x_dtype) != AQ_OK)
-        return AQ_EINVAL;
-    const AqGemmTask* tasks =
-        reinterpret_cast<const AqGemmTask*>(static_cast<const uint8_t*>(plan_dev) + sizeof(GemmPlanHeader));
+    return h.magic == GEMM_PLAN_MAGIC && h.count >= 1 && h.total_wgs >= 1 && (h.bits == 0 || (h.bits >= 2 && h.bits <= 4)) &&
+           check_dtype(h.x_dtype) == AQ_OK && h.retile_count >= 1 && h.retile_count <= h.count &&
+           h.retile_max_blocks >= 1 && h.workspace_bytes >= 1024;
+}
+
+size_t aq_qgemm_batch_workspace_size(const void* plan_host)
+{
+    GemmPlanHeader h;
+    if (!plan_host || !read_gemm_plan(plan_host, h)) return 0;
+    return (size_t)h.workspace_bytes;
+}
+
+int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!plan_host || !plan_dev || !workspace) return AQ_ENULL;
+    if (!aligned16(plan_dev) || !aligned16(workspace)) return AQ_EALIGN;
+    GemmPlanHeader h;
+    if (!read_gemm_plan(plan_host, h)) return AQ_EINVAL;
+    if (workspace_bytes < (size_t)h.workspace_bytes) return AQ_ESIZE;
+    const uint8_t* dev = static_cast<const uint8_t*>(plan_dev);
+    const AqGemmTask* tasks = reinterpret_cast<const AqGemmTask*>(dev + sizeof(GemmPlanHeader));
+    const AqRetileTask* rtasks =
+        reinterpret_cast<const AqRetileTask*>(dev + sizeof(GemmPlanHeader) + (size_t)h.count * sizeof(AqGemmTask));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    AqRetileTask rnone;
+    std::memset(&rnone, 0, sizeof(rnone));
+    if (aqk_retile(rtasks, h.retile_count, rnone, h.retile_max_blocks, workspace, s) != hipSuccess) return AQ_ELAUNCH;
     AqGemmTask none;
     std::memset(&none, 0, sizeof(none));
-    return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.total_wgs,
-                    static_cast<hipStream_t>(stream)) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.total_wgs, workspace, s) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
 }
 
 int aq_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream)

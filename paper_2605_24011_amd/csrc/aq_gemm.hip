@@ -7,13 +7,20 @@
 // rounded into a 16-bit weight, so only fp32 summation rounds (rel-L2 ~1e-7).  The price is one fp32
 // FMA per 32 MFMA multiply-adds: the vector ALU is busy for as long as the matrix pipe.
 //
-// Workgroup = 4 wavefronts, tile = 64 n (4 row tiles of the blob, one unit per wavefront and chunk)
-// x MT m with MT = 64*A (A = 5: all 300 prefill rows in one workgroup, so every weight is unpacked
-// once).  Wavefront w owns m-tiles [w*A, (w+1)*A) x all 64 n: A*4 accumulator tiles.  Its rows of X
-// are private, so X goes global -> registers in MFMA layout (two 32-k steps ahead) and only the
-// unpacked weights pass through LDS, double-buffered per 256-k chunk: one barrier per chunk.
-// A batched launch runs a list of matrices in one grid (a lone 4096-row matrix fills 64 of 256 CUs).
+// Workgroup = 8 wavefronts, tile = 128 n (one row group of the blob: one unit per wavefront and chunk)
+// x up to 384 m (A = 3 m-tiles per wavefront: all 300 prefill rows in one workgroup, so every weight
+// is unpacked once).  The wavefronts split m only: each owns 2 or 3 m-tiles x all 128 n, 16 or 24
+// accumulator tiles.  Its rows of X are private, so X goes global -> registers (two 32-k steps ahead)
+// and only the unpacked weights pass through LDS, double-buffered per 256-k chunk: one barrier per
+// chunk.  Splitting n across wavefronts instead would make several wavefronts request the same X;
+// hits or not, the CU's L1 path delivers 64 bytes per clock and was the measured limit of that shape.
+// A lane of an MFMA A operand holds 16 bytes of ONE row, and neighbouring lanes hold different rows:
+// read from a row-major X that is 64 cache lines per load instruction.  So a small pre-pass re-tiles X
+// once per product list into operand order (retile_kernel) and the main kernel's loads are 1 KiB
+// contiguous.  A batched launch runs a list of matrices in one grid (a lone 4096-row matrix gives only
+// 32 workgroups for 256 CUs).
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include "aq_layout.h"
 #include "aq_kernels.h"
 #include "aq_codec.h"
@@ -23,9 +30,9 @@ namespace {
 using namespace aqdev;
 typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 
-constexpr int GM_WAVES = 4;
+constexpr int GM_WAVES = 8;                        // all along m: each wavefront covers the workgroup's 128 n
 constexpr int GM_THREADS = GM_WAVES * 64;
-constexpr int GM_NT = 64;                          // n per workgroup
+constexpr int GM_NT = AQ_GROUP_ROWS;               // n per workgroup = one 128-row group of the blob
 constexpr int W_ROW = AQ_CHUNK_K * 2 + 16;         // LDS row stride of the W chunk tile: 528 B
 
 // words of one block -> 16 registers, each a pair of exact (q - z) in fp16 or bf16
@@ -59,6 +66,15 @@ __device__ __forceinline__ float4v mfma16(const u32x4& a, const u32x4& b, const 
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory, which
+// costs a full drain of the vector-memory queue (vmcnt 0) and with it the X prefetch, once per chunk.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 #define AQ_FIND_GEMM_TASK(t, wg)                                                  \
     AqGemmTask t;                                                                 \
     int wg = blockIdx.x;                                                          \
@@ -78,7 +94,7 @@ __device__ __forceinline__ float4v mfma16(const u32x4& a, const u32x4& b, const 
 // BITS_T == 0: the tasks' bit-widths differ, branch per workgroup
 template <int BITS_T, bool XBF, int A>
 __global__ __launch_bounds__(GM_THREADS) void qgemm_kernel(const AqGemmTask* __restrict__ tasks, int count,
-                                                           AqGemmTask single)
+                                                           AqGemmTask single, const uint8_t* __restrict__ workspace)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     AQ_FIND_GEMM_TASK(t, wg);
@@ -94,49 +110,91 @@ __global__ __launch_bounds__(GM_THREADS) void qgemm_kernel(const AqGemmTask* __r
     }
 }
 
+// X[M][ldx] (16-bit elements) -> Xt in operand order.  Thread e handles the 16-byte piece j = e % (K/8)
+// of row e / (K/8): reads run along the rows of X, rows in [M, 16*ceil(M/16)) are written as zeros.
+__global__ __launch_bounds__(256) void retile_kernel(const AqRetileTask* __restrict__ tasks, int count,
+                                                     AqRetileTask single, uint8_t* __restrict__ workspace)
+{
+    AqRetileTask t;
+    if (count == 0) t = single; else t = tasks[blockIdx.y];
+    if ((int)blockIdx.x >= t.blocks) return;
+    const int pieces = t.K >> 3;                               // 16-byte pieces per row
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = e / pieces;
+    const int j = (int)(e - row * pieces);
+    const int64_t mpad = (t.M + 15) & ~(int64_t)15;
+    if (row >= mpad) return;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (row < t.M) v = *as_global<u32x4>(t.X + row * t.ldx + (int64_t)j * 8);
+    const int64_t mtile = row >> 4;
+    const int c = (int)(row & 15), step = j >> 2, g = j & 3;
+    const int64_t ksteps = t.K >> 5;
+    u32x4* dst = reinterpret_cast<u32x4*>(workspace + t.xt_offset);
+    dst[(mtile * ksteps + step) * 64 + g * 16 + c] = v;
+}
+
 template <int BITS_T, bool XBF>
-void launch_a(int A, dim3 grid, size_t lds, hipStream_t s, const AqGemmTask* tasks, int count, const AqGemmTask& single)
+void launch_a(int A, dim3 grid, size_t lds, hipStream_t s, const AqGemmTask* tasks, int count, const AqGemmTask& single,
+              const uint8_t* ws)
 {
     dim3 block(GM_THREADS);
+#define AQ_LAUNCH(AA)                                                                                          \
+    do {                                                                                                       \
+        auto k = qgemm_kernel<BITS_T, XBF, AA>;                                                                \
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                  (int)lds);               /* more than the 64 KiB default */                  \
+        hipLaunchKernelGGL(k, grid, block, lds, s, tasks, count, single, ws);                                  \
+    } while (0)
     switch (A) {
-        case 1: hipLaunchKernelGGL((qgemm_kernel<BITS_T, XBF, 1>), grid, block, lds, s, tasks, count, single); break;
-        case 2: hipLaunchKernelGGL((qgemm_kernel<BITS_T, XBF, 2>), grid, block, lds, s, tasks, count, single); break;
-        case 3: hipLaunchKernelGGL((qgemm_kernel<BITS_T, XBF, 3>), grid, block, lds, s, tasks, count, single); break;
-        default: hipLaunchKernelGGL((qgemm_kernel<BITS_T, XBF, 5>), grid, block, lds, s, tasks, count, single); break;
+        case 1: AQ_LAUNCH(1); break;
+        case 2: AQ_LAUNCH(2); break;
+        default: AQ_LAUNCH(3); break;
     }
+#undef AQ_LAUNCH
 }
 
 }  // namespace
 
-// m-tiles (16 rows) per wavefront for M rows of activations: the workgroup covers 64*A rows
+// most m-tiles (16 rows) per wavefront for M rows of activations: a workgroup covers up to 8*A m-tiles
 int aqk_gemm_mtiles(int64_t M)
 {
-    if (M <= 64) return 1;
-    if (M <= 128) return 2;
-    if (M <= 192) return 3;
-    return 5;
+    if (M <= 128) return 1;
+    if (M <= 256) return 2;
+    return 3;
 }
 
 int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int* slabs)
 {
-    const int sl = (int)(aq_num_groups(N) * 2);
+    const int sl = (int)aq_num_groups(N);
     if (slabs) *slabs = sl;
-    return sl * (int)((M + 64 * A - 1) / (64 * A));
+    const int64_t rows = (int64_t)GM_WAVES * 16 * A;
+    return sl * (int)((M + rows - 1) / rows);
 }
 
-size_t aqk_gemm_workspace(int64_t, int64_t, int64_t, int) { return 0; }
+size_t aqk_retile_bytes(int64_t M, int64_t K) { return (size_t)(((M + 15) / 16) * 16 * K * 2); }
+
+int aqk_retile_blocks(int64_t M, int64_t K) { return (int)((((M + 15) / 16) * 16 * (K / 8) + 255) / 256); }
+
+hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int max_blocks,
+                      void* workspace, hipStream_t s)
+{
+    const dim3 grid((unsigned)max_blocks, (unsigned)(count == 0 ? 1 : count));
+    hipLaunchKernelGGL(retile_kernel, grid, dim3(256), 0, s, tasks_dev, count, single, static_cast<uint8_t*>(workspace));
+    return hipGetLastError();
+}
 
 // bits == 0: mixed bit-widths; x_dtype is common to all tasks of a launch
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
-                    int total_wgs, hipStream_t s)
+                    int total_wgs, const void* workspace, hipStream_t s)
 {
     const size_t lds = 2 * ((size_t)GM_NT * W_ROW + GM_NT * 8 * sizeof(float));     // two chunk buffers
     const dim3 grid((unsigned)total_wgs);
     const bool bf = (x_dtype == 2);
+    const uint8_t* ws = static_cast<const uint8_t*>(workspace);
 #define AQ_GO(B)                                                                     \
     do {                                                                             \
-        if (bf) launch_a<B, true>(A, grid, lds, s, tasks_dev, count, single);        \
-        else launch_a<B, false>(A, grid, lds, s, tasks_dev, count, single);          \
+        if (bf) launch_a<B, true>(A, grid, lds, s, tasks_dev, count, single, ws);    \
+        else launch_a<B, false>(A, grid, lds, s, tasks_dev, count, single, ws);      \
     } while (0)
     if (bits == 2) AQ_GO(2);
     else if (bits == 3) AQ_GO(3);

@@ -32,25 +32,42 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg);
 hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
                     int total_wgs, int max_K, hipStream_t s);
 
+// Prefill.  The activations are first re-tiled into the order the matrix cores read them ("Xt"):
+//   Xt[m / 16][k / 32][lane = 16*g + c] = the 16 bytes X[16*(m/16) + c][32*(k/32) + 8g .. 8g+7],
+// rows beyond M zero, so that a wavefront's A operand of one (m-tile, 32-k step) is 1 KiB contiguous.
+// Xt lives in the caller's workspace at `xt_offset`; several products may share one Xt.
+struct AqRetileTask {
+    const uint16_t* X;
+    int64_t M, ldx;
+    int64_t xt_offset;  // bytes from the workspace base, multiple of 1024
+    int32_t K;
+    int32_t blocks;     // workgroups of 256 threads, one 16-byte piece per thread
+};
+static_assert(sizeof(AqRetileTask) == 40, "AqRetileTask must stay 40 bytes");
+
 // One prefill product Y = X W^T as the kernel sees it (device-visible, 96 bytes).
 struct AqGemmTask {
     const uint8_t* blob;
-    const uint16_t* X;
     float* Y;
-    int64_t N, M, ldx, ldy;
+    int64_t N, M, ldy;
+    int64_t xt_offset;  // this product's Xt, bytes from the workspace base
     int32_t K;
     int32_t bits;
     int32_t nchunks;    // ceil(K / 256)
-    int32_t slabs;      // 64-row slabs of W (N rounded up to 128, / 64)
+    int32_t slabs;      // 128-row groups of W
     int32_t wg_begin;   // first workgroup of this task inside a batched launch
     int32_t wg_count;   // slabs * m-tiles
-    int64_t pad[2];
+    int64_t pad[3];
 };
 static_assert(sizeof(AqGemmTask) == 96, "AqGemmTask must stay 96 bytes");
 
 int aqk_gemm_mtiles(int64_t M);
 int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int* slabs);
-size_t aqk_gemm_workspace(int64_t M, int64_t N, int64_t K, int bits);
+size_t aqk_retile_bytes(int64_t M, int64_t K);
+int aqk_retile_blocks(int64_t M, int64_t K);
+// count == 0: run `single`; else `count` tasks from device memory; grid = (max_blocks, tasks)
+hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int max_blocks,
+                      void* workspace, hipStream_t s);
 // count == 0: run `single`; bits == 0: the tasks' bit-widths differ; x_dtype and A are per launch
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
-                    int total_wgs, hipStream_t s);
+                    int total_wgs, const void* workspace, hipStream_t s);

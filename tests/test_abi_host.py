@@ -82,3 +82,58 @@ def test_batch_plan_validation(L):
     bad = ctypes.create_string_buffer(size)
     assert L.aq_qgemv_batch(bad, A, None) == aq.AQ_EINVAL     # not a plan image
     assert L.aq_qgemv_batch(buf, None, None) == aq.AQ_ENULL
+
+
+def test_gemm_batch_plan_validation_and_workspace(L):
+    """Host-side planning of a prefill list: sizes, shared activations, every error path (no GPU work)."""
+    A = 4096
+    n = 4
+    descs = (aq.aq_gemm_desc * n)()
+    shapes = [(4096, 4096), (1024, 4096), (512, 2048), (4096, 4096)]
+    for i, (d, (N, K)) in enumerate(zip(descs, shapes)):
+        d.packed, d.Y, d.N, d.K, d.M, d.ldx, d.ldy = A, A, N, K, 300, K, N
+        d.bits, d.x_dtype = 2 + i % 3, aq.AQ_BF16
+    # products 0, 1 and 3 read the same activations; product 2 its own
+    descs[0].X = descs[1].X = descs[3].X = A
+    descs[2].X = 2 * A
+    size = L.aq_qgemm_batch_plan_size(n)
+    assert size >= n * 96
+    buf = ctypes.create_string_buffer(size)
+    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_OK
+    # one re-ordered copy per distinct X: rows rounded up to 16, 2 bytes per element
+    assert L.aq_qgemm_batch_workspace_size(buf) == 304 * 4096 * 2 + 304 * 2048 * 2
+    assert L.aq_qgemm_workspace_size(300, 4096, 4096, 2) == 304 * 4096 * 2
+    assert L.aq_qgemm_workspace_size(1, 16, 32, 4) == 16 * 32 * 2
+    # same pointer but another row stride is another copy
+    descs[1].ldx = 4096 + 8
+    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_OK
+    assert L.aq_qgemm_batch_workspace_size(buf) == 2 * 304 * 4096 * 2 + 304 * 2048 * 2
+    descs[1].ldx = 4096
+    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size - 1) == aq.AQ_ESIZE
+    assert L.aq_qgemm_batch_plan(descs, 0, 32, buf, size) == aq.AQ_EINVAL
+    assert L.aq_qgemm_batch_plan(descs, n, 64, buf, size) == aq.AQ_EINVAL
+    descs[2].x_dtype = aq.AQ_F16
+    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_EDTYPE     # one dtype per plan
+    descs[2].x_dtype = aq.AQ_BF16
+    descs[2].ldx = 2048 + 4
+    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_EINVAL     # rows of X lose 16-byte alignment
+    descs[2].ldx = 2048
+    descs[3].Y = None
+    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_ENULL
+    descs[3].Y = A
+    descs[3].X = A + 2
+    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_EALIGN
+    descs[3].X = A
+    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_OK
+    ws = L.aq_qgemm_batch_workspace_size(buf)
+    assert ws == 304 * 4096 * 2 + 304 * 2048 * 2
+    bad = ctypes.create_string_buffer(size)
+    assert L.aq_qgemm_batch_workspace_size(bad) == 0
+    assert L.aq_qgemm_batch(bad, A, A, ws, None) == aq.AQ_EINVAL              # not a plan image
+    assert L.aq_qgemm_batch(buf, None, A, ws, None) == aq.AQ_ENULL
+    assert L.aq_qgemm_batch(buf, A, None, ws, None) == aq.AQ_ENULL
+    assert L.aq_qgemm_batch(buf, A, A + 4, ws, None) == aq.AQ_EALIGN
+    assert L.aq_qgemm_batch(buf, A, A, ws - 1, None) == aq.AQ_ESIZE
+    # single call: the workspace is required and checked before anything is launched
+    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, None, 0, None) == aq.AQ_ENULL
+    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, A, 1024, None) == aq.AQ_ESIZE

@@ -160,8 +160,9 @@ def test_qgemv_batch_matches_single_calls(gpu, oracle):
         assert oracle.rel_l2(got, single) <= 1e-5
 
 
-GEMM_CASES = [  # (N, K, M)
+GEMM_CASES = [  # (N, K, M): M spans 1..3 m-tiles per wavefront, uneven tile deals and two workgroups along m
     (64, 256, 16), (17, 96, 1), (200, 1056, 7), (256, 2048, 64), (512, 512, 300), (130, 4096, 81),
+    (128, 512, 129), (144, 288, 257), (96, 544, 385), (260, 256, 800),
 ]
 
 
@@ -327,3 +328,30 @@ def test_qgemm_batch_matches_single_calls(gpu, oracle):
         assert oracle.rel_l2(got, ref) <= REL_L2_EXPECTED
         single = aq.aq_qgemm(packed, N, K, bits, Xd).cpu().numpy()
         assert oracle.rel_l2(got, single) <= 1e-5
+
+
+def test_qgemm_batch_shares_and_separates_activations(gpu, oracle):
+    """Products that read the same X share one re-ordered copy; a view with another row stride gets its own."""
+    torch, aq = gpu
+    K, M = 1056, 300
+    X = wl.draw_activations(M, K, "bf16", 16, 0, image_rows=256, image_gain=3.0)
+    X2 = wl.draw_activations(M, K, "bf16", 16, 1)
+    Xd = _dev(torch, X, "bf16")
+    wide = torch.zeros((M, K + 24), dtype=torch.bfloat16, device="cuda")
+    wide[:, :K] = _dev(torch, X2, "bf16")
+    X2d = wide[:, :K]                                   # row stride K + 24
+    items, refs = [], []
+    for i, (N, bits, xd, x) in enumerate([(272, 2, Xd, X), (130, 3, Xd, X), (512, 4, X2d, X2), (64, 2, Xd, X)]):
+        codes, scales = wl.draw_matrix(N, K, bits, 16, i)
+        packed = _pack(torch, aq, codes, scales, N, K, bits)
+        Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, xd, Y))
+        refs.append(oracle.qmatmul(codes, scales, N, K, bits, x, "bf16"))
+    batch = aq.GemmBatch(items)
+    assert batch.workspace_bytes == 2 * 304 * K * 2     # two distinct activation matrices
+    batch.run()
+    torch.cuda.synchronize()
+    for (packed, N, K_, bits, xd, Y), ref in zip(items, refs):
+        got = Y.cpu().numpy()
+        assert np.isfinite(got).all()
+        assert oracle.rel_l2(got, ref) <= REL_L2_EXPECTED
