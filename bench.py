@@ -76,6 +76,7 @@ def main():
     ap.add_argument("--skip-by-bits", action="store_true")
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--skip-gemma", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=5)
     ap.add_argument("--decode-only", action="store_true",
                     help="only the timed decode stream (short run for rocprofv3 --pmc passes)")
@@ -83,7 +84,7 @@ def main():
                     help="run a plain 1 GiB device copy 5 times and exit: scales the FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.decode_only:
-        args.skip_by_bits = args.skip_prefill = args.skip_cpu = True
+        args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = True
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists).", file=sys.stderr)
         sys.exit(2)
@@ -235,6 +236,39 @@ def main():
             "mfma_frac_of_bf16_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
             "prefill_tokens_per_s": round(M / (ms * 1e-3), 1),
         }
+
+    # ---- Gemma-2B-shaped stream, uniform 3 bits (3.5 bits/weight stored), bf16 activations ----------
+    if not args.skip_gemma:
+        del items, batch
+        torch.cuda.empty_cache()
+        gs = wl.backbone_stream("gemma-2b", "b3")
+        gitems = build_stream(aq, wl, torch, gs, "bf16", 5)
+        gweights = sum(m.weights for m in gs)
+        gb = aq.GemvBatch(gitems)
+        gbytes = sum(gemv_bytes(m.N, m.K, m.bits) for m in gs)
+        d, w = time_launches(torch, gb.run, max(10, args.steps // 2), 3)
+        ms = sum(d) / len(d)
+        gem = {"workload": "gemma-2b-shaped stream, 126 matrices, 3 bits (3.5 bits/weight stored), bf16 activations",
+               "decode": {"GB/s": round(gbytes / (ms * 1e-3) / 1e9, 1),
+                          "pct_hbm_peak": round(100 * gbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+                          "ms": round(ms, 4), "tokens_per_s": round(1e3 / ms, 1), "bytes": gbytes}}
+        for M in (16, 64, wl.PREFILL_M):
+            Xs = {K: wl.draw_activations_torch(M, K, "bf16", "cuda", 6, K, M) for K in sorted({m.K for m in gs})}
+            Ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({m.N for m in gs})}
+            g2 = aq.GemmBatch([(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in gitems])
+            d, w = time_launches(torch, g2.run, args.prefill_steps, 1)
+            ms = sum(d) / len(d)
+            flops = 2.0 * M * gweights
+            nbytes = sum(stored_bytes(m.N, m.K, m.bits) + 2 * M * m.K + 4 * M * m.N for m in gs)
+            t_hbm, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+            gem["prefill_M%d" % M] = {
+                "ms": round(ms, 4), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
+                "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                "bound": "hbm" if t_hbm > t_mfma else "mfma",
+                "frac_of_min_roofline": round(max(t_hbm, t_mfma) / (ms * 1e-3), 4),
+                "tokens_per_s": round(M / (ms * 1e-3), 1)}
+            del g2, Xs, Ys
+        out["gemma"] = gem
 
     print(json.dumps(out), flush=True)
 

@@ -50,10 +50,11 @@ struct GemmPlanHeader {
     int32_t retile_count;    // distinct activation matrices
     int32_t retile_max_blocks;
     int64_t workspace_bytes;
-    int32_t reserved[6];
+    int32_t nsplit;          // wavefronts along n, from the largest M
+    int32_t reserved[5];
 };
 static_assert(sizeof(GemmPlanHeader) == 64, "GemmPlanHeader must stay 64 bytes");
-constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514732u;  // "AQG2"
+constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514733u;  // "AQG3"
 
 int check_gemm(int64_t N, int64_t K, int bits, int block, int64_t M, int64_t ldx, int64_t ldy, int x_dtype,
                const void* packed, const void* X, const void* Y)
@@ -69,7 +70,7 @@ int check_gemm(int64_t N, int64_t K, int bits, int block, int64_t M, int64_t ldx
 }
 
 AqGemmTask make_gemm_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset,
-                          float* Y, int64_t ldy, int A, int wg_begin)
+                          float* Y, int64_t ldy, int A, int nsplit, int wg_begin)
 {
     AqGemmTask t;
     std::memset(&t, 0, sizeof(t));
@@ -80,7 +81,7 @@ AqGemmTask make_gemm_task(const void* packed, int64_t N, int64_t K, int bits, in
     t.K = (int32_t)K; t.bits = bits; t.nchunks = (int32_t)aq_num_chunks(K);
     int slabs = 0;
     t.wg_begin = wg_begin;
-    t.wg_count = aqk_gemm_wg_count(N, M, A, &slabs);
+    t.wg_count = aqk_gemm_wg_count(N, M, A, nsplit, &slabs);
     t.slabs = slabs;
     return t;
 }
@@ -245,9 +246,10 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, cons
     hipStream_t s = static_cast<hipStream_t>(stream);
     const AqRetileTask r = make_retile_task(X, M, K, ldx, 0);
     if (aqk_retile(nullptr, 0, r, r.blocks, workspace, s) != hipSuccess) return AQ_ELAUNCH;
-    const int A = aqk_gemm_mtiles(M);
-    AqGemmTask t = make_gemm_task(packed, N, K, bits, M, 0, Y, ldy, A, 0);
-    return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    const int A = aqk_gemm_mtiles(M), nsplit = aqk_gemm_nsplit(M);
+    AqGemmTask t = make_gemm_task(packed, N, K, bits, M, 0, Y, ldy, A, nsplit, 0);
+    return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, nsplit, t.wg_count, workspace, s) == hipSuccess ? AQ_OK
+                                                                                                    : AQ_ELAUNCH;
 }
 
 // plan image: header, `count` product tasks, then up to `count` re-tiling tasks
@@ -277,6 +279,7 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, void* p
     h.bits = descs[0].bits;
     h.x_dtype = descs[0].x_dtype;
     h.mtiles = aqk_gemm_mtiles(max_M);
+    h.nsplit = aqk_gemm_nsplit(max_M);
     uint8_t* base = static_cast<uint8_t*>(plan_host);
     uint8_t* tasks = base + sizeof(GemmPlanHeader);
     uint8_t* rtasks = tasks + (size_t)count * sizeof(AqGemmTask);
@@ -295,7 +298,7 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, void* p
             ws += (int64_t)aqk_retile_bytes(d.M, d.K);
             if (rt.back().blocks > h.retile_max_blocks) h.retile_max_blocks = rt.back().blocks;
         }
-        AqGemmTask t = make_gemm_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, h.mtiles, (int)begin);
+        AqGemmTask t = make_gemm_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, h.mtiles, h.nsplit, (int)begin);
         begin += t.wg_count;
         if (begin > 0x7FFFFFFF) return AQ_EINVAL;
         std::memcpy(tasks + (size_t)i * sizeof(AqGemmTask), &t, sizeof(t));
@@ -314,7 +317,8 @@ static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
     std::memcpy(&h, plan_host, sizeof(h));
     return h.magic == GEMM_PLAN_MAGIC && h.count >= 1 && h.total_wgs >= 1 && (h.bits == 0 || (h.bits >= 2 && h.bits <= 4)) &&
            check_dtype(h.x_dtype) == AQ_OK && h.retile_count >= 1 && h.retile_count <= h.count &&
-           h.retile_max_blocks >= 1 && h.workspace_bytes >= 1024;
+           h.retile_max_blocks >= 1 && h.workspace_bytes >= 1024 &&
+           (h.nsplit == 1 || ((h.nsplit == 2 || h.nsplit == 4 || h.nsplit == 8) && h.mtiles == 1));
 }
 
 size_t aq_qgemm_batch_workspace_size(const void* plan_host)
@@ -341,7 +345,7 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
     if (aqk_retile(rtasks, h.retile_count, rnone, h.retile_max_blocks, workspace, s) != hipSuccess) return AQ_ELAUNCH;
     AqGemmTask none;
     std::memset(&none, 0, sizeof(none));
-    return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.total_wgs, workspace, s) == hipSuccess
+    return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.nsplit, h.total_wgs, workspace, s) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
 }
 

@@ -33,7 +33,9 @@ typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
 constexpr int GM_WAVES = 8;                        // all along m: each wavefront covers the workgroup's 128 n
 constexpr int GM_THREADS = GM_WAVES * 64;
 constexpr int GM_NT = AQ_GROUP_ROWS;               // n per workgroup = one 128-row group of the blob
-constexpr int W_ROW = AQ_CHUNK_K * 2 + 16;         // LDS row stride of the W chunk tile: 528 B
+constexpr int W_ROW = AQ_CHUNK_K * 2 + 32;         // LDS row stride of the W chunk tile: 544 B.  A stride of 64j + 32 bytes
+                                                   // lets the b128 operand reads (16 rows x 4 quarters per instruction)
+                                                   // run at ~175 B/clk/CU; 64j + 16 gives ~125, 64j gives 33-66 (measured)
 
 // words of one block -> 16 registers, each a pair of exact (q - z) in fp16 or bf16
 template <int BITS, bool XBF>
@@ -92,7 +94,7 @@ __device__ __forceinline__ void lds_barrier()
     if (wg >= t.wg_count) return
 
 // BITS_T == 0: the tasks' bit-widths differ, branch per workgroup
-template <int BITS_T, bool XBF, int A>
+template <int BITS_T, bool XBF, int A, int NW>
 __global__ __launch_bounds__(GM_THREADS) void qgemm_kernel(const AqGemmTask* __restrict__ tasks, int count,
                                                            AqGemmTask single, const uint8_t* __restrict__ workspace)
 {
@@ -134,28 +136,33 @@ __global__ __launch_bounds__(256) void retile_kernel(const AqRetileTask* __restr
 }
 
 template <int BITS_T, bool XBF>
-void launch_a(int A, dim3 grid, size_t lds, hipStream_t s, const AqGemmTask* tasks, int count, const AqGemmTask& single,
-              const uint8_t* ws)
+void launch_a(int A, int NW, dim3 grid, size_t lds, hipStream_t s, const AqGemmTask* tasks, int count,
+              const AqGemmTask& single, const uint8_t* ws)
 {
     dim3 block(GM_THREADS);
-#define AQ_LAUNCH(AA)                                                                                          \
+#define AQ_LAUNCH(AA, NN)                                                                                      \
     do {                                                                                                       \
-        auto k = qgemm_kernel<BITS_T, XBF, AA>;                                                                \
+        auto k = qgemm_kernel<BITS_T, XBF, AA, NN>;                                                            \
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                   (int)lds);               /* more than the 64 KiB default */                  \
         hipLaunchKernelGGL(k, grid, block, lds, s, tasks, count, single, ws);                                  \
     } while (0)
-    switch (A) {
-        case 1: AQ_LAUNCH(1); break;
-        case 2: AQ_LAUNCH(2); break;
-        default: AQ_LAUNCH(3); break;
+    switch (A * 16 + NW) {
+        case 1 * 16 + 8: AQ_LAUNCH(1, 8); break;
+        case 1 * 16 + 4: AQ_LAUNCH(1, 4); break;
+        case 1 * 16 + 2: AQ_LAUNCH(1, 2); break;
+        case 1 * 16 + 1: AQ_LAUNCH(1, 1); break;
+        case 2 * 16 + 1: AQ_LAUNCH(2, 1); break;
+        default: AQ_LAUNCH(3, 1); break;
     }
 #undef AQ_LAUNCH
 }
 
 }  // namespace
 
-// most m-tiles (16 rows) per wavefront for M rows of activations: a workgroup covers up to 8*A m-tiles
+// Shape of the wavefront grid for M rows of activations.  mtiles = most m-tiles (16 rows) per wavefront;
+// nsplit = wavefronts side by side along n (the 8 wavefronts form an (8 / nsplit) x nsplit grid): when M has
+// fewer m-tiles than wavefronts the spare ones take a share of the 128 n instead of idling.
 int aqk_gemm_mtiles(int64_t M)
 {
     if (M <= 128) return 1;
@@ -163,11 +170,19 @@ int aqk_gemm_mtiles(int64_t M)
     return 3;
 }
 
-int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int* slabs)
+int aqk_gemm_nsplit(int64_t M)
+{
+    if (M <= 16) return 8;
+    if (M <= 32) return 4;
+    if (M <= 64) return 2;
+    return 1;
+}
+
+int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int nsplit, int* slabs)
 {
     const int sl = (int)aq_num_groups(N);
     if (slabs) *slabs = sl;
-    const int64_t rows = (int64_t)GM_WAVES * 16 * A;
+    const int64_t rows = (int64_t)(GM_WAVES / nsplit) * 16 * A;
     return sl * (int)((M + rows - 1) / rows);
 }
 
@@ -185,7 +200,7 @@ hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTa
 
 // bits == 0: mixed bit-widths; x_dtype is common to all tasks of a launch
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
-                    int total_wgs, const void* workspace, hipStream_t s)
+                    int nsplit, int total_wgs, const void* workspace, hipStream_t s)
 {
     const size_t lds = 2 * ((size_t)GM_NT * W_ROW + GM_NT * 8 * sizeof(float));     // two chunk buffers
     const dim3 grid((unsigned)total_wgs);
@@ -193,8 +208,8 @@ hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& si
     const uint8_t* ws = static_cast<const uint8_t*>(workspace);
 #define AQ_GO(B)                                                                     \
     do {                                                                             \
-        if (bf) launch_a<B, true>(A, grid, lds, s, tasks_dev, count, single, ws);    \
-        else launch_a<B, false>(A, grid, lds, s, tasks_dev, count, single, ws);      \
+        if (bf) launch_a<B, true>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);  \
+        else launch_a<B, false>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);    \
     } while (0)
     if (bits == 2) AQ_GO(2);
     else if (bits == 3) AQ_GO(3);

@@ -62,12 +62,13 @@ struct AqGemmTask {
 static_assert(sizeof(AqGemmTask) == 96, "AqGemmTask must stay 96 bytes");
 
 int aqk_gemm_mtiles(int64_t M);
-int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int* slabs);
+int aqk_gemm_nsplit(int64_t M);
+int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int nsplit, int* slabs);
 size_t aqk_retile_bytes(int64_t M, int64_t K);
 int aqk_retile_blocks(int64_t M, int64_t K);
 // count == 0: run `single`; else `count` tasks from device memory; grid = (max_blocks, tasks)
 hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int max_blocks,
                       void* workspace, hipStream_t s);
-// count == 0: run `single`; bits == 0: the tasks' bit-widths differ; x_dtype and A are per launch
+// count == 0: run `single`; bits == 0: the tasks' bit-widths differ; x_dtype, A and nsplit are per launch
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
-                    int total_wgs, const void* workspace, hipStream_t s);
+                    int nsplit, int total_wgs, const void* workspace, hipStream_t s);
