@@ -91,6 +91,16 @@ def f32_to_f16_bits(a: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
 
 
+def bf16_bits_to_f32(a: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) -> float32 values (exact)."""
+    return (np.asarray(a, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def f16_bits_to_f32(a: np.ndarray) -> np.ndarray:
+    """binary16 bit patterns (uint16) -> float32 values (exact)."""
+    return np.asarray(a, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
 def draw_codes(N: int, K: int, bits: int, *key: int) -> np.ndarray:
     """Canonical code bitstream uint8[N, K/32, 4*bits] of iid uniform codes."""
     assert K % BLOCK == 0 and bits in (2, 3, 4)

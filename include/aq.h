@@ -45,7 +45,7 @@ extern "C" {
 #endif
 
 #define AQ_OK        0
-#define AQ_EINVAL   (-1)  /* bits not in {2,3,4}; block != 32; N, K or M < 1; K % 32 != 0; ld too small; count < 1 */
+#define AQ_EINVAL   (-1)  /* bits not in {2,3,4}; block != 32; N, K or M < 1; K % 32 != 0; ld too small; count < 1; unknown flags */
 #define AQ_ENULL    (-2)  /* a required pointer is NULL */
 #define AQ_EALIGN   (-3)  /* a device pointer is not 16-byte aligned */
 #define AQ_ESIZE    (-4)  /* a caller-provided buffer is too small */
@@ -60,8 +60,8 @@ const char* aq_status_string(int status);
 
 /* Bytes of the packed device blob of an N x K matrix, 0 if the arguments are invalid.
  * The blob stores exactly the canonical information (bits/8 + 1/16 bytes per weight)
- * re-tiled for the kernels, with N rounded up to 128 and K to 256; its layout is
- * private to this build of the library. */
+ * re-tiled for the kernels, with N rounded up to 128 and K to 256, plus 256 bytes of
+ * per-matrix summary (the largest |d|); its layout is private to this build of the library. */
 size_t aq_packed_size(int64_t N, int64_t K, int bits, int block);
 
 /* Eq. 1's stored form -> device blob (re-tiling only, no value changes).
@@ -103,21 +103,32 @@ int aq_qgemv_batch_plan(const aq_gemv_desc* descs /*HOST*/, int count, int block
                         void* plan_host, size_t plan_bytes);
 int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
 
-/* Prefill: Y[m, n] = sum_k X[m, k] * w_hat[n, k] for M rows of activations; code tiles are
- * unpacked to exact small integers (q - 2^(bits-1)) in LDS, multiplied on the matrix cores,
- * and the fp16 block scale d is applied in fp32 to each block's partial sum (Eq. 1 with the
- * factor d taken out of the block's sum), fp32 accumulation.
- *   X   DEVICE uint16 [M][ldx], ldx >= K and ldx % 8 == 0, x_dtype = AQ_BF16 (AQ_F16 also accepted)
+/* Prefill: Y[m, n] = sum_k X[m, k] * w_hat[n, k] for M rows of activations, on the matrix cores.
+ * flags selects how Eq. 1's scale meets the product:
+ *   AQ_GEMM_EXACT  code tiles are unpacked to the exact small integers (q - 2^(bits-1)) in LDS and the fp16
+ *       block scale d multiplies each block's partial sum in fp32 (Eq. 1 with the factor d taken out of
+ *       the block's sum): no weight is ever rounded, only fp32 summation rounds (rel-L2 ~1e-7).  One fp32
+ *       multiply-add per 32 matrix-core multiply-adds: the vector ALU bounds the speed.
+ *   AQ_GEMM_FAST   w_hat = d * (q - 2^(bits-1)) is formed in binary16 while unpacking ("dequantize on the fly",
+ *       Appendix D) and the matrix cores accumulate over all of K.  The product is exact for bits = 2; for
+ *       bits = 3, 4 some codes need up to 14 significant bits and are rounded to binary16's 11
+ *       (relative error <= 2^-12 per weight, rel-L2 of Y ~1e-4).  bf16 activations are first converted to
+ *       binary16 with one power-of-two factor per row (exact unless an element is 2^38 times smaller than
+ *       its row's largest).  A matrix whose largest |d| * 2^(bits-1) would overflow binary16 is computed as
+ *       in AQ_GEMM_EXACT (decided on the device from the blob).
+ *   X   DEVICE uint16 [M][ldx], ldx >= K and ldx % 8 == 0, x_dtype = AQ_BF16 or AQ_F16
  *   Y   DEVICE float  [M][ldy], ldy >= N, overwritten for m < M, n < N
  *   workspace DEVICE, 16-byte aligned, workspace_bytes >= aq_qgemm_workspace_size(M, N, K, bits)
- *       (= 2 bytes per element of X with M rounded up to 16).  The call first copies X into it in
- *       the order the matrix cores read their operands (a permutation, no value changes), then
- *       runs the product from that copy.  Contents need no initialisation and are scratch: calls
- *       that share a workspace must be ordered on one stream. */
+ *       (2 bytes per element of X with M rounded up to 16, plus 4 bytes per row).  The call first copies
+ *       X into it in the order the matrix cores read their operands, then runs the product from that
+ *       copy.  Contents need no initialisation and are scratch: calls that share a workspace must be
+ *       ordered on one stream. */
+#define AQ_GEMM_EXACT 0
+#define AQ_GEMM_FAST  1
 size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits);
 int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block,
              const void* X, int64_t M, int64_t ldx, int x_dtype,
-             float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+             float* Y, int64_t ldy, int flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /* A list of independent prefill products in TWO launches (a whole backbone pass; a lone 4096-row
  * matrix fills only a quarter of the GPU): one that re-orders every distinct activation matrix of
@@ -125,7 +136,7 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block,
  * the products.  Steps: plan on the host (aq_qgemm_batch_plan writes aq_qgemm_batch_plan_size(count)
  * bytes), copy the plan image to 16-byte-aligned DEVICE memory, provide a DEVICE workspace of
  * aq_qgemm_batch_workspace_size(plan_host) bytes, launch; the launch may be repeated.  All
- * descriptors of a plan share x_dtype. */
+ * descriptors of a plan share x_dtype and the plan's flags (AQ_GEMM_EXACT or AQ_GEMM_FAST). */
 typedef struct aq_gemm_desc {
     const void* packed;   /* DEVICE blob */
     const void* X;        /* DEVICE uint16 [M][ldx] */
@@ -136,7 +147,7 @@ typedef struct aq_gemm_desc {
 } aq_gemm_desc;
 
 size_t aq_qgemm_batch_plan_size(int count);
-int aq_qgemm_batch_plan(const aq_gemm_desc* descs /*HOST*/, int count, int block,
+int aq_qgemm_batch_plan(const aq_gemm_desc* descs /*HOST*/, int count, int block, int flags,
                         void* plan_host, size_t plan_bytes);
 size_t aq_qgemm_batch_workspace_size(const void* plan_host);   /* 0 if the plan image is invalid */
 int aq_qgemm_batch(const void* plan_host, const void* plan_dev,

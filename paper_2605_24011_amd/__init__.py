@@ -14,6 +14,7 @@ from typing import Sequence
 AQ_OK = 0
 AQ_EINVAL, AQ_ENULL, AQ_EALIGN, AQ_ESIZE, AQ_EDTYPE, AQ_ELAUNCH = -1, -2, -3, -4, -5, -6
 AQ_F16, AQ_BF16 = 1, 2
+AQ_GEMM_EXACT, AQ_GEMM_FAST = 0, 1
 BLOCK = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -59,10 +60,10 @@ def lib() -> ctypes.CDLL:
         L.aq_qgemv_batch.argtypes = [_p, _p, _p]
         L.aq_qgemm_workspace_size.restype = _sz
         L.aq_qgemm_workspace_size.argtypes = [_i64, _i64, _i64, _int]
-        L.aq_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
+        L.aq_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _int, _p, _sz, _p]
         L.aq_qgemm_batch_plan_size.restype = _sz
         L.aq_qgemm_batch_plan_size.argtypes = [_int]
-        L.aq_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _p, _sz]
+        L.aq_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _int, _p, _sz]
         L.aq_qgemm_batch_workspace_size.restype = _sz
         L.aq_qgemm_batch_workspace_size.argtypes = [_p]
         L.aq_qgemm_batch.argtypes = [_p, _p, _p, _sz, _p]
@@ -148,8 +149,10 @@ def aq_qgemm_workspace_size(M: int, N: int, K: int, bits: int) -> int:
     return int(lib().aq_qgemm_workspace_size(M, N, K, bits))
 
 
-def aq_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None):
-    """X: cuda bfloat16/float16 [M, K] (row stride = X.stride(0)) -> Y: cuda float32 [M, N]."""
+def aq_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None,
+             fast: bool = False):
+    """X: cuda bfloat16/float16 [M, K] (row stride = X.stride(0)) -> Y: cuda float32 [M, N].
+    fast selects AQ_GEMM_FAST (weights formed in binary16) instead of AQ_GEMM_EXACT."""
     import torch
     M = X.shape[0]
     if Y is None:
@@ -160,14 +163,15 @@ def aq_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().aq_qgemm(packed.data_ptr(), N, K, bits, block, X.data_ptr(), M, X.stride(0), _dtype_code(X),
-                          Y.data_ptr(), Y.stride(0), ws_ptr, ws_bytes, _stream(stream)), "aq_qgemm")
+                          Y.data_ptr(), Y.stride(0), AQ_GEMM_FAST if fast else AQ_GEMM_EXACT, ws_ptr, ws_bytes,
+                          _stream(stream)), "aq_qgemm")
     return Y
 
 
 class GemmBatch:
     """A planned list of prefill products (one launch).  Holds references to every tensor."""
 
-    def __init__(self, items: Sequence[tuple], block: int = BLOCK):
+    def __init__(self, items: Sequence[tuple], block: int = BLOCK, fast: bool = False):
         """items: (packed, N, K, bits, X, Y) per matrix; X [M, K] half/bfloat16, Y [M, N] float32."""
         import torch
         n = len(items)
@@ -178,7 +182,8 @@ class GemmBatch:
             d.bits, d.x_dtype = bits, _dtype_code(X)
         size = int(lib().aq_qgemm_batch_plan_size(n))
         self.plan_host = torch.empty(size, dtype=torch.uint8)
-        _check(lib().aq_qgemm_batch_plan(descs, n, block, self.plan_host.data_ptr(), size), "aq_qgemm_batch_plan")
+        _check(lib().aq_qgemm_batch_plan(descs, n, block, AQ_GEMM_FAST if fast else AQ_GEMM_EXACT,
+                                         self.plan_host.data_ptr(), size), "aq_qgemm_batch_plan")
         self.plan_dev = self.plan_host.to(items[0][0].device)
         self.workspace_bytes = int(lib().aq_qgemm_batch_workspace_size(self.plan_host.data_ptr()))
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=items[0][0].device)

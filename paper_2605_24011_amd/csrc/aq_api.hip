@@ -51,10 +51,11 @@ struct GemmPlanHeader {
     int32_t retile_max_blocks;
     int64_t workspace_bytes;
     int32_t nsplit;          // wavefronts along n, from the largest M
-    int32_t reserved[5];
+    int32_t fast;            // fp16-weight mode
+    int32_t reserved[4];
 };
 static_assert(sizeof(GemmPlanHeader) == 64, "GemmPlanHeader must stay 64 bytes");
-constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514733u;  // "AQG3"
+constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514734u;  // "AQG4"
 
 int check_gemm(int64_t N, int64_t K, int bits, int block, int64_t M, int64_t ldx, int64_t ldy, int x_dtype,
                const void* packed, const void* X, const void* Y)
@@ -86,16 +87,19 @@ AqGemmTask make_gemm_task(const void* packed, int64_t N, int64_t K, int bits, in
     return t;
 }
 
-AqRetileTask make_retile_task(const void* X, int64_t M, int64_t K, int64_t ldx, int64_t xt_offset)
+AqRetileTask make_retile_task(const void* X, int64_t M, int64_t K, int64_t ldx, int64_t xt_offset, int convert)
 {
     AqRetileTask r;
     std::memset(&r, 0, sizeof(r));
     r.X = static_cast<const uint16_t*>(X);
     r.M = M; r.ldx = ldx; r.xt_offset = xt_offset;
     r.K = (int32_t)K;
-    r.blocks = aqk_retile_blocks(M, K);
+    r.convert = convert;
+    r.blocks = aqk_retile_blocks(M, K, convert);
     return r;
 }
+
+int check_flags(int flags) { return (flags == AQ_GEMM_EXACT || flags == AQ_GEMM_FAST) ? AQ_OK : AQ_EINVAL; }
 
 AqGemvTask make_task(const void* packed, int64_t N, int64_t K, int bits, const void* x, int dt, float* y)
 {
@@ -235,21 +239,23 @@ size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits)
 }
 
 int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M,
-             int64_t ldx, int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes,
+             int64_t ldx, int x_dtype, float* Y, int64_t ldy, int flags, void* workspace, size_t workspace_bytes,
              void* stream)
 {
     int rc = check_gemm(N, K, bits, block, M, ldx, ldy, x_dtype, packed, X, Y);
     if (rc != AQ_OK) return rc;
+    if ((rc = check_flags(flags)) != AQ_OK) return rc;
     if (!workspace) return AQ_ENULL;
     if (!aligned16(workspace)) return AQ_EALIGN;
     if (workspace_bytes < aqk_retile_bytes(M, K)) return AQ_ESIZE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const AqRetileTask r = make_retile_task(X, M, K, ldx, 0);
-    if (aqk_retile(nullptr, 0, r, r.blocks, workspace, s) != hipSuccess) return AQ_ELAUNCH;
+    const int fast = flags == AQ_GEMM_FAST, convert = fast && x_dtype == AQ_BF16;
+    const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
+    if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
     const int A = aqk_gemm_mtiles(M), nsplit = aqk_gemm_nsplit(M);
     AqGemmTask t = make_gemm_task(packed, N, K, bits, M, 0, Y, ldy, A, nsplit, 0);
-    return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, nsplit, t.wg_count, workspace, s) == hipSuccess ? AQ_OK
-                                                                                                    : AQ_ELAUNCH;
+    return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, nsplit, fast, t.wg_count, workspace, s) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
 }
 
 // plan image: header, `count` product tasks, then up to `count` re-tiling tasks
@@ -259,9 +265,10 @@ size_t aq_qgemm_batch_plan_size(int count)
     return sizeof(GemmPlanHeader) + (size_t)count * (sizeof(AqGemmTask) + sizeof(AqRetileTask));
 }
 
-int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, void* plan_host, size_t plan_bytes)
+int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int flags, void* plan_host,
+                        size_t plan_bytes)
 {
-    if (count < 1) return AQ_EINVAL;
+    if (count < 1 || check_flags(flags) != AQ_OK) return AQ_EINVAL;
     if (!descs || !plan_host) return AQ_ENULL;
     if (plan_bytes < aq_qgemm_batch_plan_size(count)) return AQ_ESIZE;
     int64_t max_M = 0;
@@ -280,6 +287,8 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, void* p
     h.x_dtype = descs[0].x_dtype;
     h.mtiles = aqk_gemm_mtiles(max_M);
     h.nsplit = aqk_gemm_nsplit(max_M);
+    h.fast = flags == AQ_GEMM_FAST;
+    const int convert = h.fast && h.x_dtype == AQ_BF16;
     uint8_t* base = static_cast<uint8_t*>(plan_host);
     uint8_t* tasks = base + sizeof(GemmPlanHeader);
     uint8_t* rtasks = tasks + (size_t)count * sizeof(AqGemmTask);
@@ -294,7 +303,7 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, void* p
             if (r.X == d.X && r.M == d.M && r.K == d.K && r.ldx == d.ldx) { off = r.xt_offset; break; }
         if (off < 0) {
             off = ws;
-            rt.push_back(make_retile_task(d.X, d.M, d.K, d.ldx, off));
+            rt.push_back(make_retile_task(d.X, d.M, d.K, d.ldx, off, convert));
             ws += (int64_t)aqk_retile_bytes(d.M, d.K);
             if (rt.back().blocks > h.retile_max_blocks) h.retile_max_blocks = rt.back().blocks;
         }
@@ -318,7 +327,8 @@ static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
     return h.magic == GEMM_PLAN_MAGIC && h.count >= 1 && h.total_wgs >= 1 && (h.bits == 0 || (h.bits >= 2 && h.bits <= 4)) &&
            check_dtype(h.x_dtype) == AQ_OK && h.retile_count >= 1 && h.retile_count <= h.count &&
            h.retile_max_blocks >= 1 && h.workspace_bytes >= 1024 &&
-           (h.nsplit == 1 || ((h.nsplit == 2 || h.nsplit == 4 || h.nsplit == 8) && h.mtiles == 1));
+           (h.nsplit == 1 || ((h.nsplit == 2 || h.nsplit == 4 || h.nsplit == 8) && h.mtiles == 1)) &&
+           (h.fast == 0 || h.fast == 1);
 }
 
 size_t aq_qgemm_batch_workspace_size(const void* plan_host)
@@ -342,10 +352,12 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
     hipStream_t s = static_cast<hipStream_t>(stream);
     AqRetileTask rnone;
     std::memset(&rnone, 0, sizeof(rnone));
-    if (aqk_retile(rtasks, h.retile_count, rnone, h.retile_max_blocks, workspace, s) != hipSuccess) return AQ_ELAUNCH;
+    const int convert = h.fast && h.x_dtype == AQ_BF16;
+    if (aqk_retile(rtasks, h.retile_count, rnone, h.retile_max_blocks, convert, workspace, s) != hipSuccess)
+        return AQ_ELAUNCH;
     AqGemmTask none;
     std::memset(&none, 0, sizeof(none));
-    return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.nsplit, h.total_wgs, workspace, s) == hipSuccess
+    return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.nsplit, h.fast, h.total_wgs, workspace, s) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
 }
 

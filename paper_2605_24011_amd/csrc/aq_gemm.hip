@@ -93,22 +93,53 @@ __device__ __forceinline__ void lds_barrier()
     }                                                                             \
     if (wg >= t.wg_count) return
 
-// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup
-template <int BITS_T, bool XBF, int A, int NW>
+// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup.
+// FAST: fp16-weight mode.  Xt holds binary16 activations (XBF is false) with a power-of-two factor per row;
+// the workgroup forms w = d * (q - z) in binary16 while unpacking ("FOLD") and the MFMAs accumulate across
+// blocks with no per-block fp32 scaling.  d * (q - z) needs at most 14 significant bits: exact for 2 bits
+// (q - z is 0 or a power of two), rounded to 11 bits (relative error <= 2^-12) for some codes of 3 and 4
+// bits.  If the matrix holds a scale so large that the product could overflow binary16 (trailer word of
+// the blob), the workgroup takes the exact per-block path instead, on the same binary16 activations.
+template <int BITS_T, bool XBF, int A, int NW, bool FAST>
 __global__ __launch_bounds__(GM_THREADS) void qgemm_kernel(const AqGemmTask* __restrict__ tasks, int count,
                                                            AqGemmTask single, const uint8_t* __restrict__ workspace)
 {
     extern __shared__ __align__(16) uint8_t smem[];
+    static_assert(!(FAST && XBF), "the fp16-weight mode multiplies binary16 operands");
     AQ_FIND_GEMM_TASK(t, wg);
+    bool fold = false;
+    if (FAST) {
+        const uint32_t max_d = *reinterpret_cast<const uint32_t*>(
+            t.blob + (int64_t)t.slabs * t.nchunks * AQ_GROUP_TILES * aq_unit_bytes(t.bits));
+        fold = max_d <= 0x7BFFu - (uint32_t)(t.bits - 1) * 0x400u;      // max|d| * 2^(bits-1) <= 65504
+    }
     if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) {
         constexpr int BITS = 2;
+        if (FAST && fold) {
+            constexpr bool FOLD = true;
 #include "aq_gemm_body.inc"
+        } else {
+            constexpr bool FOLD = false;
+#include "aq_gemm_body.inc"
+        }
     } else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) {
         constexpr int BITS = 3;
+        if (FAST && fold) {
+            constexpr bool FOLD = true;
 #include "aq_gemm_body.inc"
+        } else {
+            constexpr bool FOLD = false;
+#include "aq_gemm_body.inc"
+        }
     } else {
         constexpr int BITS = 4;
+        if (FAST && fold) {
+            constexpr bool FOLD = true;
 #include "aq_gemm_body.inc"
+        } else {
+            constexpr bool FOLD = false;
+#include "aq_gemm_body.inc"
+        }
     }
 }
 
@@ -133,16 +164,79 @@ __global__ __launch_bounds__(256) void retile_kernel(const AqRetileTask* __restr
     const int64_t ksteps = t.K >> 5;
     u32x4* dst = reinterpret_cast<u32x4*>(workspace + t.xt_offset);
     dst[(mtile * ksteps + step) * 64 + g * 16 + c] = v;
+    if (j == 0) reinterpret_cast<int32_t*>(workspace + t.xt_offset + mpad * t.K * 2)[row] = 0;       // rowexp
 }
 
-template <int BITS_T, bool XBF>
+// bf16 X[M][ldx] -> binary16 Xt with one power-of-two factor per row.  One workgroup per padded row:
+// pass 1 finds the row's largest magnitude, pass 2 scales, converts (round to nearest even) and scatters
+// the 16-byte pieces into operand order; rowexp[row] = the exponent the product kernel adds back.
+__global__ __launch_bounds__(256) void retile_convert_kernel(const AqRetileTask* __restrict__ tasks, int count,
+                                                             AqRetileTask single, uint8_t* __restrict__ workspace)
+{
+    __shared__ uint32_t wave_max[4];
+    AqRetileTask t;
+    if (count == 0) t = single; else t = tasks[blockIdx.y];
+    const int64_t row = blockIdx.x;
+    const int64_t mpad = (t.M + 15) & ~(int64_t)15;
+    if (row >= mpad) return;                                   // uniform per workgroup
+    const int pieces = t.K >> 3, tid = threadIdx.x;
+    const int64_t ksteps = t.K >> 5;
+    u32x4* dst = reinterpret_cast<u32x4*>(workspace + t.xt_offset);
+    int32_t* rowexp = reinterpret_cast<int32_t*>(workspace + t.xt_offset + mpad * t.K * 2);
+    const int64_t base = ((row >> 4) * ksteps) * 64 + (row & 15);
+    if (row >= t.M) {
+        for (int j = tid; j < pieces; j += 256) dst[base + (int64_t)(j >> 2) * 64 + (j & 3) * 16] = u32x4{0u, 0u, 0u, 0u};
+        if (tid == 0) rowexp[row] = 0;
+        return;
+    }
+    const AQ_GLOBAL u32x4* src = as_global<u32x4>(t.X + row * t.ldx);
+    uint32_t mx = 0;                                           // bf16 magnitudes order like unsigned integers
+    for (int j = tid; j < pieces; j += 256) {
+        const u32x4 v = src[j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo = v[i] & 0x7FFFu, hi = (v[i] >> 16) & 0x7FFFu;
+            mx = lo > mx ? lo : mx;
+            mx = hi > mx ? hi : mx;
+        }
+    }
+    for (int o = 32; o >= 1; o >>= 1) {
+        const uint32_t other = (uint32_t)__shfl_xor((int)mx, o);
+        mx = other > mx ? other : mx;
+    }
+    if ((tid & 63) == 0) wave_max[tid >> 6] = mx;
+    __syncthreads();
+    mx = wave_max[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) mx = wave_max[i] > mx ? wave_max[i] : mx;
+    int shift = 0;                                             // x * 2^shift has its largest magnitude in [2^14, 2^15)
+    if (mx != 0) {
+        const int field = (int)(mx >> 7);                      // biased exponent; 0 = bf16 subnormal, 255 = inf / NaN
+        shift = 14 - ((field ? field : 1) - 127);
+    }
+    for (int j = tid; j < pieces; j += 256) {
+        const u32x4 v = src[j];
+        u32x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float lo = ldexpf(__uint_as_float(v[i] << 16), shift);
+            const float hi = ldexpf(__uint_as_float(v[i] & 0xFFFF0000u), shift);
+            const half2v h = {(_Float16)lo, (_Float16)hi};
+            o[i] = __builtin_bit_cast(uint32_t, h);
+        }
+        dst[base + (int64_t)(j >> 2) * 64 + (j & 3) * 16] = o;
+    }
+    if (tid == 0) rowexp[row] = -shift;
+}
+
+template <int BITS_T, bool XBF, bool FAST>
 void launch_a(int A, int NW, dim3 grid, size_t lds, hipStream_t s, const AqGemmTask* tasks, int count,
               const AqGemmTask& single, const uint8_t* ws)
 {
     dim3 block(GM_THREADS);
 #define AQ_LAUNCH(AA, NN)                                                                                      \
     do {                                                                                                       \
-        auto k = qgemm_kernel<BITS_T, XBF, AA, NN>;                                                            \
+        auto k = qgemm_kernel<BITS_T, XBF, AA, NN, FAST>;                                                      \
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                   (int)lds);               /* more than the 64 KiB default */                  \
         hipLaunchKernelGGL(k, grid, block, lds, s, tasks, count, single, ws);                                  \
@@ -186,30 +280,44 @@ int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int nsplit, int* slabs)
     return sl * (int)((M + rows - 1) / rows);
 }
 
-size_t aqk_retile_bytes(int64_t M, int64_t K) { return (size_t)(((M + 15) / 16) * 16 * K * 2); }
+// Xt (2 bytes per element, rows padded to 16) followed by rowexp (one int32 per padded row), rounded up to 1 KiB
+size_t aqk_retile_bytes(int64_t M, int64_t K)
+{
+    const int64_t mpad = ((M + 15) / 16) * 16;
+    return (size_t)(mpad * K * 2 + ((mpad * 4 + 1023) / 1024) * 1024);
+}
 
-int aqk_retile_blocks(int64_t M, int64_t K) { return (int)((((M + 15) / 16) * 16 * (K / 8) + 255) / 256); }
+int aqk_retile_blocks(int64_t M, int64_t K, int convert)
+{
+    const int64_t mpad = ((M + 15) / 16) * 16;
+    return convert ? (int)mpad : (int)((mpad * (K / 8) + 255) / 256);
+}
 
 hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int max_blocks,
-                      void* workspace, hipStream_t s)
+                      int convert, void* workspace, hipStream_t s)
 {
     const dim3 grid((unsigned)max_blocks, (unsigned)(count == 0 ? 1 : count));
-    hipLaunchKernelGGL(retile_kernel, grid, dim3(256), 0, s, tasks_dev, count, single, static_cast<uint8_t*>(workspace));
+    if (convert)
+        hipLaunchKernelGGL(retile_convert_kernel, grid, dim3(256), 0, s, tasks_dev, count, single,
+                           static_cast<uint8_t*>(workspace));
+    else
+        hipLaunchKernelGGL(retile_kernel, grid, dim3(256), 0, s, tasks_dev, count, single, static_cast<uint8_t*>(workspace));
     return hipGetLastError();
 }
 
-// bits == 0: mixed bit-widths; x_dtype is common to all tasks of a launch
+// bits == 0: mixed bit-widths; x_dtype, the wavefront grid and the mode are common to all tasks of a launch
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
-                    int nsplit, int total_wgs, const void* workspace, hipStream_t s)
+                    int nsplit, int fast, int total_wgs, const void* workspace, hipStream_t s)
 {
     const size_t lds = 2 * ((size_t)GM_NT * W_ROW + GM_NT * 8 * sizeof(float));     // two chunk buffers
     const dim3 grid((unsigned)total_wgs);
-    const bool bf = (x_dtype == 2);
+    const bool bf = (x_dtype == 2) && !fast;         // the fp16-weight mode reads binary16 activations from Xt
     const uint8_t* ws = static_cast<const uint8_t*>(workspace);
-#define AQ_GO(B)                                                                     \
-    do {                                                                             \
-        if (bf) launch_a<B, true>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);  \
-        else launch_a<B, false>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);    \
+#define AQ_GO(B)                                                                                     \
+    do {                                                                                             \
+        if (fast) launch_a<B, false, true>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);   \
+        else if (bf) launch_a<B, true, false>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws); \
+        else launch_a<B, false, false>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);       \
     } while (0)
     if (bits == 2) AQ_GO(2);
     else if (bits == 3) AQ_GO(3);

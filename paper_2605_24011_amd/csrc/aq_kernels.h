@@ -35,15 +35,21 @@ hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& si
 // Prefill.  The activations are first re-tiled into the order the matrix cores read them ("Xt"):
 //   Xt[m / 16][k / 32][lane = 16*g + c] = the 16 bytes X[16*(m/16) + c][32*(k/32) + 8g .. 8g+7],
 // rows beyond M zero, so that a wavefront's A operand of one (m-tile, 32-k step) is 1 KiB contiguous.
-// Xt lives in the caller's workspace at `xt_offset`; several products may share one Xt.
+// Xt lives in the caller's workspace at `xt_offset`, followed by one int32 per padded row ("rowexp");
+// several products may share one Xt.  convert == 0: the elements are copied, rowexp = 0.
+// convert == 1 (bf16 input of the fp16-weight mode): row m is multiplied by 2^-rowexp[m], the power of
+// two that puts its largest magnitude in [2^14, 2^15), and written as binary16 (exact unless an element
+// is more than 2^38 times smaller than the row's largest); the product kernel scales row m of Y back.
 struct AqRetileTask {
     const uint16_t* X;
     int64_t M, ldx;
     int64_t xt_offset;  // bytes from the workspace base, multiple of 1024
     int32_t K;
-    int32_t blocks;     // workgroups of 256 threads, one 16-byte piece per thread
+    int32_t blocks;     // workgroups of 256 threads: one 16-byte piece per thread, or one row per workgroup
+    int32_t convert;
+    int32_t pad;
 };
-static_assert(sizeof(AqRetileTask) == 40, "AqRetileTask must stay 40 bytes");
+static_assert(sizeof(AqRetileTask) == 48, "AqRetileTask must stay 48 bytes");
 
 // One prefill product Y = X W^T as the kernel sees it (device-visible, 96 bytes).
 struct AqGemmTask {
@@ -65,10 +71,12 @@ int aqk_gemm_mtiles(int64_t M);
 int aqk_gemm_nsplit(int64_t M);
 int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int nsplit, int* slabs);
 size_t aqk_retile_bytes(int64_t M, int64_t K);
-int aqk_retile_blocks(int64_t M, int64_t K);
-// count == 0: run `single`; else `count` tasks from device memory; grid = (max_blocks, tasks)
+int aqk_retile_blocks(int64_t M, int64_t K, int convert);
+// count == 0: run `single`; else `count` tasks from device memory; grid = (max_blocks, tasks); every task
+// of a launch has the same `convert`
 hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int max_blocks,
-                      void* workspace, hipStream_t s);
-// count == 0: run `single`; bits == 0: the tasks' bit-widths differ; x_dtype, A and nsplit are per launch
+                      int convert, void* workspace, hipStream_t s);
+// count == 0: run `single`; bits == 0: the tasks' bit-widths differ; x_dtype, A, nsplit and fast are per
+// launch.  fast != 0: weights are formed as binary16 d * (q - z) and the activations in Xt are binary16.
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
-                    int nsplit, int total_wgs, const void* workspace, hipStream_t s);
+                    int nsplit, int fast, int total_wgs, const void* workspace, hipStream_t s);

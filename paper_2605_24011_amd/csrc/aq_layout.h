@@ -10,7 +10,10 @@
 //   group  = 8 consecutive tiles = 128 rows
 //
 // Blob = units in the order [group][chunk][tile in group]; rows are padded to a multiple
-// of 128 and blocks to a multiple of 8 with zero codes and zero scales.
+// of 128 and blocks to a multiple of 8 with zero codes and zero scales.  A 256-byte trailer
+// follows the units; its first 32-bit word is the largest |d| of the matrix as a binary16
+// bit pattern (0x7C00 and above: an infinity or NaN is present).  The prefill kernel reads
+// it to decide whether d * (q - z) can be formed in binary16 without overflow.
 //
 // Inside a unit, lane l = 16*g + i (g = l / 16, i = l % 16) of a wavefront owns row i of
 // the tile and the two blocks 2g, 2g+1 of the chunk.  A block is `bits` 32-bit words; each
@@ -52,10 +55,12 @@ AQ_HD int64_t aq_unit_index(int64_t group, int64_t chunk, int tile_in_group, int
 {
     return (group * nchunks + chunk) * AQ_GROUP_TILES + tile_in_group;
 }
-AQ_HD int64_t aq_blob_bytes(int64_t N, int64_t K, int bits)
+#define AQ_TRAILER_BYTES 256
+AQ_HD int64_t aq_trailer_offset(int64_t N, int64_t K, int bits)
 {
     return aq_num_groups(N) * aq_num_chunks(K) * AQ_GROUP_TILES * aq_unit_bytes(bits);
 }
+AQ_HD int64_t aq_blob_bytes(int64_t N, int64_t K, int bits) { return aq_trailer_offset(N, K, bits) + AQ_TRAILER_BYTES; }
 
 // byte offset inside a unit of word `wi` (0 .. 2*bits-1) of lane `l`
 AQ_HD int aq_word_offset(int bits, int l, int wi)

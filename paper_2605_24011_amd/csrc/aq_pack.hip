@@ -21,11 +21,12 @@ __device__ inline uint32_t canon_code(const uint8_t* blk, int bits, int e)
 __global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ codes,
                                                    const uint16_t* __restrict__ scales,
                                                    int64_t N, int64_t K, int bits,
-                                                   uint8_t* __restrict__ blob, int64_t n_units)
+                                                   uint8_t* __restrict__ blob, int64_t n_units,
+                                                   uint32_t* __restrict__ trailer)
 {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t unit = gid >> 6;
-    if (unit >= n_units) return;
+    if (unit >= n_units) return;                   // whole wavefronts leave together: 64 threads per unit
     int l = (int)(gid & 63), g = l >> 4, i = l & 15;
     int64_t nb = K / AQ_BLOCK, nchunks = aq_num_chunks(K);
     int til = (int)(unit % AQ_GROUP_TILES);
@@ -47,14 +48,28 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ c
             *reinterpret_cast<uint32_t*>(u + aq_word_offset(bits, l, blk * bits + h)) = w[h];
     }
     // scales: lane (g, c) with c < 8 stores rows 4g..4g+3 of block c
+    uint32_t mag = 0;                               // largest |d| bit pattern this thread stored
     if (i < 8) {
         int64_t j = chunk * AQ_CHUNK_BLOCKS + i;
         for (int r = 0; r < 4; ++r) {
             int64_t rr = row0 + 4 * g + r;
             uint16_t s = (rr < N && j < nb) ? scales[rr * nb + j] : (uint16_t)0;
             *reinterpret_cast<uint16_t*>(u + aq_scale_offset(bits, g, i, r)) = s;
+            uint32_t m = s & 0x7FFFu;
+            mag = m > mag ? m : mag;
         }
     }
+    // trailer word 0 = max over the matrix (binary16 magnitudes order like unsigned integers)
+    for (int o = 32; o >= 1; o >>= 1) {
+        uint32_t other = (uint32_t)__shfl_xor((int)mag, o);
+        mag = other > mag ? other : mag;
+    }
+    if (l == 0 && mag != 0) atomicMax(trailer, mag);
+}
+
+__global__ void clear_trailer_kernel(uint32_t* trailer)
+{
+    if (threadIdx.x < AQ_TRAILER_BYTES / 4) trailer[threadIdx.x] = 0u;
 }
 
 // one thread per (row, block): writes 32 codes or 32 dequantised weights
@@ -98,8 +113,10 @@ hipError_t aqk_pack(const uint8_t* codes, const uint16_t* scales, int64_t N, int
     int64_t n_units = aq_num_groups(N) * aq_num_chunks(K) * AQ_GROUP_TILES;
     int64_t threads = n_units * 64;
     unsigned grid = (unsigned)((threads + 255) / 256);
+    uint32_t* trailer = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(blob) + aq_trailer_offset(N, K, bits));
+    hipLaunchKernelGGL(clear_trailer_kernel, dim3(1), dim3(64), 0, s, trailer);
     hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), 0, s, codes, scales, N, K, bits,
-                       static_cast<uint8_t*>(blob), n_units);
+                       static_cast<uint8_t*>(blob), n_units, trailer);
     return hipGetLastError();
 }
 

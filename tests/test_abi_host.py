@@ -28,12 +28,13 @@ def test_every_declared_symbol_is_exported(L):
 
 
 def test_packed_size_is_canonical_bytes_on_aligned_shapes(L):
-    # bits/8 + 1/16 bytes per weight when N % 128 == 0 and K % 256 == 0
+    # bits/8 + 1/16 bytes per weight when N % 128 == 0 and K % 256 == 0, plus a 256-byte trailer
+    T = 256
     for b, want in ((2, 5_242_880), (3, 7_340_032), (4, 9_437_184)):
-        assert aq.aq_packed_size(4096, 4096, b) == want
-    assert aq.aq_packed_size(11008, 4096, 4) == 25_362_432
-    assert aq.aq_packed_size(4096, 11008, 2) == 14_090_240
-    assert aq.aq_packed_size(16384, 2048, 3) == 14_680_064
+        assert aq.aq_packed_size(4096, 4096, b) == want + T
+    assert aq.aq_packed_size(11008, 4096, 4) == 25_362_432 + T
+    assert aq.aq_packed_size(4096, 11008, 2) == 14_090_240 + T
+    assert aq.aq_packed_size(16384, 2048, 3) == 14_680_064 + T
     # padded shapes are never smaller than the canonical form
     assert aq.aq_packed_size(17, 96, 3) >= 17 * 96 * 3 // 8 + 17 * 3 * 2
     # invalid arguments give 0
@@ -52,10 +53,10 @@ def test_argument_validation_without_a_gpu(L):
     assert L.aq_qgemv(A, 16, 64, 4, 32, None, aq.AQ_F16, A, None) == aq.AQ_ENULL
     assert L.aq_qgemv(A, 16, 64, 4, 32, A, aq.AQ_F16, A + 8, None) == aq.AQ_EALIGN
     assert L.aq_qgemv(A, 0, 64, 4, 32, A, aq.AQ_F16, A, None) == aq.AQ_EINVAL
-    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 0, 64, aq.AQ_BF16, A, 16, None, 0, None) == aq.AQ_EINVAL
-    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 32, aq.AQ_BF16, A, 16, None, 0, None) == aq.AQ_EINVAL   # ldx < K
-    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, aq.AQ_BF16, A, 8, None, 0, None) == aq.AQ_EINVAL    # ldy < N
-    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, 9, A, 16, None, 0, None) == aq.AQ_EDTYPE
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 0, 64, aq.AQ_BF16, A, 16, 0, None, 0, None) == aq.AQ_EINVAL
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 32, aq.AQ_BF16, A, 16, 0, None, 0, None) == aq.AQ_EINVAL   # ldx < K
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, aq.AQ_BF16, A, 8, 0, None, 0, None) == aq.AQ_EINVAL    # ldy < N
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, 9, A, 16, 0, None, 0, None) == aq.AQ_EDTYPE
     assert L.aq_unpack_codes(None, 16, 64, 4, 32, A, None) == aq.AQ_ENULL
     assert L.aq_dequant_f32(A, 16, 64, 3, 32, A + 2, None) == aq.AQ_EALIGN
     for s in (0, -1, -2, -3, -4, -5, -6, -99):
@@ -99,34 +100,34 @@ def test_gemm_batch_plan_validation_and_workspace(L):
     size = L.aq_qgemm_batch_plan_size(n)
     assert size >= n * 96
     buf = ctypes.create_string_buffer(size)
-    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_OK
+    assert L.aq_qgemm_batch_plan(descs, n, 32, 0, buf, size) == aq.AQ_OK
     # one re-ordered copy per distinct X: rows rounded up to 16, 2 bytes per element
-    assert L.aq_qgemm_batch_workspace_size(buf) == 304 * 4096 * 2 + 304 * 2048 * 2
-    assert L.aq_qgemm_workspace_size(300, 4096, 4096, 2) == 304 * 4096 * 2
-    assert L.aq_qgemm_workspace_size(1, 16, 32, 4) == 16 * 32 * 2
+    assert L.aq_qgemm_batch_workspace_size(buf) == (304 * 4096 * 2 + 2048) + (304 * 2048 * 2 + 2048)
+    assert L.aq_qgemm_workspace_size(300, 4096, 4096, 2) == 304 * 4096 * 2 + 2048
+    assert L.aq_qgemm_workspace_size(1, 16, 32, 4) == 16 * 32 * 2 + 1024
     # same pointer but another row stride is another copy
     descs[1].ldx = 4096 + 8
-    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_OK
-    assert L.aq_qgemm_batch_workspace_size(buf) == 2 * 304 * 4096 * 2 + 304 * 2048 * 2
+    assert L.aq_qgemm_batch_plan(descs, n, 32, 0, buf, size) == aq.AQ_OK
+    assert L.aq_qgemm_batch_workspace_size(buf) == 2 * (304 * 4096 * 2 + 2048) + (304 * 2048 * 2 + 2048)
     descs[1].ldx = 4096
-    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size - 1) == aq.AQ_ESIZE
-    assert L.aq_qgemm_batch_plan(descs, 0, 32, buf, size) == aq.AQ_EINVAL
-    assert L.aq_qgemm_batch_plan(descs, n, 64, buf, size) == aq.AQ_EINVAL
+    assert L.aq_qgemm_batch_plan(descs, n, 32, 0, buf, size - 1) == aq.AQ_ESIZE
+    assert L.aq_qgemm_batch_plan(descs, 0, 32, 0, buf, size) == aq.AQ_EINVAL
+    assert L.aq_qgemm_batch_plan(descs, n, 64, 0, buf, size) == aq.AQ_EINVAL
     descs[2].x_dtype = aq.AQ_F16
-    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_EDTYPE     # one dtype per plan
+    assert L.aq_qgemm_batch_plan(descs, n, 32, 0, buf, size) == aq.AQ_EDTYPE     # one dtype per plan
     descs[2].x_dtype = aq.AQ_BF16
     descs[2].ldx = 2048 + 4
-    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_EINVAL     # rows of X lose 16-byte alignment
+    assert L.aq_qgemm_batch_plan(descs, n, 32, 0, buf, size) == aq.AQ_EINVAL     # rows of X lose 16-byte alignment
     descs[2].ldx = 2048
     descs[3].Y = None
-    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_ENULL
+    assert L.aq_qgemm_batch_plan(descs, n, 32, 0, buf, size) == aq.AQ_ENULL
     descs[3].Y = A
     descs[3].X = A + 2
-    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_EALIGN
+    assert L.aq_qgemm_batch_plan(descs, n, 32, 0, buf, size) == aq.AQ_EALIGN
     descs[3].X = A
-    assert L.aq_qgemm_batch_plan(descs, n, 32, buf, size) == aq.AQ_OK
+    assert L.aq_qgemm_batch_plan(descs, n, 32, 0, buf, size) == aq.AQ_OK
     ws = L.aq_qgemm_batch_workspace_size(buf)
-    assert ws == 304 * 4096 * 2 + 304 * 2048 * 2
+    assert ws == (304 * 4096 * 2 + 2048) + (304 * 2048 * 2 + 2048)
     bad = ctypes.create_string_buffer(size)
     assert L.aq_qgemm_batch_workspace_size(bad) == 0
     assert L.aq_qgemm_batch(bad, A, A, ws, None) == aq.AQ_EINVAL              # not a plan image
@@ -135,5 +136,7 @@ def test_gemm_batch_plan_validation_and_workspace(L):
     assert L.aq_qgemm_batch(buf, A, A + 4, ws, None) == aq.AQ_EALIGN
     assert L.aq_qgemm_batch(buf, A, A, ws - 1, None) == aq.AQ_ESIZE
     # single call: the workspace is required and checked before anything is launched
-    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, None, 0, None) == aq.AQ_ENULL
-    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, A, 1024, None) == aq.AQ_ESIZE
+    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, 0, None, 0, None) == aq.AQ_ENULL
+    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, 1, A, 1024, None) == aq.AQ_ESIZE
+    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, 2, A, 1 << 24, None) == aq.AQ_EINVAL
+    assert L.aq_qgemm_batch_plan(descs, n, 32, 7, buf, size) == aq.AQ_EINVAL          # unknown flags

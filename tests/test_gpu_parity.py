@@ -348,10 +348,116 @@ def test_qgemm_batch_shares_and_separates_activations(gpu, oracle):
         items.append((packed, N, K, bits, xd, Y))
         refs.append(oracle.qmatmul(codes, scales, N, K, bits, x, "bf16"))
     batch = aq.GemmBatch(items)
-    assert batch.workspace_bytes == 2 * 304 * K * 2     # two distinct activation matrices
+    assert batch.workspace_bytes == 2 * (304 * K * 2 + 2048)     # two distinct activation matrices (+ row factors)
     batch.run()
     torch.cuda.synchronize()
     for (packed, N, K_, bits, xd, Y), ref in zip(items, refs):
         got = Y.cpu().numpy()
         assert np.isfinite(got).all()
         assert oracle.rel_l2(got, ref) <= REL_L2_EXPECTED
+
+
+# ---- prefill, fp16-weight mode (AQ_GEMM_FAST) ---------------------------------------------------------
+# d * (q - z) is formed in binary16: exact for 2 bits; for 3 and 4 bits the codes whose product needs more
+# than 11 significant bits are rounded (relative error <= 2^-12 per weight), which shows as rel-L2 ~1e-4.
+FAST_EXPECTED = {2: 2e-5, 3: 3e-4, 4: 3e-4}
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K,M", [(200, 1056, 7), (256, 2048, 64), (512, 512, 300), (130, 4096, 81), (96, 544, 385)])
+def test_qgemm_fast_matches_oracle(gpu, oracle, bits, N, K, M, dtype):
+    torch, aq = gpu
+    codes, scales = wl.draw_matrix(N, K, bits, 18, N, K)
+    X = wl.draw_activations(M, K, dtype, 18, N, K, image_rows=min(256, M) if M >= 256 else 0, image_gain=3.0)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, dtype), fast=True).cpu().numpy()
+    ref = oracle.qmatmul(codes, scales, N, K, bits, X, dtype)
+    assert np.isfinite(Y).all()
+    err = oracle.rel_l2(Y, ref)
+    assert err <= REL_L2_BAR
+    assert err <= FAST_EXPECTED[bits], err
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_qgemm_fast_is_exact_where_the_products_are(gpu, oracle, bits):
+    """Power-of-two scales make every d * (q - z) a binary16 number: with integer activations the result is
+    exact whatever the summation order; one-hot rows return the dequantised weights themselves."""
+    torch, aq = gpu
+    N, K, M = 96, 1056, 40
+    codes = wl.draw_codes(N, K, bits, 19, bits)
+    scales = wl.draw_pow2_scales(N, K, 19, bits)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    for dtype in ("bf16", "f16"):
+        X = wl.draw_int_activations(M, K, dtype, 19, bits)
+        Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, dtype), fast=True).cpu().numpy()
+        assert np.array_equal(Y.astype(np.float64), oracle.qmatmul(codes, scales, N, K, bits, X, dtype))
+    ks = [0, 1, 31, 32, 33, 255, 256, 700, K - 1]
+    X = np.zeros((len(ks), K), dtype=np.uint16)
+    for m, k in enumerate(ks):
+        X[m, k] = 0x3F80          # bf16 1.0
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
+    W = oracle.dequant(codes, scales, N, K, bits)
+    assert np.array_equal(Y.astype(np.float64), W[:, ks].T)
+    # two bits: q - z is 0 or a power of two, so random scales are exact as well
+    if bits == 2:
+        codes, scales = wl.draw_matrix(N, K, bits, 20, bits)
+        packed = _pack(torch, aq, codes, scales, N, K, bits)
+        Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
+        assert np.array_equal(Y.astype(np.float64), oracle.dequant(codes, scales, N, K, bits)[:, ks].T)
+
+
+def test_qgemm_fast_row_factors_and_large_scales(gpu, oracle):
+    """bf16 rows 2^60 apart in magnitude (each row gets its own power-of-two factor), an all-zero row, and a
+    matrix whose scales would overflow binary16 once multiplied by q - z (computed on the exact path)."""
+    torch, aq = gpu
+    N, K, M, bits = 144, 2048, 37, 4
+    codes, scales = wl.draw_matrix(N, K, bits, 21, 0)
+    Xf = wl.bf16_bits_to_f32(wl.draw_activations(M, K, "bf16", 21, 0))
+    for m in range(M):
+        Xf[m] = np.ldexp(Xf[m], (m % 7 - 3) * 10)       # 2^-30 .. 2^+30
+    Xf[5] = 0.0
+    X = wl.f32_to_bf16_bits(Xf)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
+    ref = oracle.qmatmul(codes, scales, N, K, bits, X, "bf16")
+    assert np.isfinite(Y).all() and not Y[5].any()
+    for m in range(M):
+        if m != 5:
+            assert oracle.rel_l2(Y[m], ref[m]) <= FAST_EXPECTED[bits], m
+    # scales around 2^14: 8 * d exceeds 65504
+    big = wl.f32_to_f16_bits(np.ldexp(wl.f16_bits_to_f32(scales), 19))
+    assert wl.f16_bits_to_f32(big).max() > 8192 and np.isfinite(wl.f16_bits_to_f32(big)).all()
+    packed = _pack(torch, aq, codes, big, N, K, bits)
+    X = wl.draw_activations(M, K, "bf16", 21, 1)
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
+    ref = oracle.qmatmul(codes, big, N, K, bits, X, "bf16")
+    assert np.isfinite(Y).all()
+    assert oracle.rel_l2(Y, ref) <= 2e-5                # no weight was rounded
+
+
+def test_qgemm_fast_batch_full_size_sampled(gpu, oracle):
+    """One LLaMA-shaped layer (7 matrices, mixed bit-widths) at M = 300 in the launch shape the bench times, fast
+    mode: sampled output columns against the oracle."""
+    torch, aq = gpu
+    specs = wl.backbone_stream("llama2-7b", "mixed", layers=1)
+    M = wl.PREFILL_M
+    Xs = {K: wl.draw_activations(M, K, "bf16", 22, K, image_rows=wl.PREFILL_IMAGE_ROWS, image_gain=wl.PREFILL_IMAGE_GAIN)
+          for K in sorted({m.K for m in specs})}
+    Xd = {K: _dev(torch, x, "bf16") for K, x in Xs.items()}
+    items, keep = [], []
+    for m in specs:
+        codes, scales = wl.draw_matrix(m.N, m.K, m.bits, 22, m.index)
+        packed = _pack(torch, aq, codes, scales, m.N, m.K, m.bits)
+        Y = torch.full((M, m.N), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, m.N, m.K, m.bits, Xd[m.K], Y))
+        rows = np.unique(np.concatenate([[0, 127, 128, m.N - 1], np.random.default_rng(m.index).integers(0, m.N, 28)]))
+        keep.append((codes.reshape(m.N, -1)[rows], scales[rows], rows))
+    batch = aq.GemmBatch(items, fast=True)
+    batch.run()
+    torch.cuda.synchronize()
+    for m, (packed, N, K, bits, xd, Y), (crow, srow, rows) in zip(specs, items, keep):
+        got = Y.cpu().numpy()
+        assert np.isfinite(got).all()
+        ref = oracle.qmatmul(crow, srow, len(rows), K, bits, Xs[K], "bf16")
+        assert oracle.rel_l2(got[:, rows], ref) <= FAST_EXPECTED[bits], (m.name, bits)
