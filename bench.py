@@ -10,8 +10,9 @@ Printed JSON line (rank 0): metric/value = algorithmic GB/s of that decode pass 
 + fp16 scales + activations + outputs, divided by wall time); `roofline` = the decode kernel
 against the 8 TB/s HBM peak from HIP-event launch durations; `by_bits` = the same pass at a
 uniform 2, 3 and 4 bits; `prefill` = the M = 300 prefill GEMM over the same matrices in
-TFLOP/s against the dense bf16 MFMA peak; `cpu_baseline` = the CPU oracle timed on a bounded
-sample of the same workload on this host's cores.
+TFLOP/s against the dense bf16 MFMA peak, in both modes of the library; `gemma` = the
+Gemma-2B-shaped stream (decode, prefill at M = 16, 64, 300); `cpu_baseline` = the CPU oracle
+timed on a bounded sample of the same workload on this host's cores.
 """
 from __future__ import annotations
 
@@ -221,21 +222,24 @@ def main():
                                               image_gain=wl.PREFILL_IMAGE_GAIN)
         # one output buffer per distinct N, shared by the matrices of that shape (outputs are not consumed)
         Ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({m.N for m in specs})}
-        gbatch = aq.GemmBatch([(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in items])
-
-        def prefill_pass():
-            gbatch.run()
-
-        d, w = time_launches(torch, prefill_pass, args.prefill_steps, 1)
-        ms = sum(d) / len(d)
         flops = 2.0 * M * weights
-        out["prefill"] = {
-            "workload": "M=300 (256 image rows x3 + 44 text rows, bf16) over the same 224 matrices, one batched launch",
-            "ms": round(ms, 3),
-            "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
-            "mfma_frac_of_bf16_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-            "prefill_tokens_per_s": round(M / (ms * 1e-3), 1),
-        }
+        pre = {"workload": "M=300 (256 image rows x3 + 44 text rows, bf16) over the same 224 matrices: one launch that "
+                           "re-orders X and one batched product launch"}
+        for mode, fast in (("exact", False), ("fast", True)):
+            gbatch = aq.GemmBatch([(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in items], fast=fast)
+            d, w = time_launches(torch, gbatch.run, args.prefill_steps, 1)
+            ms = sum(d) / len(d)
+            pre[mode] = {
+                "ms": round(ms, 3),
+                "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
+                "mfma_frac_of_bf16_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "prefill_tokens_per_s": round(M / (ms * 1e-3), 1),
+            }
+            del gbatch
+        pre["modes"] = ("exact: integer codes on the matrix cores, fp16 block scale applied to each block's sum in fp32 "
+                        "(no weight rounded); fast: d*(q-z) rounded to binary16 while unpacking (exact for 2 bits), "
+                        "bf16 activations converted to binary16 with a power-of-two factor per row")
+        out["prefill"] = pre
 
     # ---- Gemma-2B-shaped stream, uniform 3 bits (3.5 bits/weight stored), bf16 activations ----------
     if not args.skip_gemma:
@@ -255,19 +259,21 @@ def main():
         for M in (16, 64, wl.PREFILL_M):
             Xs = {K: wl.draw_activations_torch(M, K, "bf16", "cuda", 6, K, M) for K in sorted({m.K for m in gs})}
             Ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({m.N for m in gs})}
-            g2 = aq.GemmBatch([(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in gitems])
-            d, w = time_launches(torch, g2.run, args.prefill_steps, 1)
-            ms = sum(d) / len(d)
             flops = 2.0 * M * gweights
             nbytes = sum(stored_bytes(m.N, m.K, m.bits) + 2 * M * m.K + 4 * M * m.N for m in gs)
             t_hbm, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-            gem["prefill_M%d" % M] = {
-                "ms": round(ms, 4), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
-                "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
-                "bound": "hbm" if t_hbm > t_mfma else "mfma",
-                "frac_of_min_roofline": round(max(t_hbm, t_mfma) / (ms * 1e-3), 4),
-                "tokens_per_s": round(M / (ms * 1e-3), 1)}
-            del g2, Xs, Ys
+            cell = {"bound": "hbm" if t_hbm > t_mfma else "mfma"}
+            for mode, fast in (("exact", False), ("fast", True)):
+                g2 = aq.GemmBatch([(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in gitems], fast=fast)
+                d, w = time_launches(torch, g2.run, args.prefill_steps, 1)
+                ms = sum(d) / len(d)
+                cell[mode] = {"ms": round(ms, 4), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
+                              "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                              "frac_of_min_roofline": round(max(t_hbm, t_mfma) / (ms * 1e-3), 4),
+                              "tokens_per_s": round(M / (ms * 1e-3), 1)}
+                del g2
+            gem["prefill_M%d" % M] = cell
+            del Xs, Ys
         out["gemma"] = gem
 
     print(json.dumps(out), flush=True)
