@@ -79,11 +79,16 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-gemma", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=5)
+    ap.add_argument("--prefill-only", action="store_true",
+                    help="the timed decode stream with 2 steps, then only the M = 300 prefill (short run for rocprofv3 --pmc passes)")
     ap.add_argument("--decode-only", action="store_true",
                     help="only the timed decode stream (short run for rocprofv3 --pmc passes)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy 5 times and exit: scales the FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
+    if args.prefill_only:
+        args.skip_by_bits = args.skip_cpu = args.skip_gemma = True
+        args.steps, args.warmup = 2, 1
     if args.decode_only:
         args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = True
     if args.gpus != 1:
