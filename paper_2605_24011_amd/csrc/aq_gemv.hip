@@ -271,6 +271,8 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg)
 hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
                     int total_wgs, int max_K, hipStream_t s)
 {
+    // the grid was sized for `tiles_per_wg` tiles per workgroup: only the two shapes the kernels are built for
+    if ((tiles_per_wg != 4 && tiles_per_wg != 8) || (bits == 0 && tiles_per_wg != 8)) return hipErrorInvalidValue;
     const size_t lds = gemv_lds_bytes(max_K);
     const dim3 grid((unsigned)total_wgs), block(THREADS);
 #define AQ_LAUNCH(BITS, TW) hipLaunchKernelGGL((qgemv_kernel<BITS, TW>), grid, block, lds, s, tasks_dev, count, single)
