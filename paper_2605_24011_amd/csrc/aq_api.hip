@@ -2,6 +2,7 @@
 // before every argument has been checked, so the error paths can be tested on a machine
 // without one.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <cstring>
 #include <vector>
 #include "../../include/aq.h"
@@ -97,6 +98,16 @@ AqRetileTask make_retile_task(const void* X, int64_t M, int64_t K, int64_t ldx, 
     r.convert = convert;
     r.blocks = aqk_retile_blocks(M, K, convert);
     return r;
+}
+
+// indices 0 .. count-1 by descending K, ties in the caller's order
+template <class KeyFn>
+std::vector<int> longest_k_first(int count, KeyFn key)
+{
+    std::vector<int> order(count);
+    for (int i = 0; i < count; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return key(a) > key(b); });
+    return order;
 }
 
 int check_flags(int flags) { return (flags == AQ_GEMM_EXACT || flags == AQ_GEMM_FAST) ? AQ_OK : AQ_EINVAL; }
@@ -202,14 +213,17 @@ int aq_qgemv_batch_plan(const aq_gemv_desc* descs, int count, int block, void* p
     AqGemvTask* tasks = reinterpret_cast<AqGemvTask*>(static_cast<uint8_t*>(plan_host) + sizeof(PlanHeader));
     int32_t begin = 0;
     h.bits = descs[0].bits;
-    for (int i = 0; i < count; ++i) {
-        const aq_gemv_desc& d = descs[i];
+    // The products of a list are independent, so their workgroups may run in any order.  A workgroup walks the
+    // whole K of its rows: those of the longest K go first, so that the launch does not end on a few long ones.
+    std::vector<int> order = longest_k_first(count, [&](int i) { return descs[i].K; });
+    for (int j = 0; j < count; ++j) {
+        const aq_gemv_desc& d = descs[order[j]];
         if (d.bits != descs[0].bits) h.bits = 0;
         AqGemvTask t = make_task(d.packed, d.N, d.K, d.bits, d.x, d.x_dtype, d.y);
         t.wg_begin = begin;
         t.wg_count = aqk_gemv_wg_count(d.N, rt);
         begin += t.wg_count;
-        std::memcpy(&tasks[i], &t, sizeof(t));
+        std::memcpy(&tasks[j], &t, sizeof(t));
     }
     h.total_wgs = begin;
     std::memcpy(plan_host, &h, sizeof(h));
@@ -295,8 +309,10 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int fla
     // products that read the same activations (same pointer, shape and row stride) share one re-tiled copy
     std::vector<AqRetileTask> rt;
     int64_t begin = 0, ws = 0;
-    for (int i = 0; i < count; ++i) {
-        const aq_gemm_desc& d = descs[i];
+    std::vector<int> order = longest_k_first(count, [&](int i) { return descs[i].K; });   // see aq_qgemv_batch_plan
+    for (int j = 0; j < count; ++j) {
+        const int i = j;
+        const aq_gemm_desc& d = descs[order[j]];
         if (d.bits != descs[0].bits) h.bits = 0;
         int64_t off = -1;
         for (const AqRetileTask& r : rt)
