@@ -18,6 +18,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "aq_oracle.c")
+_SRC_SCALE = os.path.join(_HERE, "aq_scale_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
@@ -28,9 +29,10 @@ _p = ctypes.c_void_p
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (OpenMP on the plain loops, nothing else)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_SCALE))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC, "-lm"]
+               "-o", _LIB, _SRC, _SRC_SCALE, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -55,6 +57,9 @@ def _load():
         lib.aqo_stored_bytes.restype = _i64
         lib.aqo_stored_bytes.argtypes = [_i64, _i64, _int, _int]
         lib.aqo_num_threads.restype = _int
+        lib.aqs_f64_to_f16.restype = ctypes.c_uint16
+        lib.aqs_f64_to_f16.argtypes = [ctypes.c_double]
+        lib.aqs_optimize.argtypes = [_p, _p, _i64, _i64, _int, _int, _int, _p, _p, _p]
         _lib = lib
     return _lib
 
@@ -197,3 +202,26 @@ def footprint_gb(fp16_gb: float, avg_bpw: float) -> float:
     `avg_bpw` bits per weight on average (Table 1's Mem. column against its
     'VLA BPW' column)."""
     return fp16_gb * avg_bpw / 16.0
+
+
+# ---- block-level scale optimisation (Section 4.2, Eq. 10-11; see aq_scale_oracle.c) -------------
+def f64_to_f16_bits(x: float) -> int:
+    """binary16 bit pattern of a double, round to nearest even."""
+    return int(_load().aqs_f64_to_f16(float(x)))
+
+
+def scale_optimize(W: np.ndarray, F, bits: int, rounds: int, block: int = 32, trace: bool = False):
+    """Alternating code assignment / closed-form scale of Eq. 11 on every block of W[N, K].
+
+    W float32 [N, K]; F float32 [N, K] (the diagonal sensitivities of Eq. 10) or None for all ones.
+    Returns (codes uint8 [N, K] in {0..2^bits-1}, scales uint16 [N, K/block] binary16 bits[, trace])."""
+    W = _c(W, np.float32)
+    N, K = W.shape
+    assert K % block == 0
+    Fc = None if F is None else _c(F, np.float32)
+    codes = np.empty((N, K), dtype=np.uint8)
+    scales = np.empty((N, K // block), dtype=np.uint16)
+    tr = np.zeros((N * (K // block), 2 * rounds + 3), dtype=np.float64) if trace else None
+    _load().aqs_optimize(_ptr(W), None if Fc is None else _ptr(Fc), N, K, bits, block, rounds,
+                         _ptr(codes), _ptr(scales), None if tr is None else _ptr(tr))
+    return (codes, scales, tr) if trace else (codes, scales)
