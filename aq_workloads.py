@@ -91,6 +91,24 @@ def f32_to_f16_bits(a: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
 
 
+def draw_weights(N: int, K: int, *key: int, sigma: float = 0.02, outlier_rate: float = 0.01) -> np.ndarray:
+    """fp32 weights N(0, sigma^2) with a share `outlier_rate` of elements drawn 8 times wider (trained matrices
+    have heavy tails; the optimiser's scale has to trade them against the bulk)."""
+    g = _rng(606, *key)
+    w = g.standard_normal((N, K)).astype(np.float32) * np.float32(sigma)
+    wide = g.random((N, K)) < outlier_rate
+    return np.where(wide, w * np.float32(8.0), w).astype(np.float32)
+
+
+def draw_sensitivities(N: int, K: int, *key: int) -> np.ndarray:
+    """Positive fp32 sensitivities: squared-gradient-like, gamma(0.5) times a per-row and a per-column factor
+    (mean squared gradients vary by orders of magnitude across rows and input channels)."""
+    g = _rng(707, *key)
+    f = g.gamma(0.5, 2.0, size=(N, K))
+    f *= np.exp(g.standard_normal((N, 1))) * np.exp(g.standard_normal((1, K)))
+    return f.astype(np.float32)
+
+
 def bf16_bits_to_f32(a: np.ndarray) -> np.ndarray:
     """bfloat16 bit patterns (uint16) -> float32 values (exact)."""
     return (np.asarray(a, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)

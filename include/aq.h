@@ -153,6 +153,25 @@ size_t aq_qgemm_batch_workspace_size(const void* plan_host);   /* 0 if the plan 
 int aq_qgemm_batch(const void* plan_host, const void* plan_dev,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* Block-level scale optimisation (Section 4.2, Eq. 10-11): the step that produces the codes and scales
+ * aq_pack_weights consumes.  For every block of 32 weights along K:
+ *   omega_i = F_i * sqrt(sigma_b^2 + w_i^2)       sigma_b^2 = the block's mean squared weight   (Eq. 10, left)
+ *   minimise  Phi_b = sum_i omega_i (w_i - s q_i)^2  over the scale s and the codes q_i          (Eq. 10, right)
+ *   by alternating  q_i = the codebook entry nearest to w_i / s   and   s = sum(omega w q) / sum(omega q^2)  (Eq. 11)
+ * Fixed here where the paper is silent: the codebook is the integers -2^(bits-1) .. 2^(bits-1)-1 (the format's
+ * q - z); the start is s = max|w| / 2^(bits-1); `rounds` (0 .. AQ_MAX_ROUNDS) counts scale updates, 0 = plain
+ * nearest-code quantisation at the start scale; a block stops early when sum(omega w q) <= 0 or
+ * sum(omega q^2) = 0; ties go to the smaller code; the stored scale is d = binary16(s), round to nearest even,
+ * capped at 65504, and the stored codes are one more assignment against d; an all-zero block gets d = 0 and
+ * the code of zero.  Arithmetic is fp64.
+ *   W      DEVICE float  [N][K]   weights
+ *   F      DEVICE float  [N][K]   non-negative sensitivities (the diagonal of Eq. 9), or NULL for all ones
+ *   codes  DEVICE uint8  [N][K/32][4*bits]   canonical bitstream, written entirely
+ *   scales DEVICE uint16 [N][K/32]           binary16 bit patterns, written entirely */
+#define AQ_MAX_ROUNDS 64
+int aq_optimize_scales(const float* W, const float* F, int64_t N, int64_t K, int bits, int block, int rounds,
+                       uint8_t* codes, uint16_t* scales, void* stream);
+
 /* Parity / debug: the blob decoded back to what Eq. 1 defines.
  *   codes_u8 DEVICE uint8 [N][K]  one code per byte
  *   W        DEVICE float [N][K]  d * (q - 2^(bits-1)); exact in fp32 (11-bit x 4-bit significands) */

@@ -67,6 +67,7 @@ def lib() -> ctypes.CDLL:
         L.aq_qgemm_batch_workspace_size.restype = _sz
         L.aq_qgemm_batch_workspace_size.argtypes = [_p]
         L.aq_qgemm_batch.argtypes = [_p, _p, _p, _sz, _p]
+        L.aq_optimize_scales.argtypes = [_p, _p, _i64, _i64, _int, _int, _int, _p, _p, _p]
         L.aq_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         _lib = L
@@ -192,6 +193,20 @@ class GemmBatch:
     def run(self, stream=None) -> None:
         _check(lib().aq_qgemm_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), self.workspace.data_ptr(),
                                     self.workspace_bytes, _stream(stream)), "aq_qgemm_batch")
+
+
+def aq_optimize_scales(W, F, bits: int, rounds: int = 4, block: int = BLOCK, stream=None):
+    """W (and F, or None) cuda float32 [N, K] -> (codes uint8 [N, K/32, 4*bits], scales int16 view of fp16 bits
+    [N, K/32]): the canonical form aq_pack_weights takes."""
+    import torch
+    N, K = W.shape
+    assert W.dtype == torch.float32 and W.is_contiguous() and (F is None or (F.dtype == torch.float32 and F.is_contiguous()
+                                                                              and F.shape == W.shape))
+    codes = torch.empty((N, K // block, 4 * bits), dtype=torch.uint8, device=W.device)
+    scales = torch.empty((N, K // block), dtype=torch.float16, device=W.device)
+    _check(lib().aq_optimize_scales(W.data_ptr(), None if F is None else F.data_ptr(), N, K, bits, block, rounds,
+                                    codes.data_ptr(), scales.data_ptr(), _stream(stream)), "aq_optimize_scales")
+    return codes, scales
 
 
 def aq_unpack_codes(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):

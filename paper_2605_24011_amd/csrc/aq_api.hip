@@ -377,6 +377,19 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
                ? AQ_OK : AQ_ELAUNCH;
 }
 
+int aq_optimize_scales(const float* W, const float* F, int64_t N, int64_t K, int bits, int block, int rounds,
+                       uint8_t* codes, uint16_t* scales, void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if (rounds < 0 || rounds > AQ_MAX_ROUNDS) return AQ_EINVAL;
+    if (N * K > (int64_t)1 << 40) return AQ_EINVAL;
+    if (!W || !codes || !scales) return AQ_ENULL;
+    if (!aligned16(W) || (F && !aligned16(F)) || !aligned16(codes) || !aligned16(scales)) return AQ_EALIGN;
+    return aqk_optimize_scales(W, F, N, K, bits, rounds, codes, scales, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
 int aq_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream)
 {
     int rc = check_matrix(N, K, bits, block);

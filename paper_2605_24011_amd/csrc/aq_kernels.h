@@ -80,3 +80,7 @@ hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTa
 // launch.  fast != 0: weights are formed as binary16 d * (q - z) and the activations in Xt are binary16.
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
                     int nsplit, int fast, int total_wgs, const void* workspace, hipStream_t s);
+
+// Block-level scale optimisation: fp32 W, F (F may be null = all ones) -> canonical codes + fp16 scales
+hipError_t aqk_optimize_scales(const float* W, const float* F, int64_t N, int64_t K, int bits, int rounds,
+                               uint8_t* codes, uint16_t* scales, hipStream_t s);

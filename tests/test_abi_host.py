@@ -140,3 +140,16 @@ def test_gemm_batch_plan_validation_and_workspace(L):
     assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, 1, A, 1024, None) == aq.AQ_ESIZE
     assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, 2, A, 1 << 24, None) == aq.AQ_EINVAL
     assert L.aq_qgemm_batch_plan(descs, n, 32, 7, buf, size) == aq.AQ_EINVAL          # unknown flags
+
+
+def test_optimize_scales_validation_without_a_gpu(L):
+    A = 4096
+    assert L.aq_optimize_scales(A, A, 16, 64, 7, 32, 4, A, A, None) == aq.AQ_EINVAL
+    assert L.aq_optimize_scales(A, A, 16, 48, 4, 32, 4, A, A, None) == aq.AQ_EINVAL
+    assert L.aq_optimize_scales(A, A, 16, 64, 4, 64, 4, A, A, None) == aq.AQ_EINVAL
+    assert L.aq_optimize_scales(A, A, 16, 64, 4, 32, 65, A, A, None) == aq.AQ_EINVAL
+    assert L.aq_optimize_scales(A, A, 16, 64, 4, 32, -1, A, A, None) == aq.AQ_EINVAL
+    assert L.aq_optimize_scales(None, A, 16, 64, 4, 32, 4, A, A, None) == aq.AQ_ENULL
+    assert L.aq_optimize_scales(A, None, 16, 64, 4, 32, 4, A, None, None) == aq.AQ_ENULL
+    assert L.aq_optimize_scales(A, A + 4, 16, 64, 4, 32, 4, A, A, None) == aq.AQ_EALIGN
+    assert L.aq_optimize_scales(A, None, 16, 64, 4, 32, 4, A + 8, A, None) == aq.AQ_EALIGN

@@ -461,3 +461,101 @@ def test_qgemm_fast_batch_full_size_sampled(gpu, oracle):
         assert np.isfinite(got).all()
         ref = oracle.qmatmul(crow, srow, len(rows), K, bits, Xs[K], "bf16")
         assert oracle.rel_l2(got[:, rows], ref) <= FAST_EXPECTED[bits], (m.name, bits)
+
+
+# ---- block-level scale optimisation (Section 4.2, Eq. 10-11) -------------------------------------------
+def _check_scale_opt(torch, aq, oracle, W, F, bits, rounds):
+    N, K = W.shape
+    Wd = torch.from_numpy(W).cuda()
+    Fd = None if F is None else torch.from_numpy(F).cuda()
+    codes_d, scales_d = aq.aq_optimize_scales(Wd, Fd, bits, rounds)
+    got_codes = codes_d.cpu().numpy()
+    got_scales = scales_d.view(torch.int16).cpu().numpy().view(np.uint16)
+    ref_q, ref_scales = oracle.scale_optimize(W, F, bits, rounds)
+    ref_codes = oracle.pack(ref_q, bits)
+    assert np.array_equal(got_scales, ref_scales)
+    assert np.array_equal(got_codes, ref_codes)
+    return codes_d, scales_d, ref_q, ref_scales
+
+
+@pytest.mark.parametrize("rounds", [0, 1, 4, 9])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_optimize_scales_matches_oracle(gpu, oracle, bits, rounds):
+    """Codes and scales are decisions taken in fp64 on both sides: required bit-exact."""
+    torch, aq = gpu
+    for (N, K, with_F) in [(7, 96, True), (130, 1056, True), (64, 2048, False)]:
+        W = wl.draw_weights(N, K, 30, bits, rounds, N)
+        F = wl.draw_sensitivities(N, K, 30, bits, rounds, N) if with_F else None
+        _check_scale_opt(torch, aq, oracle, W, F, bits, rounds)
+
+
+def test_optimize_scales_degenerate_blocks(gpu, oracle):
+    """All-zero blocks, one non-zero element, one sign only, magnitudes beyond the fp16 scale range at both ends,
+    zero sensitivities, and a block whose sensitivities single out one element."""
+    torch, aq = gpu
+    rng = np.random.default_rng(31)
+    W = (rng.standard_normal((12, 64)) * 0.02).astype(np.float32)
+    F = rng.uniform(0.1, 2.0, size=W.shape).astype(np.float32)
+    W[0, :32] = 0.0
+    W[1, :] = 0.0
+    W[1, 5] = 0.3
+    W[2, :32] = np.abs(W[2, :32])
+    W[3, :32] = -np.abs(W[3, :32])
+    W[4, :32] *= np.float32(1e7)                 # max|w| / 8 far above 65504: the scale saturates
+    W[5, :32] *= np.float32(1e-7)                # scales in fp16's subnormal range
+    W[6, :32] *= np.float32(1e-12)               # below the smallest subnormal: d = 0
+    F[7, :32] = 0.0                              # nothing to fit: the start scale is kept
+    F[8, :32] = 1e-6
+    F[8, 3] = 1e6
+    for bits in (2, 3, 4):
+        _check_scale_opt(torch, aq, oracle, W, F, bits, 4)
+        _check_scale_opt(torch, aq, oracle, W, None, bits, 2)
+
+
+def test_optimize_scales_feeds_the_matmul(gpu, oracle):
+    """End to end: optimise, pack, multiply; equal to the oracle's chain, and closer to the fp32 weights' product
+    than plain nearest-code quantisation at the absmax scale (rounds = 0) in the sensitivity-weighted error."""
+    torch, aq = gpu
+    N, K, bits = 256, 2048, 3
+    W = wl.draw_weights(N, K, 32, 0)
+    F = wl.draw_sensitivities(N, K, 32, 0)
+    codes_d, scales_d, ref_q, ref_scales = _check_scale_opt(torch, aq, oracle, W, F, bits, 4)
+    packed = aq.aq_pack_weights(codes_d, scales_d, N, K, bits)
+    x = wl.draw_activations(1, K, "f16", 32, 1)
+    y = aq.aq_qgemv(packed, N, K, bits, _dev(torch, x[0], "f16")).cpu().numpy()
+    ref = oracle.qmatmul(oracle.pack(ref_q, bits), ref_scales, N, K, bits, x, "f16")[0]
+    assert oracle.rel_l2(y, ref) <= REL_L2_EXPECTED
+    z = 1 << (bits - 1)
+    def weighted_error(q, scales):
+        what = oracle.f16_to_f64(scales).repeat(32, axis=1) * (q.astype(np.float64) - z)
+        w = W.astype(np.float64)
+        sig = np.sqrt(np.repeat((w.reshape(N, -1, 32) ** 2).mean(axis=2), 32, axis=1) + w * w)
+        return float(np.sum(F * sig * (w - what) ** 2))
+    q0, s0 = oracle.scale_optimize(W, F, bits, 0)
+    assert weighted_error(ref_q, ref_scales) < 0.8 * weighted_error(q0, s0)
+
+
+def test_optimize_scales_full_size_sampled(gpu, oracle):
+    """A 4096 x 4096 matrix in the launch shape the bench times; the oracle checks sampled rows."""
+    torch, aq = gpu
+    N, K, bits = 4096, 4096, 2
+    g = torch.Generator(device="cuda").manual_seed(33)
+    Wd = torch.randn((N, K), generator=g, device="cuda", dtype=torch.float32) * 0.02
+    Fd = torch.rand((N, K), generator=g, device="cuda", dtype=torch.float32) + 0.05
+    codes_d, scales_d = aq.aq_optimize_scales(Wd, Fd, bits, 4)
+    rows = [0, 1, 127, 128, 2049, 4095]
+    W, F = Wd[rows].cpu().numpy(), Fd[rows].cpu().numpy()
+    ref_q, ref_scales = oracle.scale_optimize(W, F, bits, 4)
+    assert np.array_equal(scales_d[rows].view(torch.int16).cpu().numpy().view(np.uint16), ref_scales)
+    assert np.array_equal(codes_d[rows].cpu().numpy(), oracle.pack(ref_q, bits))
+
+
+def test_optimize_scales_errors(gpu):
+    torch, aq = gpu
+    W = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(aq.AqError):
+        aq.aq_optimize_scales(W, None, 5, 4)
+    with pytest.raises(aq.AqError):
+        aq.aq_optimize_scales(W, None, 4, 65)
+    with pytest.raises(aq.AqError):
+        aq.aq_optimize_scales(W, None, 4, -1)
