@@ -11,8 +11,9 @@ Printed JSON line (rank 0): metric/value = algorithmic GB/s of that decode pass 
 against the 8 TB/s HBM peak from HIP-event launch durations; `by_bits` = the same pass at a
 uniform 2, 3 and 4 bits; `prefill` = the M = 300 prefill GEMM over the same matrices in
 TFLOP/s against the dense bf16 MFMA peak, in both modes of the library; `gemma` = the
-Gemma-2B-shaped stream (decode, prefill at M = 16, 64, 300); `cpu_baseline` = the CPU oracle
-timed on a bounded sample of the same workload on this host's cores.
+Gemma-2B-shaped stream (decode, prefill at M = 16, 64, 300); `scale_opt` = the block-level scale
+optimisation that produces codes and scales; `cpu_baseline` = the CPU oracle timed on a bounded
+sample of the same workload on this host's cores.
 """
 from __future__ import annotations
 
@@ -78,6 +79,7 @@ def main():
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-gemma", action="store_true")
+    ap.add_argument("--skip-quant", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=5)
     ap.add_argument("--prefill-only", action="store_true",
                     help="the timed decode stream with 2 steps, then only the M = 300 prefill (short run for rocprofv3 --pmc passes)")
@@ -87,10 +89,10 @@ def main():
                     help="run a plain 1 GiB device copy 5 times and exit: scales the FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.prefill_only:
-        args.skip_by_bits = args.skip_cpu = args.skip_gemma = True
+        args.skip_by_bits = args.skip_cpu = args.skip_gemma = args.skip_quant = True
         args.steps, args.warmup = 2, 1
     if args.decode_only:
-        args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = True
+        args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = args.skip_quant = True
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists).", file=sys.stderr)
         sys.exit(2)
@@ -280,6 +282,41 @@ def main():
             gem["prefill_M%d" % M] = cell
             del Xs, Ys
         out["gemma"] = gem
+
+    # ---- block-level scale optimisation (the step that produces codes and scales), one 11008 x 4096 matrix ----
+    if not args.skip_quant:
+        torch.cuda.empty_cache()
+        N, K, rounds = 11008, 4096, 4
+        g = torch.Generator(device="cuda").manual_seed(7)
+        W = torch.randn((N, K), generator=g, device="cuda", dtype=torch.float32) * 0.02
+        W = torch.where(torch.rand((N, K), generator=g, device="cuda") < 0.01, W * 8.0, W)
+        F = torch.empty((N, K), device="cuda", dtype=torch.float32).exponential_(generator=g) + 1e-3
+        quant = {"workload": "W fp32 [11008, 4096] N(0, 0.02^2) with 1 percent of elements 8x wider, F fp32 positive; "
+                             "rounds = %d scale updates per block" % rounds,
+                 "fp64_valu_peak_Tinstr_per_s": 39.3}
+        for b in (2, 3, 4):
+            for r in (0, rounds):
+                d, w = time_launches(torch, lambda: aq.aq_optimize_scales(W, F, b, r), 10, 2)
+                ms = sum(d) / len(d)
+                nbytes = N * K * (8 + b / 8 + 1 / 16)
+                quant["b%d_rounds%d" % (b, r)] = {
+                    "ms": round(ms, 4), "Gweights/s": round(N * K / (ms * 1e-3) / 1e9, 1),
+                    "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                    "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        if not args.skip_cpu:
+            from oracle import aq_oracle
+            rows = N                   # the whole matrix: about 1.5 s on one core
+            Wc, Fc = W[:rows].cpu().numpy(), F[:rows].cpu().numpy()
+            t0 = time.perf_counter()
+            rq, rs = aq_oracle.scale_optimize(Wc, Fc, 3, rounds)
+            cpu_s = time.perf_counter() - t0
+            cd, sd = aq.aq_optimize_scales(W, F, 3, rounds)
+            same = bool(np.array_equal(cd[:rows].cpu().numpy(), aq_oracle.pack(rq, 3)) and
+                        np.array_equal(sd[:rows].view(torch.int16).cpu().numpy().view(np.uint16), rs))
+            quant["cpu_oracle"] = {"Gweights/s": round(rows * K / cpu_s / 1e9, 5), "cores": 1,
+                                   "sample": "all %d rows of the same matrix, 3 bits, %.2f s on one core" % (rows, cpu_s),
+                                   "gpu_equals_oracle_on_sample": same}
+        out["scale_opt"] = quant
 
     print(json.dumps(out), flush=True)
 
