@@ -172,6 +172,21 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev,
 int aq_optimize_scales(const float* W, const float* F, int64_t N, int64_t K, int bits, int block, int rounds,
                        uint8_t* codes, uint16_t* scales, void* stream);
 
+/* Layer-balanced bit allocation (Section 4.1, Eq. 6 and paragraph "Solver"): HOST-only, no GPU work.
+ * Chooses one bit-width per tensor (J tensors in each of L layers) to minimise  sum_l E_l^2,
+ * E_l = sum_j S[l][j] * 2^(-2 bits[l][j]),  subject to  sum(bits * size) / sum(size) <= avg_bits_budget,
+ * with the paper's greedy procedure: every tensor starts at choices[0]; at each step the single upgrade to the
+ * next larger entry of `choices` with the largest (E_l^2 - E~_l^2) / extra_bits is applied.  Fixed here where the
+ * paper is silent: an upgrade that would exceed the budget is not a candidate; the loop ends when no candidate is
+ * left or no upgrade lowers the objective (S may be negative); ties go to the first tensor in (layer, tensor) order.
+ *   S        HOST double  [L][J]   sensitivities (Eq. 5)
+ *   sizes    HOST int64   [L][J]   elements per tensor, >= 1
+ *   choices  HOST int     [n_choices]  strictly ascending bit-widths in 1..16 (e.g. 2, 3, 4)
+ *   bits_out HOST int     [L][J]
+ * AQ_EINVAL if choices[0] everywhere already exceeds the budget. */
+int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const int* choices, int n_choices,
+                     double avg_bits_budget, int* bits_out);
+
 /* Parity / debug: the blob decoded back to what Eq. 1 defines.
  *   codes_u8 DEVICE uint8 [N][K]  one code per byte
  *   W        DEVICE float [N][K]  d * (q - 2^(bits-1)); exact in fp32 (11-bit x 4-bit significands) */

@@ -68,6 +68,7 @@ def lib() -> ctypes.CDLL:
         L.aq_qgemm_batch_workspace_size.argtypes = [_p]
         L.aq_qgemm_batch.argtypes = [_p, _p, _p, _sz, _p]
         L.aq_optimize_scales.argtypes = [_p, _p, _i64, _i64, _int, _int, _int, _p, _p, _p]
+        L.aq_allocate_bits.argtypes = [_p, _p, _int, _int, _p, _int, ctypes.c_double, _p]
         L.aq_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         _lib = L
@@ -207,6 +208,17 @@ def aq_optimize_scales(W, F, bits: int, rounds: int = 4, block: int = BLOCK, str
     _check(lib().aq_optimize_scales(W.data_ptr(), None if F is None else F.data_ptr(), N, K, bits, block, rounds,
                                     codes.data_ptr(), scales.data_ptr(), _stream(stream)), "aq_optimize_scales")
     return codes, scales
+
+
+def aq_allocate_bits(S, sizes, choices=(2, 3, 4), avg_bits_budget: float = 2.5):
+    """Host-only greedy layer-balanced allocation.  S, sizes: [L][J] nested sequences -> bits [L][J] (lists)."""
+    L, J = len(S), len(S[0])
+    Sa = (ctypes.c_double * (L * J))(*[float(v) for row in S for v in row])
+    na = (ctypes.c_int64 * (L * J))(*[int(v) for row in sizes for v in row])
+    ca = (ctypes.c_int * len(choices))(*[int(c) for c in choices])
+    out = (ctypes.c_int * (L * J))()
+    _check(lib().aq_allocate_bits(Sa, na, L, J, ca, len(choices), float(avg_bits_budget), out), "aq_allocate_bits")
+    return [[int(out[l * J + j]) for j in range(J)] for l in range(L)]
 
 
 def aq_unpack_codes(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):

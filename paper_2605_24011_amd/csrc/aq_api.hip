@@ -3,6 +3,7 @@
 // without one.
 #include <hip/hip_runtime.h>
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <vector>
 #include "../../include/aq.h"
@@ -388,6 +389,54 @@ int aq_optimize_scales(const float* W, const float* F, int64_t N, int64_t K, int
     if (!aligned16(W) || (F && !aligned16(F)) || !aligned16(codes) || !aligned16(scales)) return AQ_EALIGN;
     return aqk_optimize_scales(W, F, N, K, bits, rounds, codes, scales, static_cast<hipStream_t>(stream)) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
+}
+
+// Host-only: the greedy solver of the layer-balanced allocation problem (Section 4.1, Eq. 6 and "Solver").
+int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const int* choices, int n_choices,
+                     double avg_bits_budget, int* bits_out)
+{
+    if (L < 1 || J < 1 || n_choices < 1 || n_choices > 16) return AQ_EINVAL;
+    if (!S || !sizes || !choices || !bits_out) return AQ_ENULL;
+    for (int c = 0; c < n_choices; ++c)
+        if (choices[c] < 1 || choices[c] > 16 || (c && choices[c] <= choices[c - 1])) return AQ_EINVAL;
+    double total = 0.0, used = 0.0;
+    for (int64_t i = 0; i < (int64_t)L * J; ++i) {
+        if (sizes[i] < 1) return AQ_EINVAL;
+        total += (double)sizes[i];
+        used += (double)choices[0] * (double)sizes[i];
+    }
+    if (!(avg_bits_budget * total >= used)) return AQ_EINVAL;      // even the cheapest type everywhere is over budget
+    std::vector<int> level((size_t)L * J, 0);
+    auto eta = [](int b) { return std::ldexp(1.0, -2 * b); };       // per-element squared error of a b-bit type
+    auto layer_error = [&](int l, int swap_j, int swap_bits) {      // E_l, tensor swap_j taken at swap_bits
+        double e = 0.0;
+        for (int j = 0; j < J; ++j) {
+            const int b = j == swap_j ? swap_bits : choices[level[(size_t)l * J + j]];
+            e += S[(size_t)l * J + j] * eta(b);
+        }
+        return e;
+    };
+    for (;;) {
+        int best_l = -1, best_j = -1;
+        double best_ratio = 0.0, best_dbits = 0.0;
+        for (int l = 0; l < L; ++l) {
+            const double e_now = layer_error(l, -1, 0);
+            for (int j = 0; j < J; ++j) {
+                const int lv = level[(size_t)l * J + j];
+                if (lv + 1 >= n_choices) continue;
+                const double dbits = (double)(choices[lv + 1] - choices[lv]) * (double)sizes[(size_t)l * J + j];
+                if (used + dbits > avg_bits_budget * total) continue;
+                const double e_new = layer_error(l, j, choices[lv + 1]);
+                const double ratio = (e_now * e_now - e_new * e_new) / dbits;
+                if (ratio > best_ratio) { best_ratio = ratio; best_l = l; best_j = j; best_dbits = dbits; }
+            }
+        }
+        if (best_l < 0) break;
+        ++level[(size_t)best_l * J + best_j];
+        used += best_dbits;
+    }
+    for (int64_t i = 0; i < (int64_t)L * J; ++i) bits_out[i] = choices[level[(size_t)i]];
+    return AQ_OK;
 }
 
 int aq_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream)
