@@ -243,6 +243,20 @@ def backbone_stream(model: str, allocation: str = "mixed", seed: int = BASE_SEED
     return [MatrixSpec(i, l, nm, N, K, b) for i, ((l, nm, N, K), b) in enumerate(zip(flat, bits))]
 
 
+def draw_tensor_sensitivities(model: str, *key: int) -> np.ndarray:
+    """Synthetic per-tensor sensitivities [L, 7] for a backbone-shaped stream: gamma(0.7) times a log-normal
+    per-layer factor (a few tensors and a few layers stand out).  Stands in for the HSIC scores of Eq. 5, which need
+    a model and calibration data."""
+    shp, L = layer_shapes(model)
+    g = _rng(808, *key)
+    return g.gamma(0.7, 1.0, size=(L, len(shp))) * np.exp(0.5 * g.standard_normal((L, 1)))
+
+
+def with_bits(stream: Sequence[MatrixSpec], bits: Sequence[int]) -> List[MatrixSpec]:
+    """The same stream with the given per-matrix bit-widths (e.g. from an allocator)."""
+    return [dataclasses.replace(m, bits=int(b)) for m, b in zip(stream, bits)]
+
+
 def stored_bits_per_weight(stream: Sequence[MatrixSpec]) -> float:
     """Bits per weight of the canonical form, fp16 block scales included."""
     tot = sum(m.weights for m in stream)

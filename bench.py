@@ -219,6 +219,26 @@ def main():
             del its, bt
             torch.cuda.empty_cache()
         out["by_bits"] = by_bits
+        # the same pass with the paper's greedy layer-balanced allocation (host-side solver of the library) on
+        # synthetic per-tensor sensitivities, mean of 2.5 code bits
+        base = wl.backbone_stream("llama2-7b", "b2")
+        S = wl.draw_tensor_sensitivities("llama2-7b", 11)
+        sizes = [[m.weights for m in base[7 * l:7 * l + 7]] for l in range(32)]
+        alloc = aq.aq_allocate_bits(S.tolist(), sizes, (2, 3, 4), 2.5)
+        sp = wl.with_bits(base, [b for row in alloc for b in row])
+        its = build_stream(aq, wl, torch, sp, "f16", 30)
+        bt = aq.GemvBatch(its)
+        nbytes = sum(gemv_bytes(m.N, m.K, m.bits) for m in sp)
+        d, w = time_launches(torch, bt.run, max(10, args.steps // 2), 3)
+        ms = sum(d) / len(d)
+        out["greedy_allocation"] = {
+            "bits_histogram": {str(b): sum(1 for m in sp if m.bits == b) for b in (2, 3, 4)},
+            "stored_bits_per_weight": round(wl.stored_bits_per_weight(sp), 4),
+            "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "pct_hbm_peak": round(100 * nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+            "ms": round(ms, 4), "tokens_per_s": round(1e3 / ms, 1), "bytes": nbytes}
+        del its, bt
+        torch.cuda.empty_cache()
 
     # ---- prefill: M = 300 over the same mixed stream -------------------------------------
     if not args.skip_prefill:
