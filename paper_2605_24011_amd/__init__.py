@@ -47,6 +47,14 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2605_24011_amd.build` "
                               "(there is no fallback path)")
+        # PyTorch ships its own copy of the HIP runtime.  The library's kernels must register with the runtime
+        # that owns torch's devices and streams, so torch's copy has to be in the process before libaq.so is
+        # loaded (its libamdhip64 dependency then resolves to it); loaded the other way round, every launch
+        # from this library fails.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         L.aq_status_string.restype = ctypes.c_char_p
         L.aq_status_string.argtypes = [_int]
