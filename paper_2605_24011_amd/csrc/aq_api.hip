@@ -267,7 +267,7 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, cons
     const int fast = flags == AQ_GEMM_FAST, convert = fast && x_dtype == AQ_BF16;
     const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
     if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
-    const int A = aqk_gemm_mtiles(M), nsplit = aqk_gemm_nsplit(M);
+    const int A = aqk_gemm_mtiles(M, aq_num_groups(N)), nsplit = aqk_gemm_nsplit(M);
     AqGemmTask t = make_gemm_task(packed, N, K, bits, M, 0, Y, ldy, A, nsplit, 0);
     return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, nsplit, fast, t.wg_count, workspace, s) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
@@ -300,7 +300,9 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int fla
     h.count = count;
     h.bits = descs[0].bits;
     h.x_dtype = descs[0].x_dtype;
-    h.mtiles = aqk_gemm_mtiles(max_M);
+    int64_t groups = 0;
+    for (int i = 0; i < count; ++i) groups += aq_num_groups(descs[i].N);
+    h.mtiles = aqk_gemm_mtiles(max_M, groups);
     h.nsplit = aqk_gemm_nsplit(max_M);
     h.fast = flags == AQ_GEMM_FAST;
     const int convert = h.fast && h.x_dtype == AQ_BF16;

@@ -257,11 +257,18 @@ void launch_a(int A, int NW, dim3 grid, size_t lds, hipStream_t s, const AqGemmT
 // Shape of the wavefront grid for M rows of activations.  mtiles = most m-tiles (16 rows) per wavefront;
 // nsplit = wavefronts side by side along n (the 8 wavefronts form an (8 / nsplit) x nsplit grid): when M has
 // fewer m-tiles than wavefronts the spare ones take a share of the 128 n instead of idling.
-int aqk_gemm_mtiles(int64_t M)
+int aqk_gemm_mtiles(int64_t M, int64_t groups)
 {
-    if (M <= 128) return 1;
-    if (M <= 256) return 2;
-    return 3;
+    const int most = M <= 128 ? 1 : M <= 256 ? 2 : 3;       // all rows of X in one workgroup: weights unpacked once
+    // A launch with few 128-row groups (a lone matrix) would leave most of the 256 CUs idle: split m over more
+    // workgroups (each unpacks the weights again) while that adds workgroups the chip has room for.
+    int best = most;
+    int64_t best_wgs = groups * ((M + GM_WAVES * 16 * most - 1) / (GM_WAVES * 16 * most));
+    for (int a = most - 1; a >= 1 && best_wgs < 192; --a) {
+        const int64_t wgs = groups * ((M + GM_WAVES * 16 * a - 1) / (GM_WAVES * 16 * a));
+        if (wgs > best_wgs && wgs <= 320) { best = a; best_wgs = wgs; }
+    }
+    return best;
 }
 
 int aqk_gemm_nsplit(int64_t M)

@@ -67,7 +67,7 @@ struct AqGemmTask {
 };
 static_assert(sizeof(AqGemmTask) == 96, "AqGemmTask must stay 96 bytes");
 
-int aqk_gemm_mtiles(int64_t M);
+int aqk_gemm_mtiles(int64_t M, int64_t groups);   // groups = 128-row groups over all products of the launch
 int aqk_gemm_nsplit(int64_t M);
 int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int nsplit, int* slabs);
 size_t aqk_retile_bytes(int64_t M, int64_t K);
