@@ -80,6 +80,7 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-gemma", action="store_true")
     ap.add_argument("--skip-quant", action="store_true")
+    ap.add_argument("--skip-cells", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=5)
     ap.add_argument("--prefill-only", action="store_true",
                     help="the timed decode stream with 2 steps, then only the M = 300 prefill (short run for rocprofv3 --pmc passes)")
@@ -89,10 +90,10 @@ def main():
                     help="run a plain 1 GiB device copy 5 times and exit: scales the FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.prefill_only:
-        args.skip_by_bits = args.skip_cpu = args.skip_gemma = args.skip_quant = True
+        args.skip_by_bits = args.skip_cpu = args.skip_gemma = args.skip_quant = args.skip_cells = True
         args.steps, args.warmup = 2, 1
     if args.decode_only:
-        args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = args.skip_quant = True
+        args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = args.skip_quant = args.skip_cells = True
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists).", file=sys.stderr)
         sys.exit(2)
@@ -239,6 +240,35 @@ def main():
             "ms": round(ms, 4), "tokens_per_s": round(1e3 / ms, 1), "bytes": nbytes}
         del its, bt
         torch.cuda.empty_cache()
+
+    # ---- single shapes, cold: enough distinct copies of one matrix to exceed every cache (>= 512 MB) --------
+    if not args.skip_cells:
+        cells = {}
+        shapes = (("4096x4096", 4096, 4096), ("11008x4096", 11008, 4096), ("4096x11008", 4096, 11008))
+        for name, N, K in shapes:
+            for b in (2, 3, 4):
+                per = gemv_bytes(N, K, b)
+                copies = max(2, -(-(512 << 20) // per))
+                sp = [wl.MatrixSpec(i, 0, name, N, K, b) for i in range(copies)]
+                its = build_stream(aq, wl, torch, sp, "f16", 40 + b)
+                bt = aq.GemvBatch(its)
+                d, w = time_launches(torch, bt.run, 20, 3)
+                ms = sum(d) / len(d)
+                cell = {"copies": copies, "batched_GB/s": round(copies * per / (ms * 1e-3) / 1e9, 1),
+                        "batched_pct_hbm_peak": round(100 * copies * per / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
+                if name == "4096x4096":
+                    # one aq_qgemv call per matrix, rotating through the copies (launch-bound: 9.4 MB is 1.2 us of HBM time)
+                    def lone():
+                        for (packed, N_, K_, b_, x, y) in its:
+                            aq.aq_qgemv(packed, N_, K_, b_, x, y)
+                    d, w = time_launches(torch, lone, 5, 1)
+                    ms1 = sum(d) / len(d) / copies
+                    cell["per_call_us"] = round(ms1 * 1e3, 2)
+                    cell["per_call_GB/s"] = round(per / (ms1 * 1e-3) / 1e9, 1)
+                cells["%s_b%d" % (name, b)] = cell
+                del its, bt
+                torch.cuda.empty_cache()
+        out["cells_cold"] = cells
 
     # ---- prefill: M = 300 over the same mixed stream -------------------------------------
     if not args.skip_prefill:
