@@ -54,10 +54,11 @@ struct GemmPlanHeader {
     int64_t workspace_bytes;
     int32_t nsplit;          // wavefronts along n, from the largest M
     int32_t fast;            // fp16-weight mode
-    int32_t reserved[4];
+    int32_t small_mt;        // > 0: the small-M streaming kernel with that many m-tiles (fast mode, M <= 64)
+    int32_t reserved[3];
 };
 static_assert(sizeof(GemmPlanHeader) == 64, "GemmPlanHeader must stay 64 bytes");
-constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514734u;  // "AQG4"
+constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514735u;  // "AQG5"
 
 int check_gemm(int64_t N, int64_t K, int bits, int block, int64_t M, int64_t ldx, int64_t ldy, int x_dtype,
                const void* packed, const void* X, const void* Y)
@@ -109,6 +110,36 @@ std::vector<int> longest_k_first(int count, KeyFn key)
     for (int i = 0; i < count; ++i) order[i] = i;
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return key(a) > key(b); });
     return order;
+}
+
+constexpr int64_t SMALL_M = 64;      // fast-mode products with M up to this run the streaming kernel
+
+AqGemmTask make_small_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset,
+                           float* Y, int64_t ldy, int wg_begin)
+{
+    AqGemmTask t;
+    std::memset(&t, 0, sizeof(t));
+    t.blob = static_cast<const uint8_t*>(packed);
+    t.Y = Y;
+    t.N = N; t.M = M; t.ldy = ldy;
+    t.xt_offset = xt_offset;
+    t.K = (int32_t)K; t.bits = bits; t.nchunks = (int32_t)aq_num_chunks(K);
+    t.slabs = (int32_t)aq_num_groups(N);
+    t.wg_begin = wg_begin;
+    t.wg_count = t.slabs;                 // one workgroup per 128-row group, all rows of X
+    return t;
+}
+
+AqRetileTask make_small_retile_task(const void* X, int64_t M, int64_t K, int64_t ldx, int64_t xt_offset, int MT)
+{
+    AqRetileTask r;
+    std::memset(&r, 0, sizeof(r));
+    r.X = static_cast<const uint16_t*>(X);
+    r.M = M; r.ldx = ldx; r.xt_offset = xt_offset;
+    r.K = (int32_t)K;
+    r.blocks = MT * 16;
+    r.pad = MT;
+    return r;
 }
 
 int check_flags(int flags) { return (flags == AQ_GEMM_EXACT || flags == AQ_GEMM_FAST) ? AQ_OK : AQ_EINVAL; }
@@ -250,7 +281,8 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream)
 size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits)
 {
     if (check_matrix(N, K, bits, AQ_BLOCK) != AQ_OK || M < 1 || M > AQ_MAX_M) return 0;
-    return aqk_retile_bytes(M, K);
+    const size_t a = aqk_retile_bytes(M, K), b = M <= SMALL_M ? aqk_small_retile_bytes(M, K) : 0;
+    return a > b ? a : b;      // either mode's layout of X fits
 }
 
 int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M,
@@ -262,9 +294,16 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, cons
     if ((rc = check_flags(flags)) != AQ_OK) return rc;
     if (!workspace) return AQ_ENULL;
     if (!aligned16(workspace)) return AQ_EALIGN;
-    if (workspace_bytes < aqk_retile_bytes(M, K)) return AQ_ESIZE;
+    if (workspace_bytes < aq_qgemm_workspace_size(M, N, K, bits)) return AQ_ESIZE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int fast = flags == AQ_GEMM_FAST, convert = fast && x_dtype == AQ_BF16;
+    if (fast && M <= SMALL_M) {
+        const int MT = aqk_small_mtiles(M);
+        const AqRetileTask r = make_small_retile_task(X, M, K, ldx, 0, MT);
+        if (aqk_small_retile(nullptr, 0, r, MT, x_dtype == AQ_BF16, workspace, s) != hipSuccess) return AQ_ELAUNCH;
+        const AqGemmTask t = make_small_task(packed, N, K, bits, M, 0, Y, ldy, 0);
+        return aqk_gemm_small(nullptr, 0, t, bits, MT, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    }
     const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
     if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
     const int A = aqk_gemm_mtiles(M, aq_num_groups(N)), nsplit = aqk_gemm_nsplit(M);
@@ -305,6 +344,7 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int fla
     h.mtiles = aqk_gemm_mtiles(max_M, groups);
     h.nsplit = aqk_gemm_nsplit(max_M);
     h.fast = flags == AQ_GEMM_FAST;
+    h.small_mt = (h.fast && max_M <= SMALL_M) ? aqk_small_mtiles(max_M) : 0;
     const int convert = h.fast && h.x_dtype == AQ_BF16;
     uint8_t* base = static_cast<uint8_t*>(plan_host);
     uint8_t* tasks = base + sizeof(GemmPlanHeader);
@@ -322,11 +362,17 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int fla
             if (r.X == d.X && r.M == d.M && r.K == d.K && r.ldx == d.ldx) { off = r.xt_offset; break; }
         if (off < 0) {
             off = ws;
-            rt.push_back(make_retile_task(d.X, d.M, d.K, d.ldx, off, convert));
-            ws += (int64_t)aqk_retile_bytes(d.M, d.K);
+            if (h.small_mt) {
+                rt.push_back(make_small_retile_task(d.X, d.M, d.K, d.ldx, off, h.small_mt));
+                ws += (int64_t)aqk_small_retile_bytes(max_M, d.K);
+            } else {
+                rt.push_back(make_retile_task(d.X, d.M, d.K, d.ldx, off, convert));
+                ws += (int64_t)aqk_retile_bytes(d.M, d.K);
+            }
             if (rt.back().blocks > h.retile_max_blocks) h.retile_max_blocks = rt.back().blocks;
         }
-        AqGemmTask t = make_gemm_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, h.mtiles, h.nsplit, (int)begin);
+        AqGemmTask t = h.small_mt ? make_small_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, (int)begin)
+                                  : make_gemm_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, h.mtiles, h.nsplit, (int)begin);
         begin += t.wg_count;
         if (begin > 0x7FFFFFFF) return AQ_EINVAL;
         std::memcpy(tasks + (size_t)i * sizeof(AqGemmTask), &t, sizeof(t));
@@ -347,7 +393,8 @@ static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
            check_dtype(h.x_dtype) == AQ_OK && h.retile_count >= 1 && h.retile_count <= h.count &&
            h.retile_max_blocks >= 1 && h.workspace_bytes >= 1024 &&
            (h.nsplit == 1 || ((h.nsplit == 2 || h.nsplit == 4 || h.nsplit == 8) && h.mtiles == 1)) &&
-           (h.fast == 0 || h.fast == 1);
+           (h.fast == 0 || h.fast == 1) &&
+           (h.small_mt == 0 || (h.fast == 1 && (h.small_mt == 1 || h.small_mt == 2 || h.small_mt == 4)));
 }
 
 size_t aq_qgemm_batch_workspace_size(const void* plan_host)
@@ -372,10 +419,16 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
     AqRetileTask rnone;
     std::memset(&rnone, 0, sizeof(rnone));
     const int convert = h.fast && h.x_dtype == AQ_BF16;
-    if (aqk_retile(rtasks, h.retile_count, rnone, h.retile_max_blocks, convert, workspace, s) != hipSuccess)
-        return AQ_ELAUNCH;
     AqGemmTask none;
     std::memset(&none, 0, sizeof(none));
+    if (h.small_mt) {
+        if (aqk_small_retile(rtasks, h.retile_count, rnone, h.small_mt, h.x_dtype == AQ_BF16, workspace, s) != hipSuccess)
+            return AQ_ELAUNCH;
+        return aqk_gemm_small(tasks, h.count, none, h.bits, h.small_mt, h.total_wgs, workspace, s) == hipSuccess
+                   ? AQ_OK : AQ_ELAUNCH;
+    }
+    if (aqk_retile(rtasks, h.retile_count, rnone, h.retile_max_blocks, convert, workspace, s) != hipSuccess)
+        return AQ_ELAUNCH;
     return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.nsplit, h.fast, h.total_wgs, workspace, s) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
 }

@@ -47,7 +47,7 @@ struct AqRetileTask {
     int32_t K;
     int32_t blocks;     // workgroups of 256 threads: one 16-byte piece per thread, or one row per workgroup
     int32_t convert;
-    int32_t pad;
+    int32_t pad;        // small-M layout: m-tiles of the launch (1, 2, 4); else 0
 };
 static_assert(sizeof(AqRetileTask) == 48, "AqRetileTask must stay 48 bytes");
 
@@ -84,3 +84,11 @@ hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& si
 // Block-level scale optimisation: fp32 W, F (F may be null = all ones) -> canonical codes + fp16 scales
 hipError_t aqk_optimize_scales(const float* W, const float* F, int64_t N, int64_t K, int bits, int rounds,
                                uint8_t* codes, uint16_t* scales, hipStream_t s);
+
+// Prefill for M <= 64 in the fp16-weight mode: streaming kernel, its own X layout ("Xs")
+int aqk_small_mtiles(int64_t M);
+size_t aqk_small_retile_bytes(int64_t M, int64_t K);
+hipError_t aqk_small_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int MT, int bf16,
+                            void* workspace, hipStream_t s);
+hipError_t aqk_gemm_small(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int MT,
+                          int total_wgs, const void* workspace, hipStream_t s);

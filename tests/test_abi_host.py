@@ -104,7 +104,9 @@ def test_gemm_batch_plan_validation_and_workspace(L):
     # one re-ordered copy per distinct X: rows rounded up to 16, 2 bytes per element
     assert L.aq_qgemm_batch_workspace_size(buf) == (304 * 4096 * 2 + 2048) + (304 * 2048 * 2 + 2048)
     assert L.aq_qgemm_workspace_size(300, 4096, 4096, 2) == 304 * 4096 * 2 + 2048
-    assert L.aq_qgemm_workspace_size(1, 16, 32, 4) == 16 * 32 * 2 + 1024
+    # M <= 64: room for the streaming kernel's layout as well (k padded to 256, 16 rows: 8 KiB per chunk, + 1 KiB)
+    assert L.aq_qgemm_workspace_size(1, 16, 32, 4) == 8 * 1024 + 1024
+    assert L.aq_qgemm_workspace_size(64, 16, 2048, 4) == 8 * 8 * 4 * 1024 + 1024
     # same pointer but another row stride is another copy
     descs[1].ldx = 4096 + 8
     assert L.aq_qgemm_batch_plan(descs, n, 32, 0, buf, size) == aq.AQ_OK

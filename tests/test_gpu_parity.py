@@ -365,7 +365,8 @@ FAST_EXPECTED = {2: 2e-5, 3: 3e-4, 4: 3e-4}
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("N,K,M", [(200, 1056, 7), (256, 2048, 64), (512, 512, 300), (130, 4096, 81), (96, 544, 385)])
+@pytest.mark.parametrize("N,K,M", [(200, 1056, 7), (256, 2048, 64), (512, 512, 300), (130, 4096, 81), (96, 544, 385),
+                                   (17, 96, 1), (144, 288, 16), (272, 1056, 17), (128, 2048, 33), (1000, 4096, 48)])
 def test_qgemm_fast_matches_oracle(gpu, oracle, bits, N, K, M, dtype):
     torch, aq = gpu
     codes, scales = wl.draw_matrix(N, K, bits, 18, N, K)
@@ -429,11 +430,14 @@ def test_qgemm_fast_row_factors_and_large_scales(gpu, oracle):
     big = wl.f32_to_f16_bits(np.ldexp(wl.f16_bits_to_f32(scales), 19))
     assert wl.f16_bits_to_f32(big).max() > 8192 and np.isfinite(wl.f16_bits_to_f32(big)).all()
     packed = _pack(torch, aq, codes, big, N, K, bits)
-    X = wl.draw_activations(M, K, "bf16", 21, 1)
-    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
-    ref = oracle.qmatmul(codes, big, N, K, bits, X, "bf16")
-    assert np.isfinite(Y).all()
-    assert oracle.rel_l2(Y, ref) <= 2e-5                # no weight was rounded
+    # M > 64: the workgroups take the exact path (no weight is rounded); M <= 64 runs the streaming kernel, which
+    # scales every d by a power of two before the binary16 product instead
+    for M2, bar in ((100, 2e-5), (M, FAST_EXPECTED[bits])):
+        X = wl.draw_activations(M2, K, "bf16", 21, M2)
+        Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
+        ref = oracle.qmatmul(codes, big, N, K, bits, X, "bf16")
+        assert np.isfinite(Y).all()
+        assert oracle.rel_l2(Y, ref) <= bar, M2
 
 
 def test_qgemm_fast_batch_full_size_sampled(gpu, oracle):
@@ -559,3 +563,27 @@ def test_optimize_scales_errors(gpu):
         aq.aq_optimize_scales(W, None, 4, 65)
     with pytest.raises(aq.AqError):
         aq.aq_optimize_scales(W, None, 4, -1)
+
+
+def test_qgemm_fast_small_m_batch(gpu, oracle):
+    """Mixed-bit list at M <= 64 (the streaming kernel), shared and separate activations, f16 and bf16."""
+    torch, aq = gpu
+    for dtype in ("bf16", "f16"):
+        M = 40
+        Xs = {K: wl.draw_activations(M, K, dtype, 23, K) for K in (1056, 2048)}
+        Xd = {K: _dev(torch, x, dtype) for K, x in Xs.items()}
+        items, refs = [], []
+        for i, (N, K, bits) in enumerate([(272, 1056, 2), (130, 2048, 3), (512, 1056, 4), (64, 2048, 2), (1000, 2048, 4)]):
+            codes, scales = wl.draw_matrix(N, K, bits, 23, i)
+            packed = _pack(torch, aq, codes, scales, N, K, bits)
+            Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+            items.append((packed, N, K, bits, Xd[K], Y))
+            refs.append((oracle.qmatmul(codes, scales, N, K, bits, Xs[K], dtype), bits))
+        batch = aq.GemmBatch(items, fast=True)
+        batch.run()
+        batch.run()
+        torch.cuda.synchronize()
+        for (packed, N, K, bits, xd, Y), (ref, b) in zip(items, refs):
+            got = Y.cpu().numpy()
+            assert np.isfinite(got).all()
+            assert oracle.rel_l2(got, ref) <= FAST_EXPECTED[b]
