@@ -115,7 +115,10 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
  *       (relative error <= 2^-12 per weight, rel-L2 of Y ~1e-4).  bf16 activations are first converted to
  *       binary16 with one power-of-two factor per row (exact unless an element is 2^38 times smaller than
  *       its row's largest).  A matrix whose largest |d| * 2^(bits-1) would overflow binary16 is computed as
- *       in AQ_GEMM_EXACT (decided on the device from the blob).
+ *       in AQ_GEMM_EXACT (decided on the device from the blob).  For M <= 64 the product runs in a kernel
+ *       bound by the weight stream (wavefronts keep their packed tiles in registers over all of K; weights
+ *       never pass through LDS); there such a matrix has every scale multiplied by one power of two
+ *       2^-s first (s <= 4) and the result by 2^s, same error bound unless d < 2^(s-14).
  *   X   DEVICE uint16 [M][ldx], ldx >= K and ldx % 8 == 0, x_dtype = AQ_BF16 or AQ_F16
  *   Y   DEVICE float  [M][ldy], ldy >= N, overwritten for m < M, n < N
  *   workspace DEVICE, 16-byte aligned, workspace_bytes >= aq_qgemm_workspace_size(M, N, K, bits)
