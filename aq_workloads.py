@@ -284,6 +284,89 @@ def iter_stream_inputs(stream: Sequence[MatrixSpec], M: int, dtype: str, seed: i
 # from the numpy draws (another generator) but follow the same recipe; the bench
 # copies what the oracle needs back to the host.
 # ----------------------------------------------------------------------------
+# transformer blocks for the layer-by-layer decode step: the seven matrices of a layer with scales sized so
+# that a matrix maps a vector of unit rms to one of rms `gain` (sub-layer outputs stay a fraction of the
+# residual stream, as in a trained model), norm multipliers near one, x ~ N(0,1)
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class BlockShape:
+    d_model: int
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    d_ff: int
+    act: str
+    eps: float
+
+    def matrix_shape(self, name: str) -> Tuple[int, int]:
+        dq, dkv = self.n_heads * self.head_dim, self.n_kv_heads * self.head_dim
+        return {"q": (dq, self.d_model), "k": (dkv, self.d_model), "v": (dkv, self.d_model),
+                "o": (self.d_model, dq), "gate": (self.d_ff, self.d_model), "up": (self.d_ff, self.d_model),
+                "down": (self.d_model, self.d_ff)}[name]
+
+
+BLOCK_MATRICES = ("q", "k", "v", "o", "gate", "up", "down")
+BLOCK_SHAPES = {
+    "llama2-7b": BlockShape(4096, 32, 32, 128, 11008, "silu", 1e-5),
+    "gemma-2b": BlockShape(2048, 8, 1, 256, 16384, "gelu_tanh", 1e-6),
+}
+BLOCK_GAIN = {"q": 1.0, "k": 1.0, "v": 1.0, "o": 0.3, "gate": 1.0, "up": 1.0, "down": 0.6}
+
+
+def code_rms(bits: int) -> float:
+    """Root mean square of (q - 2^(bits-1)) for q uniform over the 2^bits codes."""
+    z = 1 << (bits - 1)
+    return float(np.sqrt(np.mean([(q - z) ** 2 for q in range(1 << bits)])))
+
+
+def draw_gain_scales(N: int, K: int, bits: int, gain: float, *key: int) -> np.ndarray:
+    """fp16 bit patterns uint16[N, K/32] of d = fp16(N(0,1) * gain / (code_rms * sqrt(K))).  The sign is kept:
+    the code grid {-z .. z-1} is not symmetric, and blocks whose scale is negative use its mirror image, so the
+    weights have zero mean (uniform codes under positive scales would all lean to the negative side and the
+    residual stream would drift along the all-ones direction)."""
+    nb = K // BLOCK
+    g = _rng(202, *key)
+    d = g.standard_normal(size=(N, nb), dtype=np.float32) * np.float32(gain / (code_rms(bits) * np.sqrt(K)))
+    return f32_to_f16_bits(d)
+
+
+def draw_norm_weights(n: int, *key: int) -> np.ndarray:
+    g = _rng(909, *key)
+    return (1.0 + 0.1 * g.standard_normal(size=n, dtype=np.float32)).astype(np.float32)
+
+
+def draw_residual(n: int, *key: int) -> np.ndarray:
+    return _rng(910, *key).standard_normal(size=n, dtype=np.float32)
+
+
+def draw_block_stack(shape: BlockShape, bits: Sequence[Sequence[int]], *key: int) -> List[dict]:
+    """layers[l] = {name: (codes, scales, bits) for the seven matrices, "norm_attn": g, "norm_mlp": g};
+    bits[l][j] is the bit-width of matrix j (order of BLOCK_MATRICES) of layer l."""
+    layers = []
+    for l, row in enumerate(bits):
+        layer = {}
+        for j, name in enumerate(BLOCK_MATRICES):
+            N, K = shape.matrix_shape(name)
+            b = int(row[j])
+            layer[name] = (draw_codes(N, K, b, *key, l, j), draw_gain_scales(N, K, b, BLOCK_GAIN[name], *key, l, j), b)
+        layer["norm_attn"] = draw_norm_weights(shape.d_model, *key, l, 0)
+        layer["norm_mlp"] = draw_norm_weights(shape.d_model, *key, l, 1)
+        layers.append(layer)
+    return layers
+
+
+def draw_gain_matrix_torch(N: int, K: int, bits: int, gain: float, device, *key: int):
+    """Device-side draw of the same distribution as draw_codes + draw_gain_scales (other random numbers)."""
+    import torch
+    nb = K // BLOCK
+    g = _torch_gen(device, 101, *key)
+    codes = torch.randint(0, 256, (N, nb, 4 * bits), dtype=torch.uint8, device=device, generator=g)
+    d = torch.randn((N, nb), dtype=torch.float32, device=device, generator=g)
+    d.mul_(float(gain / (code_rms(bits) * np.sqrt(K))))
+    return codes, d.to(torch.float16)
+
+
+# ----------------------------------------------------------------------------
 def _torch_gen(device, *key: int):
     import torch
     g = torch.Generator(device=device)
