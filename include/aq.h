@@ -190,6 +190,52 @@ int aq_optimize_scales(const float* W, const float* F, int64_t N, int64_t K, int
 int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const int* choices, int n_choices,
                      double avg_bits_budget, int* bits_out);
 
+/* One decode step (M = 1) through a stack of transformer blocks, layer by layer, with what sits between the
+ * matrices fused into the matrix-vector kernels.  Section 3 ("Vision-Language-Action models") names a block's
+ * matrices: the attention projections W_Q, W_K, W_V, W_O and the MLP's W_gate, W_up, W_down; the rest is the
+ * published architecture of the backbones the paper quantises (LLaMA-2-7B; a Gemma-2B-sized one):
+ *     h = rmsnorm(x; norm_attn)                  rmsnorm(x; g)_i = x_i / sqrt(mean(x^2) + eps) * g_i
+ *     q, k, v = W_Q h, W_K h, W_V h              written to qkv[layer] = [q | k | v] (what a key/value cache
+ *                                                and a later attention read; no rotary embedding applied)
+ *     x += W_O a                                 a = attention over the ONE visible key (the step is the first
+ *                                                token of a sequence): query head i gets value head
+ *                                                i / (n_heads / n_kv_heads).  Attention over a longer cache
+ *                                                is not part of this library.
+ *     h2 = rmsnorm(x; norm_mlp);  x += W_down (act(W_gate h2) * W_up h2)
+ * Four dependent launches per layer (q/k/v; o; gate/up; down) plus one that clears qkv.  Inputs of the
+ * products are rounded to binary16 times a power of two (11 significant bits); sums are fp32; a stage's partial
+ * sums meet in fp32 atomic additions, so the last bits of a result can differ between runs.
+ *   shape      HOST; d_model, d_ff, n_heads * head_dim multiples of 32 and <= 65536, head_dim a multiple of 8,
+ *              n_heads a multiple of n_kv_heads, act = AQ_ACT_SILU or AQ_ACT_GELU_TANH, eps >= 0
+ *   blocks     HOST array of `layers` records: w[0..6] = DEVICE blobs (aq_pack_weights) of q, k, v, o, gate, up,
+ *              down with the shapes the block shape implies and bit-widths bits[0..6]; norm_attn, norm_mlp =
+ *              DEVICE float [d_model], 16-byte aligned (the multipliers themselves; a Gemma checkpoint stores g - 1)
+ *   x          DEVICE float [d_model], 16-byte aligned: the residual stream, read and overwritten by a step
+ *   qkv        DEVICE float [layers][n_heads * head_dim + 2 * n_kv_heads * head_dim], overwritten by a step
+ *   workspace  DEVICE, 16-byte aligned, aq_decode_workspace_size(shape) bytes (gate and up of the current layer)
+ * aq_decode_plan binds these buffers into a plan image of aq_decode_plan_size(layers) bytes on the HOST; copy
+ * the image to 16-byte-aligned DEVICE memory and pass both to aq_decode_step, which may be repeated (each call
+ * advances x by one pass through the stack).  Steps that share buffers must be ordered on one stream. */
+#define AQ_ACT_SILU      0
+#define AQ_ACT_GELU_TANH 1
+typedef struct aq_block_shape {
+    int32_t d_model, n_heads, n_kv_heads, head_dim, d_ff;
+    int32_t act;
+    float   eps;
+} aq_block_shape;
+typedef struct aq_block_desc {
+    const void*  w[7];
+    int32_t      bits[7];
+    const float* norm_attn;
+    const float* norm_mlp;
+} aq_block_desc;
+size_t aq_decode_plan_size(int layers);
+size_t aq_decode_workspace_size(const aq_block_shape* shape);
+int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks /*HOST*/, int layers, int block,
+                   float* x, float* qkv, void* workspace, size_t workspace_bytes,
+                   void* plan_host, size_t plan_bytes);
+int aq_decode_step(const void* plan_host, const void* plan_dev, void* stream);
+
 /* Parity / debug: the blob decoded back to what Eq. 1 defines.
  *   codes_u8 DEVICE uint8 [N][K]  one code per byte
  *   W        DEVICE float [N][K]  d * (q - 2^(bits-1)); exact in fp32 (11-bit x 4-bit significands) */

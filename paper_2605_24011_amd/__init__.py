@@ -15,6 +15,8 @@ AQ_OK = 0
 AQ_EINVAL, AQ_ENULL, AQ_EALIGN, AQ_ESIZE, AQ_EDTYPE, AQ_ELAUNCH = -1, -2, -3, -4, -5, -6
 AQ_F16, AQ_BF16 = 1, 2
 AQ_GEMM_EXACT, AQ_GEMM_FAST = 0, 1
+AQ_ACT_SILU, AQ_ACT_GELU_TANH = 0, 1
+BLOCK_MATRICES = ("q", "k", "v", "o", "gate", "up", "down")
 BLOCK = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -33,6 +35,15 @@ class AqError(RuntimeError):
 class aq_gemv_desc(ctypes.Structure):
     _fields_ = [("packed", _p), ("x", _p), ("y", _p), ("N", _i64), ("K", _i64),
                 ("bits", ctypes.c_int32), ("x_dtype", ctypes.c_int32)]
+
+
+class aq_block_shape(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("act", ctypes.c_int32), ("eps", ctypes.c_float)]
+
+
+class aq_block_desc(ctypes.Structure):
+    _fields_ = [("w", _p * 7), ("bits", ctypes.c_int32 * 7), ("norm_attn", _p), ("norm_mlp", _p)]
 
 
 class aq_gemm_desc(ctypes.Structure):
@@ -77,6 +88,13 @@ def lib() -> ctypes.CDLL:
         L.aq_qgemm_batch.argtypes = [_p, _p, _p, _sz, _p]
         L.aq_optimize_scales.argtypes = [_p, _p, _i64, _i64, _int, _int, _int, _p, _p, _p]
         L.aq_allocate_bits.argtypes = [_p, _p, _int, _int, _p, _int, ctypes.c_double, _p]
+        L.aq_decode_plan_size.restype = _sz
+        L.aq_decode_plan_size.argtypes = [_int]
+        L.aq_decode_workspace_size.restype = _sz
+        L.aq_decode_workspace_size.argtypes = [ctypes.POINTER(aq_block_shape)]
+        L.aq_decode_plan.argtypes = [ctypes.POINTER(aq_block_shape), ctypes.POINTER(aq_block_desc), _int, _int,
+                                     _p, _p, _p, _sz, _p, _sz]
+        L.aq_decode_step.argtypes = [_p, _p, _p]
         L.aq_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         _lib = L
@@ -227,6 +245,42 @@ def aq_allocate_bits(S, sizes, choices=(2, 3, 4), avg_bits_budget: float = 2.5):
     out = (ctypes.c_int * (L * J))()
     _check(lib().aq_allocate_bits(Sa, na, L, J, ca, len(choices), float(avg_bits_budget), out), "aq_allocate_bits")
     return [[int(out[l * J + j]) for j in range(J)] for l in range(L)]
+
+
+class DecodeStep:
+    """A planned decode step through a stack of transformer blocks (aq_decode_plan / aq_decode_step).
+
+    layers[l] = {"q": (packed, bits), ..., "down": (packed, bits), "norm_attn": float32 tensor, "norm_mlp": ...};
+    x: float32 [d_model] residual stream (advanced in place by run()); qkv: float32
+    [layers, n_heads*head_dim + 2*n_kv_heads*head_dim], overwritten by run().  Holds references to every tensor."""
+
+    def __init__(self, d_model: int, n_heads: int, n_kv_heads: int, head_dim: int, d_ff: int, act: str, eps: float,
+                 layers: Sequence[dict], x, qkv, block: int = BLOCK):
+        import torch
+        acts = {"silu": AQ_ACT_SILU, "gelu_tanh": AQ_ACT_GELU_TANH}
+        if act not in acts:
+            raise AqError(AQ_EINVAL, "DecodeStep")
+        self.shape = aq_block_shape(d_model, n_heads, n_kv_heads, head_dim, d_ff, acts[act], eps)
+        n = len(layers)
+        descs = (aq_block_desc * max(n, 1))()
+        for d, layer in zip(descs, layers):
+            for j, name in enumerate(BLOCK_MATRICES):
+                packed, bits = layer[name]
+                d.w[j] = packed.data_ptr()
+                d.bits[j] = bits
+            d.norm_attn, d.norm_mlp = layer["norm_attn"].data_ptr(), layer["norm_mlp"].data_ptr()
+        ws = int(lib().aq_decode_workspace_size(ctypes.byref(self.shape)))
+        self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=x.device)
+        size = int(lib().aq_decode_plan_size(n))
+        self.plan_host = torch.empty(max(size, 16), dtype=torch.uint8)
+        _check(lib().aq_decode_plan(ctypes.byref(self.shape), descs, n, block, x.data_ptr(), qkv.data_ptr(),
+                                    self.workspace.data_ptr(), ws, self.plan_host.data_ptr(), size), "aq_decode_plan")
+        self.plan_dev = self.plan_host.to(x.device)
+        self.layers, self.x, self.qkv = list(layers), x, qkv
+
+    def run(self, stream=None) -> None:
+        _check(lib().aq_decode_step(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), _stream(stream)),
+               "aq_decode_step")
 
 
 def aq_unpack_codes(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):

@@ -159,6 +159,36 @@ AqGemvTask make_task(const void* packed, int64_t N, int64_t K, int bits, const v
     return t;
 }
 
+// Plan image of the layer-by-layer decode step: this header, one DecodeStage per launch, the task records.
+struct DecodePlanHeader {
+    uint32_t magic;
+    int32_t layers;
+    int32_t stages;
+    int32_t reserved;
+    float* qkv;              // cleared at the start of every step
+    int64_t qkv_floats;
+    float* gateup;           // cleared by the o stage of every layer
+    int64_t gateup_floats;
+};
+static_assert(sizeof(DecodePlanHeader) == 48, "DecodePlanHeader must stay 48 bytes");
+struct DecodeStage {
+    int32_t task_begin, task_count, total_wgs, clears_gateup;
+};
+constexpr uint32_t DECODE_MAGIC = 0x41514431u;  // "AQD1"
+constexpr int DECODE_TARGET_WGS = 768;          // workgroups a stage is split into, about (3 per compute unit)
+
+// chunks per workgroup: as many as keep the stage at DECODE_TARGET_WGS workgroups or more, at least 2 when the
+// matrices are deep enough (both ring slots of a wavefront in use), at most AQ_STAGE_MAX_PART
+int decode_part_chunks(int64_t stage_rows, int nchunks)
+{
+    const int64_t groups = (stage_rows + AQ_GROUP_ROWS - 1) / AQ_GROUP_ROWS;
+    int64_t p = groups * nchunks / DECODE_TARGET_WGS;
+    if (p < 2) p = 2;
+    if (p > AQ_STAGE_MAX_PART) p = AQ_STAGE_MAX_PART;
+    if (p > nchunks) p = nchunks;
+    return (int)p;
+}
+
 }  // namespace
 
 extern "C" {
@@ -491,6 +521,148 @@ int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const 
         used += best_dbits;
     }
     for (int64_t i = 0; i < (int64_t)L * J; ++i) bits_out[i] = choices[level[(size_t)i]];
+    return AQ_OK;
+}
+
+size_t aq_decode_plan_size(int layers)
+{
+    if (layers < 1) return 0;
+    return sizeof(DecodePlanHeader) + (size_t)layers * (4 * sizeof(DecodeStage) + 7 * sizeof(AqStageTask));
+}
+
+size_t aq_decode_workspace_size(const aq_block_shape* shape)
+{
+    if (!shape || shape->d_ff < 1) return 0;
+    return (size_t)2 * (size_t)shape->d_ff * sizeof(float);
+}
+
+int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int layers, int block,
+                   float* x, float* qkv, void* workspace, size_t workspace_bytes, void* plan_host, size_t plan_bytes)
+{
+    if (!shape || !blocks || !x || !qkv || !workspace || !plan_host) return AQ_ENULL;
+    if (layers < 1 || block != AQ_BLOCK) return AQ_EINVAL;
+    const aq_block_shape& sh = *shape;
+    if (sh.d_model < 32 || sh.d_ff < 32 || sh.d_model % 32 || sh.d_ff % 32 || sh.d_model > 65536 || sh.d_ff > 65536)
+        return AQ_EINVAL;
+    if (sh.n_heads < 1 || sh.n_kv_heads < 1 || sh.n_heads % sh.n_kv_heads || sh.head_dim < 8 || sh.head_dim % 8)
+        return AQ_EINVAL;
+    const int64_t dq = (int64_t)sh.n_heads * sh.head_dim, dkv = (int64_t)sh.n_kv_heads * sh.head_dim;
+    if (dq % 32 || dkv % 32 || dq > 65536) return AQ_EINVAL;
+    if (sh.act != AQ_ACT_SILU && sh.act != AQ_ACT_GELU_TANH) return AQ_EINVAL;
+    if (!(sh.eps >= 0.f)) return AQ_EINVAL;
+    if (!aligned16(x) || !aligned16(qkv) || !aligned16(workspace)) return AQ_EALIGN;
+    if (workspace_bytes < aq_decode_workspace_size(shape) || plan_bytes < aq_decode_plan_size(layers)) return AQ_ESIZE;
+    for (int l = 0; l < layers; ++l) {
+        for (int j = 0; j < 7; ++j) {
+            if (!blocks[l].w[j]) return AQ_ENULL;
+            if (!aligned16(blocks[l].w[j])) return AQ_EALIGN;
+            if (blocks[l].bits[j] < 2 || blocks[l].bits[j] > 4) return AQ_EINVAL;
+        }
+        if (!blocks[l].norm_attn || !blocks[l].norm_mlp) return AQ_ENULL;
+        if (!aligned16(blocks[l].norm_attn) || !aligned16(blocks[l].norm_mlp)) return AQ_EALIGN;
+    }
+
+    float* gate = static_cast<float*>(workspace);
+    float* up = gate + sh.d_ff;
+    const int64_t per_layer = dq + 2 * dkv;
+    DecodePlanHeader h;
+    std::memset(&h, 0, sizeof(h));
+    h.magic = DECODE_MAGIC;
+    h.layers = layers;
+    h.stages = 4 * layers;
+    h.qkv = qkv;
+    h.qkv_floats = per_layer * layers;
+    h.gateup = gate;
+    h.gateup_floats = 2 * (int64_t)sh.d_ff;
+    uint8_t* base = static_cast<uint8_t*>(plan_host);
+    DecodeStage* stages = reinterpret_cast<DecodeStage*>(base + sizeof(DecodePlanHeader));
+    AqStageTask* tasks = reinterpret_cast<AqStageTask*>(base + sizeof(DecodePlanHeader) + (size_t)h.stages * sizeof(DecodeStage));
+
+    auto make = [&](const aq_block_desc& b, int j, int64_t N, int64_t K, int part, float* y, const float* in0,
+                    const float* in1, int prologue, int& wgs) {
+        AqStageTask t;
+        std::memset(&t, 0, sizeof(t));
+        t.blob = static_cast<const uint8_t*>(b.w[j]);
+        t.y = y;
+        t.in0 = in0;
+        t.in1 = in1;
+        t.N = (int32_t)N;
+        t.K = (int32_t)K;
+        t.bits = b.bits[j];
+        t.nchunks = (int32_t)aq_num_chunks(K);
+        t.part_chunks = part;
+        t.parts = (t.nchunks + part - 1) / part;
+        t.wg_begin = wgs;
+        t.wg_count = (int32_t)(aq_num_groups(N) * t.parts);
+        t.prologue = prologue;
+        t.act = sh.act;
+        t.head_dim = sh.head_dim;
+        t.rep = (prologue == AQ_PRO_PLAIN) ? sh.n_heads / sh.n_kv_heads : 1;
+        t.eps = sh.eps;
+        wgs += t.wg_count;
+        return t;
+    };
+
+    int nt = 0;
+    for (int l = 0; l < layers; ++l) {
+        const aq_block_desc& b = blocks[l];
+        float* q = qkv + per_layer * l;
+        float* k = q + dq;
+        float* v = k + dkv;
+        DecodeStage* st = stages + 4 * l;
+        int wgs = 0;
+        // q, k, v from the normalised residual stream
+        int part = decode_part_chunks(dq + 2 * dkv, (int)aq_num_chunks(sh.d_model));
+        st[0].task_begin = nt;
+        tasks[nt++] = make(b, 0, dq, sh.d_model, part, q, x, b.norm_attn, AQ_PRO_NORM, wgs);
+        tasks[nt++] = make(b, 1, dkv, sh.d_model, part, k, x, b.norm_attn, AQ_PRO_NORM, wgs);
+        tasks[nt++] = make(b, 2, dkv, sh.d_model, part, v, x, b.norm_attn, AQ_PRO_NORM, wgs);
+        st[0].task_count = 3; st[0].total_wgs = wgs; st[0].clears_gateup = 0;
+        // x += W_O a, a = the value head of each query head (attention over the one visible key)
+        wgs = 0;
+        part = decode_part_chunks(sh.d_model, (int)aq_num_chunks(dq));
+        st[1].task_begin = nt;
+        tasks[nt++] = make(b, 3, sh.d_model, dq, part, x, v, nullptr, AQ_PRO_PLAIN, wgs);
+        st[1].task_count = 1; st[1].total_wgs = wgs; st[1].clears_gateup = 1;
+        // gate, up from the normalised residual stream
+        wgs = 0;
+        part = decode_part_chunks(2 * (int64_t)sh.d_ff, (int)aq_num_chunks(sh.d_model));
+        st[2].task_begin = nt;
+        tasks[nt++] = make(b, 4, sh.d_ff, sh.d_model, part, gate, x, b.norm_mlp, AQ_PRO_NORM, wgs);
+        tasks[nt++] = make(b, 5, sh.d_ff, sh.d_model, part, up, x, b.norm_mlp, AQ_PRO_NORM, wgs);
+        st[2].task_count = 2; st[2].total_wgs = wgs; st[2].clears_gateup = 0;
+        // x += W_down (act(gate) * up)
+        wgs = 0;
+        part = decode_part_chunks(sh.d_model, (int)aq_num_chunks(sh.d_ff));
+        st[3].task_begin = nt;
+        tasks[nt++] = make(b, 6, sh.d_model, sh.d_ff, part, x, gate, up, AQ_PRO_GATED, wgs);
+        st[3].task_count = 1; st[3].total_wgs = wgs; st[3].clears_gateup = 0;
+    }
+    std::memcpy(base, &h, sizeof(h));
+    return AQ_OK;
+}
+
+int aq_decode_step(const void* plan_host, const void* plan_dev, void* stream)
+{
+    if (!plan_host || !plan_dev) return AQ_ENULL;
+    if (!aligned16(plan_dev)) return AQ_EALIGN;
+    DecodePlanHeader h;
+    std::memcpy(&h, plan_host, sizeof(h));
+    if (h.magic != DECODE_MAGIC || h.layers < 1 || h.stages != 4 * h.layers) return AQ_EINVAL;
+    const uint8_t* hb = static_cast<const uint8_t*>(plan_host);
+    const DecodeStage* stages = reinterpret_cast<const DecodeStage*>(hb + sizeof(DecodePlanHeader));
+    const AqStageTask* tasks_dev = reinterpret_cast<const AqStageTask*>(
+        static_cast<const uint8_t*>(plan_dev) + sizeof(DecodePlanHeader) + (size_t)h.stages * sizeof(DecodeStage));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (aqk_fill_zero(h.qkv, h.qkv_floats, s) != hipSuccess) return AQ_ELAUNCH;
+    for (int i = 0; i < h.stages; ++i) {
+        const DecodeStage& st = stages[i];
+        if (st.task_count < 1 || st.total_wgs < 1) return AQ_EINVAL;
+        if (aqk_layer_stage(tasks_dev + st.task_begin, st.task_count, st.total_wgs,
+                            st.clears_gateup ? h.gateup : nullptr, st.clears_gateup ? (int)h.gateup_floats : 0,
+                            s) != hipSuccess)
+            return AQ_ELAUNCH;
+    }
     return AQ_OK;
 }
 

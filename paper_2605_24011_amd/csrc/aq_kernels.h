@@ -92,3 +92,36 @@ hipError_t aqk_small_retile(const AqRetileTask* tasks_dev, int count, const AqRe
                             void* workspace, hipStream_t s);
 hipError_t aqk_gemm_small(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int MT,
                           int total_wgs, const void* workspace, hipStream_t s);
+
+// Layer-by-layer decode step.  One matrix of one stage as the kernel sees it (device-visible, 96 bytes):
+// y[n] += sum over the k of a workgroup's part of W[n][k] * f(in)[k], with f chosen by `prologue`:
+//   AQ_PRO_PLAIN  f(in)[k] = in0[src(k)], src(k) = ((k / head_dim) / rep) * head_dim + k % head_dim
+//                 (rep query heads read one value head; rep = 1: src(k) = k)
+//   AQ_PRO_NORM   f(in)[k] = in0[k] / sqrt(mean(in0^2) + eps) * in1[k]         (in0 has K elements)
+//   AQ_PRO_GATED  f(in)[k] = act(in0[k]) * in1[k]                              (act 0: SiLU, 1: tanh-GELU)
+#define AQ_PRO_PLAIN 0
+#define AQ_PRO_NORM  1
+#define AQ_PRO_GATED 2
+#define AQ_STAGE_MAX_PART 8      // chunks of 256 k per workgroup at most (sets the kernel's LDS)
+struct AqStageTask {
+    const uint8_t* blob;
+    float* y;
+    const float* in0;
+    const float* in1;
+    int32_t N, K;
+    int32_t bits, nchunks;
+    int32_t part_chunks, parts;   // parts = ceil(nchunks / part_chunks), 1 <= part_chunks <= AQ_STAGE_MAX_PART
+    int32_t wg_begin, wg_count;   // wg_count = groups of 128 rows * parts
+    int32_t prologue, act;
+    int32_t head_dim, rep;
+    float eps;
+    int32_t pad0;
+    int64_t pad1;
+};
+static_assert(sizeof(AqStageTask) == 96, "AqStageTask must stay 96 bytes");
+
+// Runs the `count` (>= 1) tasks of one stage in `total_wgs` workgroups; the launch also clears
+// zero_ptr[0 .. zero_count) (a buffer that a LATER stage accumulates into; may be null with count 0).
+hipError_t aqk_layer_stage(const AqStageTask* tasks_dev, int count, int total_wgs, float* zero_ptr, int zero_count,
+                           hipStream_t s);
+hipError_t aqk_fill_zero(float* p, int64_t n, hipStream_t s);
