@@ -164,29 +164,36 @@ struct DecodePlanHeader {
     uint32_t magic;
     int32_t layers;
     int32_t stages;
-    int32_t reserved;
+    int32_t mode;            // AQ_DECODE_AUTO / _PER_STAGE / _ONE_LAUNCH
     float* qkv;              // cleared at the start of every step
     int64_t qkv_floats;
     float* gateup;           // cleared by the o stage of every layer
     int64_t gateup_floats;
+    float* x;
+    uint32_t* bar;           // two words after gate/up in the workspace: arrival counter, give-up flag
+    int32_t d_model;
+    int32_t max_wgs;         // items of the largest stage
+    int32_t spin_limit;      // polls of a grid barrier before it gives up
+    int32_t reserved;
 };
-static_assert(sizeof(DecodePlanHeader) == 48, "DecodePlanHeader must stay 48 bytes");
-struct DecodeStage {
-    int32_t task_begin, task_count, total_wgs, clears_gateup;
-};
+static_assert(sizeof(DecodePlanHeader) == 80, "DecodePlanHeader must stay 80 bytes");
+typedef AqStageEntry DecodeStage;
+constexpr int DECODE_SPIN_LIMIT = 1 << 21;      // about a second of polling
 constexpr uint32_t DECODE_MAGIC = 0x41514431u;  // "AQD1"
-constexpr int DECODE_TARGET_WGS = 768;          // workgroups a stage is split into, about (3 per compute unit)
+constexpr int DECODE_TARGET_WGS = 768;          // 256 compute units x 3 resident workgroups
 
-// chunks per workgroup: as many as keep the stage at DECODE_TARGET_WGS workgroups or more, at least 2 when the
-// matrices are deep enough (both ring slots of a wavefront in use), at most AQ_STAGE_MAX_PART
-int decode_part_chunks(int64_t stage_rows, int nchunks)
+// chunks per workgroup: the fewest (at least 2 when the matrices are deep enough, so that both ring slots of a
+// wavefront are in use; at most AQ_STAGE_MAX_PART) for which the whole stage fits the GPU in ONE round of
+// workgroups (3 per compute unit): a second, partial round would double the stage's latency
+int decode_part_chunks(const int64_t* rows, int matrices, int nchunks)
 {
-    const int64_t groups = (stage_rows + AQ_GROUP_ROWS - 1) / AQ_GROUP_ROWS;
-    int64_t p = groups * nchunks / DECODE_TARGET_WGS;
-    if (p < 2) p = 2;
-    if (p > AQ_STAGE_MAX_PART) p = AQ_STAGE_MAX_PART;
-    if (p > nchunks) p = nchunks;
-    return (int)p;
+    int p = nchunks < 2 ? nchunks : 2;
+    for (; p < AQ_STAGE_MAX_PART && p < nchunks; ++p) {
+        int64_t wgs = 0;
+        for (int i = 0; i < matrices; ++i) wgs += aq_num_groups(rows[i]) * ((nchunks + p - 1) / p);
+        if (wgs <= DECODE_TARGET_WGS) break;
+    }
+    return p;
 }
 
 }  // namespace
@@ -533,7 +540,7 @@ size_t aq_decode_plan_size(int layers)
 size_t aq_decode_workspace_size(const aq_block_shape* shape)
 {
     if (!shape || shape->d_ff < 1) return 0;
-    return (size_t)2 * (size_t)shape->d_ff * sizeof(float);
+    return (size_t)2 * (size_t)shape->d_ff * sizeof(float) + 64;     // gate, up, the barrier words
 }
 
 int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int layers, int block,
@@ -574,6 +581,11 @@ int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int
     h.qkv_floats = per_layer * layers;
     h.gateup = gate;
     h.gateup_floats = 2 * (int64_t)sh.d_ff;
+    h.x = x;
+    h.bar = reinterpret_cast<uint32_t*>(up + sh.d_ff);
+    h.d_model = sh.d_model;
+    h.mode = AQ_DECODE_AUTO;
+    h.spin_limit = DECODE_SPIN_LIMIT;
     uint8_t* base = static_cast<uint8_t*>(plan_host);
     DecodeStage* stages = reinterpret_cast<DecodeStage*>(base + sizeof(DecodePlanHeader));
     AqStageTask* tasks = reinterpret_cast<AqStageTask*>(base + sizeof(DecodePlanHeader) + (size_t)h.stages * sizeof(DecodeStage));
@@ -612,7 +624,8 @@ int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int
         DecodeStage* st = stages + 4 * l;
         int wgs = 0;
         // q, k, v from the normalised residual stream
-        int part = decode_part_chunks(dq + 2 * dkv, (int)aq_num_chunks(sh.d_model));
+        const int64_t rows_qkv[3] = {dq, dkv, dkv}, rows_o[1] = {sh.d_model}, rows_mlp[2] = {sh.d_ff, sh.d_ff};
+        int part = decode_part_chunks(rows_qkv, 3, (int)aq_num_chunks(sh.d_model));
         st[0].task_begin = nt;
         tasks[nt++] = make(b, 0, dq, sh.d_model, part, q, x, b.norm_attn, AQ_PRO_NORM, wgs);
         tasks[nt++] = make(b, 1, dkv, sh.d_model, part, k, x, b.norm_attn, AQ_PRO_NORM, wgs);
@@ -620,25 +633,40 @@ int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int
         st[0].task_count = 3; st[0].total_wgs = wgs; st[0].clears_gateup = 0;
         // x += W_O a, a = the value head of each query head (attention over the one visible key)
         wgs = 0;
-        part = decode_part_chunks(sh.d_model, (int)aq_num_chunks(dq));
+        part = decode_part_chunks(rows_o, 1, (int)aq_num_chunks(dq));
         st[1].task_begin = nt;
         tasks[nt++] = make(b, 3, sh.d_model, dq, part, x, v, nullptr, AQ_PRO_PLAIN, wgs);
         st[1].task_count = 1; st[1].total_wgs = wgs; st[1].clears_gateup = 1;
         // gate, up from the normalised residual stream
         wgs = 0;
-        part = decode_part_chunks(2 * (int64_t)sh.d_ff, (int)aq_num_chunks(sh.d_model));
+        part = decode_part_chunks(rows_mlp, 2, (int)aq_num_chunks(sh.d_model));
         st[2].task_begin = nt;
         tasks[nt++] = make(b, 4, sh.d_ff, sh.d_model, part, gate, x, b.norm_mlp, AQ_PRO_NORM, wgs);
         tasks[nt++] = make(b, 5, sh.d_ff, sh.d_model, part, up, x, b.norm_mlp, AQ_PRO_NORM, wgs);
         st[2].task_count = 2; st[2].total_wgs = wgs; st[2].clears_gateup = 0;
         // x += W_down (act(gate) * up)
         wgs = 0;
-        part = decode_part_chunks(sh.d_model, (int)aq_num_chunks(sh.d_ff));
+        part = decode_part_chunks(rows_o, 1, (int)aq_num_chunks(sh.d_ff));
         st[3].task_begin = nt;
         tasks[nt++] = make(b, 6, sh.d_model, sh.d_ff, part, x, gate, up, AQ_PRO_GATED, wgs);
         st[3].task_count = 1; st[3].total_wgs = wgs; st[3].clears_gateup = 0;
     }
+    for (int i = 0; i < h.stages; ++i) h.max_wgs = std::max(h.max_wgs, stages[i].total_wgs);
     std::memcpy(base, &h, sizeof(h));
+    return AQ_OK;
+}
+
+int aq_decode_plan_option(void* plan_host, int mode, int spin_limit)
+{
+    if (!plan_host) return AQ_ENULL;
+    DecodePlanHeader h;
+    std::memcpy(&h, plan_host, sizeof(h));
+    if (h.magic != DECODE_MAGIC) return AQ_EINVAL;
+    if (mode != AQ_DECODE_AUTO && mode != AQ_DECODE_PER_STAGE && mode != AQ_DECODE_ONE_LAUNCH) return AQ_EINVAL;
+    if (spin_limit < 0) return AQ_EINVAL;
+    h.mode = mode;
+    h.spin_limit = spin_limit == 0 ? DECODE_SPIN_LIMIT : spin_limit;
+    std::memcpy(plan_host, &h, sizeof(h));
     return AQ_OK;
 }
 
@@ -651,17 +679,33 @@ int aq_decode_step(const void* plan_host, const void* plan_dev, void* stream)
     if (h.magic != DECODE_MAGIC || h.layers < 1 || h.stages != 4 * h.layers) return AQ_EINVAL;
     const uint8_t* hb = static_cast<const uint8_t*>(plan_host);
     const DecodeStage* stages = reinterpret_cast<const DecodeStage*>(hb + sizeof(DecodePlanHeader));
-    const AqStageTask* tasks_dev = reinterpret_cast<const AqStageTask*>(
-        static_cast<const uint8_t*>(plan_dev) + sizeof(DecodePlanHeader) + (size_t)h.stages * sizeof(DecodeStage));
+    const AqStageTask* tasks = reinterpret_cast<const AqStageTask*>(
+        hb + sizeof(DecodePlanHeader) + (size_t)h.stages * sizeof(DecodeStage));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (aqk_fill_zero(h.qkv, h.qkv_floats, s) != hipSuccess) return AQ_ELAUNCH;
+    bool one_launch = h.mode != AQ_DECODE_PER_STAGE;
+    if (one_launch && h.max_wgs > aqk_decode_step_capacity()) {
+        if (h.mode == AQ_DECODE_ONE_LAUNCH) return AQ_ELAUNCH;
+        one_launch = false;
+    }
+    if (aqk_fill_zero(h.qkv, h.qkv_floats, h.bar, 2, s) != hipSuccess) return AQ_ELAUNCH;
+    if (one_launch) {
+        const uint8_t* db = static_cast<const uint8_t*>(plan_dev);
+        const AqStageEntry* stages_dev = reinterpret_cast<const AqStageEntry*>(db + sizeof(DecodePlanHeader));
+        const AqStageTask* tasks_dev = reinterpret_cast<const AqStageTask*>(
+            db + sizeof(DecodePlanHeader) + (size_t)h.stages * sizeof(DecodeStage));
+        return aqk_decode_step(tasks_dev, stages_dev, h.stages, h.max_wgs, h.bar, h.gateup, (int)h.gateup_floats, h.x,
+                               h.d_model, h.spin_limit, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    }
     for (int i = 0; i < h.stages; ++i) {
         const DecodeStage& st = stages[i];
-        if (st.task_count < 1 || st.total_wgs < 1) return AQ_EINVAL;
-        if (aqk_layer_stage(tasks_dev + st.task_begin, st.task_count, st.total_wgs,
-                            st.clears_gateup ? h.gateup : nullptr, st.clears_gateup ? (int)h.gateup_floats : 0,
-                            s) != hipSuccess)
-            return AQ_ELAUNCH;
+        if (st.task_count < 1 || st.task_count > AQ_STAGE_MAX_TASKS || st.total_wgs < 1) return AQ_EINVAL;
+        AqStageArgs args;
+        std::memset(&args, 0, sizeof(args));
+        for (int j = 0; j < st.task_count; ++j) args.task[j] = tasks[st.task_begin + j];
+        args.count = st.task_count;
+        args.zero_ptr = st.clears_gateup ? h.gateup : nullptr;
+        args.zero_count = st.clears_gateup ? (int)h.gateup_floats : 0;
+        if (aqk_layer_stage(args, st.total_wgs, s) != hipSuccess) return AQ_ELAUNCH;
     }
     return AQ_OK;
 }

@@ -45,8 +45,9 @@ __device__ __forceinline__ void block_corrections(const uint8_t* xl, float* corr
 // One unit (16 rows x 8 blocks): unpack the ring slot, optionally refill it from `next`, run the
 // 8 MFMAs against the block-diagonal B and fold the block sums, times their fp16 scales, into the
 // tile's running sums (registers; lane (g, c) holds rows 4g .. 4g+3 of block column c).
-template <int BITS, bool REFILL>
-__device__ __forceinline__ void unit_step(uint32_t (&raw)[Codec<BITS>::WORDS], u32x2& sc,
+// RS = words per ring row: Codec<BITS>::WORDS for a ring of one bit-width, 8 for a ring that serves all three.
+template <int BITS, bool REFILL, int RS>
+__device__ __forceinline__ void unit_step(uint32_t (&raw)[RS], u32x2& sc,
                                           typename Codec<BITS>::Magic& magic, const half8 (&B)[8],
                                           const float4v& negc, const uint8_t* next, int lane, int sc_off,
                                           float (&acc)[4])
@@ -61,7 +62,7 @@ __device__ __forceinline__ void unit_step(uint32_t (&raw)[Codec<BITS>::WORDS], u
     Codec<BITS>::unpack(&raw[BITS], magic, a1);
     const half4v d4 = __builtin_bit_cast(half4v, sc);           // scales of rows 4g .. 4g+3
     if (REFILL) {
-        Codec<BITS>::load(next, lane, raw);
+        Codec<BITS>::load(next, lane, *reinterpret_cast<uint32_t(*)[Codec<BITS>::WORDS]>(&raw));
         sc = __builtin_nontemporal_load(as_global<u32x2>(next + sc_off));
     }
     float4v D = negc;
@@ -78,8 +79,8 @@ __device__ __forceinline__ void unit_step(uint32_t (&raw)[Codec<BITS>::WORDS], u
 
 // One chunk for the wavefront's TW tiles: fetch the chunk's B operand from LDS, then one unit per
 // tile out of ring slots slot0 .. slot0+TW-1, each refilled from the chunk two ahead.
-template <int BITS, int TW, bool REFILL>
-__device__ __forceinline__ void chunk_step(uint32_t (*raw)[Codec<BITS>::WORDS], u32x2* sc,
+template <int BITS, int TW, bool REFILL, int RS>
+__device__ __forceinline__ void chunk_step(uint32_t (*raw)[RS], u32x2* sc,
                                            typename Codec<BITS>::Magic& magic, const uint8_t* xl,
                                            const float* corr, const uint8_t* zeros, int ch, bool diag,
                                            int c, const uint8_t* refill, int lane, int sc_off, float (*acc)[4])

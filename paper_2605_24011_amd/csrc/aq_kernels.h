@@ -120,8 +120,27 @@ struct AqStageTask {
 };
 static_assert(sizeof(AqStageTask) == 96, "AqStageTask must stay 96 bytes");
 
-// Runs the `count` (>= 1) tasks of one stage in `total_wgs` workgroups; the launch also clears
-// zero_ptr[0 .. zero_count) (a buffer that a LATER stage accumulates into; may be null with count 0).
-hipError_t aqk_layer_stage(const AqStageTask* tasks_dev, int count, int total_wgs, float* zero_ptr, int zero_count,
+// One stage = one launch: up to AQ_STAGE_MAX_TASKS matrices that share their input, passed BY VALUE as the
+// kernel argument, and a buffer the launch clears (one that a LATER stage accumulates into; zero_count may be 0).
+#define AQ_STAGE_MAX_TASKS 3
+struct AqStageArgs {
+    AqStageTask task[AQ_STAGE_MAX_TASKS];
+    float* zero_ptr;
+    int32_t zero_count;
+    int32_t count;
+};
+hipError_t aqk_layer_stage(const AqStageArgs& args, int total_wgs, hipStream_t s);
+
+// One stage of a decode plan as the single-launch kernel reads it from device memory.
+struct AqStageEntry {
+    int32_t task_begin, task_count;   // its matrices in the task table
+    int32_t total_wgs;                // its items
+    int32_t clears_gateup;            // the stage also clears the gate/up buffer
+};
+// All stages in ONE cooperative launch of `grid` workgroups (>= the largest total_wgs, <= the capacity below);
+// bar = two zeroed words in device memory (arrival counter, give-up flag).
+int aqk_decode_step_capacity();
+hipError_t aqk_decode_step(const AqStageTask* tasks_dev, const AqStageEntry* stages_dev, int nstages, int grid,
+                           uint32_t* bar, float* gateup, int gateup_floats, float* x, int d_model, int spin_limit,
                            hipStream_t s);
-hipError_t aqk_fill_zero(float* p, int64_t n, hipStream_t s);
+hipError_t aqk_fill_zero(float* p, int64_t n, uint32_t* q, int m, hipStream_t s);
