@@ -205,14 +205,8 @@ int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const 
  * A layer is four dependent stages (q/k/v; o; gate/up; down).  Inputs of the products are rounded to binary16
  * times a power of two (11 significant bits); sums are fp32; a stage's partial sums meet in fp32 atomic
  * additions, so the last bits of a result can differ between runs.
- * Launch structure (aq_decode_plan_option, default AQ_DECODE_AUTO):
- *   AQ_DECODE_ONE_LAUNCH  one launch that clears qkv, then ONE cooperative launch for all stages of all layers,
- *       separated by grid-wide barriers, the next stage's weights requested while a barrier is crossed.  Needs
- *       every workgroup resident at once (AQ_ELAUNCH if the device cannot hold them).  A barrier polls at most
- *       spin_limit times (0 = the default, about a second); if one gives up -- which takes another kernel
- *       holding the device's compute units for that long -- the step still ends, and x is set to NaN.
- *   AQ_DECODE_PER_STAGE   one launch per stage (4 per layer) plus the clearing launch.
- *   AQ_DECODE_AUTO        ONE_LAUNCH if the device can hold the grid, else PER_STAGE.
+ * One launch per stage (4 per layer, each taking its matrices' records as kernel arguments) plus one that clears
+ * qkv; consecutive launches on one stream are the barriers between dependent stages.
  *   shape      HOST; d_model, d_ff, n_heads * head_dim multiples of 32 and <= 65536, head_dim a multiple of 8,
  *              n_heads a multiple of n_kv_heads, act = AQ_ACT_SILU or AQ_ACT_GELU_TANH, eps >= 0
  *   blocks     HOST array of `layers` records: w[0..6] = DEVICE blobs (aq_pack_weights) of q, k, v, o, gate, up,
@@ -221,14 +215,11 @@ int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const 
  *   x          DEVICE float [d_model], 16-byte aligned: the residual stream, read and overwritten by a step
  *   qkv        DEVICE float [layers][n_heads * head_dim + 2 * n_kv_heads * head_dim], overwritten by a step
  *   workspace  DEVICE, 16-byte aligned, aq_decode_workspace_size(shape) bytes (gate and up of the current layer)
- * aq_decode_plan binds these buffers into a plan image of aq_decode_plan_size(layers) bytes on the HOST; copy
- * the image to 16-byte-aligned DEVICE memory and pass both to aq_decode_step, which may be repeated (each call
- * advances x by one pass through the stack).  Steps that share buffers must be ordered on one stream. */
+ * aq_decode_plan binds these buffers into a plan image of aq_decode_plan_size(layers) bytes on the HOST (nothing
+ * of it is read by the device); aq_decode_step may be repeated (each call advances x by one pass through the
+ * stack).  Steps that share buffers must be ordered on one stream. */
 #define AQ_ACT_SILU      0
 #define AQ_ACT_GELU_TANH 1
-#define AQ_DECODE_AUTO       0
-#define AQ_DECODE_PER_STAGE  1
-#define AQ_DECODE_ONE_LAUNCH 2
 typedef struct aq_block_shape {
     int32_t d_model, n_heads, n_kv_heads, head_dim, d_ff;
     int32_t act;
@@ -245,8 +236,7 @@ size_t aq_decode_workspace_size(const aq_block_shape* shape);
 int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks /*HOST*/, int layers, int block,
                    float* x, float* qkv, void* workspace, size_t workspace_bytes,
                    void* plan_host, size_t plan_bytes);
-int aq_decode_plan_option(void* plan_host /*before it is copied to the device*/, int mode, int spin_limit);
-int aq_decode_step(const void* plan_host, const void* plan_dev, void* stream);
+int aq_decode_step(const void* plan_host, void* stream);
 
 /* Parity / debug: the blob decoded back to what Eq. 1 defines.
  *   codes_u8 DEVICE uint8 [N][K]  one code per byte

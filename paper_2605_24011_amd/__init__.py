@@ -16,7 +16,6 @@ AQ_EINVAL, AQ_ENULL, AQ_EALIGN, AQ_ESIZE, AQ_EDTYPE, AQ_ELAUNCH = -1, -2, -3, -4
 AQ_F16, AQ_BF16 = 1, 2
 AQ_GEMM_EXACT, AQ_GEMM_FAST = 0, 1
 AQ_ACT_SILU, AQ_ACT_GELU_TANH = 0, 1
-AQ_DECODE_AUTO, AQ_DECODE_PER_STAGE, AQ_DECODE_ONE_LAUNCH = 0, 1, 2
 BLOCK_MATRICES = ("q", "k", "v", "o", "gate", "up", "down")
 BLOCK = 32
 
@@ -95,8 +94,7 @@ def lib() -> ctypes.CDLL:
         L.aq_decode_workspace_size.argtypes = [ctypes.POINTER(aq_block_shape)]
         L.aq_decode_plan.argtypes = [ctypes.POINTER(aq_block_shape), ctypes.POINTER(aq_block_desc), _int, _int,
                                      _p, _p, _p, _sz, _p, _sz]
-        L.aq_decode_plan_option.argtypes = [_p, _int, _int]
-        L.aq_decode_step.argtypes = [_p, _p, _p]
+        L.aq_decode_step.argtypes = [_p, _p]
         L.aq_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         _lib = L
@@ -257,7 +255,7 @@ class DecodeStep:
     [layers, n_heads*head_dim + 2*n_kv_heads*head_dim], overwritten by run().  Holds references to every tensor."""
 
     def __init__(self, d_model: int, n_heads: int, n_kv_heads: int, head_dim: int, d_ff: int, act: str, eps: float,
-                 layers: Sequence[dict], x, qkv, block: int = BLOCK, mode: int = AQ_DECODE_AUTO, spin_limit: int = 0):
+                 layers: Sequence[dict], x, qkv, block: int = BLOCK):
         import torch
         acts = {"silu": AQ_ACT_SILU, "gelu_tanh": AQ_ACT_GELU_TANH}
         if act not in acts:
@@ -277,12 +275,10 @@ class DecodeStep:
         self.plan_host = torch.empty(max(size, 16), dtype=torch.uint8)
         _check(lib().aq_decode_plan(ctypes.byref(self.shape), descs, n, block, x.data_ptr(), qkv.data_ptr(),
                                     self.workspace.data_ptr(), ws, self.plan_host.data_ptr(), size), "aq_decode_plan")
-        _check(lib().aq_decode_plan_option(self.plan_host.data_ptr(), mode, spin_limit), "aq_decode_plan_option")
-        self.plan_dev = self.plan_host.to(x.device)
         self.layers, self.x, self.qkv = list(layers), x, qkv
 
     def run(self, stream=None) -> None:
-        _check(lib().aq_decode_step(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), _stream(stream)),
+        _check(lib().aq_decode_step(self.plan_host.data_ptr(), _stream(stream)),
                "aq_decode_step")
 
 

@@ -164,21 +164,16 @@ struct DecodePlanHeader {
     uint32_t magic;
     int32_t layers;
     int32_t stages;
-    int32_t mode;            // AQ_DECODE_AUTO / _PER_STAGE / _ONE_LAUNCH
+    int32_t reserved;
     float* qkv;              // cleared at the start of every step
     int64_t qkv_floats;
     float* gateup;           // cleared by the o stage of every layer
     int64_t gateup_floats;
-    float* x;
-    uint32_t* bar;           // two words after gate/up in the workspace: arrival counter, give-up flag
-    int32_t d_model;
-    int32_t max_wgs;         // items of the largest stage
-    int32_t spin_limit;      // polls of a grid barrier before it gives up
-    int32_t reserved;
 };
-static_assert(sizeof(DecodePlanHeader) == 80, "DecodePlanHeader must stay 80 bytes");
-typedef AqStageEntry DecodeStage;
-constexpr int DECODE_SPIN_LIMIT = 1 << 21;      // about a second of polling
+static_assert(sizeof(DecodePlanHeader) == 48, "DecodePlanHeader must stay 48 bytes");
+struct DecodeStage {
+    int32_t task_begin, task_count, total_wgs, clears_gateup;
+};
 constexpr uint32_t DECODE_MAGIC = 0x41514431u;  // "AQD1"
 constexpr int DECODE_TARGET_WGS = 768;          // 256 compute units x 3 resident workgroups
 
@@ -540,7 +535,7 @@ size_t aq_decode_plan_size(int layers)
 size_t aq_decode_workspace_size(const aq_block_shape* shape)
 {
     if (!shape || shape->d_ff < 1) return 0;
-    return (size_t)2 * (size_t)shape->d_ff * sizeof(float) + 64;     // gate, up, the barrier words
+    return (size_t)2 * (size_t)shape->d_ff * sizeof(float);
 }
 
 int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int layers, int block,
@@ -581,11 +576,6 @@ int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int
     h.qkv_floats = per_layer * layers;
     h.gateup = gate;
     h.gateup_floats = 2 * (int64_t)sh.d_ff;
-    h.x = x;
-    h.bar = reinterpret_cast<uint32_t*>(up + sh.d_ff);
-    h.d_model = sh.d_model;
-    h.mode = AQ_DECODE_AUTO;
-    h.spin_limit = DECODE_SPIN_LIMIT;
     uint8_t* base = static_cast<uint8_t*>(plan_host);
     DecodeStage* stages = reinterpret_cast<DecodeStage*>(base + sizeof(DecodePlanHeader));
     AqStageTask* tasks = reinterpret_cast<AqStageTask*>(base + sizeof(DecodePlanHeader) + (size_t)h.stages * sizeof(DecodeStage));
@@ -651,29 +641,13 @@ int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int
         tasks[nt++] = make(b, 6, sh.d_model, sh.d_ff, part, x, gate, up, AQ_PRO_GATED, wgs);
         st[3].task_count = 1; st[3].total_wgs = wgs; st[3].clears_gateup = 0;
     }
-    for (int i = 0; i < h.stages; ++i) h.max_wgs = std::max(h.max_wgs, stages[i].total_wgs);
     std::memcpy(base, &h, sizeof(h));
     return AQ_OK;
 }
 
-int aq_decode_plan_option(void* plan_host, int mode, int spin_limit)
+int aq_decode_step(const void* plan_host, void* stream)
 {
     if (!plan_host) return AQ_ENULL;
-    DecodePlanHeader h;
-    std::memcpy(&h, plan_host, sizeof(h));
-    if (h.magic != DECODE_MAGIC) return AQ_EINVAL;
-    if (mode != AQ_DECODE_AUTO && mode != AQ_DECODE_PER_STAGE && mode != AQ_DECODE_ONE_LAUNCH) return AQ_EINVAL;
-    if (spin_limit < 0) return AQ_EINVAL;
-    h.mode = mode;
-    h.spin_limit = spin_limit == 0 ? DECODE_SPIN_LIMIT : spin_limit;
-    std::memcpy(plan_host, &h, sizeof(h));
-    return AQ_OK;
-}
-
-int aq_decode_step(const void* plan_host, const void* plan_dev, void* stream)
-{
-    if (!plan_host || !plan_dev) return AQ_ENULL;
-    if (!aligned16(plan_dev)) return AQ_EALIGN;
     DecodePlanHeader h;
     std::memcpy(&h, plan_host, sizeof(h));
     if (h.magic != DECODE_MAGIC || h.layers < 1 || h.stages != 4 * h.layers) return AQ_EINVAL;
@@ -682,20 +656,7 @@ int aq_decode_step(const void* plan_host, const void* plan_dev, void* stream)
     const AqStageTask* tasks = reinterpret_cast<const AqStageTask*>(
         hb + sizeof(DecodePlanHeader) + (size_t)h.stages * sizeof(DecodeStage));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    bool one_launch = h.mode != AQ_DECODE_PER_STAGE;
-    if (one_launch && h.max_wgs > aqk_decode_step_capacity()) {
-        if (h.mode == AQ_DECODE_ONE_LAUNCH) return AQ_ELAUNCH;
-        one_launch = false;
-    }
-    if (aqk_fill_zero(h.qkv, h.qkv_floats, h.bar, 2, s) != hipSuccess) return AQ_ELAUNCH;
-    if (one_launch) {
-        const uint8_t* db = static_cast<const uint8_t*>(plan_dev);
-        const AqStageEntry* stages_dev = reinterpret_cast<const AqStageEntry*>(db + sizeof(DecodePlanHeader));
-        const AqStageTask* tasks_dev = reinterpret_cast<const AqStageTask*>(
-            db + sizeof(DecodePlanHeader) + (size_t)h.stages * sizeof(DecodeStage));
-        return aqk_decode_step(tasks_dev, stages_dev, h.stages, h.max_wgs, h.bar, h.gateup, (int)h.gateup_floats, h.x,
-                               h.d_model, h.spin_limit, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
-    }
+    if (aqk_fill_zero(h.qkv, h.qkv_floats, s) != hipSuccess) return AQ_ELAUNCH;
     for (int i = 0; i < h.stages; ++i) {
         const DecodeStage& st = stages[i];
         if (st.task_count < 1 || st.task_count > AQ_STAGE_MAX_TASKS || st.total_wgs < 1) return AQ_EINVAL;

@@ -131,16 +131,4 @@ struct AqStageArgs {
 };
 hipError_t aqk_layer_stage(const AqStageArgs& args, int total_wgs, hipStream_t s);
 
-// One stage of a decode plan as the single-launch kernel reads it from device memory.
-struct AqStageEntry {
-    int32_t task_begin, task_count;   // its matrices in the task table
-    int32_t total_wgs;                // its items
-    int32_t clears_gateup;            // the stage also clears the gate/up buffer
-};
-// All stages in ONE cooperative launch of `grid` workgroups (>= the largest total_wgs, <= the capacity below);
-// bar = two zeroed words in device memory (arrival counter, give-up flag).
-int aqk_decode_step_capacity();
-hipError_t aqk_decode_step(const AqStageTask* tasks_dev, const AqStageEntry* stages_dev, int nstages, int grid,
-                           uint32_t* bar, float* gateup, int gateup_floats, float* x, int d_model, int spin_limit,
-                           hipStream_t s);
-hipError_t aqk_fill_zero(float* p, int64_t n, uint32_t* q, int m, hipStream_t s);
+hipError_t aqk_fill_zero(float* p, int64_t n, hipStream_t s);

@@ -33,7 +33,7 @@ def bar(layers: int) -> float:
     return 1e-3 * max(1.0, (layers / 4.0) ** 0.5)
 
 
-def build_step(torch, aq, shape: wl.BlockShape, layers, x0, mode=0, spin_limit=0):
+def build_step(torch, aq, shape: wl.BlockShape, layers, x0):
     dev_layers = []
     for layer in layers:
         d = {}
@@ -50,14 +50,14 @@ def build_step(torch, aq, shape: wl.BlockShape, layers, x0, mode=0, spin_limit=0
     per_layer = (shape.n_heads + 2 * shape.n_kv_heads) * shape.head_dim
     qkv = torch.full((len(layers), per_layer), float("nan"), dtype=torch.float32, device="cuda")
     step = aq.DecodeStep(shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff, shape.act,
-                         shape.eps, dev_layers, x, qkv, mode=mode, spin_limit=spin_limit)
+                         shape.eps, dev_layers, x, qkv)
     return step, x, qkv
 
 
-def check(torch, aq, lo, oracle, shape: wl.BlockShape, bits, key, steps=1, mode=0):
+def check(torch, aq, lo, oracle, shape: wl.BlockShape, bits, key, steps=1):
     layers = wl.draw_block_stack(shape, bits, *key)
     x0 = wl.draw_residual(shape.d_model, *key)
-    step, x, qkv = build_step(torch, aq, shape, layers, x0, mode=mode)
+    step, x, qkv = build_step(torch, aq, shape, layers, x0)
     oshape = lo.Shape(shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff, shape.act, shape.eps)
     want_x = x0.astype(np.float64)
     for _ in range(steps):
@@ -92,36 +92,30 @@ CASES = [
 ]
 
 
-MODES = [1, 2]     # AQ_DECODE_PER_STAGE, AQ_DECODE_ONE_LAUNCH
-
-
-@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("d_model,heads,kv,hd,d_ff,act,L", CASES)
-def test_decode_step_matches_oracle(gpu, oracle, layer_oracle, d_model, heads, kv, hd, d_ff, act, L, mode):
+def test_decode_step_matches_oracle(gpu, oracle, layer_oracle, d_model, heads, kv, hd, d_ff, act, L):
     torch, aq = gpu
     shape = wl.BlockShape(d_model, heads, kv, hd, d_ff, act, 1e-5)
     rng = np.random.default_rng(d_model + d_ff)
     bits = rng.integers(2, 5, size=(L, 7))
-    check(torch, aq, layer_oracle, oracle, shape, bits, (31, d_model, d_ff), mode=mode)
+    check(torch, aq, layer_oracle, oracle, shape, bits, (31, d_model, d_ff))
 
 
-@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("b", [2, 3, 4])
-def test_decode_step_uniform_bits(gpu, oracle, layer_oracle, b, mode):
+def test_decode_step_uniform_bits(gpu, oracle, layer_oracle, b):
     torch, aq = gpu
     shape = wl.BlockShape(384, 6, 2, 64, 1280, "silu", 1e-6)
-    check(torch, aq, layer_oracle, oracle, shape, [[b] * 7] * 2, (32, b), mode=mode)
+    check(torch, aq, layer_oracle, oracle, shape, [[b] * 7] * 2, (32, b))
 
 
-@pytest.mark.parametrize("mode", MODES)
-def test_decode_step_deep_stack_and_repeated_steps(gpu, oracle, layer_oracle, mode):
+def test_decode_step_deep_stack_and_repeated_steps(gpu, oracle, layer_oracle):
     torch, aq = gpu
     shape = wl.BlockShape(256, 4, 4, 64, 704, "silu", 1e-5)
     rng = np.random.default_rng(9)
-    worst = check(torch, aq, layer_oracle, oracle, shape, rng.integers(2, 5, size=(32, 7)), (33,), mode=mode)
+    worst = check(torch, aq, layer_oracle, oracle, shape, rng.integers(2, 5, size=(32, 7)), (33,))
     assert worst <= bar(32)
     # the step advances x in place and clears what it accumulates into: two calls = the stack applied twice
-    check(torch, aq, layer_oracle, oracle, shape, rng.integers(2, 5, size=(3, 7)), (34,), steps=2, mode=mode)
+    check(torch, aq, layer_oracle, oracle, shape, rng.integers(2, 5, size=(3, 7)), (34,), steps=2)
 
 
 def test_decode_step_hand_worked_block(gpu, oracle, layer_oracle):
@@ -152,27 +146,13 @@ def test_decode_step_hand_worked_block(gpu, oracle, layer_oracle):
     assert np.array_equal(qkv.cpu().numpy()[0], np.concatenate([v, v, v]))
 
 
-@pytest.mark.parametrize("mode", MODES)
-def test_decode_step_full_size_layers(gpu, oracle, layer_oracle, mode):
+def test_decode_step_full_size_layers(gpu, oracle, layer_oracle):
     """Two layers at the LLaMA-2-7B shapes: the launch configuration the bench times (the split of every stage
     depends on the shapes only)."""
     torch, aq = gpu
     shape = wl.BLOCK_SHAPES["llama2-7b"]
-    worst = check(torch, aq, layer_oracle, oracle, shape, [[3, 2, 4, 3, 2, 4, 3], [4, 3, 2, 2, 3, 2, 4]], (35,),
-                  mode=mode)
+    worst = check(torch, aq, layer_oracle, oracle, shape, [[3, 2, 4, 3, 2, 4, 3], [4, 3, 2, 2, 3, 2, 4]], (35,))
     assert worst <= 1e-3
-
-
-def test_decode_step_barrier_gives_up_and_says_so(gpu):
-    """A barrier that is allowed a single poll gives up (forced from the host: the kernel's own bounded wait); the
-    step must still end, and must not leave numbers that could pass for a result."""
-    torch, aq = gpu
-    shape = wl.BlockShape(256, 4, 4, 64, 704, "silu", 1e-5)
-    layers = wl.draw_block_stack(shape, [[3] * 7] * 8, 36)
-    step, x, qkv = build_step(torch, aq, shape, layers, wl.draw_residual(256, 36), mode=2, spin_limit=1)
-    step.run()
-    torch.cuda.synchronize()
-    assert bool(torch.isnan(x).all())
 
 
 def test_decode_step_errors(gpu):
