@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--skip-gemma", action="store_true")
     ap.add_argument("--skip-quant", action="store_true")
     ap.add_argument("--skip-cells", action="store_true")
+    ap.add_argument("--skip-layer-step", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=5)
     ap.add_argument("--prefill-only", action="store_true",
                     help="the timed decode stream with 2 steps, then only the M = 300 prefill (short run for rocprofv3 --pmc passes)")
@@ -91,9 +92,11 @@ def main():
     args = ap.parse_args()
     if args.prefill_only:
         args.skip_by_bits = args.skip_cpu = args.skip_gemma = args.skip_quant = args.skip_cells = True
+        args.skip_layer_step = True
         args.steps, args.warmup = 2, 1
     if args.decode_only:
         args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = args.skip_quant = args.skip_cells = True
+        args.skip_layer_step = True
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists).", file=sys.stderr)
         sys.exit(2)
@@ -334,6 +337,48 @@ def main():
         out["gemma"] = gem
 
     # ---- block-level scale optimisation (the step that produces codes and scales), one 11008 x 4096 matrix ----
+    if not args.skip_layer_step:
+        # the same weights volume walked layer by layer: RMSNorm, q/k/v, first-token attention, o, gated MLP and the
+        # two residual additions, four dependent launches per layer (the independent-stream figure above is the
+        # kernel's throughput; this is what one token costs when every product waits for the one before)
+        step_out = {}
+        for model, alloc in (("llama2-7b", "mixed"), ("gemma-2b", "b3")):
+            torch.cuda.empty_cache()
+            shape = wl.BLOCK_SHAPES[model]
+            specs = wl.backbone_stream(model, alloc)
+            n_layers = specs[-1].layer + 1
+            layers, nbytes = [], 0
+            for l in range(n_layers):
+                d = {}
+                for j, name in enumerate(wl.BLOCK_MATRICES):
+                    m = specs[l * 7 + j]
+                    codes, scales = wl.draw_gain_matrix_torch(m.N, m.K, m.bits, wl.BLOCK_GAIN[name], "cuda", 11, l, j)
+                    d[name] = (aq.aq_pack_weights(codes, scales, m.N, m.K, m.bits), m.bits)
+                    nbytes += stored_bytes(m.N, m.K, m.bits)
+                    del codes, scales
+                d["norm_attn"] = torch.from_numpy(wl.draw_norm_weights(shape.d_model, 11, l, 0)).cuda()
+                d["norm_mlp"] = torch.from_numpy(wl.draw_norm_weights(shape.d_model, 11, l, 1)).cuda()
+                layers.append(d)
+            x0 = torch.from_numpy(wl.draw_residual(shape.d_model, 11)).cuda()
+            x = x0.clone()
+            qkv = torch.empty((n_layers, (shape.n_heads + 2 * shape.n_kv_heads) * shape.head_dim), device="cuda")
+            step = aq.DecodeStep(shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff, shape.act,
+                                 shape.eps, layers, x, qkv)
+
+            def one_token():
+                x.copy_(x0, non_blocking=True)
+                step.run()
+            d, w = time_launches(torch, one_token, max(10, args.steps // 2), 3)
+            ms = sum(d) / len(d)
+            step_out[model] = {
+                "allocation": alloc, "layers": n_layers, "launches_per_token": 4 * n_layers + 2,
+                "ms_per_token": round(ms, 4), "tokens_per_s": round(1e3 / ms, 1),
+                "weight_GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "result_finite": bool(torch.isfinite(x).all())}
+            del layers, step
+        out["layer_step"] = step_out
+
     if not args.skip_quant:
         torch.cuda.empty_cache()
         N, K, rounds = 11008, 4096, 4

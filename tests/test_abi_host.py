@@ -155,3 +155,66 @@ def test_optimize_scales_validation_without_a_gpu(L):
     assert L.aq_optimize_scales(A, None, 16, 64, 4, 32, 4, A, None, None) == aq.AQ_ENULL
     assert L.aq_optimize_scales(A, A + 4, 16, 64, 4, 32, 4, A, A, None) == aq.AQ_EALIGN
     assert L.aq_optimize_scales(A, None, 16, 64, 4, 32, 4, A + 8, A, None) == aq.AQ_EALIGN
+
+
+def _decode_plan(L, shape, blocks, layers, x=4096, qkv=8192, ws=16384, ws_bytes=None, plan_bytes=None, block=32):
+    sh = aq.aq_block_shape(*shape)
+    need_ws = L.aq_decode_workspace_size(ctypes.byref(sh))
+    size = L.aq_decode_plan_size(max(layers, 1))
+    buf = (ctypes.c_uint8 * max(size, 16))()
+    rc = L.aq_decode_plan(ctypes.byref(sh), blocks, layers, block, x, qkv, ws,
+                          need_ws if ws_bytes is None else ws_bytes, buf, size if plan_bytes is None else plan_bytes)
+    return rc, buf, size
+
+
+def test_decode_plan_validation_and_stage_split(L):
+    A = 1 << 20
+    blocks = (aq.aq_block_desc * 2)()
+    for b in blocks:
+        for j in range(7):
+            b.w[j] = A + 4096 * j
+            b.bits[j] = 2 + j % 3
+        b.norm_attn, b.norm_mlp = A, A
+    good = (4096, 32, 32, 128, 11008, aq.AQ_ACT_SILU, 1e-5)
+    rc, buf, size = _decode_plan(L, good, blocks, 2)
+    assert rc == aq.AQ_OK
+    assert size == 48 + 2 * (4 * 16 + 7 * 96)
+    assert L.aq_decode_workspace_size(ctypes.byref(aq.aq_block_shape(*good))) == 2 * 11008 * 4
+    # the plan: 4 stages per layer; every stage fits one round of 768 workgroups and covers all of K
+    import numpy as np
+    raw = np.frombuffer(bytes(buf), dtype=np.uint8)
+    head = raw[:16].view(np.int32)
+    assert head[1] == 2 and head[2] == 8
+    stages = raw[48:48 + 8 * 16].view(np.int32).reshape(8, 4)
+    tasks = raw[48 + 8 * 16:48 + 8 * 16 + 14 * 96].view(np.int32).reshape(14, 24)
+    assert stages[:, 1].tolist() == [3, 1, 2, 1] * 2 and stages[:, 3].tolist() == [0, 1, 0, 0] * 2
+    assert (stages[:, 2] <= 768).all() and (stages[:, 2] >= 256).all()
+    for st in stages:
+        total = 0
+        for t in tasks[st[0]:st[0] + st[1]]:
+            N, K, nchunks, part, parts, wg_begin, wg_count = t[8], t[9], t[11], t[12], t[13], t[14], t[15]
+            assert nchunks == (K + 255) // 256 and 1 <= part <= 8 and parts == (nchunks + part - 1) // part
+            assert wg_begin == total and wg_count == ((N + 127) // 128) * parts
+            total += wg_count
+        assert total == st[2]
+    # rejected before anything touches a device
+    assert _decode_plan(L, (4090, 32, 32, 128, 11008, 0, 1e-5), blocks, 2)[0] == aq.AQ_EINVAL     # d_model % 32
+    assert _decode_plan(L, (4096, 32, 5, 128, 11008, 0, 1e-5), blocks, 2)[0] == aq.AQ_EINVAL      # heads % kv heads
+    assert _decode_plan(L, (4096, 32, 32, 124, 11008, 0, 1e-5), blocks, 2)[0] == aq.AQ_EINVAL     # head_dim % 8
+    assert _decode_plan(L, (4096, 32, 32, 128, 11008, 7, 1e-5), blocks, 2)[0] == aq.AQ_EINVAL     # activation
+    assert _decode_plan(L, (4096, 32, 32, 128, 11008, 0, -1.0), blocks, 2)[0] == aq.AQ_EINVAL     # eps
+    assert _decode_plan(L, good, blocks, 0)[0] == aq.AQ_EINVAL
+    assert _decode_plan(L, good, blocks, 2, block=64)[0] == aq.AQ_EINVAL
+    assert _decode_plan(L, good, blocks, 2, x=None)[0] == aq.AQ_ENULL
+    assert _decode_plan(L, good, blocks, 2, x=4100)[0] == aq.AQ_EALIGN
+    assert _decode_plan(L, good, blocks, 2, ws_bytes=100)[0] == aq.AQ_ESIZE
+    assert _decode_plan(L, good, blocks, 2, plan_bytes=size - 1)[0] == aq.AQ_ESIZE
+    blocks[1].bits[3] = 5
+    assert _decode_plan(L, good, blocks, 2)[0] == aq.AQ_EINVAL
+    blocks[1].bits[3] = 3
+    blocks[1].norm_mlp = None
+    assert _decode_plan(L, good, blocks, 2)[0] == aq.AQ_ENULL
+    # a step needs a plan
+    assert L.aq_decode_step(None, None) == aq.AQ_ENULL
+    junk = (ctypes.c_uint8 * 4096)()
+    assert L.aq_decode_step(junk, None) == aq.AQ_EINVAL
