@@ -113,6 +113,7 @@ std::vector<int> longest_k_first(int count, KeyFn key)
 }
 
 constexpr int64_t SMALL_M = 64;      // fast-mode products with M up to this run the streaming kernel
+constexpr int64_t SMALL_M_EXACT = 32;  // exact-mode products with M up to this run it too, weights as two binary16 terms
 
 AqGemmTask make_small_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset,
                            float* Y, int64_t ldy, int wg_begin)
@@ -329,12 +330,12 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, cons
     if (workspace_bytes < aq_qgemm_workspace_size(M, N, K, bits)) return AQ_ESIZE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int fast = flags == AQ_GEMM_FAST, convert = fast && x_dtype == AQ_BF16;
-    if (fast && M <= SMALL_M) {
+    if (M <= (fast ? SMALL_M : SMALL_M_EXACT)) {
         const int MT = aqk_small_mtiles(M);
         const AqRetileTask r = make_small_retile_task(X, M, K, ldx, 0, MT);
         if (aqk_small_retile(nullptr, 0, r, MT, x_dtype == AQ_BF16, workspace, s) != hipSuccess) return AQ_ELAUNCH;
         const AqGemmTask t = make_small_task(packed, N, K, bits, M, 0, Y, ldy, 0);
-        return aqk_gemm_small(nullptr, 0, t, bits, MT, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+        return aqk_gemm_small(nullptr, 0, t, bits, MT, !fast, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     }
     const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
     if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
@@ -376,7 +377,7 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int fla
     h.mtiles = aqk_gemm_mtiles(max_M, groups);
     h.nsplit = aqk_gemm_nsplit(max_M);
     h.fast = flags == AQ_GEMM_FAST;
-    h.small_mt = (h.fast && max_M <= SMALL_M) ? aqk_small_mtiles(max_M) : 0;
+    h.small_mt = max_M <= (h.fast ? SMALL_M : SMALL_M_EXACT) ? aqk_small_mtiles(max_M) : 0;
     const int convert = h.fast && h.x_dtype == AQ_BF16;
     uint8_t* base = static_cast<uint8_t*>(plan_host);
     uint8_t* tasks = base + sizeof(GemmPlanHeader);
@@ -426,7 +427,7 @@ static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
            h.retile_max_blocks >= 1 && h.workspace_bytes >= 1024 &&
            (h.nsplit == 1 || ((h.nsplit == 2 || h.nsplit == 4 || h.nsplit == 8) && h.mtiles == 1)) &&
            (h.fast == 0 || h.fast == 1) &&
-           (h.small_mt == 0 || (h.fast == 1 && (h.small_mt == 1 || h.small_mt == 2 || h.small_mt == 4)));
+           (h.small_mt == 0 || h.small_mt == 1 || h.small_mt == 2 || (h.small_mt == 4 && h.fast == 1));
 }
 
 size_t aq_qgemm_batch_workspace_size(const void* plan_host)
@@ -456,7 +457,7 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
     if (h.small_mt) {
         if (aqk_small_retile(rtasks, h.retile_count, rnone, h.small_mt, h.x_dtype == AQ_BF16, workspace, s) != hipSuccess)
             return AQ_ELAUNCH;
-        return aqk_gemm_small(tasks, h.count, none, h.bits, h.small_mt, h.total_wgs, workspace, s) == hipSuccess
+        return aqk_gemm_small(tasks, h.count, none, h.bits, h.small_mt, h.fast == 0, h.total_wgs, workspace, s) == hipSuccess
                    ? AQ_OK : AQ_ELAUNCH;
     }
     if (aqk_retile(rtasks, h.retile_count, rnone, h.retile_max_blocks, convert, workspace, s) != hipSuccess)

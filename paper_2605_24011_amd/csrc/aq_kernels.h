@@ -91,7 +91,7 @@ size_t aqk_small_retile_bytes(int64_t M, int64_t K);
 hipError_t aqk_small_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int MT, int bf16,
                             void* workspace, hipStream_t s);
 hipError_t aqk_gemm_small(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int MT,
-                          int total_wgs, const void* workspace, hipStream_t s);
+                          bool split, int total_wgs, const void* workspace, hipStream_t s);
 
 // Layer-by-layer decode step.  One matrix of one stage as the kernel sees it (device-visible, 96 bytes):
 // y[n] += sum over the k of a workgroup's part of W[n][k] * f(in)[k], with f chosen by `prologue`:

@@ -587,3 +587,50 @@ def test_qgemm_fast_small_m_batch(gpu, oracle):
             got = Y.cpu().numpy()
             assert np.isfinite(got).all()
             assert oracle.rel_l2(got, ref) <= FAST_EXPECTED[b]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K,M", [(200, 1056, 7), (272, 2048, 16), (130, 4096, 29), (128, 512, 32)])
+def test_qgemm_exact_small_m_rounds_no_weight(gpu, oracle, bits, N, K, M, dtype):
+    """Exact mode at M <= 32 runs the streaming kernel with every weight as the sum of two binary16 terms: the
+    error must be that of fp32 summation (1e-7), far below what one rounded term per weight gives at 3 and 4 bits
+    (1e-4), also with scales at both ends of binary16's range."""
+    torch, aq = gpu
+    codes, scales = wl.draw_matrix(N, K, bits, 51, N, K)
+    X = wl.draw_activations(M, K, dtype, 51, N, K)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, dtype)).cpu().numpy()
+    ref = oracle.qmatmul(codes, scales, N, K, bits, X, dtype)
+    assert oracle.rel_l2(Y, ref) <= 2e-6
+    # a matrix of tiny (subnormal) scales, and one of scales so large that d * (q - z) leaves binary16's range
+    for value, bar in ((3.0e-6, 2e-6), (20000.0, 2e-6)):
+        s2 = scales.copy()
+        s2[0::2] = wl.f32_to_f16_bits(np.full(s2[0::2].shape, value, dtype=np.float32))
+        if value < 1.0:
+            s2[1::2] = wl.f32_to_f16_bits(np.full(s2[1::2].shape, value * 37.0, dtype=np.float32))
+        packed = _pack(torch, aq, codes, s2, N, K, bits)
+        Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, dtype)).cpu().numpy()
+        ref = oracle.qmatmul(codes, s2, N, K, bits, X, dtype)
+        for rows in (slice(0, None, 2), slice(1, None, 2)):
+            assert oracle.rel_l2(Y[:, rows], ref[:, rows]) <= bar, (value, rows)
+
+
+def test_qgemm_exact_small_m_batch(gpu, oracle):
+    """A planned exact-mode batch with every M <= 32 (the streaming kernel, mixed bit-widths, shared activations)."""
+    torch, aq = gpu
+    shapes = [(256, 1024, 2), (384, 1024, 3), (128, 1024, 4), (200, 544, 3)]
+    M = 24
+    Xs = {K: wl.draw_activations(M, K, "bf16", 52, K) for K in (1024, 544)}
+    Xd = {K: _dev(torch, v, "bf16") for K, v in Xs.items()}
+    items, refs = [], []
+    for i, (N, K, bits) in enumerate(shapes):
+        codes, scales = wl.draw_matrix(N, K, bits, 52, i)
+        packed = _pack(torch, aq, codes, scales, N, K, bits)
+        Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, Xd[K], Y))
+        refs.append(oracle.qmatmul(codes, scales, N, K, bits, Xs[K], "bf16"))
+    aq.GemmBatch(items).run()
+    torch.cuda.synchronize()
+    for it, ref in zip(items, refs):
+        assert oracle.rel_l2(it[5].cpu().numpy(), ref) <= 2e-6
