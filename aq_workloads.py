@@ -284,6 +284,23 @@ def iter_stream_inputs(stream: Sequence[MatrixSpec], M: int, dtype: str, seed: i
 # from the numpy draws (another generator) but follow the same recipe; the bench
 # copies what the oracle needs back to the host.
 # ----------------------------------------------------------------------------
+# two-level variant of the format: 4-bit scale and offset codes per block, two fp16 numbers per super-block
+# ----------------------------------------------------------------------------
+def draw_affine_params(N: int, K: int, bits: int, *key: int) -> Tuple[np.ndarray, np.ndarray]:
+    """(sub uint8[N, K/32], sup uint16[N, ceil(K/256), 2]): scale codes uniform on {1..15}, offset codes uniform
+    on {0..15}, D = fp16(|N(0,1)| * 0.02 / 8), M = fp16(D * 2^(bits-1) * u), u uniform on [0.5, 1.5): the block's
+    zero point s_b z_b / s_b scatters around the middle of the code range."""
+    nb, ns = K // BLOCK, (K + 8 * BLOCK - 1) // (8 * BLOCK)
+    g = _rng(404, *key)
+    a = g.integers(1, 16, size=(N, nb), dtype=np.uint8)
+    c = g.integers(0, 16, size=(N, nb), dtype=np.uint8)
+    D = np.abs(g.standard_normal(size=(N, ns), dtype=np.float32)) * np.float32(0.02 / 8)
+    M = D * np.float32(1 << (bits - 1)) * (0.5 + g.random(size=(N, ns), dtype=np.float32))
+    sup = np.stack([f32_to_f16_bits(D), f32_to_f16_bits(M)], axis=2)
+    return (a | (c << 4)).astype(np.uint8), sup
+
+
+# ----------------------------------------------------------------------------
 # transformer blocks for the layer-by-layer decode step: the seven matrices of a layer with scales sized so
 # that a matrix maps a vector of unit rms to one of rms `gain` (sub-layer outputs stay a fraction of the
 # residual stream, as in a trained model), norm multipliers near one, x ~ N(0,1)
