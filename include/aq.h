@@ -193,6 +193,32 @@ int aq_optimize_scales(const float* W, const float* F, int64_t N, int64_t K, int
 int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const int* choices, int n_choices,
                      double avg_bits_budget, int* bits_out);
 
+/* Two-level variant of the format: Eq. 1 in its general form, w_hat = s_b (q - z_b) with a stored scale AND a stored
+ * real zero point per block of 32, both compressed by the parameters of the super-block (Section 3, "Weight
+ * quantization").  The paragraph leaves the compression open; here a super-block is 8 blocks (256 consecutive k of
+ * a row) with two binary16 numbers D, M, and a block stores two 4-bit codes a, c:
+ *     s_b = D * a,   s_b z_b = M * c,   w_hat = D a q - M c          (bits + 0.375 bits per weight stored)
+ * Canonical inputs of aq2_pack_weights (DEVICE, 16-byte aligned):
+ *   codes   uint8  [N][K/32][4*bits]     the code bitstream, as for aq_pack_weights
+ *   sub     uint8  [N][K/32]             a in the low nibble, c in the high nibble
+ *   sup     uint16 [N][ceil(K/256)][2]   binary16 bit patterns of D, M
+ * The packed blob (aq2_packed_size bytes) has the base format's tiling with the parameters next to the codes they
+ * scale.  aq2_qgemv is aq_qgemv for such a blob: the codes meet x as exact integers on the matrix cores, and a
+ * block's sum B = sum (q - 2^(bits-1)) x becomes (D a) B + (2^(bits-1) D a - M c) * (sum of x over the block) in
+ * fp32.  aq2_qgemv_batch_plan plans a list of such products (every blob of the list in this format); the plan is
+ * launched with aq_qgemv_batch.  aq2_unpack_codes / aq2_dequant_f32 are the parity inverses (the latter returns
+ * fp32(D a q - M c), rounded once).  Decode only: prefill and the decode step through the blocks take the base
+ * format.  Arguments, limits and errors as for the base functions. */
+size_t aq2_packed_size(int64_t N, int64_t K, int bits, int block);
+int aq2_pack_weights(const uint8_t* codes, const uint8_t* sub, const uint16_t* sup, int64_t N, int64_t K, int bits,
+                     int block, void* packed, size_t packed_bytes, void* stream);
+int aq2_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, const void* x, int x_dtype,
+              float* y, void* stream);
+int aq2_qgemv_batch_plan(const aq_gemv_desc* descs /*HOST*/, int count, int block,
+                         void* plan_host, size_t plan_bytes);
+int aq2_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream);
+int aq2_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int block, float* W, void* stream);
+
 /* One decode step (M = 1) through a stack of transformer blocks, layer by layer, with what sits between the
  * matrices fused into the matrix-vector kernels.  Section 3 ("Vision-Language-Action models") names a block's
  * matrices: the attention projections W_Q, W_K, W_V, W_O and the MLP's W_gate, W_up, W_down; the rest is the

@@ -88,6 +88,13 @@ def lib() -> ctypes.CDLL:
         L.aq_qgemm_batch.argtypes = [_p, _p, _p, _sz, _p]
         L.aq_optimize_scales.argtypes = [_p, _p, _i64, _i64, _int, _int, _int, _p, _p, _p]
         L.aq_allocate_bits.argtypes = [_p, _p, _int, _int, _p, _int, ctypes.c_double, _p]
+        L.aq2_packed_size.restype = _sz
+        L.aq2_packed_size.argtypes = [_i64, _i64, _int, _int]
+        L.aq2_pack_weights.argtypes = [_p, _p, _p, _i64, _i64, _int, _int, _p, _sz, _p]
+        L.aq2_qgemv.argtypes = [_p, _i64, _i64, _int, _int, _p, _int, _p, _p]
+        L.aq2_qgemv_batch_plan.argtypes = [ctypes.POINTER(aq_gemv_desc), _int, _int, _p, _sz]
+        L.aq2_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
+        L.aq2_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq_decode_plan_size.restype = _sz
         L.aq_decode_plan_size.argtypes = [_int]
         L.aq_decode_workspace_size.restype = _sz
@@ -154,8 +161,9 @@ def aq_qgemv(packed, N: int, K: int, bits: int, x, y=None, block: int = BLOCK, s
 class GemvBatch:
     """A planned stream of decode products (one launch).  Holds references to every tensor."""
 
-    def __init__(self, items: Sequence[tuple], block: int = BLOCK):
-        """items: (packed, N, K, bits, x, y) per matrix."""
+    def __init__(self, items: Sequence[tuple], block: int = BLOCK, two_level: bool = False):
+        """items: (packed, N, K, bits, x, y) per matrix; two_level: every blob is in the two-level format variant
+        (aq2_pack_weights) and the list is planned with aq2_qgemv_batch_plan."""
         import torch
         n = len(items)
         descs = (aq_gemv_desc * n)()
@@ -164,7 +172,8 @@ class GemvBatch:
             d.N, d.K, d.bits, d.x_dtype = N, K, bits, _dtype_code(x)
         size = int(lib().aq_qgemv_batch_plan_size(n))
         self.plan_host = torch.empty(size, dtype=torch.uint8)
-        _check(lib().aq_qgemv_batch_plan(descs, n, block, self.plan_host.data_ptr(), size), "aq_qgemv_batch_plan")
+        plan = lib().aq2_qgemv_batch_plan if two_level else lib().aq_qgemv_batch_plan
+        _check(plan(descs, n, block, self.plan_host.data_ptr(), size), "aq_qgemv_batch_plan")
         self.plan_dev = self.plan_host.to(items[0][0].device)
         self.items = list(items)
 
@@ -295,4 +304,47 @@ def aq_dequant_f32(packed, N: int, K: int, bits: int, block: int = BLOCK, stream
     out = torch.empty((N, K), dtype=torch.float32, device=packed.device)
     _check(lib().aq_dequant_f32(packed.data_ptr(), N, K, bits, block, out.data_ptr(), _stream(stream)),
            "aq_dequant_f32")
+    return out
+
+
+# ---- two-level variant of the format (include/aq.h, aq2_*) ----
+def aq2_packed_size(N: int, K: int, bits: int, block: int = BLOCK) -> int:
+    return int(lib().aq2_packed_size(N, K, bits, block))
+
+
+def aq2_pack_weights(codes, sub, sup, N: int, K: int, bits: int, block: int = BLOCK, stream=None):
+    """codes: cuda uint8 [N, K/32, 4*bits]; sub: cuda uint8 [N, K/32]; sup: cuda int16/uint16/float16
+    [N, ceil(K/256), 2] -> uint8 blob."""
+    import torch
+    size = aq2_packed_size(N, K, bits, block)
+    if size == 0:
+        raise AqError(AQ_EINVAL, "aq2_packed_size")
+    packed = torch.empty(size, dtype=torch.uint8, device=codes.device)
+    _check(lib().aq2_pack_weights(codes.data_ptr(), sub.data_ptr(), sup.data_ptr(), N, K, bits, block,
+                                  packed.data_ptr(), size, _stream(stream)), "aq2_pack_weights")
+    return packed
+
+
+def aq2_qgemv(packed, N: int, K: int, bits: int, x, y=None, block: int = BLOCK, stream=None):
+    import torch
+    if y is None:
+        y = torch.empty(N, dtype=torch.float32, device=x.device)
+    _check(lib().aq2_qgemv(packed.data_ptr(), N, K, bits, block, x.data_ptr(), _dtype_code(x),
+                           y.data_ptr(), _stream(stream)), "aq2_qgemv")
+    return y
+
+
+def aq2_unpack_codes(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):
+    import torch
+    out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(lib().aq2_unpack_codes(packed.data_ptr(), N, K, bits, block, out.data_ptr(), _stream(stream)),
+           "aq2_unpack_codes")
+    return out
+
+
+def aq2_dequant_f32(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):
+    import torch
+    out = torch.empty((N, K), dtype=torch.float32, device=packed.device)
+    _check(lib().aq2_dequant_f32(packed.data_ptr(), N, K, bits, block, out.data_ptr(), _stream(stream)),
+           "aq2_dequant_f32")
     return out

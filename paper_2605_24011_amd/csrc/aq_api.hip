@@ -24,7 +24,8 @@ struct PlanHeader {
     int32_t max_K;
     int32_t bits;            // the common bit-width of all tasks, 0 if they differ
     int32_t total_wgs;
-    int32_t reserved[10];
+    int32_t format;          // 0: base format, 1: two-level variant
+    int32_t reserved[9];
 };
 static_assert(sizeof(PlanHeader) == 64, "PlanHeader must stay 64 bytes");
 constexpr uint32_t PLAN_MAGIC = 0x41515031u;  // "AQP1"
@@ -250,7 +251,7 @@ size_t aq_qgemv_batch_plan_size(int count)
     return sizeof(PlanHeader) + (size_t)count * sizeof(AqGemvTask);
 }
 
-int aq_qgemv_batch_plan(const aq_gemv_desc* descs, int count, int block, void* plan_host, size_t plan_bytes)
+static int gemv_plan(const aq_gemv_desc* descs, int count, int block, void* plan_host, size_t plan_bytes, int format)
 {
     if (count < 1) return AQ_EINVAL;
     if (!descs || !plan_host) return AQ_ENULL;
@@ -275,6 +276,7 @@ int aq_qgemv_batch_plan(const aq_gemv_desc* descs, int count, int block, void* p
     h.count = count;
     h.tiles_per_wg = rt;
     h.max_K = max_K;
+    h.format = format;
     AqGemvTask* tasks = reinterpret_cast<AqGemvTask*>(static_cast<uint8_t*>(plan_host) + sizeof(PlanHeader));
     int32_t begin = 0;
     h.bits = descs[0].bits;
@@ -295,18 +297,86 @@ int aq_qgemv_batch_plan(const aq_gemv_desc* descs, int count, int block, void* p
     return AQ_OK;
 }
 
+int aq_qgemv_batch_plan(const aq_gemv_desc* descs, int count, int block, void* plan_host, size_t plan_bytes)
+{
+    return gemv_plan(descs, count, block, plan_host, plan_bytes, 0);
+}
+
+int aq2_qgemv_batch_plan(const aq_gemv_desc* descs, int count, int block, void* plan_host, size_t plan_bytes)
+{
+    return gemv_plan(descs, count, block, plan_host, plan_bytes, 1);
+}
+
+size_t aq2_packed_size(int64_t N, int64_t K, int bits, int block)
+{
+    if (check_matrix(N, K, bits, block) != AQ_OK) return 0;
+    return (size_t)aq2_blob_bytes(N, K, bits);
+}
+
+int aq2_pack_weights(const uint8_t* codes, const uint8_t* sub, const uint16_t* sup, int64_t N, int64_t K, int bits,
+                     int block, void* packed, size_t packed_bytes, void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if (!codes || !sub || !sup || !packed) return AQ_ENULL;
+    if (!aligned16(codes) || !aligned16(sub) || !aligned16(sup) || !aligned16(packed)) return AQ_EALIGN;
+    if (packed_bytes < (size_t)aq2_blob_bytes(N, K, bits)) return AQ_ESIZE;
+    return aqk2_pack(codes, sub, sup, N, K, bits, packed, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
+int aq2_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, const void* x, int x_dtype,
+              float* y, void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if ((rc = check_dtype(x_dtype)) != AQ_OK) return rc;
+    if (!packed || !x || !y) return AQ_ENULL;
+    if (!aligned16(packed) || !aligned16(x) || !aligned16(y)) return AQ_EALIGN;
+    AqGemvTask t = make_task(packed, N, K, bits, x, x_dtype, y);
+    int rt = aqk_gemv_tiles_per_wg(N, false);
+    t.wg_begin = 0;
+    t.wg_count = aqk_gemv_wg_count(N, rt);
+    return aqk2_gemv(nullptr, 0, t, bits, rt, t.wg_count, (int)K, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
+int aq2_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if (!packed || !codes_u8) return AQ_ENULL;
+    if (!aligned16(packed) || !aligned16(codes_u8)) return AQ_EALIGN;
+    return aqk2_unpack_codes(packed, N, K, bits, codes_u8, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
+int aq2_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int block, float* W, void* stream)
+{
+    int rc = check_matrix(N, K, bits, block);
+    if (rc != AQ_OK) return rc;
+    if (!packed || !W) return AQ_ENULL;
+    if (!aligned16(packed) || !aligned16(W)) return AQ_EALIGN;
+    return aqk2_dequant(packed, N, K, bits, W, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
 int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream)
 {
     if (!plan_host || !plan_dev) return AQ_ENULL;
     if (!aligned16(plan_dev)) return AQ_EALIGN;
     PlanHeader h;
     std::memcpy(&h, plan_host, sizeof(h));
-    if (h.magic != PLAN_MAGIC || h.count < 1 || h.total_wgs < 1 || (h.bits != 0 && (h.bits < 2 || h.bits > 4)))
+    if (h.magic != PLAN_MAGIC || h.count < 1 || h.total_wgs < 1 || (h.bits != 0 && (h.bits < 2 || h.bits > 4)) ||
+        (h.format != 0 && h.format != 1))
         return AQ_EINVAL;
     const AqGemvTask* tasks =
         reinterpret_cast<const AqGemvTask*>(static_cast<const uint8_t*>(plan_dev) + sizeof(PlanHeader));
     AqGemvTask none;
     std::memset(&none, 0, sizeof(none));
+    if (h.format == 1)
+        return aqk2_gemv(tasks, h.count, none, h.bits, h.tiles_per_wg, h.total_wgs, h.max_K,
+                         static_cast<hipStream_t>(stream)) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     return aqk_gemv(tasks, h.count, none, h.bits, h.tiles_per_wg, h.total_wgs, h.max_K,
                     static_cast<hipStream_t>(stream)) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
 }

@@ -4,6 +4,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include "aq_layout.h"
+#include <hip/hip_fp16.h>
+#include "aq_kernels.h"
 #include "aq_codec.h"
 
 namespace aqdev {
@@ -40,6 +42,73 @@ __device__ __forceinline__ void block_corrections(const uint8_t* xl, float* corr
         }
         corr[b] = s;
     }
+}
+
+__device__ inline float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Stage x into LDS as fp16 and compute corr[] per block.  bf16 input is multiplied by a power of
+// two chosen from max|x| so that it lands in fp16's range (bf16 has 8 significant bits, fp16 11:
+// the conversion is exact unless an element is > 2^28 times smaller than the largest); the
+// returned factor undoes it at the end.
+template <int BITS, int THREADS>
+__device__ float stage_x(const AqGemvTask& t, uint8_t* xl, float* corr, float* scratch)
+{
+    const int tid = threadIdx.x;
+    const int K = t.K, Kpad = t.nchunks * AQ_CHUNK_K;
+    float unscale = 1.0f;
+    for (int e = tid; e < t.nchunks * 4 * 8; e += THREADS)           // the zero middles of all entries
+        *reinterpret_cast<u32x2*>(xl + e * X_ENTRY_BYTES + 8) = u32x2{0u, 0u};
+    if (t.x_dtype == 1) {   // AQ_F16: copy
+        for (int i = tid * 8; i < Kpad; i += THREADS * 8) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (i < K) v = *(as_global<u32x4>(t.x + i));
+            *reinterpret_cast<u32x2*>(xl + x_lds_offset(i >> 5, (i & 31) >> 2)) = u32x2{v.x, v.y};
+            *reinterpret_cast<u32x2*>(xl + x_lds_offset(i >> 5, ((i & 31) >> 2) + 1)) = u32x2{v.z, v.w};
+        }
+    } else {                // AQ_BF16
+        float amax = 0.f;
+        for (int i = tid * 8; i < K; i += THREADS * 8) {
+            u32x4 v = *(as_global<u32x4>(t.x + i));
+            uint32_t ws[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                amax = fmaxf(amax, fabsf(bf16_bits_to_f32(ws[j] & 0xFFFFu)));
+                amax = fmaxf(amax, fabsf(bf16_bits_to_f32(ws[j] >> 16)));
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+        if ((tid & 63) == 0) scratch[tid >> 6] = amax;
+        __syncthreads();
+        amax = fmaxf(fmaxf(scratch[0], scratch[1]), fmaxf(scratch[2], scratch[3]));
+        int e = 0;
+        if (amax > 0.f && amax < 3.0e38f) {
+            e = (int)((__float_as_uint(amax) >> 23) & 0xFF) - 127 - 14;   // amax * 2^-e in [2^14, 2^15)
+            e = e < -100 ? -100 : e;
+        }
+        const float scale = __uint_as_float((uint32_t)(127 - e) << 23);   // 2^-e
+        unscale = __uint_as_float((uint32_t)(127 + e) << 23);            // 2^e
+        for (int i = tid * 8; i < Kpad; i += THREADS * 8) {
+            u32x4 o = {0u, 0u, 0u, 0u};
+            if (i < K) {
+                u32x4 v = *(as_global<u32x4>(t.x + i));
+                uint32_t ws[4] = {v.x, v.y, v.z, v.w}, os[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    __half lo = __float2half_rn(bf16_bits_to_f32(ws[j] & 0xFFFFu) * scale);
+                    __half hi = __float2half_rn(bf16_bits_to_f32(ws[j] >> 16) * scale);
+                    os[j] = (uint32_t)__half_as_ushort(lo) | ((uint32_t)__half_as_ushort(hi) << 16);
+                }
+                o.x = os[0]; o.y = os[1]; o.z = os[2]; o.w = os[3];
+            }
+            *reinterpret_cast<u32x2*>(xl + x_lds_offset(i >> 5, (i & 31) >> 2)) = u32x2{o.x, o.y};
+            *reinterpret_cast<u32x2*>(xl + x_lds_offset(i >> 5, ((i & 31) >> 2) + 1)) = u32x2{o.z, o.w};
+        }
+    }
+    __syncthreads();
+    block_corrections<BITS, THREADS>(xl, corr, t.nchunks * AQ_CHUNK_BLOCKS);
+    __syncthreads();
+    return unscale;
 }
 
 // One unit (16 rows x 8 blocks): unpack the ring slot, optionally refill it from `next`, run the

@@ -32,6 +32,15 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg);
 hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
                     int total_wgs, int max_K, hipStream_t s);
 
+// Two-level variant of the format (layout in aq_layout.h): same contracts as the three functions and the decode
+// launcher above, other blobs.
+hipError_t aqk2_pack(const uint8_t* codes, const uint8_t* sub, const uint16_t* sup, int64_t N, int64_t K, int bits,
+                     void* blob, hipStream_t s);
+hipError_t aqk2_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, uint8_t* out, hipStream_t s);
+hipError_t aqk2_dequant(const void* blob, int64_t N, int64_t K, int bits, float* out, hipStream_t s);
+hipError_t aqk2_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
+                     int total_wgs, int max_K, hipStream_t s);
+
 // Prefill.  The activations are first re-tiled into the order the matrix cores read them ("Xt"):
 //   Xt[m / 16][k / 32][lane = 16*g + c] = the 16 bytes X[16*(m/16) + c][32*(k/32) + 8g .. 8g+7],
 // rows beyond M zero, so that a wavefront's A operand of one (m-tile, 32-k step) is 1 KiB contiguous.

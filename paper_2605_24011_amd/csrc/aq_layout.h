@@ -74,6 +74,22 @@ AQ_HD int aq_scale_offset(int bits, int g, int c, int r)
     return 512 * bits + (g * 8 + c) * 8 + 2 * r;
 }
 
+// ---- two-level variant of the format: w = D_S * a_b * q - M_S * c_b (a_b, c_b 4-bit codes of block b, D_S, M_S
+// binary16 numbers of the super-block = the 8 blocks of a row inside one chunk).  Same tiling and the same code
+// words as the base format; the unit's 256 bytes of scales are replaced by 192 bytes of parameters:
+//   bytes 512*bits + (g*8 + blk)*4 + r   : a | c << 4 of row 4g + r, block blk          (128 bytes)
+//   bytes 512*bits + 128 + (g*4 + r)*4   : D (2 bytes), M (2 bytes) of row 4g + r        (64 bytes)
+// so that lane (g, c) of the decode kernel reads its 4 rows of block c & 7 as ONE 32-bit word and the 4 rows'
+// D, M as one 16-byte vector.  No trailer.
+#define AQ2_PARAM_BYTES 192
+AQ_HD int64_t aq2_unit_bytes(int bits) { return 512 * (int64_t)bits + AQ2_PARAM_BYTES; }
+AQ_HD int64_t aq2_blob_bytes(int64_t N, int64_t K, int bits)
+{
+    return aq_num_groups(N) * aq_num_chunks(K) * AQ_GROUP_TILES * aq2_unit_bytes(bits);
+}
+AQ_HD int aq2_sub_offset(int bits, int g, int blk, int r) { return 512 * bits + (g * 8 + blk) * 4 + r; }
+AQ_HD int aq2_sup_offset(int bits, int g, int r) { return 512 * bits + 128 + (g * 4 + r) * 4; }
+
 // element e (0..31) of a block given the block's `bits` words
 AQ_HD uint32_t aq_block_get(const uint32_t* w, int bits, int e)
 {

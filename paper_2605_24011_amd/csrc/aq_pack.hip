@@ -105,6 +105,86 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     }
 }
 
+// ---- two-level variant: same code words, parameters instead of scales (see aq_layout.h) ----
+__global__ __launch_bounds__(256) void pack2_kernel(const uint8_t* __restrict__ codes, const uint8_t* __restrict__ sub,
+                                                    const uint16_t* __restrict__ sup, int64_t N, int64_t K, int bits,
+                                                    uint8_t* __restrict__ blob, int64_t n_units)
+{
+    int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t unit = gid >> 6;
+    if (unit >= n_units) return;
+    int l = (int)(gid & 63), g = l >> 4, i = l & 15;
+    int64_t nb = K / AQ_BLOCK, nchunks = aq_num_chunks(K);
+    int til = (int)(unit % AQ_GROUP_TILES);
+    int64_t chunk = (unit / AQ_GROUP_TILES) % nchunks;
+    int64_t group = unit / (AQ_GROUP_TILES * nchunks);
+    uint8_t* u = blob + unit * aq2_unit_bytes(bits);
+    int64_t row0 = (group * AQ_GROUP_TILES + til) * AQ_TILE_ROWS;
+    int64_t row = row0 + i;
+    for (int blk = 0; blk < 2; ++blk) {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        int64_t j = chunk * AQ_CHUNK_BLOCKS + 2 * g + blk;
+        if (row < N && j < nb) {
+            const uint8_t* src = codes + (row * nb + j) * (4 * bits);
+            for (int e = 0; e < 32; ++e) aq_block_put(w, bits, e, canon_code(src, bits, e));
+        }
+        for (int h = 0; h < bits; ++h)
+            *reinterpret_cast<uint32_t*>(u + aq_word_offset(bits, l, blk * bits + h)) = w[h];
+    }
+    // lane (g, i < 8): the codes of rows 4g..4g+3 of block i; lane (g, i in 8..11): D, M of row 4g + i - 8
+    if (i < 8) {
+        int64_t j = chunk * AQ_CHUNK_BLOCKS + i;
+        for (int r = 0; r < 4; ++r) {
+            int64_t rr = row0 + 4 * g + r;
+            u[aq2_sub_offset(bits, g, i, r)] = (rr < N && j < nb) ? sub[rr * nb + j] : (uint8_t)0;
+        }
+    } else if (i < 12) {
+        int r = i - 8;
+        int64_t rr = row0 + 4 * g + r;
+        uint16_t D = 0, M = 0;
+        if (rr < N) {
+            D = sup[(rr * nchunks + chunk) * 2];
+            M = sup[(rr * nchunks + chunk) * 2 + 1];
+        }
+        *reinterpret_cast<uint16_t*>(u + aq2_sup_offset(bits, g, r)) = D;
+        *reinterpret_cast<uint16_t*>(u + aq2_sup_offset(bits, g, r) + 2) = M;
+    }
+}
+
+// one thread per (row, block): 32 codes or 32 dequantised weights, fp32(D a q - M c) with ONE rounding
+template <bool DEQUANT>
+__global__ __launch_bounds__(256) void decode2_kernel(const uint8_t* __restrict__ blob, int64_t N, int64_t K,
+                                                      int bits, uint8_t* __restrict__ out_codes,
+                                                      float* __restrict__ out_w)
+{
+    int64_t nb = K / AQ_BLOCK;
+    int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= N * nb) return;
+    int64_t row = gid / nb, j = gid % nb;
+    int64_t tile = row / AQ_TILE_ROWS;
+    int i = (int)(row % AQ_TILE_ROWS);
+    int64_t group = tile / AQ_GROUP_TILES;
+    int til = (int)(tile % AQ_GROUP_TILES);
+    int64_t chunk = j / AQ_CHUNK_BLOCKS;
+    int c = (int)(j % AQ_CHUNK_BLOCKS);
+    const uint8_t* u = blob + aq_unit_index(group, chunk, til, aq_num_chunks(K)) * aq2_unit_bytes(bits);
+    int l = 16 * (c >> 1) + i, blk = c & 1;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    for (int h = 0; h < bits; ++h)
+        w[h] = *reinterpret_cast<const uint32_t*>(u + aq_word_offset(bits, l, blk * bits + h));
+    if (DEQUANT) {
+        const uint8_t sb = u[aq2_sub_offset(bits, i >> 2, c, i & 3)];
+        const float D = __half2float(__ushort_as_half(*reinterpret_cast<const uint16_t*>(u + aq2_sup_offset(bits, i >> 2, i & 3))));
+        const float M = __half2float(__ushort_as_half(*reinterpret_cast<const uint16_t*>(u + aq2_sup_offset(bits, i >> 2, i & 3) + 2)));
+        const float s = D * (float)(sb & 15), off = M * (float)(sb >> 4);      // both exact in fp32
+        for (int e = 0; e < 32; ++e)
+            out_w[row * K + j * AQ_BLOCK + e] = fmaf(s, (float)aq_block_get(w, bits, e), -off);
+    } else {
+        for (int e = 0; e < 32; ++e)
+            out_codes[row * K + j * AQ_BLOCK + e] = (uint8_t)aq_block_get(w, bits, e);
+    }
+}
+
 }  // namespace
 
 hipError_t aqk_pack(const uint8_t* codes, const uint16_t* scales, int64_t N, int64_t K, int bits,
@@ -134,6 +214,32 @@ hipError_t aqk_dequant(const void* blob, int64_t N, int64_t K, int bits, float* 
     int64_t threads = N * (K / AQ_BLOCK);
     unsigned grid = (unsigned)((threads + 255) / 256);
     hipLaunchKernelGGL(decode_kernel<true>, dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(blob),
+                       N, K, bits, (uint8_t*)nullptr, out);
+    return hipGetLastError();
+}
+
+hipError_t aqk2_pack(const uint8_t* codes, const uint8_t* sub, const uint16_t* sup, int64_t N, int64_t K, int bits,
+                     void* blob, hipStream_t s)
+{
+    int64_t n_units = aq_num_groups(N) * aq_num_chunks(K) * AQ_GROUP_TILES;
+    unsigned grid = (unsigned)((n_units * 64 + 255) / 256);
+    hipLaunchKernelGGL(pack2_kernel, dim3(grid), dim3(256), 0, s, codes, sub, sup, N, K, bits,
+                       static_cast<uint8_t*>(blob), n_units);
+    return hipGetLastError();
+}
+
+hipError_t aqk2_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, uint8_t* out, hipStream_t s)
+{
+    unsigned grid = (unsigned)((N * (K / AQ_BLOCK) + 255) / 256);
+    hipLaunchKernelGGL(decode2_kernel<false>, dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(blob),
+                       N, K, bits, out, (float*)nullptr);
+    return hipGetLastError();
+}
+
+hipError_t aqk2_dequant(const void* blob, int64_t N, int64_t K, int bits, float* out, hipStream_t s)
+{
+    unsigned grid = (unsigned)((N * (K / AQ_BLOCK) + 255) / 256);
+    hipLaunchKernelGGL(decode2_kernel<true>, dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(blob),
                        N, K, bits, (uint8_t*)nullptr, out);
     return hipGetLastError();
 }

@@ -1,0 +1,144 @@
+"""Parity of the two-level format variant (aq2_* entry points, through the C ABI) against its fp64 oracle on the
+same seeded inputs.  Bars: codes bit-exact; dequantised weights equal to the oracle's value rounded once to fp32;
+decode outputs relative L2 <= 1e-3 (expected ~1e-6: exact integer products on the matrix cores, fp32 sums)."""
+import numpy as np
+import pytest
+
+import aq_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    import paper_2605_24011_amd as aq
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    aq.lib()
+    return torch, aq
+
+
+@pytest.fixture(scope="module")
+def af():
+    from oracle import aq_affine_oracle
+    return aq_affine_oracle
+
+
+def dev(torch, a, kind=None):
+    t = torch.from_numpy(np.ascontiguousarray(a).view(np.int16) if a.dtype == np.uint16 else np.ascontiguousarray(a)).cuda()
+    if kind == "f16":
+        t = t.view(torch.float16)
+    elif kind == "bf16":
+        t = t.view(torch.bfloat16)
+    return t
+
+
+def pack(torch, aq, codes, sub, sup, N, K, bits):
+    return aq.aq2_pack_weights(dev(torch, codes), dev(torch, sub), dev(torch, sup), N, K, bits)
+
+
+SHAPES = [(8, 32), (16, 256), (17, 96), (200, 1056), (128, 512), (300, 4096), (131, 2048)]
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K", SHAPES)
+def test_codes_and_dequant(gpu, oracle, af, bits, N, K):
+    torch, aq = gpu
+    codes = wl.draw_codes(N, K, bits, 71, N, K)
+    sub, sup = wl.draw_affine_params(N, K, bits, 71, N, K)
+    packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+    assert packed.numel() == aq.aq2_packed_size(N, K, bits)
+    assert np.array_equal(aq.aq2_unpack_codes(packed, N, K, bits).cpu().numpy(), oracle.unpack(codes, N, K, bits))
+    W = aq.aq2_dequant_f32(packed, N, K, bits).cpu().numpy()
+    want = af.dequant(codes, sub, sup, N, K, bits)
+    assert np.array_equal(W, want.astype(np.float32))            # D a q and M c are exact; their difference rounds once
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K", SHAPES + [(4096, 4096), (512, 11008)])
+def test_qgemv_matches_oracle(gpu, oracle, af, bits, N, K, dtype):
+    torch, aq = gpu
+    codes = wl.draw_codes(N, K, bits, 72, N, K)
+    sub, sup = wl.draw_affine_params(N, K, bits, 72, N, K)
+    x = wl.draw_activations(1, K, dtype, 72, N, K)[0]
+    packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+    y = aq.aq2_qgemv(packed, N, K, bits, dev(torch, x, dtype)).cpu().numpy()
+    ref = af.qmatvec(codes, sub, sup, N, K, bits, x, dtype)
+    err = oracle.rel_l2(y, ref)
+    assert err <= 1e-3
+    assert err <= 2e-5, err
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_reduces_to_the_base_kernel_and_reads_weights(gpu, oracle, af, bits):
+    torch, aq = gpu
+    N, K = 144, 800
+    codes = wl.draw_codes(N, K, bits, 73, bits)
+    # one-hot x reads single dequantised weights
+    sub, sup = wl.draw_affine_params(N, K, bits, 73, bits)
+    packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+    W = af.dequant(codes, sub, sup, N, K, bits)
+    for k in (0, 31, 32, 255, 256, 500, K - 1):
+        x = np.zeros(K, dtype=np.uint16); x[k] = 0x3C00         # binary16 1.0
+        y = aq.aq2_qgemv(packed, N, K, bits, dev(torch, x, "f16")).cpu().numpy()
+        assert np.allclose(y, W[:, k], rtol=1e-6, atol=1e-6 * np.abs(W).max()), k   # (D a)(q - z) and z D a - M c may cancel
+    # c = a, M = D 2^(bits-1): the base format with d = D a; integer x and power-of-two D make every sum exact
+    rng = np.random.default_rng(bits)
+    a = rng.integers(0, 16, size=(N, K // 32)).astype(np.uint8)
+    D = (2.0 ** rng.integers(-8, -2, size=(N, (K + 255) // 256))).astype(np.float32)
+    sup = np.stack([wl.f32_to_f16_bits(D), wl.f32_to_f16_bits(D * (1 << (bits - 1)))], axis=2)
+    sub = (a | (a << 4)).astype(np.uint8)
+    x = wl.draw_int_activations(1, K, "f16", 73, bits)[0]
+    packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+    y = aq.aq2_qgemv(packed, N, K, bits, dev(torch, x, "f16")).cpu().numpy()
+    d = D[:, np.arange(K // 32) // 8] * a
+    base = oracle.qmatmul(codes, wl.f32_to_f16_bits(d), N, K, bits, x.reshape(1, K), "f16")[0]
+    assert np.array_equal(y.astype(np.float64), base)
+
+
+def test_batch_plan_matches_single_calls_and_rejects_nothing_valid(gpu, oracle, af):
+    torch, aq = gpu
+    shapes = [(256, 1024, 2), (384, 2048, 3), (130, 544, 4), (512, 1024, 3)]
+    items, refs = [], []
+    for i, (N, K, bits) in enumerate(shapes):
+        codes = wl.draw_codes(N, K, bits, 74, i)
+        sub, sup = wl.draw_affine_params(N, K, bits, 74, i)
+        x = wl.draw_activations(1, K, "bf16", 74, i)[0]
+        packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+        y = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, dev(torch, x, "bf16"), y))
+        refs.append(af.qmatvec(codes, sub, sup, N, K, bits, x, "bf16"))
+    aq.GemvBatch(items, two_level=True).run()
+    torch.cuda.synchronize()
+    for it, ref in zip(items, refs):
+        assert oracle.rel_l2(it[5].cpu().numpy(), ref) <= 2e-5
+    uniform = [it for it in items if it[3] == 3]
+    for it in uniform:
+        it[5].fill_(float("nan"))
+    aq.GemvBatch(uniform, two_level=True).run()
+    torch.cuda.synchronize()
+    for it, ref in zip(uniform, [r for r, s in zip(refs, shapes) if s[2] == 3]):
+        assert oracle.rel_l2(it[5].cpu().numpy(), ref) <= 2e-5
+
+
+def test_full_size_sampled_rows(gpu, oracle, af):
+    """A LLaMA-shaped layer in one batched launch, the configuration the bench times; sampled rows against the oracle."""
+    torch, aq = gpu
+    rng = np.random.default_rng(75)
+    items, checks = [], []
+    for j, (name, N, K) in enumerate(wl.LLAMA2_7B_LAYER):
+        bits = 2 + j % 3
+        codes = wl.draw_codes(N, K, bits, 75, j)
+        sub, sup = wl.draw_affine_params(N, K, bits, 75, j)
+        x = wl.draw_activations(1, K, "bf16", 75, j)[0]
+        packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+        y = torch.empty(N, dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, dev(torch, x, "bf16"), y))
+        rows = np.sort(rng.choice(N, size=48, replace=False))
+        nb = K // 32
+        checks.append((rows, af.qmatvec(codes.reshape(N, nb, -1)[rows], sub[rows], sup[rows], len(rows), K, bits, x, "bf16")))
+    aq.GemvBatch(items, two_level=True).run()
+    torch.cuda.synchronize()
+    for it, (rows, ref) in zip(items, checks):
+        assert oracle.rel_l2(it[5].cpu().numpy()[rows], ref) <= 2e-5
