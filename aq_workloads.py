@@ -402,6 +402,19 @@ def draw_matrix_torch(N: int, K: int, bits: int, device, *key: int):
     return codes, d.to(torch.float16)
 
 
+def draw_affine_params_torch(N: int, K: int, bits: int, device, *key: int):
+    """Device-side draw of the same distribution as draw_affine_params (other random numbers):
+    (sub uint8 [N, K/32], sup float16 [N, ceil(K/256), 2])."""
+    import torch
+    nb, ns = K // BLOCK, (K + 8 * BLOCK - 1) // (8 * BLOCK)
+    g = _torch_gen(device, 404, *key)
+    a = torch.randint(1, 16, (N, nb), dtype=torch.uint8, device=device, generator=g)
+    c = torch.randint(0, 16, (N, nb), dtype=torch.uint8, device=device, generator=g)
+    D = torch.randn((N, ns), dtype=torch.float32, device=device, generator=g).abs_().mul_(0.02 / 8)
+    M = D * float(1 << (bits - 1)) * (0.5 + torch.rand((N, ns), dtype=torch.float32, device=device, generator=g))
+    return a | (c << 4), torch.stack([D, M], dim=2).to(torch.float16).contiguous()
+
+
 def draw_activations_torch(M: int, K: int, dtype: str, device, *key: int,
                            image_rows: int = 0, image_gain: float = 1.0):
     """Activations [M, K] of torch.float16 / torch.bfloat16 on `device`."""

@@ -82,6 +82,7 @@ def main():
     ap.add_argument("--skip-quant", action="store_true")
     ap.add_argument("--skip-cells", action="store_true")
     ap.add_argument("--skip-layer-step", action="store_true")
+    ap.add_argument("--skip-two-level", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=5)
     ap.add_argument("--prefill-only", action="store_true",
                     help="the timed decode stream with 2 steps, then only the M = 300 prefill (short run for rocprofv3 --pmc passes)")
@@ -92,11 +93,11 @@ def main():
     args = ap.parse_args()
     if args.prefill_only:
         args.skip_by_bits = args.skip_cpu = args.skip_gemma = args.skip_quant = args.skip_cells = True
-        args.skip_layer_step = True
+        args.skip_layer_step = args.skip_two_level = True
         args.steps, args.warmup = 2, 1
     if args.decode_only:
         args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = args.skip_quant = args.skip_cells = True
-        args.skip_layer_step = True
+        args.skip_layer_step = args.skip_two_level = True
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists).", file=sys.stderr)
         sys.exit(2)
@@ -378,6 +379,34 @@ def main():
                 "result_finite": bool(torch.isfinite(x).all())}
             del layers, step
         out["layer_step"] = step_out
+
+    if not args.skip_two_level:
+        # the decode pass over the same shapes with every matrix in the two-level format variant
+        # (bits + 0.375 bits per weight stored): uniform 2-bit codes = 2.375 bits/weight, and the seeded mixed allocation
+        two = {"format": "w = D a q - M c: 4-bit a, c per block of 32, fp16 D, M per 256 weights of a row"}
+        for alloc in ("b2", "mixed"):
+            torch.cuda.empty_cache()
+            specs = wl.backbone_stream("llama2-7b", alloc)
+            items, nbytes = [], 0
+            for m in specs:
+                codes, _ = wl.draw_matrix_torch(m.N, m.K, m.bits, "cuda", 12, m.index)
+                sub, sup = wl.draw_affine_params_torch(m.N, m.K, m.bits, "cuda", 12, m.index)
+                packed = aq.aq2_pack_weights(codes, sub, sup, m.N, m.K, m.bits)
+                x = wl.draw_activations_torch(1, m.K, "bf16", "cuda", 12, m.index)[0].contiguous()
+                y = torch.empty(m.N, dtype=torch.float32, device="cuda")
+                items.append((packed, m.N, m.K, m.bits, x, y))
+                nbytes += m.N * m.K * m.bits // 8 + m.N * (m.K // 32) + m.N * ((m.K + 255) // 256) * 4 + 2 * m.K + 4 * m.N
+                del codes, sub, sup
+            bt = aq.GemvBatch(items, two_level=True)
+            d, w = time_launches(torch, bt.run, max(10, args.steps // 2), 3)
+            ms = sum(d) / len(d)
+            weights = sum(m.N * m.K for m in specs)
+            two[alloc] = {"stored_bits_per_weight": round(8.0 * sum(it[0].numel() for it in items) / weights, 4),
+                          "bytes": nbytes, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                          "pct_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),
+                          "tokens_per_s": round(1e3 / ms, 1)}
+            del items, bt
+        out["two_level_format"] = two
 
     if not args.skip_quant:
         torch.cuda.empty_cache()

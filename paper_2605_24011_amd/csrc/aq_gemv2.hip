@@ -4,9 +4,10 @@
 // The arithmetic on the codes is the base kernel's: exact small integers on the matrix cores against the
 // block-diagonal x, which leaves in lane (g, c) the sums  B[r] = sum_k (q - z) x  of block c for rows 4g .. 4g+3
 // (z = 2^(bits-1), the offset the unpack constants are built around).  What changes is what happens to a block sum:
-//     sum_k x (D a q - M c)  =  (D a) * B[r]  +  (z D a - M c) * X_b,      X_b = sum of x over the block,
-// two fp32 multiply-adds per row and block, with X_b computed once per workgroup while x is staged (next to the
-// correction terms) and the two coefficients formed from the lane's 4 bytes of codes and 4 (D, M) pairs.
+//     sum_k x (D a q - M c)  =  (D a) * (B[r] + z X_b)  -  (M c) * X_b,      X_b = sum of x over the block,
+// two fp32 multiply-adds per row and block; X_b is computed once per workgroup while x is staged (next to the
+// correction terms), z X_b rides in the MFMAs' C operand, and the two coefficients are formed from the lane's
+// 4 bytes of codes and 4 (D, M) pairs.
 // Same work split, ring and launch shapes as the base kernel; a unit is 64 bytes shorter.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
@@ -62,15 +63,14 @@ __device__ __forceinline__ void unit_step2(uint32_t (&raw)[Codec<BITS>::WORDS], 
         u32x4 av = {a0[2 * m], a0[2 * m + 1], a1[2 * m], a1[2 * m + 1]};
         D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, av), B[m], D, 0, 0, 0);
     }
-    const float z = (float)(1 << (BITS - 1));
+    // D[r] = sum_k q x of the block (the caller put z * X_b into the MFMAs' C operand next to the correction term)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const float a = (float)((s4 >> (8 * r)) & 15u), c = (float)((s4 >> (8 * r + 4)) & 15u);
         const float Dr = (float)__builtin_bit_cast(_Float16, (uint16_t)(p[r] & 0xFFFFu));
         const float Mr = (float)__builtin_bit_cast(_Float16, (uint16_t)(p[r] >> 16));
-        const float ca = Dr * a;                         // the block's scale s_b, exact in fp32
-        const float cb = fmaf(z, ca, -(Mr * c));         // z s_b - s_b z_b
-        acc[r] = fmaf(D[r], ca, fmaf(xs, cb, acc[r]));
+        acc[r] = fmaf(D[r], Dr * a, acc[r]);             // s_b * sum q x
+        acc[r] = fmaf(xs, -(Mr * c), acc[r]);            // - s_b z_b * X_b
     }
 }
 
@@ -87,9 +87,10 @@ __device__ __forceinline__ void chunk_step2(uint32_t (*raw)[Codec<BITS>::WORDS],
 #pragma unroll
     for (int m = 0; m < 8; ++m)
         B[m] = __builtin_bit_cast(half8, *reinterpret_cast<const u32x4_a8*>(bp + m * X_ENTRY_BYTES));
-    const float nc = -corr[ch * AQ_CHUNK_BLOCKS + (c & 7)];
-    const float4v negc = {nc, nc, nc, nc};
     const float xs = xsum[ch * AQ_CHUNK_BLOCKS + (c & 7)];
+    // C operand: minus the correction term (which takes the codes from magic + q to q - z) plus z * X_b (back to q)
+    const float nc = fmaf((float)(1 << (BITS - 1)), xs, -corr[ch * AQ_CHUNK_BLOCKS + (c & 7)]);
+    const float4v negc = {nc, nc, nc, nc};
 #pragma unroll
     for (int tw = 0; tw < TW; ++tw)
         unit_step2<BITS, REFILL>(raw[tw], sub[tw], sup[tw], magic, B, negc, xs, refill + tw * UNIT, lane, sub_off,
