@@ -218,3 +218,38 @@ def test_decode_plan_validation_and_stage_split(L):
     assert L.aq_decode_step(None, None) == aq.AQ_ENULL
     junk = (ctypes.c_uint8 * 4096)()
     assert L.aq_decode_step(junk, None) == aq.AQ_EINVAL
+
+
+def test_two_level_variant_validation_without_a_gpu(L):
+    A = 1 << 20
+    L.aq2_packed_size.restype = ctypes.c_size_t
+    # same tiling as the base format, 192 bytes of parameters per unit instead of 256 bytes of scales, no trailer
+    assert L.aq2_packed_size(128, 256, 2, 32) == 8 * (512 * 2 + 192)
+    assert L.aq2_packed_size(129, 257 - 1 + 32, 3, 32) == 2 * 2 * 8 * (512 * 3 + 192)
+    assert L.aq2_packed_size(128, 256, 5, 32) == 0 and L.aq2_packed_size(128, 250, 2, 32) == 0
+    size = L.aq2_packed_size(64, 512, 4, 32)
+    assert L.aq2_pack_weights(A, A, A, 64, 512, 4, 32, A, size, None) in (aq.AQ_OK, aq.AQ_ELAUNCH)   # valid: reaches the launch
+    assert L.aq2_pack_weights(A, A, A, 64, 512, 4, 32, A, size - 1, None) == aq.AQ_ESIZE
+    assert L.aq2_pack_weights(A, None, A, 64, 512, 4, 32, A, size, None) == aq.AQ_ENULL
+    assert L.aq2_pack_weights(A, A, A + 2, 64, 512, 4, 32, A, size, None) == aq.AQ_EALIGN
+    assert L.aq2_pack_weights(A, A, A, 64, 500, 4, 32, A, size, None) == aq.AQ_EINVAL
+    assert L.aq2_qgemv(A, 64, 512, 4, 32, A, 7, A, None) == aq.AQ_EDTYPE
+    assert L.aq2_qgemv(A, 64, 512, 6, 32, A, aq.AQ_F16, A, None) == aq.AQ_EINVAL
+    assert L.aq2_qgemv(A, 64, 512, 4, 32, None, aq.AQ_F16, A, None) == aq.AQ_ENULL
+    assert L.aq2_qgemv(A, 64, 512, 4, 32, A + 8, aq.AQ_F16, A, None) == aq.AQ_EALIGN
+    assert L.aq2_dequant_f32(A, 64, 512, 4, 32, None, None) == aq.AQ_ENULL
+    assert L.aq2_unpack_codes(A, 64, 512, 1, 32, A, None) == aq.AQ_EINVAL
+    # a plan of two-level products is marked as such and launched through the common entry point
+    descs = (aq.aq_gemv_desc * 2)()
+    for d, (N, K, b) in zip(descs, [(256, 1024, 2), (128, 512, 3)]):
+        d.packed, d.x, d.y, d.N, d.K, d.bits, d.x_dtype = A, A, A, N, K, b, aq.AQ_BF16
+    size = L.aq_qgemv_batch_plan_size(2)
+    buf = (ctypes.c_uint8 * size)()
+    assert L.aq2_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_OK
+    import numpy as np
+    head = np.frombuffer(bytes(buf[:64]), dtype=np.int32)
+    assert head[1] == 2 and head[4] == 0 and head[6] == 1          # count, mixed bit-widths, format
+    assert L.aq_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_OK
+    assert np.frombuffer(bytes(buf[:64]), dtype=np.int32)[6] == 0
+    descs[1].bits = 9
+    assert L.aq2_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_EINVAL
