@@ -118,7 +118,8 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
  *       (relative error <= 2^-12 per weight, rel-L2 of Y ~1e-4).  bf16 activations are first converted to
  *       binary16 with one power-of-two factor per row (exact unless an element is 2^38 times smaller than
  *       its row's largest).  A matrix whose largest |d| * 2^(bits-1) would overflow binary16 is computed as
- *       in AQ_GEMM_EXACT (decided on the device from the blob).  For M <= 64 the product runs in a kernel
+ *       in AQ_GEMM_EXACT (decided on the device from the blob) by the shared-role kernel; the producer /
+ *       consumer kernel that serves M = 300-like sizes scales d by a power of two instead, as below.  For M <= 64 the product runs in a kernel
  *       bound by the weight stream (wavefronts keep their packed tiles in registers over all of K; weights
  *       never pass through LDS); there such a matrix has every scale multiplied by one power of two
  *       2^-s first (s <= 4) and the result by 2^s, same error bound unless d < 2^(s-14).

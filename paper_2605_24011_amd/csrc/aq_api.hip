@@ -56,7 +56,8 @@ struct GemmPlanHeader {
     int32_t nsplit;          // wavefronts along n, from the largest M
     int32_t fast;            // fp16-weight mode
     int32_t small_mt;        // > 0: the small-M streaming kernel with that many m-tiles (fast mode, M <= 64)
-    int32_t reserved[3];
+    int32_t pc;              // the producer / consumer kernel (fast mode, prefill-sized M)
+    int32_t reserved[2];
 };
 static_assert(sizeof(GemmPlanHeader) == 64, "GemmPlanHeader must stay 64 bytes");
 constexpr uint32_t GEMM_PLAN_MAGIC = 0x41514735u;  // "AQG5"
@@ -114,6 +115,32 @@ std::vector<int> longest_k_first(int count, KeyFn key)
 }
 
 constexpr int64_t SMALL_M = 64;      // fast-mode products with M up to this run the streaming kernel
+// The producer / consumer kernel computes blocks of 20 m-tiles (320 rows of X) whole: used when at least 4 of 5
+// of them are real rows.
+bool use_pc(int fast, int64_t M)
+{
+    if (!fast || M <= 64) return false;
+    const int64_t tiles = (M + 15) / 16, blocks = (tiles + 19) / 20;
+    return tiles * 5 >= blocks * 20 * 4;
+}
+
+AqGemmTask make_pc_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset, float* Y,
+                        int64_t ldy, int wg_begin)
+{
+    AqGemmTask t;
+    std::memset(&t, 0, sizeof(t));
+    t.blob = static_cast<const uint8_t*>(packed);
+    t.Y = Y;
+    t.N = N; t.M = M; t.ldy = ldy;
+    t.xt_offset = xt_offset;
+    t.K = (int32_t)K; t.bits = bits; t.nchunks = (int32_t)aq_num_chunks(K);
+    int slabs = 0;
+    t.wg_begin = wg_begin;
+    t.wg_count = aqk_gemm_pc_wg_count(N, M, &slabs);
+    t.slabs = slabs;
+    return t;
+}
+
 constexpr int64_t SMALL_M_EXACT = 32;  // exact-mode products with M up to this run it too, weights as two binary16 terms
 
 AqGemmTask make_small_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset,
@@ -409,6 +436,10 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, cons
     }
     const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
     if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
+    if (use_pc(fast, M)) {
+        const AqGemmTask t = make_pc_task(packed, N, K, bits, M, 0, Y, ldy, 0);
+        return aqk_gemm_pc(nullptr, 0, t, bits, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    }
     const int A = aqk_gemm_mtiles(M, aq_num_groups(N)), nsplit = aqk_gemm_nsplit(M);
     AqGemmTask t = make_gemm_task(packed, N, K, bits, M, 0, Y, ldy, A, nsplit, 0);
     return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, nsplit, fast, t.wg_count, workspace, s) == hipSuccess
@@ -448,6 +479,8 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int fla
     h.nsplit = aqk_gemm_nsplit(max_M);
     h.fast = flags == AQ_GEMM_FAST;
     h.small_mt = max_M <= (h.fast ? SMALL_M : SMALL_M_EXACT) ? aqk_small_mtiles(max_M) : 0;
+    h.pc = 1;
+    for (int i = 0; i < count; ++i) h.pc = h.pc && use_pc(h.fast, descs[i].M);      // every product of the list
     const int convert = h.fast && h.x_dtype == AQ_BF16;
     uint8_t* base = static_cast<uint8_t*>(plan_host);
     uint8_t* tasks = base + sizeof(GemmPlanHeader);
@@ -475,6 +508,7 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int fla
             if (rt.back().blocks > h.retile_max_blocks) h.retile_max_blocks = rt.back().blocks;
         }
         AqGemmTask t = h.small_mt ? make_small_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, (int)begin)
+                       : h.pc ? make_pc_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, (int)begin)
                                   : make_gemm_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, h.mtiles, h.nsplit, (int)begin);
         begin += t.wg_count;
         if (begin > 0x7FFFFFFF) return AQ_EINVAL;
@@ -497,7 +531,8 @@ static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
            h.retile_max_blocks >= 1 && h.workspace_bytes >= 1024 &&
            (h.nsplit == 1 || ((h.nsplit == 2 || h.nsplit == 4 || h.nsplit == 8) && h.mtiles == 1)) &&
            (h.fast == 0 || h.fast == 1) &&
-           (h.small_mt == 0 || h.small_mt == 1 || h.small_mt == 2 || (h.small_mt == 4 && h.fast == 1));
+           (h.small_mt == 0 || h.small_mt == 1 || h.small_mt == 2 || (h.small_mt == 4 && h.fast == 1)) &&
+           (h.pc == 0 || (h.pc == 1 && h.fast == 1 && h.small_mt == 0));
 }
 
 size_t aq_qgemm_batch_workspace_size(const void* plan_host)
@@ -532,6 +567,8 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
     }
     if (aqk_retile(rtasks, h.retile_count, rnone, h.retile_max_blocks, convert, workspace, s) != hipSuccess)
         return AQ_ELAUNCH;
+    if (h.pc)
+        return aqk_gemm_pc(tasks, h.count, none, h.bits, h.total_wgs, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.nsplit, h.fast, h.total_wgs, workspace, s) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
 }

@@ -1,0 +1,275 @@
+// Prefill, fp16-weight mode, prefill-sized M: producer and consumer wavefronts.
+//
+// The shared-role kernel (aq_gemm.hip: 8 wavefronts that all unpack and all multiply, m split 8 ways) reads the
+// whole unpacked weight tile from LDS once per wavefront: 3 MFMAs per 1 KiB LDS read, which puts LDS traffic at
+// two thirds of its peak when the matrix pipe is full -- in practice both end up half busy.  Here the 8 wavefronts
+// of a workgroup split the ROLES, one of each per SIMD:
+//   * wavefronts 0-3 (consumers) own 5 m-tiles x all 8 n-tiles each (20 m-tiles = 320 rows of X per workgroup;
+//     160 accumulator registers).  Per 32-k step a consumer reads 8 weight operands from LDS and 5 activation
+//     operands from the re-tiled X in global memory (two steps ahead) and issues 40 MFMAs: 5 MFMAs per LDS read,
+//     half the LDS traffic of the shared-role kernel, and nothing else competes for the wavefront's issue slots.
+//   * wavefronts 4-7 (producers) own 2 of the group's 8 tiles each: load the packed units two chunks ahead,
+//     unpack, multiply by the block scale in binary16 (w = d * (q - z)) and write the next chunk's tile to the
+//     other LDS buffer.  About a quarter of a chunk's time; their vector-ALU work runs under the consumers' MFMAs.
+// One LDS-only barrier per chunk (256 k) orders "next tile written" and "current tile read".
+//
+// A matrix whose largest scale could overflow binary16 has every scale multiplied by 2^-sh first and the result by
+// 2^sh (as in the small-M kernel).  Activations: the re-tiled binary16 copy Xt with one power-of-two factor per
+// row (aq_gemm.hip's pre-pass).
+#include <hip/hip_runtime.h>
+#include "aq_layout.h"
+#include "aq_kernels.h"
+#include "aq_codec.h"
+
+namespace {
+
+using namespace aqdev;
+
+constexpr int PC_THREADS = 512;
+constexpr int PC_CONSUMERS = 4;
+constexpr int PC_MT = 5;                              // m-tiles per consumer
+constexpr int PC_MBLOCK = PC_CONSUMERS * PC_MT;       // m-tiles per workgroup
+constexpr int PC_W_ROW = AQ_CHUNK_K * 2 + 32;         // LDS row stride of the weight tile: 544 B (64 j + 32: conflict-free b128 reads)
+constexpr int PC_WBUF = AQ_GROUP_ROWS * PC_W_ROW;     // one chunk's tile: 128 rows
+
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Producer: tiles 2p, 2p+1 of the group, all chunks.  Executes nch + 1 barriers.
+template <int BITS>
+__device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, int lane, uint8_t* smem, _Float16 down)
+{
+    constexpr int WORDS = Codec<BITS>::WORDS;
+    constexpr int UNIT = 512 * BITS + 256;
+    const int g = lane >> 4, c = lane & 15;
+    const int nch = t.nchunks;
+    const uint8_t* ubase = t.blob + (((int64_t)group * nch) * AQ_GROUP_TILES + 2 * p) * UNIT;
+    const int64_t chunk_stride = (int64_t)AQ_GROUP_TILES * UNIT;
+    uint32_t raw[2][WORDS];
+    uint32_t sc[2][2];                                // scales of row c, blocks 2g and 2g + 1
+    auto load_w = [&](int ch) {
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            const uint8_t* u = ubase + ch * chunk_stride + w * UNIT;
+            Codec<BITS>::load(u, lane, raw[w]);
+            const AQ_GLOBAL uint16_t* sp = as_global<uint16_t>(u + 512 * BITS + ((c >> 2) * 8 + 2 * g) * 8 + (c & 3) * 2);
+            sc[w][0] = sp[0];
+            sc[w][1] = sp[4];
+        }
+    };
+    typename Codec<BITS>::Magic magic = Codec<BITS>::magic();
+    auto unpack_to = [&](uint8_t* buf) {
+        const float z = (float)(1 << (BITS - 1));
+#pragma unroll
+        for (int w = 0; w < 2; ++w)
+#pragma unroll
+            for (int b2 = 0; b2 < 2; ++b2) {
+                uint32_t a[16];
+                Codec<BITS>::unpack(&raw[w][b2 * BITS], magic, a);         // fp16 pairs (magic + q)
+                const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)sc[w][b2]) * down;
+                uint8_t* dst = buf + ((2 * p + w) * 16 + c) * PC_W_ROW + (2 * g + b2) * 64;
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    uint32_t o[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int pidx = 4 * q4 + i;
+                        const _Float16 k = (_Float16)(Codec<BITS>::offset(pidx) + z);
+                        const uint32_t ap = a[pidx];
+                        const half2v h = (__builtin_bit_cast(half2v, ap) - half2v{k, k}) * half2v{d, d};
+                        o[i] = __builtin_bit_cast(uint32_t, h);
+                    }
+                    *reinterpret_cast<u32x4*>(dst + 16 * q4) = u32x4{o[0], o[1], o[2], o[3]};
+                }
+            }
+    };
+    load_w(0);
+    unpack_to(smem);
+    load_w(nch > 1 ? 1 : 0);
+    lds_barrier();                                    // chunk 0 is in buffer 0
+#pragma unroll 1
+    for (int ch = 0; ch < nch; ++ch) {
+        if (ch + 1 < nch) {
+            unpack_to(smem + ((ch + 1) & 1) * PC_WBUF);
+            load_w(ch + 2 < nch ? ch + 2 : nch - 1);
+        }
+        lds_barrier();                                // chunk ch + 1 written, chunk ch read
+    }
+}
+
+// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup
+template <int BITS_T>
+__global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* __restrict__ tasks, int count,
+                                                              AqGemmTask single, const uint8_t* __restrict__ workspace)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    AqGemmTask t;
+    int wg = blockIdx.x;
+    if (count == 0) {
+        t = single;
+    } else {
+        int lo = 0, hi = count - 1;
+        while (lo < hi) {
+            int mid = (lo + hi + 1) >> 1;
+            if (tasks[mid].wg_begin <= wg) lo = mid; else hi = mid - 1;
+        }
+        t = tasks[lo];
+        wg -= t.wg_begin;
+    }
+    if (wg >= t.wg_count) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int group = wg % t.slabs, mblock = wg / t.slabs;
+    const int nch = t.nchunks;
+
+    // largest scale of the matrix (blob trailer) -> power-of-two shift that keeps d * (q - z) inside binary16
+    const uint32_t max_d = *reinterpret_cast<const uint32_t*>(
+        t.blob + (int64_t)t.slabs * nch * AQ_GROUP_TILES * aq_unit_bytes(t.bits));
+    const int max_exp = (int)(max_d >> 10) - 15 + (t.bits - 1) + 1;
+    const int sh = max_exp > 15 ? max_exp - 15 : 0;
+
+    if (wave >= PC_CONSUMERS) {
+        const _Float16 down = (_Float16)__builtin_ldexpf(1.f, -(sh < 24 ? sh : 24));
+        const int p = wave - PC_CONSUMERS;
+        if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) produce<2>(t, group, p, lane, smem, down);
+        else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) produce<3>(t, group, p, lane, smem, down);
+        else produce<4>(t, group, p, lane, smem, down);
+        return;
+    }
+
+    // the consumers' MFMAs go ahead of the producers' vector-ALU work whenever both are ready to issue
+    __builtin_amdgcn_s_setprio(3);
+
+    // ---- consumer `wave`: m-tiles mt0 .. mt0 + cnt - 1 (the workgroup's T <= 20 tiles dealt as evenly as they go)
+    const int g = lane >> 4, c = lane & 15;
+    const int K = t.K, ksteps = K / AQ_BLOCK;
+    const int64_t M = t.M;
+    const int mtiles16 = (int)((M + 15) >> 4);
+    const int wg_first = mblock * PC_MBLOCK;
+    const int T = mtiles16 - wg_first < PC_MBLOCK ? mtiles16 - wg_first : PC_MBLOCK;
+    const int cnt = T / PC_CONSUMERS + (wave < T % PC_CONSUMERS ? 1 : 0);
+    const int mt0 = wg_first + wave * (T / PC_CONSUMERS) + (wave < T % PC_CONSUMERS ? wave : T % PC_CONSUMERS);
+
+    // X operands straight from the re-tiled copy Xt[m-tile][step][lane] (1 KiB per load), two steps ahead.  A tile
+    // the wavefront does not own re-reads its first tile (or tile 0) and is never stored; a step beyond K re-reads
+    // step 0 and is never used: no branches in the loop.
+    const AQ_GLOBAL u32x4* xp[PC_MT];
+#pragma unroll
+    for (int mt = 0; mt < PC_MT; ++mt)
+        xp[mt] = as_global<u32x4>(workspace + t.xt_offset) + (int64_t)(mt < cnt ? mt0 + mt : 0) * ksteps * 64 + lane;
+    u32x4 xr[2][PC_MT];
+    auto load_x = [&](int mt, int step, u32x4& dst) {
+        const int st = step < ksteps ? step : 0;
+        dst = xp[mt][st * 64];
+    };
+#pragma unroll
+    for (int mt = 0; mt < PC_MT; ++mt) {
+        load_x(mt, 0, xr[0][mt]);
+        load_x(mt, 1, xr[1][mt]);
+    }
+
+    float4v acc[PC_MT][8];
+#pragma unroll
+    for (int mt = 0; mt < PC_MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) acc[mt][nt] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    // weight operand of n-tile nt, block blk: lane (g, c) = row nt*16 + c, k = 8g .. 8g+7 of the block
+    const int lane_off = c * PC_W_ROW + g * 16;
+    // A step is four quarters of 2 n-tiles (10 MFMAs each).  Four weight operands live in registers: the two the
+    // current quarter multiplies and the two of the next quarter, requested when the current one starts, so an LDS
+    // read has 10 MFMAs (160 cycles) to arrive.
+    u32x4 bw[2][2];
+    lds_barrier();                                    // chunk 0 is in buffer 0
+#pragma unroll 1
+    for (int ch = 0; ch < nch; ++ch) {
+        const uint8_t* cur = smem + (ch & 1) * PC_WBUF + lane_off;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bw[0][j] = *reinterpret_cast<const u32x4*>(cur + j * 16 * PC_W_ROW);
+#pragma unroll
+        for (int qs = 0; qs < 32; ++qs) {             // quarter-steps: step qs / 4, n-tiles 2 * (qs % 4), + 1
+            const int s = qs >> 2, qt = qs & 3, par = s & 1, set = qs & 1;
+            if (qs < 31) {
+                const int s2 = (qs + 1) >> 2, q2 = (qs + 1) & 3;
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    bw[set ^ 1][j] = *reinterpret_cast<const u32x4*>(cur + (2 * q2 + j) * 16 * PC_W_ROW + s2 * 64);
+            }
+            __builtin_amdgcn_sched_barrier(0);        // keep the reads up here, ahead of the MFMAs they overlap with
+#pragma unroll
+            for (int mt = 0; mt < PC_MT; ++mt) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[mt][2 * qt + j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xr[par][mt]),
+                                                                                  __builtin_bit_cast(half8, bw[set][j]),
+                                                                                  acc[mt][2 * qt + j], 0, 0, 0);
+                // the step's last quarter has used this m-tile's activation operand: request step s + 2's (from
+                // L2: as early as possible)
+                if (qt == 3) {
+                    load_x(mt, ch * 8 + s + 2, xr[par][mt]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        lds_barrier();                                // chunk ch read, chunk ch + 1 written
+    }
+
+    // D[m][n]: lane (g, c) holds rows 4g .. 4g+3 of the m-tile for column c of the n-tile
+    AQ_GLOBAL float* Y = (AQ_GLOBAL float*)(uintptr_t)t.Y;
+    const int32_t* rowexp = reinterpret_cast<const int32_t*>(workspace + t.xt_offset + (int64_t)mtiles16 * 16 * K * 2);
+#pragma unroll
+    for (int mt = 0; mt < PC_MT; ++mt) {
+        if (mt < cnt) {
+            int e[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) e[r] = rowexp[(mt0 + mt) * 16 + 4 * g + r] + sh;
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt) {
+                const int64_t n = (int64_t)group * AQ_GROUP_ROWS + nt * 16 + c;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int64_t m = (int64_t)(mt0 + mt) * 16 + 4 * g + r;
+                    if (m < M && n < t.N) Y[m * t.ldy + n] = ldexpf(acc[mt][nt][r], e[r]);
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+
+// workgroups of a product: 128-row groups of W x blocks of 320 rows of X
+int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs)
+{
+    const int sl = (int)aq_num_groups(N);
+    if (slabs) *slabs = sl;
+    return sl * (int)((M + PC_MBLOCK * 16 - 1) / (PC_MBLOCK * 16));
+}
+
+// bits == 0: mixed bit-widths.  Xt: binary16, the re-tiled layout of the shared-role kernel.
+hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int total_wgs,
+                       const void* workspace, hipStream_t s)
+{
+    const size_t lds = 2 * (size_t)PC_WBUF;
+    const dim3 grid((unsigned)total_wgs), block(PC_THREADS);
+    const uint8_t* ws = static_cast<const uint8_t*>(workspace);
+#define AQ_PC(B)                                                                                                \
+    do {                                                                                                        \
+        auto k = qgemm_pc_kernel<B>;                                                                            \
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                  (int)lds);                                                                    \
+        hipLaunchKernelGGL(k, grid, block, lds, s, tasks_dev, count, single, ws);                               \
+    } while (0)
+    if (bits == 2) AQ_PC(2);
+    else if (bits == 3) AQ_PC(3);
+    else if (bits == 4) AQ_PC(4);
+    else AQ_PC(0);
+#undef AQ_PC
+    return hipGetLastError();
+}

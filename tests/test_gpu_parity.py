@@ -634,3 +634,31 @@ def test_qgemm_exact_small_m_batch(gpu, oracle):
     torch.cuda.synchronize()
     for it, ref in zip(items, refs):
         assert oracle.rel_l2(it[5].cpu().numpy(), ref) <= 2e-6
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K,M", [(200, 1056, 257), (128, 512, 320), (260, 256, 800), (300, 2048, 300), (96, 544, 645)])
+def test_qgemm_fast_producer_consumer_shapes(gpu, oracle, bits, N, K, M):
+    """Fast mode at prefill-sized M runs the producer / consumer kernel when blocks of 320 rows are at least 4/5 full:
+    17 and 20 m-tiles in one block, 50 in three (the last one half empty), ragged N, K not a multiple of 256."""
+    torch, aq = gpu
+    codes, scales = wl.draw_matrix(N, K, bits, 53, N, K)
+    X = wl.draw_activations(M, K, "bf16", 53, N, K, image_rows=min(256, M), image_gain=3.0)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
+    ref = oracle.qmatmul(codes, scales, N, K, bits, X, "bf16")
+    assert oracle.rel_l2(Y, ref) <= FAST_EXPECTED[bits]
+    for m in range(0, M, 7):
+        assert oracle.rel_l2(Y[m], ref[m]) <= REL_L2_BAR
+    # exact where the products are: power-of-two scales, integer activations
+    scales2 = wl.draw_pow2_scales(N, K, 53, bits)
+    Xi = wl.draw_int_activations(M, K, "f16", 53, bits)
+    packed = _pack(torch, aq, codes, scales2, N, K, bits)
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, Xi, "f16"), fast=True).cpu().numpy()
+    assert np.array_equal(Y.astype(np.float64), oracle.qmatmul(codes, scales2, N, K, bits, Xi, "f16"))
+    # scales so large that d * (q - z) leaves binary16: every scale is halved a few times first
+    big = wl.f32_to_f16_bits(np.ldexp(wl.f16_bits_to_f32(scales), 19))
+    packed = _pack(torch, aq, codes, big, N, K, bits)
+    Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
+    assert np.isfinite(Y).all()
+    assert oracle.rel_l2(Y, oracle.qmatmul(codes, big, N, K, bits, X, "bf16")) <= FAST_EXPECTED[bits]
