@@ -1,5 +1,9 @@
 """Host-only checks of the C ABI: the library loads without a GPU, exports every symbol
-include/aq.h declares, and rejects bad arguments before touching the device."""
+include/aq.h declares, and rejects bad arguments before touching the device.
+
+The device pointers below are made-up numbers.  Every call that takes them must FAIL validation (or only build a
+plan on the host): these tests also run on machines with a GPU, where a call that passed validation would launch a
+kernel on those addresses."""
 import ctypes
 import os
 import re
@@ -228,7 +232,6 @@ def test_two_level_variant_validation_without_a_gpu(L):
     assert L.aq2_packed_size(129, 257 - 1 + 32, 3, 32) == 2 * 2 * 8 * (512 * 3 + 192)
     assert L.aq2_packed_size(128, 256, 5, 32) == 0 and L.aq2_packed_size(128, 250, 2, 32) == 0
     size = L.aq2_packed_size(64, 512, 4, 32)
-    assert L.aq2_pack_weights(A, A, A, 64, 512, 4, 32, A, size, None) in (aq.AQ_OK, aq.AQ_ELAUNCH)   # valid: reaches the launch
     assert L.aq2_pack_weights(A, A, A, 64, 512, 4, 32, A, size - 1, None) == aq.AQ_ESIZE
     assert L.aq2_pack_weights(A, None, A, 64, 512, 4, 32, A, size, None) == aq.AQ_ENULL
     assert L.aq2_pack_weights(A, A, A + 2, 64, 512, 4, 32, A, size, None) == aq.AQ_EALIGN
