@@ -284,6 +284,21 @@ def iter_stream_inputs(stream: Sequence[MatrixSpec], M: int, dtype: str, seed: i
 # from the numpy draws (another generator) but follow the same recipe; the bench
 # copies what the oracle needs back to the host.
 # ----------------------------------------------------------------------------
+# calibration-shaped inputs for the HSIC sensitivity: K samples of input hidden states X, of a matrix's output
+# hidden states Z (a random linear map of X plus noise: dependent on X), and of action labels Y (a random
+# low-dimensional read-out of Z plus noise)
+# ----------------------------------------------------------------------------
+def draw_hsic_inputs(K: int, d_in: int, d_out: int, d_act: int, *key: int, noise: float = 0.5):
+    g = _rng(505, *key)
+    X = g.standard_normal(size=(K, d_in), dtype=np.float32)
+    P = g.standard_normal(size=(d_in, d_out), dtype=np.float32) / np.float32(np.sqrt(d_in))
+    Z = (X @ P + np.float32(noise) * g.standard_normal(size=(K, d_out), dtype=np.float32)).astype(np.float32)
+    R = g.standard_normal(size=(d_out, d_act), dtype=np.float32) / np.float32(np.sqrt(d_out))
+    Y = np.tanh(Z @ R + np.float32(noise) * g.standard_normal(size=(K, d_act), dtype=np.float32)).astype(np.float32)
+    return X, Z, Y
+
+
+# ----------------------------------------------------------------------------
 # two-level variant of the format: 4-bit scale and offset codes per block, two fp16 numbers per super-block
 # ----------------------------------------------------------------------------
 def draw_affine_params(N: int, K: int, bits: int, *key: int) -> Tuple[np.ndarray, np.ndarray]:
