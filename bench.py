@@ -83,6 +83,7 @@ def main():
     ap.add_argument("--skip-cells", action="store_true")
     ap.add_argument("--skip-layer-step", action="store_true")
     ap.add_argument("--skip-two-level", action="store_true")
+    ap.add_argument("--skip-hsic", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=5)
     ap.add_argument("--prefill-only", action="store_true",
                     help="the timed decode stream with 2 steps, then only the M = 300 prefill (short run for rocprofv3 --pmc passes)")
@@ -93,11 +94,11 @@ def main():
     args = ap.parse_args()
     if args.prefill_only:
         args.skip_by_bits = args.skip_cpu = args.skip_gemma = args.skip_quant = args.skip_cells = True
-        args.skip_layer_step = args.skip_two_level = True
+        args.skip_layer_step = args.skip_two_level = args.skip_hsic = True
         args.steps, args.warmup = 2, 1
     if args.decode_only:
         args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = args.skip_quant = args.skip_cells = True
-        args.skip_layer_step = args.skip_two_level = True
+        args.skip_layer_step = args.skip_two_level = args.skip_hsic = True
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists).", file=sys.stderr)
         sys.exit(2)
@@ -407,6 +408,37 @@ def main():
                           "tokens_per_s": round(1e3 / ms, 1)}
             del items, bt
         out["two_level_format"] = two
+
+    if not args.skip_hsic:
+        # Eq. 5 for one weight matrix: K calibration samples of input hidden states, of the matrix's output hidden
+        # states and of 7-dimensional action labels; the cost is the three Gram products (fp32 on the matrix cores)
+        torch.cuda.empty_cache()
+        K, dx, dz, dy = 4096, 4096, 11008, 7
+        g = torch.Generator(device="cuda").manual_seed(9)
+        X = torch.randn((K, dx), generator=g, device="cuda")
+        Z = torch.randn((K, dz), generator=g, device="cuda")
+        Y = torch.tanh(torch.randn((K, dy), generator=g, device="cuda"))
+        ws = torch.empty(int(aq.lib().aq_hsic_workspace_size(K)), dtype=torch.uint8, device="cuda")
+        fn = lambda: aq.aq_hsic_sensitivity(X, 0.5 / dx, Z, 0.5 / dz, Y, 0.5 / dy, 1.0, 1.0, workspace=ws)
+        d, w = time_launches(torch, fn, 5, 2)
+        ms = sum(d) / len(d)
+        flop = 2.0 * K * K * (dx + dz + dy)
+        hs = {"workload": "K = %d samples; X [K, %d], Z [K, %d], Y [K, %d] fp32; gamma = 1 / (2 d)" % (K, dx, dz, dy),
+              "ms": round(ms, 3), "TFLOP/s": round(flop / (ms * 1e-3) / 1e12, 1),
+              "frac_fp32_mfma_peak": round(flop / (ms * 1e-3) / 1e12 / 157.3, 4)}
+        if not args.skip_cpu:
+            from oracle import aq_hsic_oracle
+            Ks = 384
+            Xc, Zc, Yc = X[:Ks].cpu().numpy(), Z[:Ks].cpu().numpy(), Y[:Ks].cpu().numpy()
+            t0 = time.perf_counter()
+            ref = aq_hsic_oracle.sensitivity(Xc, 0.5 / dx, Zc, 0.5 / dz, Yc, 0.5 / dy, 1.0, 1.0)
+            cpu_s = time.perf_counter() - t0
+            got = aq.aq_hsic_sensitivity(X[:Ks].contiguous(), 0.5 / dx, Z[:Ks].contiguous(), 0.5 / dz, Y[:Ks].contiguous(),
+                                         0.5 / dy, 1.0, 1.0).cpu().numpy()
+            hs["cpu_oracle"] = {"TFLOP/s": round(2.0 * Ks * Ks * (dx + dz + dy) / cpu_s / 1e12, 5), "cores": 1,
+                                "sample": "the first %d samples, %.2f s" % (Ks, cpu_s),
+                                "gpu_vs_oracle_rel_err": float(abs(got[2] - ref) / max(abs(ref), 1e-30))}
+        out["hsic_sensitivity"] = hs
 
     if not args.skip_quant:
         torch.cuda.empty_cache()

@@ -268,6 +268,23 @@ int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks /*HO
                    void* plan_host, size_t plan_bytes);
 int aq_decode_step(const void* plan_host, void* stream);
 
+/* Tensor sensitivity from HSIC (Section 4.1, Eq. 5; the estimator is Eq. 4 of Section 3):
+ *     HSIC(A, B) = (K - 1)^-2 tr(K_A C K_B C),  [K_A]_ij = exp(-gamma_A ||a_i - a_j||^2),  C = I - (1/K) 1 1^T
+ *     S = -alpha HSIC(X, Z) + beta HSIC(Z, Y)
+ * over K paired calibration samples: X[K][dx] the backbone's input hidden states, Z[K][dz] the output hidden states
+ * of the weight matrix being scored, Y[K][dy] the action labels (DEVICE fp32, row strides ldx, ldz, ldy in
+ * elements, 16-byte aligned).  The RBF bandwidths are inputs (gamma > 0; the paper does not fix them).
+ *   out        DEVICE double [3]: HSIC(X, Z), HSIC(Z, Y), S
+ *   workspace  DEVICE, aq_hsic_workspace_size(K) bytes (three K x K fp32 kernel matrices and their row sums)
+ * The Gram products run in fp32 on the matrix cores, the sums in fp64.  2 <= K <= 65536.
+ * aq_rbf_gram writes one kernel matrix G[K][K] (parity; workspace: K floats). */
+size_t aq_hsic_workspace_size(int64_t K);
+int aq_rbf_gram(const float* A, int64_t K, int64_t d, int64_t lda, float gamma, float* G, void* workspace,
+                size_t workspace_bytes, void* stream);
+int aq_hsic_sensitivity(const float* X, int64_t dx, int64_t ldx, float gamma_x, const float* Z, int64_t dz, int64_t ldz,
+                        float gamma_z, const float* Y, int64_t dy, int64_t ldy, float gamma_y, int64_t K, double alpha,
+                        double beta, double* out, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Parity / debug: the blob decoded back to what Eq. 1 defines.
  *   codes_u8 DEVICE uint8 [N][K]  one code per byte
  *   W        DEVICE float [N][K]  d * (q - 2^(bits-1)); exact in fp32 (11-bit x 4-bit significands) */

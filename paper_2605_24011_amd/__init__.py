@@ -95,6 +95,12 @@ def lib() -> ctypes.CDLL:
         L.aq2_qgemv_batch_plan.argtypes = [ctypes.POINTER(aq_gemv_desc), _int, _int, _p, _sz]
         L.aq2_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq2_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
+        L.aq_hsic_workspace_size.restype = _sz
+        L.aq_hsic_workspace_size.argtypes = [_i64]
+        L.aq_rbf_gram.argtypes = [_p, _i64, _i64, _i64, ctypes.c_float, _p, _p, _sz, _p]
+        L.aq_hsic_sensitivity.argtypes = [_p, _i64, _i64, ctypes.c_float, _p, _i64, _i64, ctypes.c_float,
+                                          _p, _i64, _i64, ctypes.c_float, _i64, ctypes.c_double, ctypes.c_double,
+                                          _p, _p, _sz, _p]
         L.aq_decode_plan_size.restype = _sz
         L.aq_decode_plan_size.argtypes = [_int]
         L.aq_decode_workspace_size.restype = _sz
@@ -347,4 +353,32 @@ def aq2_dequant_f32(packed, N: int, K: int, bits: int, block: int = BLOCK, strea
     out = torch.empty((N, K), dtype=torch.float32, device=packed.device)
     _check(lib().aq2_dequant_f32(packed.data_ptr(), N, K, bits, block, out.data_ptr(), _stream(stream)),
            "aq2_dequant_f32")
+    return out
+
+
+# ---- HSIC sensitivity ----
+def aq_rbf_gram(A, gamma: float, stream=None):
+    """A: cuda float32 [K, d] -> the RBF kernel matrix, cuda float32 [K, K]."""
+    import torch
+    K, d = A.shape
+    G = torch.empty((K, K), dtype=torch.float32, device=A.device)
+    ws = torch.empty(max(K, 4), dtype=torch.float32, device=A.device)
+    _check(lib().aq_rbf_gram(A.data_ptr(), K, d, A.stride(0), gamma, G.data_ptr(), ws.data_ptr(), ws.numel() * 4,
+                             _stream(stream)), "aq_rbf_gram")
+    return G
+
+
+def aq_hsic_sensitivity(X, gamma_x: float, Z, gamma_z: float, Y, gamma_y: float, alpha: float, beta: float,
+                        workspace=None, stream=None):
+    """X, Z, Y: cuda float32 [K, d*] -> cuda float64 [3]: HSIC(X, Z), HSIC(Z, Y), -alpha HSIC(X, Z) + beta HSIC(Z, Y)."""
+    import torch
+    K = X.shape[0]
+    size = int(lib().aq_hsic_workspace_size(K))
+    if workspace is None:
+        workspace = torch.empty(max(size, 16), dtype=torch.uint8, device=X.device)
+    out = torch.empty(3, dtype=torch.float64, device=X.device)
+    _check(lib().aq_hsic_sensitivity(X.data_ptr(), X.shape[1], X.stride(0), gamma_x, Z.data_ptr(), Z.shape[1], Z.stride(0),
+                                     gamma_z, Y.data_ptr(), Y.shape[1], Y.stride(0), gamma_y, K, alpha, beta,
+                                     out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)),
+           "aq_hsic_sensitivity")
     return out

@@ -779,6 +779,62 @@ int aq_decode_step(const void* plan_host, void* stream)
     return AQ_OK;
 }
 
+// ---- HSIC sensitivity ----
+// workspace layout for `vars` variables: vars Gram matrices (K*K floats each), vars * K floats of squared norms,
+// then (8-byte aligned) vars * K doubles of row sums and 8 doubles of accumulators
+static size_t hsic_ws_bytes(int64_t K, int vars)
+{
+    const size_t f = (size_t)vars * (size_t)K * (size_t)K + (size_t)vars * (size_t)K;
+    return ((f * sizeof(float) + 15) / 16) * 16 + ((size_t)vars * (size_t)K + 8) * sizeof(double);
+}
+
+size_t aq_hsic_workspace_size(int64_t K)
+{
+    if (K < 2 || K > 65536) return 0;
+    return hsic_ws_bytes(K, 3);
+}
+
+int aq_rbf_gram(const float* A, int64_t K, int64_t d, int64_t lda, float gamma, float* G, void* workspace,
+                size_t workspace_bytes, void* stream)
+{
+    if (K < 2 || K > 65536 || d < 1 || d > ((int64_t)1 << 24) || lda < d || !(gamma > 0.f)) return AQ_EINVAL;
+    if (!A || !G || !workspace) return AQ_ENULL;
+    if (!aligned16(A) || !aligned16(G) || !aligned16(workspace)) return AQ_EALIGN;
+    if (workspace_bytes < (size_t)K * sizeof(float)) return AQ_ESIZE;
+    return aqk_rbf_gram(A, K, d, lda, gamma, G, static_cast<float*>(workspace), static_cast<hipStream_t>(stream)) ==
+                   hipSuccess ? AQ_OK : AQ_ELAUNCH;
+}
+
+int aq_hsic_sensitivity(const float* X, int64_t dx, int64_t ldx, float gamma_x, const float* Z, int64_t dz, int64_t ldz,
+                        float gamma_z, const float* Y, int64_t dy, int64_t ldy, float gamma_y, int64_t K, double alpha,
+                        double beta, double* out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (K < 2 || K > 65536) return AQ_EINVAL;
+    const int64_t dmax = (int64_t)1 << 24;
+    if (dx < 1 || dz < 1 || dy < 1 || dx > dmax || dz > dmax || dy > dmax || ldx < dx || ldz < dz || ldy < dy) return AQ_EINVAL;
+    if (!(gamma_x > 0.f) || !(gamma_z > 0.f) || !(gamma_y > 0.f) || !(alpha >= 0.0) || !(beta >= 0.0)) return AQ_EINVAL;
+    if (!X || !Z || !Y || !out || !workspace) return AQ_ENULL;
+    if (!aligned16(X) || !aligned16(Z) || !aligned16(Y) || !aligned16(out) || !aligned16(workspace)) return AQ_EALIGN;
+    if (workspace_bytes < hsic_ws_bytes(K, 3)) return AQ_ESIZE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* G = static_cast<float*>(workspace);
+    float* sq = G + 3 * K * K;
+    const size_t f = (size_t)3 * K * K + (size_t)3 * K;
+    double* rs = reinterpret_cast<double*>(static_cast<uint8_t*>(workspace) + ((f * sizeof(float) + 15) / 16) * 16);
+    double* acc = rs + 3 * K;
+    const float* in[3] = {X, Z, Y};
+    const int64_t dd[3] = {dx, dz, dy}, ld[3] = {ldx, ldz, ldy};
+    const float gm[3] = {gamma_x, gamma_z, gamma_y};
+    for (int v = 0; v < 3; ++v) {
+        if (aqk_rbf_gram(in[v], K, dd[v], ld[v], gm[v], G + v * K * K, sq + v * K, s) != hipSuccess) return AQ_ELAUNCH;
+        if (aqk_rowsum(G + v * K * K, K, rs + v * K, s) != hipSuccess) return AQ_ELAUNCH;
+    }
+    if (aqk_zero_f64(acc, 8, s) != hipSuccess) return AQ_ELAUNCH;
+    if (aqk_hsic_pair(G, G + K * K, K, rs, rs + K, acc, s) != hipSuccess) return AQ_ELAUNCH;                    // (X, Z)
+    if (aqk_hsic_pair(G + K * K, G + 2 * K * K, K, rs + K, rs + 2 * K, acc + 4, s) != hipSuccess) return AQ_ELAUNCH;   // (Z, Y)
+    return aqk_hsic_finish(acc, 2, K, alpha, beta, out, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+}
+
 int aq_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream)
 {
     int rc = check_matrix(N, K, bits, block);
