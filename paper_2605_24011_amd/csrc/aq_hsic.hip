@@ -38,7 +38,8 @@ __global__ __launch_bounds__(256) void sqnorm_kernel(const float* __restrict__ A
     if (lane == 0) r[row] = s;
 }
 
-// G[i][j] = exp(-gamma * max(0, r_i + r_j - 2 a_i.a_j)) for the 128 x 128 tile (blockIdx.y, blockIdx.x)
+// G[i][j] = exp(-gamma * max(0, r_i + r_j - 2 a_i.a_j)) for the 128 x 128 tile (blockIdx.y, blockIdx.x).  The matrix
+// is symmetric: only tiles on or above the diagonal are computed, and each writes its mirror image as well.
 __global__ __launch_bounds__(256) void gram_rbf_kernel(const float* __restrict__ A, int64_t K, int64_t d, int64_t lda,
                                                        const float* __restrict__ r, float gamma, float* __restrict__ G)
 {
@@ -47,7 +48,9 @@ __global__ __launch_bounds__(256) void gram_rbf_kernel(const float* __restrict__
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wi = wave >> 1, wj = wave & 1;                 // this wavefront's 64 x 64 quadrant
+    if (blockIdx.x < blockIdx.y) return;                     // below the diagonal: the mirror tile writes it
     const int64_t i0 = (int64_t)blockIdx.y * GT, j0 = (int64_t)blockIdx.x * GT;
+    const bool mirror = blockIdx.x != blockIdx.y;
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -57,28 +60,48 @@ __global__ __launch_bounds__(256) void gram_rbf_kernel(const float* __restrict__
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    // staging: thread t copies features 4 * (t % 4) .. + 3 of rows t / 4 and t / 4 + 64 of both blocks
+    // staging: thread t copies features 4 * (t % 4) .. + 3 of rows t / 4 and t / 4 + 64 of both blocks; the next
+    // stage's 16 values are requested before the current stage is multiplied and stored after it
     const int srow = tid >> 2, sk = (tid & 3) * 4;
-    for (int64_t k0 = 0; k0 < d; k0 += KC) {
+    const bool vec = (lda & 3) == 0;                         // rows start 16-byte aligned: whole quads in one load
+    float nx[2][2][4];                                       // [row half][i / j block][element]
+    auto fetch = [&](int64_t k0) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int rr = srow + 64 * h;
-            float vi[4], vj[4];
+            const int64_t k = k0 + sk;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int64_t k = k0 + sk + e;
-                vi[e] = (i0 + rr < K && k < d) ? A[(i0 + rr) * lda + k] : 0.f;
-                vj[e] = (j0 + rr < K && k < d) ? A[(j0 + rr) * lda + k] : 0.f;
-            }
+            for (int blk = 0; blk < 2; ++blk) {
+                const int64_t row = (blk ? j0 : i0) + rr;
+                if (row < K && vec && k + 3 < d) {
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(A + row * lda + k);
+                    nx[h][blk][0] = v.x; nx[h][blk][1] = v.y; nx[h][blk][2] = v.z; nx[h][blk][3] = v.w;
+                } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ti[rr * LROW + sk + e] = vi[e];
-                tj[rr * LROW + sk + e] = vj[e];
+                    for (int e = 0; e < 4; ++e) nx[h][blk][e] = (row < K && k + e < d) ? A[row * lda + k + e] : 0.f;
+                }
             }
         }
-        __syncthreads();
-        // operand layout of the 32x32x2 MFMA: lane l supplies A[row l % 32][k l / 32] and B[k l / 32][column l % 32]
-        const int lr = lane & 31, lk = lane >> 5;
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int rr = srow + 64 * h;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                ti[rr * LROW + sk + e] = nx[h][0][e];
+                tj[rr * LROW + sk + e] = nx[h][1][e];
+            }
+        }
+    };
+    // operand layout of the 32x32x2 MFMA: lane l supplies A[row l % 32][k l / 32] and B[k l / 32][column l % 32]
+    const int lr = lane & 31, lk = lane >> 5;
+    fetch(0);
+    stash();
+    __syncthreads();
+    for (int64_t k0 = 0; k0 < d; k0 += KC) {
+        const bool more = k0 + KC < d;
+        if (more) fetch(k0 + KC);
 #pragma unroll
         for (int kk = 0; kk < KC; kk += 2) {
             float fa[2], fb[2];
@@ -92,7 +115,11 @@ __global__ __launch_bounds__(256) void gram_rbf_kernel(const float* __restrict__
                 for (int b = 0; b < 2; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a], fb[b], acc[a][b], 0, 0, 0);
         }
-        __syncthreads();
+        __syncthreads();                                     // everyone has read this stage
+        if (more) {
+            stash();
+            __syncthreads();                                 // the next stage is in place
+        }
     }
 
     // result layout: register v of lane l is row 8 * (v / 4) + 4 * (l / 32) + v % 4, column l % 32 of the 32 x 32 tile
@@ -108,7 +135,9 @@ __global__ __launch_bounds__(256) void gram_rbf_kernel(const float* __restrict__
                 const int64_t i = i0 + wi * 64 + a * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                 if (i < K && j < K) {
                     const float d2 = fmaxf(r[i] + rj - 2.f * acc[a][b][v], 0.f);
-                    G[i * K + j] = i == j ? 1.f : __expf(-gamma * d2);
+                    const float gv = i == j ? 1.f : __expf(-gamma * d2);
+                    G[i * K + j] = gv;
+                    if (mirror) G[j * K + i] = gv;
                 }
             }
         }
