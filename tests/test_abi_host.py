@@ -256,3 +256,28 @@ def test_two_level_variant_validation_without_a_gpu(L):
     assert np.frombuffer(bytes(buf[:64]), dtype=np.int32)[6] == 0
     descs[1].bits = 9
     assert L.aq2_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_EINVAL
+
+
+def test_hsic_validation_without_a_gpu(L):
+    A = 1 << 20
+    L.aq_hsic_workspace_size.restype = ctypes.c_size_t
+    K = 100
+    floats = 3 * K * K + 3 * K
+    assert L.aq_hsic_workspace_size(K) == ((floats * 4 + 15) // 16) * 16 + (3 * K + 8) * 8
+    assert L.aq_hsic_workspace_size(1) == 0 and L.aq_hsic_workspace_size(1 << 17) == 0
+    f, dbl = ctypes.c_float, ctypes.c_double
+    sens = lambda *a: L.aq_hsic_sensitivity(*a)
+    ws = L.aq_hsic_workspace_size(K)
+    good = [A, 8, 8, f(1.0), A, 8, 8, f(1.0), A, 4, 4, f(1.0), K, dbl(1.0), dbl(1.0), A, A, ws, None]
+    def with_(i, v):
+        a = list(good); a[i] = v; return a
+    assert sens(*with_(12, 1)) == aq.AQ_EINVAL                    # K < 2
+    assert sens(*with_(3, f(0.0))) == aq.AQ_EINVAL                # gamma must be positive
+    assert sens(*with_(2, 4)) == aq.AQ_EINVAL                     # row stride below the row length
+    assert sens(*with_(13, dbl(-1.0))) == aq.AQ_EINVAL            # alpha in R+
+    assert sens(*with_(4, None)) == aq.AQ_ENULL
+    assert sens(*with_(15, A + 8)) == aq.AQ_EALIGN
+    assert sens(*with_(17, ws - 1)) == aq.AQ_ESIZE
+    assert L.aq_rbf_gram(A, K, 8, 8, f(-1.0), A, A, 4 * K, None) == aq.AQ_EINVAL
+    assert L.aq_rbf_gram(A, K, 8, 8, f(1.0), None, A, 4 * K, None) == aq.AQ_ENULL
+    assert L.aq_rbf_gram(A, K, 8, 8, f(1.0), A, A, 4 * K - 1, None) == aq.AQ_ESIZE
