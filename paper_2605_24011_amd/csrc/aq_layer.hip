@@ -74,14 +74,6 @@ __device__ __forceinline__ void ring_fill(const AqStageTask& t, int wg, int wave
         }
 }
 
-__device__ __forceinline__ void ring_fill_any(const AqStageTask& t, int wg, int wave, int lane,
-                                              uint32_t (&raw)[2 * TW][8], u32x2 (&sc)[2 * TW])
-{
-    if (t.bits == 2) ring_fill<2>(t, wg, wave, lane, raw, sc);
-    else if (t.bits == 3) ring_fill<3>(t, wg, wave, lane, raw, sc);
-    else ring_fill<4>(t, wg, wave, lane, raw, sc);
-}
-
 __global__ __launch_bounds__(THREADS, 3)
 void layer_stage_kernel(const AqStageArgs args)
 {
