@@ -5,7 +5,8 @@
 // block-diagonal x, which leaves in lane (g, c) the sums  B[r] = sum_k (q - z) x  of block c for rows 4g .. 4g+3
 // (z = 2^(bits-1), the offset the unpack constants are built around).  What changes is what happens to a block sum:
 //     sum_k x (D a q - M c)  =  (D a) * (B[r] + z X_b)  -  (M c) * X_b,      X_b = sum of x over the block,
-// two fp32 multiply-adds per row and block; X_b is computed once per workgroup while x is staged (next to the
+// two fp32 multiply-adds per row and block (each lane does two of the block's four rows: the lanes of the MFMA's
+// eight empty block columns take half of their neighbours' work); X_b is computed once per workgroup while x is staged (next to the
 // correction terms), z X_b rides in the MFMAs' C operand, and the two coefficients are formed from the lane's
 // 4 bytes of codes and 4 (D, M) pairs.
 // Same work split, ring and launch shapes as the base kernel; a unit is 64 bytes shorter.
@@ -43,8 +44,8 @@ __device__ __forceinline__ void block_sums(const uint8_t* xl, float* xsum, int n
 template <int BITS, bool REFILL>
 __device__ __forceinline__ void unit_step2(uint32_t (&raw)[Codec<BITS>::WORDS], uint32_t& sub, u32x4& sup,
                                            typename Codec<BITS>::Magic& magic, const half8 (&B)[8],
-                                           const float4v& negc, float xs, const uint8_t* next, int lane, int sub_off,
-                                           int sup_off, float (&acc)[4])
+                                           const float4v& negc, float xs, bool hi, const uint8_t* next, int lane,
+                                           int sub_off, int sup_off, float (&acc)[2])
 {
     Codec<BITS>::fence(magic, acc[0]);
     uint32_t a0[16], a1[16];
@@ -63,14 +64,29 @@ __device__ __forceinline__ void unit_step2(uint32_t (&raw)[Codec<BITS>::WORDS], 
         u32x4 av = {a0[2 * m], a0[2 * m + 1], a1[2 * m], a1[2 * m + 1]};
         D = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, av), B[m], D, 0, 0, 0);
     }
-    // D[r] = sum_k q x of the block (the caller put z * X_b into the MFMAs' C operand next to the correction term)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const float a = (float)((s4 >> (8 * r)) & 15u), c = (float)((s4 >> (8 * r + 4)) & 15u);
-        const float Dr = (float)__builtin_bit_cast(_Float16, (uint16_t)(p[r] & 0xFFFFu));
-        const float Mr = (float)__builtin_bit_cast(_Float16, (uint16_t)(p[r] >> 16));
-        acc[r] = fmaf(D[r], Dr * a, acc[r]);             // s_b * sum q x
-        acc[r] = fmaf(xs, -(Mr * c), acc[r]);            // - s_b z_b * X_b
+    // D[r] = sum_k q x of the block (the caller put z * X_b into the MFMAs' C operand next to the correction term),
+    // in lanes c < 8 only: the MFMA's block columns 8..15 are empty.  Lane c + 8 takes rows 2, 3 off lane c's hands
+    // (two cross-lane moves), so every lane scales two block sums instead of half the lanes four.
+    const bool upper = hi;                                              // this lane does rows 2, 3
+    const float d0 = D[0], d1 = D[1], d2 = D[2], d3 = D[3];              // scalars first: bit_cast of a vector element misreads it
+    // row_shr:8 -- lane c + 8 receives from lane c; lanes c < 8 have no source and keep the first operand
+    const float e0 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, d0), __builtin_bit_cast(int, d2), 0x118, 0xF, 0xF, false));
+    const float e1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, d1), __builtin_bit_cast(int, d3), 0x118, 0xF, 0xF, false));
+    const uint32_t s2 = upper ? (s4 >> 16) : s4;                        // the two rows' (a, c) bytes
+    const uint32_t pa = upper ? p[2] : p[0], pb = upper ? p[3] : p[1];  // their (D, M)
+    {
+        const float a = (float)(s2 & 15u), c = (float)((s2 >> 4) & 15u);
+        const float Dr = (float)__builtin_bit_cast(_Float16, (uint16_t)(pa & 0xFFFFu));
+        const float Mr = (float)__builtin_bit_cast(_Float16, (uint16_t)(pa >> 16));
+        acc[0] = fmaf(e0, Dr * a, acc[0]);               // s_b * sum q x
+        acc[0] = fmaf(xs, -(Mr * c), acc[0]);            // - s_b z_b * X_b
+    }
+    {
+        const float a = (float)((s2 >> 8) & 15u), c = (float)((s2 >> 12) & 15u);
+        const float Dr = (float)__builtin_bit_cast(_Float16, (uint16_t)(pb & 0xFFFFu));
+        const float Mr = (float)__builtin_bit_cast(_Float16, (uint16_t)(pb >> 16));
+        acc[1] = fmaf(e1, Dr * a, acc[1]);
+        acc[1] = fmaf(xs, -(Mr * c), acc[1]);
     }
 }
 
@@ -78,7 +94,7 @@ template <int BITS, int TW, bool REFILL>
 __device__ __forceinline__ void chunk_step2(uint32_t (*raw)[Codec<BITS>::WORDS], uint32_t* sub, u32x4* sup,
                                             typename Codec<BITS>::Magic& magic, const uint8_t* xl, const float* corr,
                                             const float* xsum, const uint8_t* zeros, int ch, bool diag, int c,
-                                            const uint8_t* refill, int lane, int sub_off, int sup_off, float (*acc)[4])
+                                            const uint8_t* refill, int lane, int sub_off, int sup_off, float (*acc)[2])
 {
     constexpr int UNIT = 512 * BITS + AQ2_PARAM_BYTES;
     typedef u32x4 u32x4_a8 __attribute__((aligned(8)));
@@ -93,7 +109,7 @@ __device__ __forceinline__ void chunk_step2(uint32_t (*raw)[Codec<BITS>::WORDS],
     const float4v negc = {nc, nc, nc, nc};
 #pragma unroll
     for (int tw = 0; tw < TW; ++tw)
-        unit_step2<BITS, REFILL>(raw[tw], sub[tw], sup[tw], magic, B, negc, xs, refill + tw * UNIT, lane, sub_off,
+        unit_step2<BITS, REFILL>(raw[tw], sub[tw], sup[tw], magic, B, negc, xs, c >= 8, refill + tw * UNIT, lane, sub_off,
                                  sup_off, acc[tw]);
 }
 
