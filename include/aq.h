@@ -237,7 +237,7 @@ int aq2_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int bloc
  * additions, so the last bits of a result can differ between runs.
  * One launch per stage (4 per layer, each taking its matrices' records as kernel arguments) plus one that clears
  * qkv; consecutive launches on one stream are the barriers between dependent stages.
- *   shape      HOST; d_model, d_ff, n_heads * head_dim multiples of 32 and <= 65536, head_dim a multiple of 8,
+ *   shape      HOST; d_model, d_ff, n_heads * head_dim multiples of 32 and <= 16384 (the K limit of aq_pack_weights), head_dim a multiple of 8,
  *              n_heads a multiple of n_kv_heads, act = AQ_ACT_SILU or AQ_ACT_GELU_TANH, eps >= 0
  *   blocks     HOST array of `layers` records: w[0..6] = DEVICE blobs (aq_pack_weights) of q, k, v, o, gate, up,
  *              down with the shapes the block shape implies and bit-widths bits[0..6]; norm_attn, norm_mlp =

@@ -652,12 +652,12 @@ int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int
     if (!shape || !blocks || !x || !qkv || !workspace || !plan_host) return AQ_ENULL;
     if (layers < 1 || block != AQ_BLOCK) return AQ_EINVAL;
     const aq_block_shape& sh = *shape;
-    if (sh.d_model < 32 || sh.d_ff < 32 || sh.d_model % 32 || sh.d_ff % 32 || sh.d_model > 65536 || sh.d_ff > 65536)
+    if (sh.d_model < 32 || sh.d_ff < 32 || sh.d_model % 32 || sh.d_ff % 32 || sh.d_model > AQ_MAX_K || sh.d_ff > AQ_MAX_K)
         return AQ_EINVAL;
     if (sh.n_heads < 1 || sh.n_kv_heads < 1 || sh.n_heads % sh.n_kv_heads || sh.head_dim < 8 || sh.head_dim % 8)
         return AQ_EINVAL;
     const int64_t dq = (int64_t)sh.n_heads * sh.head_dim, dkv = (int64_t)sh.n_kv_heads * sh.head_dim;
-    if (dq % 32 || dkv % 32 || dq > 65536) return AQ_EINVAL;
+    if (dq % 32 || dkv % 32 || dq > AQ_MAX_K) return AQ_EINVAL;      // every K of a block must be one aq_pack_weights takes
     if (sh.act != AQ_ACT_SILU && sh.act != AQ_ACT_GELU_TANH) return AQ_EINVAL;
     if (!(sh.eps >= 0.f)) return AQ_EINVAL;
     if (!aligned16(x) || !aligned16(qkv) || !aligned16(workspace)) return AQ_EALIGN;
