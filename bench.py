@@ -406,7 +406,23 @@ def main():
                           "bytes": nbytes, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
                           "pct_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),
                           "tokens_per_s": round(1e3 / ms, 1)}
-            del items, bt
+            del bt
+            if alloc == "mixed":
+                # prefill over the same blobs (aq2_qgemm semantics: weights formed in binary16), M = 300
+                M = wl.PREFILL_M
+                Xs = {K: wl.draw_activations_torch(M, K, "bf16", "cuda", 13, K, image_rows=wl.PREFILL_IMAGE_ROWS,
+                                                   image_gain=wl.PREFILL_IMAGE_GAIN) for K in sorted({m.K for m in specs})}
+                Ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({m.N for m in specs})}
+                gb = aq.GemmBatch([(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in items],
+                                  two_level=True)
+                d, w = time_launches(torch, gb.run, args.prefill_steps, 1)
+                ms = sum(d) / len(d)
+                flops = 2.0 * M * weights
+                two["mixed_prefill_m300"] = {"ms": round(ms, 3), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
+                                             "mfma_frac_of_bf16_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                             "prefill_tokens_per_s": round(M / (ms * 1e-3), 1)}
+                del gb, Xs, Ys
+            del items
         out["two_level_format"] = two
 
     if not args.skip_hsic:

@@ -208,7 +208,13 @@ int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const 
  * block's sum B = sum (q - 2^(bits-1)) x becomes (D a) B + (2^(bits-1) D a - M c) * (sum of x over the block) in
  * fp32.  aq2_qgemv_batch_plan plans a list of such products (every blob of the list in this format); the plan is
  * launched with aq_qgemv_batch.  aq2_unpack_codes / aq2_dequant_f32 are the parity inverses (the latter returns
- * fp32(D a q - M c), rounded once).  Decode only: prefill and the decode step through the blocks take the base
+ * fp32(D a q - M c), rounded once).
+ * aq2_qgemm is aq_qgemm for such a blob, at any M in 1 .. AQ_MAX_M, in the AQ_GEMM_FAST mode only: a weight meets X
+ * as the binary16 number fp16(q * fp16(D a) - fp16(M c)), the subtraction fused (three roundings to 11 bits, against
+ * one in the base format), X as in AQ_GEMM_FAST; the caller keeps 15 * (2^bits - 1) * |D| and 15 * |M| inside
+ * binary16 (65504), there is no rescaling of such a matrix.  Workspace: aq_qgemm_workspace_size(M, N, K, bits) bytes.
+ * aq2_qgemm_batch_plan plans a list of such products (plan of aq_qgemm_batch_plan_size(count) bytes; workspace from
+ * aq_qgemm_batch_workspace_size; launched with aq_qgemm_batch).  The decode step through the blocks takes the base
  * format.  Arguments, limits and errors as for the base functions. */
 size_t aq2_packed_size(int64_t N, int64_t K, int bits, int block);
 int aq2_pack_weights(const uint8_t* codes, const uint8_t* sub, const uint16_t* sup, int64_t N, int64_t K, int bits,
@@ -217,6 +223,9 @@ int aq2_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, con
               float* y, void* stream);
 int aq2_qgemv_batch_plan(const aq_gemv_desc* descs /*HOST*/, int count, int block,
                          void* plan_host, size_t plan_bytes);
+int aq2_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M, int64_t ldx,
+              int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+int aq2_qgemm_batch_plan(const aq_gemm_desc* descs /*HOST*/, int count, int block, void* plan_host, size_t plan_bytes);
 int aq2_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream);
 int aq2_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int block, float* W, void* stream);
 

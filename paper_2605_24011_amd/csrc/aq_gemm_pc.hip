@@ -40,25 +40,34 @@ __device__ __forceinline__ void lds_barrier()
 }
 
 // Producer: tiles 2p, 2p+1 of the group, all chunks.  Executes nch + 1 barriers.
-template <int BITS>
+// FMT 0: the base format, w = fp16(d * (q - z)).  FMT 1: the two-level variant, w = fp16(q * fp16(D a) - fp16(M c))
+// (three roundings to 11 bits instead of one: D a and M c have up to 15 significant bits).
+template <int BITS, int FMT>
 __device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, int lane, uint8_t* smem, _Float16 down)
 {
     constexpr int WORDS = Codec<BITS>::WORDS;
-    constexpr int UNIT = 512 * BITS + 256;
+    constexpr int UNIT = 512 * BITS + (FMT ? AQ2_PARAM_BYTES : 256);
     const int g = lane >> 4, c = lane & 15;
     const int nch = t.nchunks;
     const uint8_t* ubase = t.blob + (((int64_t)group * nch) * AQ_GROUP_TILES + 2 * p) * UNIT;
     const int64_t chunk_stride = (int64_t)AQ_GROUP_TILES * UNIT;
     uint32_t raw[2][WORDS];
-    uint32_t sc[2][2];                                // scales of row c, blocks 2g and 2g + 1
+    uint32_t sc[2][2];                                // FMT 0: scales of row c, blocks 2g and 2g + 1
+                                                      // FMT 1: [0] = the (a, c) bytes of those two blocks, [1] = D | M << 16 of row c
     auto load_w = [&](int ch) {
 #pragma unroll
         for (int w = 0; w < 2; ++w) {
             const uint8_t* u = ubase + ch * chunk_stride + w * UNIT;
             Codec<BITS>::load(u, lane, raw[w]);
-            const AQ_GLOBAL uint16_t* sp = as_global<uint16_t>(u + 512 * BITS + ((c >> 2) * 8 + 2 * g) * 8 + (c & 3) * 2);
-            sc[w][0] = sp[0];
-            sc[w][1] = sp[4];
+            if (FMT) {
+                const AQ_GLOBAL uint8_t* bp = as_global<uint8_t>(u + aq2_sub_offset(BITS, c >> 2, 2 * g, c & 3));
+                sc[w][0] = (uint32_t)bp[0] | ((uint32_t)bp[4] << 8);           // next block: 4 bytes on
+                sc[w][1] = *as_global<uint32_t>(u + aq2_sup_offset(BITS, c >> 2, c & 3));
+            } else {
+                const AQ_GLOBAL uint16_t* sp = as_global<uint16_t>(u + 512 * BITS + ((c >> 2) * 8 + 2 * g) * 8 + (c & 3) * 2);
+                sc[w][0] = sp[0];
+                sc[w][1] = sp[4];
+            }
         }
     };
     typename Codec<BITS>::Magic magic = Codec<BITS>::magic();
@@ -70,7 +79,14 @@ __device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, i
             for (int b2 = 0; b2 < 2; ++b2) {
                 uint32_t a[16];
                 Codec<BITS>::unpack(&raw[w][b2 * BITS], magic, a);         // fp16 pairs (magic + q)
-                const _Float16 d = __builtin_bit_cast(_Float16, (uint16_t)sc[w][b2]) * down;
+                _Float16 d, off = (_Float16)0.0f;
+                if (FMT) {
+                    const uint32_t ac = (sc[w][0] >> (8 * b2)) & 0xFFu, dm = sc[w][1];
+                    d = (_Float16)((float)__builtin_bit_cast(_Float16, (uint16_t)(dm & 0xFFFFu)) * (float)(ac & 15u));
+                    off = (_Float16)((float)__builtin_bit_cast(_Float16, (uint16_t)(dm >> 16)) * (float)(ac >> 4));
+                } else {
+                    d = __builtin_bit_cast(_Float16, (uint16_t)sc[w][b2]) * down;
+                }
                 uint8_t* dst = buf + ((2 * p + w) * 16 + c) * PC_W_ROW + (2 * g + b2) * 64;
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
@@ -78,9 +94,10 @@ __device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, i
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int pidx = 4 * q4 + i;
-                        const _Float16 k = (_Float16)(Codec<BITS>::offset(pidx) + z);
+                        const _Float16 k = (_Float16)(Codec<BITS>::offset(pidx) + (FMT ? 0.f : z));
                         const uint32_t ap = a[pidx];
-                        const half2v h = (__builtin_bit_cast(half2v, ap) - half2v{k, k}) * half2v{d, d};
+                        const half2v qz = __builtin_bit_cast(half2v, ap) - half2v{k, k};      // q - z, or q itself
+                        const half2v h = FMT ? __builtin_elementwise_fma(qz, half2v{d, d}, half2v{-off, -off}) : qz * half2v{d, d};
                         o[i] = __builtin_bit_cast(uint32_t, h);
                     }
                     *reinterpret_cast<u32x4*>(dst + 16 * q4) = u32x4{o[0], o[1], o[2], o[3]};
@@ -101,8 +118,8 @@ __device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, i
     }
 }
 
-// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup
-template <int BITS_T>
+// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup.  FMT: see produce().
+template <int BITS_T, int FMT>
 __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* __restrict__ tasks, int count,
                                                               AqGemmTask single, const uint8_t* __restrict__ workspace)
 {
@@ -128,17 +145,21 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
     const int nch = t.nchunks;
 
     // largest scale of the matrix (blob trailer) -> power-of-two shift that keeps d * (q - z) inside binary16
-    const uint32_t max_d = *reinterpret_cast<const uint32_t*>(
-        t.blob + (int64_t)t.slabs * nch * AQ_GROUP_TILES * aq_unit_bytes(t.bits));
-    const int max_exp = (int)(max_d >> 10) - 15 + (t.bits - 1) + 1;
-    const int sh = max_exp > 15 ? max_exp - 15 : 0;
+    // (blobs of the two-level variant carry no such word: their D * 15 * (2^bits - 1) must stay inside binary16)
+    int sh = 0;
+    if (!FMT) {
+        const uint32_t max_d = *reinterpret_cast<const uint32_t*>(
+            t.blob + (int64_t)t.slabs * nch * AQ_GROUP_TILES * aq_unit_bytes(t.bits));
+        const int max_exp = (int)(max_d >> 10) - 15 + (t.bits - 1) + 1;
+        sh = max_exp > 15 ? max_exp - 15 : 0;
+    }
 
     if (wave >= PC_CONSUMERS) {
         const _Float16 down = (_Float16)__builtin_ldexpf(1.f, -(sh < 24 ? sh : 24));
         const int p = wave - PC_CONSUMERS;
-        if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) produce<2>(t, group, p, lane, smem, down);
-        else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) produce<3>(t, group, p, lane, smem, down);
-        else produce<4>(t, group, p, lane, smem, down);
+        if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) produce<2, FMT>(t, group, p, lane, smem, down);
+        else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) produce<3, FMT>(t, group, p, lane, smem, down);
+        else produce<4, FMT>(t, group, p, lane, smem, down);
         return;
     }
 
@@ -253,15 +274,16 @@ int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs)
 }
 
 // bits == 0: mixed bit-widths.  Xt: binary16, the re-tiled layout of the shared-role kernel.
-hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int total_wgs,
-                       const void* workspace, hipStream_t s)
+// two_level: the blobs are in the two-level variant of the format.
+hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int two_level,
+                       int total_wgs, const void* workspace, hipStream_t s)
 {
     const size_t lds = 2 * (size_t)PC_WBUF;
     const dim3 grid((unsigned)total_wgs), block(PC_THREADS);
     const uint8_t* ws = static_cast<const uint8_t*>(workspace);
 #define AQ_PC(B)                                                                                                \
     do {                                                                                                        \
-        auto k = qgemm_pc_kernel<B>;                                                                            \
+        auto k = two_level ? qgemm_pc_kernel<B, 1> : qgemm_pc_kernel<B, 0>;                                     \
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, \
                                   (int)lds);                                                                    \
         hipLaunchKernelGGL(k, grid, block, lds, s, tasks_dev, count, single, ws);                               \

@@ -105,8 +105,8 @@ hipError_t aqk_gemm_small(const AqGemmTask* tasks_dev, int count, const AqGemmTa
 // Prefill, fp16-weight mode, prefill-sized M: producer / consumer wavefronts (aq_gemm_pc.hip).  Reads the binary16
 // Xt + rowexp that aqk_retile writes; a task's wg_count = aqk_gemm_pc_wg_count (128-row groups x blocks of 320 rows).
 int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs);
-hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int total_wgs,
-                       const void* workspace, hipStream_t s);
+hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int two_level,
+                       int total_wgs, const void* workspace, hipStream_t s);
 
 // Layer-by-layer decode step.  One matrix of one stage as the kernel sees it (device-visible, 96 bytes):
 // y[n] += sum over the k of a workgroup's part of W[n][k] * f(in)[k], with f chosen by `prologue`:

@@ -1,6 +1,7 @@
 """Parity of the two-level format variant (aq2_* entry points, through the C ABI) against its fp64 oracle on the
 same seeded inputs.  Bars: codes bit-exact; dequantised weights equal to the oracle's value rounded once to fp32;
-decode outputs relative L2 <= 1e-3 (expected ~1e-6: exact integer products on the matrix cores, fp32 sums)."""
+decode outputs relative L2 <= 1e-3 (expected ~1e-6: exact integer products on the matrix cores, fp32 sums); prefill
+outputs (aq2_qgemm: weights formed in binary16 with three roundings) relative L2 <= 1e-3, expected a few 1e-4."""
 import numpy as np
 import pytest
 
@@ -142,3 +143,94 @@ def test_full_size_sampled_rows(gpu, oracle, af):
     torch.cuda.synchronize()
     for it, (rows, ref) in zip(items, checks):
         assert oracle.rel_l2(it[5].cpu().numpy()[rows], ref) <= 2e-5
+
+
+# ---- prefill over two-level blobs (aq2_qgemm / the two-level GemmBatch) ----
+
+def matmul_ref(oracle, af, codes, sub, sup, N, K, bits, X, dtype):
+    return oracle.activations_to_f64(X, dtype) @ af.dequant(codes, sub, sup, N, K, bits).T
+
+
+GEMM_CASES = [(8, 32, 1), (16, 256, 16), (17, 96, 7), (200, 1056, 65), (128, 512, 320), (300, 4096, 300),
+              (131, 2048, 333), (1024, 1024, 641)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K,M", GEMM_CASES)
+def test_qgemm_matches_oracle(gpu, oracle, af, bits, N, K, M, dtype):
+    torch, aq = gpu
+    codes = wl.draw_codes(N, K, bits, 76, N, K)
+    sub, sup = wl.draw_affine_params(N, K, bits, 76, N, K)
+    X = wl.draw_activations(M, K, dtype, 76, N, K)
+    packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+    Y = aq.aq2_qgemm(packed, N, K, bits, dev(torch, X, dtype)).cpu().numpy()
+    err = oracle.rel_l2(Y, matmul_ref(oracle, af, codes, sub, sup, N, K, bits, X, dtype))
+    assert err <= 1e-3, err
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_qgemm_is_exact_when_the_binary16_weights_are(gpu, oracle, af, bits):
+    """Power-of-two D and M, integer activations: q a D and c M are short integers times a power of two, so the
+    binary16 weight is the true one and every fp32 sum is exact."""
+    torch, aq = gpu
+    N, K, M = 144, 800, 70
+    codes = wl.draw_codes(N, K, bits, 77, bits)
+    rng = np.random.default_rng(100 + bits)
+    a = rng.integers(0, 16, size=(N, K // 32)).astype(np.uint8)
+    c = rng.integers(0, 16, size=(N, K // 32)).astype(np.uint8)
+    e = rng.integers(-8, -2, size=(N, (K + 255) // 256))
+    sup = np.stack([wl.f32_to_f16_bits((2.0 ** e).astype(np.float32)),
+                    wl.f32_to_f16_bits((2.0 ** (e + rng.integers(0, 3, size=e.shape))).astype(np.float32))], axis=2)
+    sub = (a | (c << 4)).astype(np.uint8)
+    X = wl.draw_int_activations(M, K, "f16", 77, bits)
+    packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+    Y = aq.aq2_qgemm(packed, N, K, bits, dev(torch, X, "f16")).cpu().numpy()
+    assert np.array_equal(Y.astype(np.float64), matmul_ref(oracle, af, codes, sub, sup, N, K, bits, X, "f16"))
+
+
+def test_qgemm_batch_matches_single_calls(gpu, oracle, af):
+    torch, aq = gpu
+    shapes = [(256, 1024, 2, 300), (384, 2048, 3, 300), (130, 544, 4, 20), (512, 1024, 3, 300)]
+    items, singles = [], []
+    Xs = {}
+    for i, (N, K, bits, M) in enumerate(shapes):
+        codes = wl.draw_codes(N, K, bits, 78, i)
+        sub, sup = wl.draw_affine_params(N, K, bits, 78, i)
+        if (M, K) not in Xs:                                   # products of equal shape read the same activations
+            Xs[(M, K)] = dev(torch, wl.draw_activations(M, K, "bf16", 78, M, K), "bf16")
+        packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+        Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, Xs[(M, K)], Y))
+        singles.append(aq.aq2_qgemm(packed, N, K, bits, Xs[(M, K)]))
+    aq.GemmBatch(items, two_level=True).run()
+    torch.cuda.synchronize()
+    for it, one in zip(items, singles):
+        assert torch.equal(it[5], one)
+
+
+def test_qgemm_full_size_sampled_columns(gpu, oracle, af):
+    """A LLaMA-shaped layer at the bench's M = 300 in one batched launch; sampled rows of W against the oracle."""
+    torch, aq = gpu
+    rng = np.random.default_rng(79)
+    M = 300
+    items, checks = [], []
+    Xs = {}
+    for j, (name, N, K) in enumerate(wl.LLAMA2_7B_LAYER):
+        bits = 2 + j % 3
+        codes = wl.draw_codes(N, K, bits, 79, j)
+        sub, sup = wl.draw_affine_params(N, K, bits, 79, j)
+        if K not in Xs:
+            Xh = wl.draw_activations(M, K, "bf16", 79, K)
+            Xs[K] = (Xh, dev(torch, Xh, "bf16"))
+        packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+        Y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, Xs[K][1], Y))
+        rows = np.sort(rng.choice(N, size=48, replace=False))
+        nb = K // 32
+        checks.append((rows, matmul_ref(oracle, af, codes.reshape(N, nb, -1)[rows], sub[rows], sup[rows], len(rows), K,
+                                        bits, Xs[K][0], "bf16")))
+    aq.GemmBatch(items, two_level=True).run()
+    torch.cuda.synchronize()
+    for it, (rows, ref) in zip(items, checks):
+        assert oracle.rel_l2(it[5].cpu().numpy()[:, rows], ref) <= 1e-3
