@@ -41,6 +41,10 @@ constexpr int THREADS = WAVES * 64;
 #ifndef AQ_GEMV_MIN_WAVES_B34
 #define AQ_GEMV_MIN_WAVES_B34 3
 #endif
+// chunks of packed units a wavefront of a lone matrix's launch requests ahead (the batched launches: 2)
+#ifndef AQ_GEMV_LONE_DEPTH
+#define AQ_GEMV_LONE_DEPTH 16
+#endif
 // Workgroup = 4 wavefronts x TW tiles (16 rows each) of one 128-row group; every wavefront walks
 // the whole K extent of its own tiles, so sums stay in registers and wavefronts never meet.  At
 // each chunk the 4 wavefronts together read one contiguous run of 4*TW units.
@@ -63,9 +67,10 @@ constexpr int THREADS = WAVES * 64;
     }                                                                             \
     if (wg >= t.wg_count) return
 
-// one bit-width per launch: the registers, and with them the occupancy, fit that bit-width
+// one bit-width per launch: the registers, and with them the occupancy, fit that bit-width (the lone-matrix shape,
+// TW == 1, may use the whole register file: its launches have few workgroups)
 template <int BITS, int TW>
-__global__ __launch_bounds__(THREADS, (BITS == 2 ? AQ_GEMV_MIN_WAVES_B2 : AQ_GEMV_MIN_WAVES_B34))
+__global__ __launch_bounds__(THREADS, (TW == 1 ? 1 : BITS == 2 ? AQ_GEMV_MIN_WAVES_B2 : AQ_GEMV_MIN_WAVES_B34))
 void qgemv_kernel(const AqGemvTask* __restrict__ tasks, int count, AqGemvTask single)
 {
     extern __shared__ __align__(16) uint8_t smem[];
