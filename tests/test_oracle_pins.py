@@ -134,6 +134,10 @@ def test_argmin_rounds_to_nearest_level(oracle):
     w = np.array([-100.0, -1.26, -0.74, 0.24, 0.26, 0.76, 100.0])
     got = oracle.rtn_codes(w, 0.5, 2.0, 2)      # levels -1, -0.5, 0, 0.5
     assert got.tolist() == [0, 0, 1, 2, 3, 3, 3]
+    # Eq. 1's argmin leaves a tie open; the oracle's stated reading is that the first (lowest) minimiser wins.
+    # The midpoints of a power-of-two grid are exact in binary, so these are true ties.
+    mid = np.array([-0.75, -0.25, 0.25])
+    assert oracle.rtn_codes(mid, 0.5, 2.0, 2).tolist() == [0, 1, 2]
 
 
 # ---------------------------------------------------------------- brute force
