@@ -495,7 +495,8 @@ def test_optimize_scales_matches_oracle(gpu, oracle, bits, rounds):
 
 def test_optimize_scales_degenerate_blocks(gpu, oracle):
     """All-zero blocks, one non-zero element, one sign only, magnitudes beyond the fp16 scale range at both ends,
-    zero sensitivities, and a block whose sensitivities single out one element."""
+    zero sensitivities, a block whose sensitivities single out one element, and a block of exact ties between
+    neighbouring codes (half-integers at a scale of one)."""
     torch, aq = gpu
     rng = np.random.default_rng(31)
     W = (rng.standard_normal((12, 64)) * 0.02).astype(np.float32)
@@ -514,6 +515,9 @@ def test_optimize_scales_degenerate_blocks(gpu, oracle):
     for bits in (2, 3, 4):
         _check_scale_opt(torch, aq, oracle, W, F, bits, 4)
         _check_scale_opt(torch, aq, oracle, W, None, bits, 2)
+        T = np.zeros((1, 32), dtype=np.float32)                              # max|w| = 2^(bits-1): start scale 1
+        T[0, :8] = [-(1 << (bits - 1)), 0.5, -1.5, -0.5, 1.5, -0.25, 0.75, 1.0]
+        _check_scale_opt(torch, aq, oracle, T, None, bits, 0)
 
 
 def test_optimize_scales_feeds_the_matmul(gpu, oracle):

@@ -46,6 +46,16 @@ def test_hand_worked_equal_magnitude_block(oracle):
     assert list(codes1[0]) == [15, 15, 15, 1, 1, 15, 15, 1]
 
 
+def test_a_tie_between_two_codes_goes_to_the_smaller_one(oracle):
+    """Eq. 11's nearest-code step leaves ties open; the stated reading is the smaller entry.  max|w| = 2 at 2 bits
+    gives s = 1 exactly, so the half-integers below are true ties."""
+    w = np.zeros((1, 32), dtype=np.float32)
+    w[0, :6] = [-2.0, 0.5, -1.5, -0.5, 1.0, 1.5]
+    codes, scales = oracle.scale_optimize(w, None, 2, 0)
+    assert int(scales[0, 0]) == 0x3C00                                       # binary16 1.0
+    assert codes[0, :6].tolist() == [0, 2, 0, 1, 3, 3] and not np.any(codes[0, 6:] != 2)
+
+
 @pytest.mark.parametrize("bits", [2, 3, 4])
 def test_zero_rounds_is_nearest_code_quantisation_at_the_absmax_scale(oracle, bits):
     """rounds = 0: d = binary16(max|w| / 2^(bits-1)) and the codes are Eq. 1's argmin for that d."""
