@@ -3,7 +3,7 @@
 //
 // The dense part is the Gram matrix A A^T of K samples x d features (2 K^2 d flop): fp32 on the matrix cores
 // (V_MFMA_F32_32X32X2_F32), one 128 x 128 tile of the K x K result per workgroup, 4 wavefronts of 64 x 64 each,
-// A staged through LDS 16 features at a time.  The kernel value follows in the epilogue from the squared norms:
+// A staged through a double-buffered LDS 32 features at a time.  The kernel value follows in the epilogue from the squared norms:
 // ||a_i - a_j||^2 = r_i + r_j - 2 a_i.a_j (clamped at 0).  Everything after that is O(K^2) streaming in fp64:
 // with a_i, b_i the row sums of K_A, K_B,
 //     tr(K_A C K_B C) = sum_ij [K_A]_ij [K_B]_ij - (2/K) sum_i a_i b_i + (1/K^2) (sum_i a_i)(sum_i b_i),
@@ -18,8 +18,19 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int GT = 128;            // tile of the Gram matrix per workgroup
-constexpr int KC = 16;             // features per LDS stage
-constexpr int LROW = KC + 1;       // LDS row stride in floats: 17 keeps the 32 rows of an operand read on 32 banks
+constexpr int KC = 32;             // features per LDS stage: 128 bytes of a row, one cache line
+constexpr int LROW = KC + 1;       // LDS row stride in floats: 33 keeps the 32 rows of an operand read on 32 banks
+constexpr int GSTAGE = 2 * GT * LROW;            // floats of one stage: the row block's rows, then the column block's
+constexpr size_t GRAM_LDS = 2 * GSTAGE * sizeof(float);     // two stages
+
+// Barrier for LDS traffic only: __syncthreads() would also wait for the global loads of the stage after next, which
+// are meant to stay in flight across it.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 // r[i] = sum_k A[i][k]^2, one wavefront per row
 __global__ __launch_bounds__(256) void sqnorm_kernel(const float* __restrict__ A, int64_t K, int64_t d, int64_t lda,
@@ -40,11 +51,14 @@ __global__ __launch_bounds__(256) void sqnorm_kernel(const float* __restrict__ A
 
 // G[i][j] = exp(-gamma * max(0, r_i + r_j - 2 a_i.a_j)) for the 128 x 128 tile (blockIdx.y, blockIdx.x).  The matrix
 // is symmetric: only tiles on or above the diagonal are computed, and each writes its mirror image as well.
-__global__ __launch_bounds__(256) void gram_rbf_kernel(const float* __restrict__ A, int64_t K, int64_t d, int64_t lda,
-                                                       const float* __restrict__ r, float gamma, float* __restrict__ G)
+//
+// Pipeline, one barrier per stage of 32 features: at the top of stage s the registers hold stage s + 1 (requested a
+// whole stage earlier); they go to the LDS buffer that stage s - 1 was read from, stage s + 2 is requested, then
+// stage s is multiplied out of the other buffer.  Eight lanes read the 128 contiguous bytes of a row's stage.
+__global__ __launch_bounds__(256, 2) void gram_rbf_kernel(const float* __restrict__ A, int64_t K, int64_t d, int64_t lda,
+                                                          const float* __restrict__ r, float gamma, float* __restrict__ G)
 {
-    __shared__ float ti[GT * LROW];      // rows of the tile's row block
-    __shared__ float tj[GT * LROW];      // rows of the tile's column block
+    extern __shared__ __align__(16) float gl[];              // [2 stages][i rows, j rows][GT][LROW]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wi = wave >> 1, wj = wave & 1;                 // this wavefront's 64 x 64 quadrant
@@ -60,66 +74,68 @@ __global__ __launch_bounds__(256) void gram_rbf_kernel(const float* __restrict__
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    // staging: thread t copies features 4 * (t % 4) .. + 3 of rows t / 4 and t / 4 + 64 of both blocks; the next
-    // stage's 16 values are requested before the current stage is multiplied and stored after it
-    const int srow = tid >> 2, sk = (tid & 3) * 4;
+    // staging: thread t copies features 4 * (t % 8) .. + 3 of rows t / 8 + 32 h (h = 0 .. 3) of both blocks
+    const int srow = tid >> 3, sk = (tid & 7) * 4;
     const bool vec = (lda & 3) == 0;                         // rows start 16-byte aligned: whole quads in one load
-    float nx[2][2][4];                                       // [row half][i / j block][element]
+    f32x4 nx[4][2];                                          // [row group][i / j block]
     auto fetch = [&](int64_t k0) {
+        const int64_t k = k0 + sk;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int rr = srow + 64 * h;
-            const int64_t k = k0 + sk;
+        for (int h = 0; h < 4; ++h) {
+            const int rr = srow + 32 * h;
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk) {
                 const int64_t row = (blk ? j0 : i0) + rr;
                 if (row < K && vec && k + 3 < d) {
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(A + row * lda + k);
-                    nx[h][blk][0] = v.x; nx[h][blk][1] = v.y; nx[h][blk][2] = v.z; nx[h][blk][3] = v.w;
+                    nx[h][blk] = *reinterpret_cast<const f32x4*>(A + row * lda + k);
                 } else {
+                    f32x4 v;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) nx[h][blk][e] = (row < K && k + e < d) ? A[row * lda + k + e] : 0.f;
+                    for (int e = 0; e < 4; ++e) v[e] = (row < K && k + e < d) ? A[row * lda + k + e] : 0.f;
+                    nx[h][blk] = v;
                 }
             }
         }
     };
-    auto stash = [&]() {
+    auto stash = [&](float* buf) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int rr = srow + 64 * h;
+        for (int h = 0; h < 4; ++h) {
+            const int rr = srow + 32 * h;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ti[rr * LROW + sk + e] = nx[h][0][e];
-                tj[rr * LROW + sk + e] = nx[h][1][e];
-            }
+            for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) buf[(blk * GT + rr) * LROW + sk + e] = nx[h][blk][e];
         }
     };
     // operand layout of the 32x32x2 MFMA: lane l supplies A[row l % 32][k l / 32] and B[k l / 32][column l % 32]
     const int lr = lane & 31, lk = lane >> 5;
+    const int64_t stages = (d + KC - 1) / KC;
     fetch(0);
-    stash();
-    __syncthreads();
-    for (int64_t k0 = 0; k0 < d; k0 += KC) {
-        const bool more = k0 + KC < d;
-        if (more) fetch(k0 + KC);
+    stash(gl);
+    if (stages > 1) fetch(KC);
+    lds_barrier();
+    for (int64_t s = 0; s < stages; ++s) {
+        const float* cur = gl + (s & 1) * GSTAGE;
+        if (s + 1 < stages) {
+            stash(gl + ((s + 1) & 1) * GSTAGE);              // read last during stage s - 1, before the barrier
+            if (s + 2 < stages) fetch((s + 2) * KC);
+        }
+        const float* ti = cur + (wi * 64 + lr) * LROW + lk;
+        const float* tj = cur + (GT + wj * 64 + lr) * LROW + lk;
 #pragma unroll
         for (int kk = 0; kk < KC; kk += 2) {
             float fa[2], fb[2];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) fa[a] = ti[(wi * 64 + a * 32 + lr) * LROW + kk + lk];
+            for (int a = 0; a < 2; ++a) fa[a] = ti[a * 32 * LROW + kk];
 #pragma unroll
-            for (int b = 0; b < 2; ++b) fb[b] = tj[(wj * 64 + b * 32 + lr) * LROW + kk + lk];
+            for (int b = 0; b < 2; ++b) fb[b] = tj[b * 32 * LROW + kk];
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a], fb[b], acc[a][b], 0, 0, 0);
         }
-        __syncthreads();                                     // everyone has read this stage
-        if (more) {
-            stash();
-            __syncthreads();                                 // the next stage is in place
-        }
+        lds_barrier();                                       // stage s read by everyone, stage s + 1 in place
     }
 
     // result layout: register v of lane l is row 8 * (v / 4) + 4 * (l / 32) + v % 4, column l % 32 of the 32 x 32 tile
@@ -215,7 +231,9 @@ hipError_t aqk_rbf_gram(const float* A, int64_t K, int64_t d, int64_t lda, float
 {
     hipLaunchKernelGGL(sqnorm_kernel, dim3((unsigned)((K + 3) / 4)), dim3(256), 0, s, A, K, d, lda, sq);
     const unsigned tiles = (unsigned)((K + GT - 1) / GT);
-    hipLaunchKernelGGL(gram_rbf_kernel, dim3(tiles, tiles), dim3(256), 0, s, A, K, d, lda, sq, gamma, G);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gram_rbf_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)GRAM_LDS);
+    hipLaunchKernelGGL(gram_rbf_kernel, dim3(tiles, tiles), dim3(256), GRAM_LDS, s, A, K, d, lda, sq, gamma, G);
     return hipGetLastError();
 }
 
