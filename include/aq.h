@@ -56,6 +56,20 @@ extern "C" {
 #define AQ_BF16  2
 
 /* Text for a status code (static storage, never NULL). */
+/* Calibration, not part of the method: what the matrix cores of this GPU sustain for a binary16 MFMA shape when the
+ * operands come from memory (random data makes the part clock down; constant data does not) and nothing else runs.
+ * A product kernel's rate is best read against this figure as well as against the published peak.
+ *   shape           0: V_MFMA_F32_16X16X32_F16 (what the prefill kernels issue), 1: V_MFMA_F32_32X32X16_F16
+ *   operands        DEVICE, 16-byte aligned, AQ_PROBE_OPERAND_BYTES bytes of binary16 values of the caller's choice
+ *   iters           1 .. 2^24 loop trips per wavefront (8 resp. 4 independent MFMAs each)
+ *   waves_per_simd  1 or 2 (workgroups of 4 wavefronts launched per compute unit)
+ *   sink            DEVICE, 256 floats, overwritten
+ *   flops           HOST, receives the floating-point operations of the launch (2 per multiply-add)
+ * One asynchronous launch on `stream`; time it with events.  Errors: AQ_EINVAL, AQ_ENULL, AQ_EALIGN, AQ_ELAUNCH. */
+#define AQ_PROBE_OPERAND_BYTES 32768
+int aq_probe_mfma(int shape, const void* operands, int iters, int waves_per_simd, float* sink, int64_t* flops,
+                  void* stream);
+
 const char* aq_status_string(int status);
 
 /* Bytes of the packed device blob of an N x K matrix, 0 if the arguments are invalid.

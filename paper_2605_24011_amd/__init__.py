@@ -93,6 +93,7 @@ def lib() -> ctypes.CDLL:
         L.aq2_pack_weights.argtypes = [_p, _p, _p, _i64, _i64, _int, _int, _p, _sz, _p]
         L.aq2_qgemv.argtypes = [_p, _i64, _i64, _int, _int, _p, _int, _p, _p]
         L.aq2_qgemv_batch_plan.argtypes = [ctypes.POINTER(aq_gemv_desc), _int, _int, _p, _sz]
+        L.aq_probe_mfma.argtypes = [_int, _p, _int, _int, _p, ctypes.POINTER(ctypes.c_int64), _p]
         L.aq2_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
         L.aq2_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _p, _sz]
         L.aq2_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
@@ -344,6 +345,21 @@ def aq2_qgemv(packed, N: int, K: int, bits: int, x, y=None, block: int = BLOCK, 
     _check(lib().aq2_qgemv(packed.data_ptr(), N, K, bits, block, x.data_ptr(), _dtype_code(x),
                            y.data_ptr(), _stream(stream)), "aq2_qgemv")
     return y
+
+
+PROBE_OPERAND_BYTES = 32768
+
+
+def aq_probe_mfma(shape: int, operands, iters: int, waves_per_simd: int = 1, stream=None) -> int:
+    """One launch of the MFMA calibration kernel (operands: cuda float16 tensor of PROBE_OPERAND_BYTES bytes);
+    returns the floating-point operations of the launch.  Time it with events."""
+    import torch
+    assert operands.numel() * operands.element_size() >= PROBE_OPERAND_BYTES
+    sink = torch.empty(256, dtype=torch.float32, device=operands.device)
+    flops = ctypes.c_int64(0)
+    _check(lib().aq_probe_mfma(shape, operands.data_ptr(), iters, waves_per_simd, sink.data_ptr(), ctypes.byref(flops),
+                               _stream(stream)), "aq_probe_mfma")
+    return int(flops.value)
 
 
 def aq2_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaq.so")
 SOURCES = ["aq_api.hip", "aq_pack.hip", "aq_gemv.hip", "aq_gemv2.hip", "aq_gemm.hip", "aq_gemm_small.hip", "aq_gemm_pc.hip", "aq_quant.hip",
-           "aq_layer.hip", "aq_hsic.hip"]
+           "aq_layer.hip", "aq_hsic.hip", "aq_probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -604,6 +604,17 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
                ? AQ_OK : AQ_ELAUNCH;
 }
 
+int aq_probe_mfma(int shape, const void* operands, int iters, int waves_per_simd, float* sink, int64_t* flops,
+                  void* stream)
+{
+    if ((shape != 0 && shape != 1) || iters < 1 || iters > (1 << 24) || (waves_per_simd != 1 && waves_per_simd != 2))
+        return AQ_EINVAL;
+    if (!operands || !sink || !flops) return AQ_ENULL;
+    if (!aligned16(operands) || !aligned16(sink)) return AQ_EALIGN;
+    return aqk_probe_mfma(shape, operands, iters, waves_per_simd, sink, flops, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? AQ_OK : AQ_ELAUNCH;
+}
+
 int aq_optimize_scales(const float* W, const float* F, int64_t N, int64_t K, int bits, int block, int rounds,
                        uint8_t* codes, uint16_t* scales, void* stream)
 {

@@ -282,6 +282,18 @@ def test_two_level_variant_validation_without_a_gpu(L):
     assert L.aq2_qgemm_batch_plan(gd, 2, 32, buf, size) == aq.AQ_EINVAL
 
 
+def test_mfma_probe_validation_without_a_gpu(L):
+    A = 1 << 20
+    flops = ctypes.c_int64(0)
+    f = ctypes.byref(flops)
+    assert L.aq_probe_mfma(2, A, 10, 1, A, f, None) == aq.AQ_EINVAL
+    assert L.aq_probe_mfma(0, A, 0, 1, A, f, None) == aq.AQ_EINVAL
+    assert L.aq_probe_mfma(0, A, 10, 3, A, f, None) == aq.AQ_EINVAL
+    assert L.aq_probe_mfma(0, None, 10, 1, A, f, None) == aq.AQ_ENULL
+    assert L.aq_probe_mfma(0, A, 10, 1, A, None, None) == aq.AQ_ENULL
+    assert L.aq_probe_mfma(0, A + 2, 10, 1, A, f, None) == aq.AQ_EALIGN
+
+
 def test_hsic_validation_without_a_gpu(L):
     A = 1 << 20
     L.aq_hsic_workspace_size.restype = ctypes.c_size_t
