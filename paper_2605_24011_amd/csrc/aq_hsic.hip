@@ -18,7 +18,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int GT = 128;            // tile of the Gram matrix per workgroup
-constexpr int KC = 32;             // features per LDS stage: 128 bytes of a row, one cache line
+#ifndef AQ_GRAM_KC
+#define AQ_GRAM_KC 32
+#endif
+#ifndef AQ_GRAM_WGS
+#define AQ_GRAM_WGS 2
+#endif
+constexpr int KC = AQ_GRAM_KC;     // features per LDS stage: 32 = 128 bytes of a row, one cache line
+constexpr int LPR = KC / 4;        // lanes that share a row's stage (one quad each)
+constexpr int NH = GT * LPR / 256; // row groups a thread copies per block and stage
 constexpr int LROW = KC + 1;       // LDS row stride in floats: 33 keeps the 32 rows of an operand read on 32 banks
 constexpr int GSTAGE = 2 * GT * LROW;            // floats of one stage: the row block's rows, then the column block's
 constexpr size_t GRAM_LDS = 2 * GSTAGE * sizeof(float);     // two stages
@@ -52,19 +60,24 @@ __global__ __launch_bounds__(256) void sqnorm_kernel(const float* __restrict__ A
 // G[i][j] = exp(-gamma * max(0, r_i + r_j - 2 a_i.a_j)) for the 128 x 128 tile (blockIdx.y, blockIdx.x).  The matrix
 // is symmetric: only tiles on or above the diagonal are computed, and each writes its mirror image as well.
 //
-// Pipeline, one barrier per stage of 32 features: at the top of stage s the registers hold stage s + 1 (requested a
-// whole stage earlier); they go to the LDS buffer that stage s - 1 was read from, stage s + 2 is requested, then
-// stage s is multiplied out of the other buffer.  Eight lanes read the 128 contiguous bytes of a row's stage.
-__global__ __launch_bounds__(256, 2) void gram_rbf_kernel(const float* __restrict__ A, int64_t K, int64_t d, int64_t lda,
+// Pipeline, one barrier per stage of 32 features: during stage s the registers that hold stage s + 1 (requested a
+// whole stage earlier) go to the LDS buffer that stage s - 1 was read from, stage s + 2 is requested into a second
+// set of registers, and stage s is multiplied out of the other buffer.  Eight lanes read the 128 contiguous bytes
+// of a row's stage.
+__global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float* __restrict__ A, int64_t K, int64_t d, int64_t lda,
                                                           const float* __restrict__ r, float gamma, float* __restrict__ G)
 {
     extern __shared__ __align__(16) float gl[];              // [2 stages][i rows, j rows][GT][LROW]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wi = wave >> 1, wj = wave & 1;                 // this wavefront's 64 x 64 quadrant
-    if (blockIdx.x < blockIdx.y) return;                     // below the diagonal: the mirror tile writes it
-    const int64_t i0 = (int64_t)blockIdx.y * GT, j0 = (int64_t)blockIdx.x * GT;
-    const bool mirror = blockIdx.x != blockIdx.y;
+    // blockIdx.x counts the tiles on or above the diagonal row by row: no workgroup is launched for the others
+    const int tiles = (int)((K + GT - 1) / GT);
+    int by = 0, bx = (int)blockIdx.x;
+    while (bx >= tiles - by) { bx -= tiles - by; ++by; }
+    bx += by;
+    const int64_t i0 = (int64_t)by * GT, j0 = (int64_t)bx * GT;
+    const bool mirror = bx != by;
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -74,68 +87,93 @@ __global__ __launch_bounds__(256, 2) void gram_rbf_kernel(const float* __restric
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    // staging: thread t copies features 4 * (t % 8) .. + 3 of rows t / 8 + 32 h (h = 0 .. 3) of both blocks
-    const int srow = tid >> 3, sk = (tid & 7) * 4;
+    // staging: thread t copies features 4 * (t % 8) .. + 3 of rows t / 8 + 32 h (h = 0 .. 3) of both blocks: per stage
+    // 8 quads = 16 pairs of floats, written to LDS one pair per group of four MFMAs so that the writes of stage s + 1
+    // sit between the MFMAs of stage s (a lone wavefront on its SIMD has nobody else to cover them)
+    const int srow = tid / LPR, sk = (tid % LPR) * 4;
     const bool vec = (lda & 3) == 0;                         // rows start 16-byte aligned: whole quads in one load
-    f32x4 nx[4][2];                                          // [row group][i / j block]
-    auto fetch = [&](int64_t k0) {
+    f32x4 nxA[NH][2], nxB[NH][2];                            // [row group][i / j block], two stages in flight
+    // No lane-dependent branches around the loads (a join after a divergent branch makes the compiler wait for every
+    // load in flight): rows beyond K re-read row K - 1 (their results are never stored), and the choice between whole
+    // quads and guarded single elements (last stage of a d that is not a multiple of 32, unaligned rows) is uniform.
+    auto fetch = [&](f32x4 (&nx)[NH][2], int64_t k0) {
         const int64_t k = k0 + sk;
+        const float* p[NH][2];
 #pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const int rr = srow + 32 * h;
+        for (int h = 0; h < NH; ++h)
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk) {
-                const int64_t row = (blk ? j0 : i0) + rr;
-                if (row < K && vec && k + 3 < d) {
-                    nx[h][blk] = *reinterpret_cast<const f32x4*>(A + row * lda + k);
-                } else {
+                const int64_t row = (blk ? j0 : i0) + srow + (GT / NH) * h;
+                p[h][blk] = A + (row < K ? row : K - 1) * lda;
+            }
+        if (vec && k0 + KC <= d) {
+#pragma unroll
+            for (int h = 0; h < NH; ++h)
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk) nx[h][blk] = *reinterpret_cast<const f32x4*>(p[h][blk] + k);
+        } else {
+#pragma unroll
+            for (int h = 0; h < NH; ++h)
+#pragma unroll
+                for (int blk = 0; blk < 2; ++blk) {
                     f32x4 v;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = (row < K && k + e < d) ? A[row * lda + k + e] : 0.f;
+                    for (int e = 0; e < 4; ++e) {
+                        const float x = p[h][blk][k + e < d ? k + e : 0];
+                        v[e] = k + e < d ? x : 0.f;
+                    }
                     nx[h][blk] = v;
                 }
-            }
         }
     };
-    auto stash = [&](float* buf) {
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const int rr = srow + 32 * h;
-#pragma unroll
-            for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) buf[(blk * GT + rr) * LROW + sk + e] = nx[h][blk][e];
-        }
+    auto stash_piece = [&](float* buf, const f32x4 (&nx)[NH][2], int g) {    // g = 0 .. KC / 2 - 1 = 4 NH - 1
+        const int h = g >> 2, blk = (g >> 1) & 1, e = 2 * (g & 1);
+        float* dst = buf + (blk * GT + srow + (GT / NH) * h) * LROW + sk + e;
+        dst[0] = nx[h][blk][e];
+        dst[1] = nx[h][blk][e + 1];
     };
     // operand layout of the 32x32x2 MFMA: lane l supplies A[row l % 32][k l / 32] and B[k l / 32][column l % 32]
     const int lr = lane & 31, lk = lane >> 5;
     const int64_t stages = (d + KC - 1) / KC;
-    fetch(0);
-    stash(gl);
-    if (stages > 1) fetch(KC);
-    lds_barrier();
-    for (int64_t s = 0; s < stages; ++s) {
-        const float* cur = gl + (s & 1) * GSTAGE;
-        if (s + 1 < stages) {
-            stash(gl + ((s + 1) & 1) * GSTAGE);              // read last during stage s - 1, before the barrier
-            if (s + 2 < stages) fetch((s + 2) * KC);
-        }
-        const float* ti = cur + (wi * 64 + lr) * LROW + lk;
-        const float* tj = cur + (GT + wj * 64 + lr) * LROW + lk;
+    // one stage: `cur` holds stage s + 1 (requested a stage ago) and goes to the other LDS buffer piece by piece,
+    // `nxt` receives stage s + 2, stage s is multiplied out of its buffer
+    auto stage = [&](int64_t s, const f32x4 (&cur)[NH][2], f32x4 (&nxt)[NH][2]) {
+        const float* buf = gl + (s & 1) * GSTAGE;
+        float* other = gl + ((s + 1) & 1) * GSTAGE;          // read last during stage s - 1, before the barrier
+        const bool more = s + 1 < stages;
+        if (s + 2 < stages) fetch(nxt, (s + 2) * KC);
+        const float* ti = buf + (wi * 64 + lr) * LROW + lk;
+        const float* tj = buf + (GT + wj * 64 + lr) * LROW + lk;
+        // operands of feature pair kk + 2 are requested before the four MFMAs of pair kk
+        float fa[2][2], fb[2][2];
+#pragma unroll
+        for (int a = 0; a < 2; ++a) { fa[0][a] = ti[a * 32 * LROW]; fb[0][a] = tj[a * 32 * LROW]; }
 #pragma unroll
         for (int kk = 0; kk < KC; kk += 2) {
-            float fa[2], fb[2];
+            const int cb = (kk >> 1) & 1;
+            if (kk + 2 < KC) {
 #pragma unroll
-            for (int a = 0; a < 2; ++a) fa[a] = ti[a * 32 * LROW + kk];
-#pragma unroll
-            for (int b = 0; b < 2; ++b) fb[b] = tj[b * 32 * LROW + kk];
+                for (int a = 0; a < 2; ++a) { fa[cb ^ 1][a] = ti[a * 32 * LROW + kk + 2]; fb[cb ^ 1][a] = tj[a * 32 * LROW + kk + 2]; }
+            }
+            if (more) stash_piece(other, cur, kk >> 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a], fb[b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[cb][a], fb[cb][b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         lds_barrier();                                       // stage s read by everyone, stage s + 1 in place
+    };
+    fetch(nxB, 0);
+#pragma unroll
+    for (int g = 0; g < KC / 2; ++g) stash_piece(gl, nxB, g);
+    if (stages > 1) fetch(nxA, KC);
+    lds_barrier();
+    for (int64_t s = 0; s < stages; s += 2) {
+        stage(s, nxA, nxB);
+        if (s + 1 < stages) stage(s + 1, nxB, nxA);
     }
 
     // result layout: register v of lane l is row 8 * (v / 4) + 4 * (l / 32) + v % 4, column l % 32 of the 32 x 32 tile
@@ -233,7 +271,7 @@ hipError_t aqk_rbf_gram(const float* A, int64_t K, int64_t d, int64_t lda, float
     const unsigned tiles = (unsigned)((K + GT - 1) / GT);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gram_rbf_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)GRAM_LDS);
-    hipLaunchKernelGGL(gram_rbf_kernel, dim3(tiles, tiles), dim3(256), GRAM_LDS, s, A, K, d, lda, sq, gamma, G);
+    hipLaunchKernelGGL(gram_rbf_kernel, dim3(tiles * (tiles + 1) / 2), dim3(256), GRAM_LDS, s, A, K, d, lda, sq, gamma, G);
     return hipGetLastError();
 }
 
