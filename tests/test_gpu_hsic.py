@@ -82,3 +82,28 @@ def test_errors(gpu):
     with pytest.raises(aq.AqError) as e:
         aq.aq_hsic_sensitivity(X, 1.0, X, 1.0, X, 1.0, 1.0, 1.0, workspace=torch.zeros(64, dtype=torch.uint8, device="cuda"))
     assert e.value.status == aq.AQ_ESIZE
+
+
+def test_rbf_gram_at_the_bench_size_sampled_entries(gpu, ho):
+    """K = 4096 samples of 11008 features, the largest Gram matrix of the bench's sensitivity (528 tiles, more than
+    the GPU holds at once): exactly symmetric (every tile writes its mirror image), ones on the diagonal, and
+    entries sampled all over the matrix against the oracle's row routine."""
+    torch, aq = gpu
+    K, d = 4096, 11008
+    g = torch.Generator(device="cuda"); g.manual_seed(93)
+    A = torch.randn((K, d), dtype=torch.float32, device="cuda", generator=g)
+    gamma = 1.0 / (2.0 * d)
+    G = aq.aq_rbf_gram(A, gamma)
+    assert torch.equal(G, G.t())
+    assert bool((torch.diagonal(G) == 1.0).all())
+    rng = np.random.default_rng(93)
+    rows = np.concatenate([[0, 127, 128, K - 1], rng.integers(0, K, size=8)])
+    Ah = A.cpu().numpy().astype(np.float64)
+    Gh = G.cpu().numpy().astype(np.float64)
+    for i in rows:
+        diff = Ah - Ah[i]
+        want = np.exp(-gamma * np.sum(diff * diff, axis=1))          # the oracle's definition, one row
+        assert np.abs(Gh[i] - want).max() <= 2e-5
+    # the same rows through the oracle's own routine on a subset it finishes quickly
+    sub = np.sort(rng.choice(K, size=64, replace=False))
+    assert np.abs(Gh[np.ix_(sub, sub)] - ho.rbf_gram(Ah[sub], gamma)).max() <= 2e-5
