@@ -64,8 +64,15 @@ __global__ __launch_bounds__(256) void sqnorm_kernel(const float* __restrict__ A
 // whole stage earlier) go to the LDS buffer that stage s - 1 was read from, stage s + 2 is requested into a second
 // set of registers, and stage s is multiplied out of the other buffer.  Eight lanes read the 128 contiguous bytes
 // of a row's stage.
+//
+// SPLIT: the features are cut into gridDim.y slices of `per` stages; every workgroup adds its slice's raw dot products
+// into G (zeroed beforehand, upper tiles only) with fp32 atomics, and gram_finish_kernel turns the sums into kernel
+// values afterwards.  Used when the tile count fits the GPU's workgroup slots badly (528 tiles on 512 slots: the last
+// 16 would run alone for as long as all the others together took).
+template <bool SPLIT>
 __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float* __restrict__ A, int64_t K, int64_t d, int64_t lda,
-                                                          const float* __restrict__ r, float gamma, float* __restrict__ G)
+                                                          const float* __restrict__ r, float gamma, float* __restrict__ G,
+                                                          int per)
 {
     extern __shared__ __align__(16) float gl[];              // [2 stages][i rows, j rows][GT][LROW]
     const int tid = threadIdx.x, lane = tid & 63;
@@ -134,14 +141,17 @@ __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float*
     };
     // operand layout of the 32x32x2 MFMA: lane l supplies A[row l % 32][k l / 32] and B[k l / 32][column l % 32]
     const int lr = lane & 31, lk = lane >> 5;
-    const int64_t stages = (d + KC - 1) / KC;
+    const int64_t all_stages = (d + KC - 1) / KC;
+    const int64_t first = SPLIT ? (int64_t)blockIdx.y * per : 0;           // this workgroup's stages: first .. first + stages - 1
+    const int64_t stages = SPLIT ? (all_stages - first < per ? all_stages - first : per) : all_stages;
+    if (stages <= 0) return;                                                // uniform
     // one stage: `cur` holds stage s + 1 (requested a stage ago) and goes to the other LDS buffer piece by piece,
     // `nxt` receives stage s + 2, stage s is multiplied out of its buffer
     auto stage = [&](int64_t s, const f32x4 (&cur)[NH][2], f32x4 (&nxt)[NH][2]) {
         const float* buf = gl + (s & 1) * GSTAGE;
         float* other = gl + ((s + 1) & 1) * GSTAGE;          // read last during stage s - 1, before the barrier
         const bool more = s + 1 < stages;
-        if (s + 2 < stages) fetch(nxt, (s + 2) * KC);
+        if (s + 2 < stages) fetch(nxt, (first + s + 2) * KC);
         const float* ti = buf + (wi * 64 + lr) * LROW + lk;
         const float* tj = buf + (GT + wj * 64 + lr) * LROW + lk;
         // operands of feature pair kk + 2 are requested before the four MFMAs of pair kk
@@ -166,10 +176,10 @@ __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float*
         }
         lds_barrier();                                       // stage s read by everyone, stage s + 1 in place
     };
-    fetch(nxB, 0);
+    fetch(nxB, first * KC);
 #pragma unroll
     for (int g = 0; g < KC / 2; ++g) stash_piece(gl, nxB, g);
-    if (stages > 1) fetch(nxA, KC);
+    if (stages > 1) fetch(nxA, (first + 1) * KC);
     lds_barrier();
     for (int64_t s = 0; s < stages; s += 2) {
         stage(s, nxA, nxB);
@@ -188,13 +198,40 @@ __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float*
             for (int v = 0; v < 16; ++v) {
                 const int64_t i = i0 + wi * 64 + a * 32 + 8 * (v >> 2) + 4 * lh + (v & 3);
                 if (i < K && j < K) {
-                    const float d2 = fmaxf(r[i] + rj - 2.f * acc[a][b][v], 0.f);
-                    const float gv = i == j ? 1.f : __expf(-gamma * d2);
-                    G[i * K + j] = gv;
-                    if (mirror) G[j * K + i] = gv;
+                    if (SPLIT) {
+                        unsafeAtomicAdd(&G[i * K + j], acc[a][b][v]);
+                    } else {
+                        const float d2 = fmaxf(r[i] + rj - 2.f * acc[a][b][v], 0.f);
+                        const float gv = i == j ? 1.f : __expf(-gamma * d2);
+                        G[i * K + j] = gv;
+                        if (mirror) G[j * K + i] = gv;
+                    }
                 }
             }
         }
+}
+
+// SPLIT path, before: zero the tiles on or above the diagonal.  After: G[i][j] holds a_i.a_j there; write the kernel
+// value and its mirror image.  One workgroup per tile (the same linear tile index), rows of 128 contiguous floats.
+template <bool FINISH>
+__global__ __launch_bounds__(256) void gram_tile_pass_kernel(int64_t K, const float* __restrict__ r, float gamma,
+                                                             float* __restrict__ G)
+{
+    const int tiles = (int)((K + GT - 1) / GT);
+    int by = 0, bx = (int)blockIdx.x;
+    while (bx >= tiles - by) { bx -= tiles - by; ++by; }
+    bx += by;
+    const int64_t i0 = (int64_t)by * GT, j0 = (int64_t)bx * GT;
+    const int64_t j = j0 + (threadIdx.x & 127);
+    if (j >= K) return;
+    const float rj = FINISH ? r[j] : 0.f;
+    for (int64_t i = i0 + (threadIdx.x >> 7); i < i0 + GT && i < K; i += 2) {
+        if (!FINISH) { G[i * K + j] = 0.f; continue; }
+        const float d2 = fmaxf(r[i] + rj - 2.f * G[i * K + j], 0.f);
+        const float gv = i == j ? 1.f : __expf(-gamma * d2);
+        G[i * K + j] = gv;
+        if (bx != by) G[j * K + i] = gv;
+    }
 }
 
 // rs[i] = sum_j G[i][j] in fp64, one wavefront per row
@@ -268,10 +305,32 @@ __global__ void finish_kernel(const double* acc, int pairs, int64_t K, double al
 hipError_t aqk_rbf_gram(const float* A, int64_t K, int64_t d, int64_t lda, float gamma, float* G, float* sq, hipStream_t s)
 {
     hipLaunchKernelGGL(sqnorm_kernel, dim3((unsigned)((K + 3) / 4)), dim3(256), 0, s, A, K, d, lda, sq);
-    const unsigned tiles = (unsigned)((K + GT - 1) / GT);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gram_rbf_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)GRAM_LDS);
-    hipLaunchKernelGGL(gram_rbf_kernel, dim3(tiles * (tiles + 1) / 2), dim3(256), GRAM_LDS, s, A, K, d, lda, sq, gamma, G);
+    const int64_t t = (K + GT - 1) / GT, ntiles = t * (t + 1) / 2, stages = (d + KC - 1) / KC;
+    // slices of the feature range: the count (1, 2 or 4) that needs the fewest rounds of workgroups, a round being
+    // AQ_GRAM_WGS workgroups on every compute unit; a slice keeps at least 16 stages
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return hipErrorInvalidDevice;
+    const int64_t slots = (int64_t)cus * AQ_GRAM_WGS;
+    int split = 1;
+    double best = (double)((ntiles + slots - 1) / slots);
+    for (int c = 2; c <= 4; c *= 2) {
+        if (stages / c < 16) break;
+        const double rounds = (double)((ntiles * c + slots - 1) / slots) / c * 1.03;      // + the two extra passes over G
+        if (rounds < best * 0.9) { best = rounds; split = c; }
+    }
+    const dim3 grid((unsigned)ntiles, (unsigned)split);
+    if (split == 1) {
+        auto k = gram_rbf_kernel<false>;
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)GRAM_LDS);
+        hipLaunchKernelGGL(k, grid, dim3(256), GRAM_LDS, s, A, K, d, lda, sq, gamma, G, 0);
+    } else {
+        auto k = gram_rbf_kernel<true>;
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)GRAM_LDS);
+        hipLaunchKernelGGL(gram_tile_pass_kernel<false>, dim3((unsigned)ntiles), dim3(256), 0, s, K, sq, gamma, G);
+        hipLaunchKernelGGL(k, grid, dim3(256), GRAM_LDS, s, A, K, d, lda, sq, gamma, G, (int)((stages + split - 1) / split));
+        hipLaunchKernelGGL(gram_tile_pass_kernel<true>, dim3((unsigned)ntiles), dim3(256), 0, s, K, sq, gamma, G);
+    }
     return hipGetLastError();
 }
 
