@@ -25,7 +25,8 @@
  * Conventions for every entry point
  *   - Pointers marked DEVICE are device (HBM) addresses, 16-byte aligned; pointers
  *     marked HOST are ordinary host memory.  The caller owns every buffer; the library
- *     allocates and frees nothing and keeps no state between calls.
+ *     allocates and frees no DEVICE memory and keeps no state between calls (the plan
+ *     builders and aq_allocate_bits use temporary host memory, std::vector, while they run).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on it and never synchronise.
  *   - Return value: AQ_OK (0) or a negative AQ_E* code.  Arguments are validated on
@@ -56,20 +57,6 @@ extern "C" {
 #define AQ_BF16  2
 
 /* Text for a status code (static storage, never NULL). */
-/* Calibration, not part of the method: what the matrix cores of this GPU sustain for a binary16 MFMA shape when the
- * operands come from memory (random data makes the part clock down; constant data does not) and nothing else runs.
- * A product kernel's rate is best read against this figure as well as against the published peak.
- *   shape           0: V_MFMA_F32_16X16X32_F16 (what the prefill kernels issue), 1: V_MFMA_F32_32X32X16_F16
- *   operands        DEVICE, 16-byte aligned, AQ_PROBE_OPERAND_BYTES bytes of binary16 values of the caller's choice
- *   iters           1 .. 2^24 loop trips per wavefront (8 resp. 4 independent MFMAs each)
- *   waves_per_simd  1 or 2 (workgroups of 4 wavefronts launched per compute unit)
- *   sink            DEVICE, 256 floats, overwritten
- *   flops           HOST, receives the floating-point operations of the launch (2 per multiply-add)
- * One asynchronous launch on `stream`; time it with events.  Errors: AQ_EINVAL, AQ_ENULL, AQ_EALIGN, AQ_ELAUNCH. */
-#define AQ_PROBE_OPERAND_BYTES 32768
-int aq_probe_mfma(int shape, const void* operands, int iters, int waves_per_simd, float* sink, int64_t* flops,
-                  void* stream);
-
 const char* aq_status_string(int status);
 
 /* Bytes of the packed device blob of an N x K matrix, 0 if the arguments are invalid.
@@ -117,22 +104,23 @@ int aq_qgemv_batch_plan(const aq_gemv_desc* descs /*HOST*/, int count, int block
                         void* plan_host, size_t plan_bytes);
 int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
 
-/* Prefill: Y[m, n] = sum_k X[m, k] * w_hat[n, k] for M rows of activations, on the matrix cores.
- * flags selects how Eq. 1's scale meets the product:
- *   AQ_GEMM_EXACT  code tiles are unpacked to the exact small integers (q - 2^(bits-1)) in LDS and the fp16
+/* Prefill: Y[m, n] = sum_k X[m, k] * w_hat[n, k] for M rows of activations, on the matrix cores (Eq. 1 fused
+ * into the product; Appendix D, "dequantize on the fly").  Two entry points, one per way Eq. 1's scale meets
+ * the product; arguments, workspace and errors are the same:
+ *   aq_qgemm       code tiles are unpacked to the exact small integers (q - 2^(bits-1)) in LDS and the fp16
  *       block scale d multiplies each block's partial sum in fp32 (Eq. 1 with the factor d taken out of
  *       the block's sum): no weight is ever rounded, only fp32 summation rounds (rel-L2 ~1e-7).  One fp32
  *       multiply-add per 32 matrix-core multiply-adds: the vector ALU bounds the speed.  For M <= 32, where the
  *       weight stream bounds the speed, the same precision is reached another way: d * (q - 2^(bits-1)) goes to the
  *       matrix cores as the exact sum of two binary16 numbers (two multiply-adds per weight) in the streaming
- *       kernel described under AQ_GEMM_FAST; bf16 activations are converted to binary16 per row as there.
- *   AQ_GEMM_FAST   w_hat = d * (q - 2^(bits-1)) is formed in binary16 while unpacking ("dequantize on the fly",
- *       Appendix D) and the matrix cores accumulate over all of K.  The product is exact for bits = 2; for
+ *       kernel described under aq_qgemm_fast; bf16 activations are converted to binary16 per row as there.
+ *   aq_qgemm_fast  w_hat = d * (q - 2^(bits-1)) is formed in binary16 while unpacking and the matrix cores
+ *       accumulate over all of K.  The product is exact for bits = 2; for
  *       bits = 3, 4 some codes need up to 14 significant bits and are rounded to binary16's 11
  *       (relative error <= 2^-12 per weight, rel-L2 of Y ~1e-4).  bf16 activations are first converted to
  *       binary16 with one power-of-two factor per row (exact unless an element is 2^38 times smaller than
  *       its row's largest).  A matrix whose largest |d| * 2^(bits-1) would overflow binary16 is computed as
- *       in AQ_GEMM_EXACT (decided on the device from the blob) by the shared-role kernel; the producer /
+ *       in aq_qgemm (decided on the device from the blob) by the shared-role kernel; the producer /
  *       consumer kernel that serves M = 300-like sizes scales d by a power of two instead, as below.  For M <= 64 the product runs in a kernel
  *       bound by the weight stream (wavefronts keep their packed tiles in registers over all of K; weights
  *       never pass through LDS); there such a matrix has every scale multiplied by one power of two
@@ -143,13 +131,18 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
  *       (2 bytes per element of X with M rounded up to 16, plus 4 bytes per row).  The call first copies
  *       X into it in the order the matrix cores read their operands, then runs the product from that
  *       copy.  Contents need no initialisation and are scratch: calls that share a workspace must be
- *       ordered on one stream. */
+ *       ordered on one stream.
+ * The list form below (aq_qgemm_batch_plan) takes the choice as `flags`: AQ_GEMM_EXACT = the arithmetic of
+ * aq_qgemm, AQ_GEMM_FAST = that of aq_qgemm_fast. */
 #define AQ_GEMM_EXACT 0
 #define AQ_GEMM_FAST  1
 size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits);
 int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block,
              const void* X, int64_t M, int64_t ldx, int x_dtype,
-             float* Y, int64_t ldy, int flags, void* workspace, size_t workspace_bytes, void* stream);
+             float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+int aq_qgemm_fast(const void* packed, int64_t N, int64_t K, int bits, int block,
+                  const void* X, int64_t M, int64_t ldx, int x_dtype,
+                  float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
 /* A list of independent prefill products in TWO launches (a whole backbone pass; a lone 4096-row
  * matrix fills only a quarter of the GPU): one that re-orders every distinct activation matrix of
@@ -223,9 +216,9 @@ int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const 
  * fp32.  aq2_qgemv_batch_plan plans a list of such products (every blob of the list in this format); the plan is
  * launched with aq_qgemv_batch.  aq2_unpack_codes / aq2_dequant_f32 are the parity inverses (the latter returns
  * fp32(D a q - M c), rounded once).
- * aq2_qgemm is aq_qgemm for such a blob, at any M in 1 .. AQ_MAX_M, in the AQ_GEMM_FAST mode only: a weight meets X
+ * aq2_qgemm is aq_qgemm_fast for such a blob, at any M in 1 .. AQ_MAX_M (there is no exact-product form of it): a weight meets X
  * as the binary16 number fp16(q * fp16(D a) - fp16(M c)), the subtraction fused (three roundings to 11 bits, against
- * one in the base format), X as in AQ_GEMM_FAST; the caller keeps 15 * (2^bits - 1) * |D| and 15 * |M| inside
+ * one in the base format), X as in aq_qgemm_fast; the caller keeps 15 * (2^bits - 1) * |D| and 15 * |M| inside
  * binary16 (65504), there is no rescaling of such a matrix.  Workspace: aq_qgemm_workspace_size(M, N, K, bits) bytes.
  * aq2_qgemm_batch_plan plans a list of such products (plan of aq_qgemm_batch_plan_size(count) bytes; workspace from
  * aq_qgemm_batch_workspace_size; launched with aq_qgemm_batch).  The decode step through the blocks takes the base
@@ -291,7 +284,7 @@ int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks /*HO
                    void* plan_host, size_t plan_bytes);
 int aq_decode_step(const void* plan_host, void* stream);
 
-/* Tensor sensitivity from HSIC (Section 4.1, Eq. 5; the estimator is Eq. 4 of Section 3):
+/* Tensor sensitivity from HSIC (Section 4.1, Eq. 5; the estimator is Eq. 2 of Section 3, "HSIC"):
  *     HSIC(A, B) = (K - 1)^-2 tr(K_A C K_B C),  [K_A]_ij = exp(-gamma_A ||a_i - a_j||^2),  C = I - (1/K) 1 1^T
  *     S = -alpha HSIC(X, Z) + beta HSIC(Z, Y)
  * over K paired calibration samples: X[K][dx] the backbone's input hidden states, Z[K][dz] the output hidden states

@@ -2,7 +2,7 @@
 tests/test_hsic_oracle_pins.py).
 
 What it follows:
-  - empirical HSIC (Section 3, "Hilbert-Schmidt Independence Criterion", Eq. 4):
+  - empirical HSIC (Section 3, "Hilbert-Schmidt Independence Criterion", Eq. 2):
         HSIC(A, B) = (K - 1)^-2 tr(K_A C K_B C),   [K_A]_ij = k_A(a_i, a_j),   C = I - (1/K) 1 1^T
     over K paired samples a_k (row k of A) and b_k (row k of B), with the RBF kernel "throughout";
   - sensitivity of a weight matrix (Section 4.1, Eq. 5):

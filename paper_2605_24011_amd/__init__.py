@@ -79,7 +79,8 @@ def lib() -> ctypes.CDLL:
         L.aq_qgemv_batch.argtypes = [_p, _p, _p]
         L.aq_qgemm_workspace_size.restype = _sz
         L.aq_qgemm_workspace_size.argtypes = [_i64, _i64, _i64, _int]
-        L.aq_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _int, _p, _sz, _p]
+        L.aq_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
+        L.aq_qgemm_fast.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
         L.aq_qgemm_batch_plan_size.restype = _sz
         L.aq_qgemm_batch_plan_size.argtypes = [_int]
         L.aq_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _int, _p, _sz]
@@ -93,7 +94,6 @@ def lib() -> ctypes.CDLL:
         L.aq2_pack_weights.argtypes = [_p, _p, _p, _i64, _i64, _int, _int, _p, _sz, _p]
         L.aq2_qgemv.argtypes = [_p, _i64, _i64, _int, _int, _p, _int, _p, _p]
         L.aq2_qgemv_batch_plan.argtypes = [ctypes.POINTER(aq_gemv_desc), _int, _int, _p, _sz]
-        L.aq_probe_mfma.argtypes = [_int, _p, _int, _int, _p, ctypes.POINTER(ctypes.c_int64), _p]
         L.aq2_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
         L.aq2_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _p, _sz]
         L.aq2_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
@@ -198,7 +198,7 @@ def aq_qgemm_workspace_size(M: int, N: int, K: int, bits: int) -> int:
 def aq_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None,
              fast: bool = False):
     """X: cuda bfloat16/float16 [M, K] (row stride = X.stride(0)) -> Y: cuda float32 [M, N].
-    fast selects AQ_GEMM_FAST (weights formed in binary16) instead of AQ_GEMM_EXACT."""
+    fast=True forwards to the C entry point aq_qgemm_fast (weights formed in binary16) instead of aq_qgemm."""
     import torch
     M = X.shape[0]
     if Y is None:
@@ -208,10 +208,15 @@ def aq_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib().aq_qgemm(packed.data_ptr(), N, K, bits, block, X.data_ptr(), M, X.stride(0), _dtype_code(X),
-                          Y.data_ptr(), Y.stride(0), AQ_GEMM_FAST if fast else AQ_GEMM_EXACT, ws_ptr, ws_bytes,
-                          _stream(stream)), "aq_qgemm")
+    fn = lib().aq_qgemm_fast if fast else lib().aq_qgemm
+    _check(fn(packed.data_ptr(), N, K, bits, block, X.data_ptr(), M, X.stride(0), _dtype_code(X),
+              Y.data_ptr(), Y.stride(0), ws_ptr, ws_bytes, _stream(stream)), "aq_qgemm_fast" if fast else "aq_qgemm")
     return Y
+
+
+def aq_qgemm_fast(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None):
+    """The C entry point aq_qgemm_fast: as aq_qgemm with the weights formed in binary16."""
+    return aq_qgemm(packed, N, K, bits, X, Y, workspace, block, stream, fast=True)
 
 
 class GemmBatch:
@@ -345,21 +350,6 @@ def aq2_qgemv(packed, N: int, K: int, bits: int, x, y=None, block: int = BLOCK, 
     _check(lib().aq2_qgemv(packed.data_ptr(), N, K, bits, block, x.data_ptr(), _dtype_code(x),
                            y.data_ptr(), _stream(stream)), "aq2_qgemv")
     return y
-
-
-PROBE_OPERAND_BYTES = 32768
-
-
-def aq_probe_mfma(shape: int, operands, iters: int, waves_per_simd: int = 1, stream=None) -> int:
-    """One launch of the MFMA calibration kernel (operands: cuda float16 tensor of PROBE_OPERAND_BYTES bytes);
-    returns the floating-point operations of the launch.  Time it with events."""
-    import torch
-    assert operands.numel() * operands.element_size() >= PROBE_OPERAND_BYTES
-    sink = torch.empty(256, dtype=torch.float32, device=operands.device)
-    flops = ctypes.c_int64(0)
-    _check(lib().aq_probe_mfma(shape, operands.data_ptr(), iters, waves_per_simd, sink.data_ptr(), ctypes.byref(flops),
-                               _stream(stream)), "aq_probe_mfma")
-    return int(flops.value)
 
 
 def aq2_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaq.so")
 SOURCES = ["aq_api.hip", "aq_pack.hip", "aq_gemv.hip", "aq_gemv2.hip", "aq_gemm.hip", "aq_gemm_small.hip", "aq_gemm_pc.hip", "aq_quant.hip",
-           "aq_layer.hip", "aq_hsic.hip", "aq_probe.hip"]
+           "aq_layer.hip", "aq_hsic.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -55,6 +55,12 @@ def build(verbose: bool = False, extra: list[str] | None = None, out: str | None
     if verbose and text:
         print(text)
     return text
+
+
+def build_extra(src: str, out: str, verbose: bool = False) -> str:
+    """One-file shared library with the same flags (the bench's calibration probe lives outside the package)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    return _run([hipcc] + HIPCC_FLAGS + ["-shared", "-o", out, src], verbose)
 
 
 if __name__ == "__main__":

@@ -416,13 +416,12 @@ size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits)
     return a > b ? a : b;      // either mode's layout of X fits
 }
 
-int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M,
-             int64_t ldx, int x_dtype, float* Y, int64_t ldy, int flags, void* workspace, size_t workspace_bytes,
-             void* stream)
+static int qgemm_one(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M,
+                     int64_t ldx, int x_dtype, float* Y, int64_t ldy, int flags, void* workspace, size_t workspace_bytes,
+                     void* stream)
 {
     int rc = check_gemm(N, K, bits, block, M, ldx, ldy, x_dtype, packed, X, Y);
     if (rc != AQ_OK) return rc;
-    if ((rc = check_flags(flags)) != AQ_OK) return rc;
     if (!workspace) return AQ_ENULL;
     if (!aligned16(workspace)) return AQ_EALIGN;
     if (workspace_bytes < aq_qgemm_workspace_size(M, N, K, bits)) return AQ_ESIZE;
@@ -445,6 +444,21 @@ int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, cons
     AqGemmTask t = make_gemm_task(packed, N, K, bits, M, 0, Y, ldy, A, nsplit, 0);
     return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, nsplit, fast, t.wg_count, workspace, s) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
+}
+
+int aq_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M,
+             int64_t ldx, int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return qgemm_one(packed, N, K, bits, block, X, M, ldx, x_dtype, Y, ldy, AQ_GEMM_EXACT, workspace, workspace_bytes,
+                     stream);
+}
+
+int aq_qgemm_fast(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M,
+                  int64_t ldx, int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes,
+                  void* stream)
+{
+    return qgemm_one(packed, N, K, bits, block, X, M, ldx, x_dtype, Y, ldy, AQ_GEMM_FAST, workspace, workspace_bytes,
+                     stream);
 }
 
 int aq2_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M, int64_t ldx,
@@ -601,17 +615,6 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
     if (h.pc)
         return aqk_gemm_pc(tasks, h.count, none, h.bits, h.format, h.total_wgs, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.nsplit, h.fast, h.total_wgs, workspace, s) == hipSuccess
-               ? AQ_OK : AQ_ELAUNCH;
-}
-
-int aq_probe_mfma(int shape, const void* operands, int iters, int waves_per_simd, float* sink, int64_t* flops,
-                  void* stream)
-{
-    if ((shape != 0 && shape != 1) || iters < 1 || iters > (1 << 24) || (waves_per_simd != 1 && waves_per_simd != 2))
-        return AQ_EINVAL;
-    if (!operands || !sink || !flops) return AQ_ENULL;
-    if (!aligned16(operands) || !aligned16(sink)) return AQ_EALIGN;
-    return aqk_probe_mfma(shape, operands, iters, waves_per_simd, sink, flops, static_cast<hipStream_t>(stream)) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
 }
 

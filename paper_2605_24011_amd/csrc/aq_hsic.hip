@@ -1,4 +1,4 @@
-// HSIC-based tensor sensitivity (Section 4.1, Eq. 5) from the empirical estimator of Eq. 4 with RBF kernels:
+// HSIC-based tensor sensitivity (Section 4.1, Eq. 5) from the empirical estimator of Eq. 2 (Section 3, "HSIC") with RBF kernels:
 //     HSIC(A, B) = (K - 1)^-2 tr(K_A C K_B C),   [K_A]_ij = exp(-gamma_A ||a_i - a_j||^2),   C = I - (1/K) 1 1^T.
 //
 // The dense part is the Gram matrix A A^T of K samples x d features (2 K^2 d flop): fp32 on the matrix cores

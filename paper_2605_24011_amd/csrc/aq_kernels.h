@@ -151,8 +151,6 @@ hipError_t aqk_fill_zero(float* p, int64_t n, hipStream_t s);
 // HSIC sensitivity (aq_hsic.hip).  aqk_rbf_gram: G (K x K) from the K rows of A, sq = K floats of scratch;
 // aqk_rowsum: fp64 row sums of a Gram matrix; aqk_hsic_pair: acc[0..3] (zeroed before) += sum GA.GB, sum a_i b_i,
 // sum a_i, sum b_i; aqk_hsic_finish: out[p] = HSIC of pair p from acc + 4 p (and Eq. 5's combination for 2 pairs).
-hipError_t aqk_probe_mfma(int shape, const void* operands, int iters, int waves_per_simd, float* sink, int64_t* flops,
-                          hipStream_t s);
 hipError_t aqk_rbf_gram(const float* A, int64_t K, int64_t d, int64_t lda, float gamma, float* G, float* sq, hipStream_t s);
 hipError_t aqk_rowsum(const float* G, int64_t K, double* rs, hipStream_t s);
 hipError_t aqk_zero_f64(double* p, int n, hipStream_t s);

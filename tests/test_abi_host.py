@@ -57,10 +57,10 @@ def test_argument_validation_without_a_gpu(L):
     assert L.aq_qgemv(A, 16, 64, 4, 32, None, aq.AQ_F16, A, None) == aq.AQ_ENULL
     assert L.aq_qgemv(A, 16, 64, 4, 32, A, aq.AQ_F16, A + 8, None) == aq.AQ_EALIGN
     assert L.aq_qgemv(A, 0, 64, 4, 32, A, aq.AQ_F16, A, None) == aq.AQ_EINVAL
-    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 0, 64, aq.AQ_BF16, A, 16, 0, None, 0, None) == aq.AQ_EINVAL
-    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 32, aq.AQ_BF16, A, 16, 0, None, 0, None) == aq.AQ_EINVAL   # ldx < K
-    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, aq.AQ_BF16, A, 8, 0, None, 0, None) == aq.AQ_EINVAL    # ldy < N
-    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, 9, A, 16, 0, None, 0, None) == aq.AQ_EDTYPE
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 0, 64, aq.AQ_BF16, A, 16, None, 0, None) == aq.AQ_EINVAL
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 32, aq.AQ_BF16, A, 16, None, 0, None) == aq.AQ_EINVAL   # ldx < K
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, aq.AQ_BF16, A, 8, None, 0, None) == aq.AQ_EINVAL    # ldy < N
+    assert L.aq_qgemm(A, 16, 64, 4, 32, A, 4, 64, 9, A, 16, None, 0, None) == aq.AQ_EDTYPE
     assert L.aq_unpack_codes(None, 16, 64, 4, 32, A, None) == aq.AQ_ENULL
     assert L.aq_dequant_f32(A, 16, 64, 3, 32, A + 2, None) == aq.AQ_EALIGN
     for s in (0, -1, -2, -3, -4, -5, -6, -99):
@@ -142,9 +142,9 @@ def test_gemm_batch_plan_validation_and_workspace(L):
     assert L.aq_qgemm_batch(buf, A, A + 4, ws, None) == aq.AQ_EALIGN
     assert L.aq_qgemm_batch(buf, A, A, ws - 1, None) == aq.AQ_ESIZE
     # single call: the workspace is required and checked before anything is launched
-    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, 0, None, 0, None) == aq.AQ_ENULL
-    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, 1, A, 1024, None) == aq.AQ_ESIZE
-    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, 2, A, 1 << 24, None) == aq.AQ_EINVAL
+    assert L.aq_qgemm(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, None, 0, None) == aq.AQ_ENULL
+    assert L.aq_qgemm_fast(A, 4096, 4096, 2, 32, A, 300, 4096, aq.AQ_BF16, A, 4096, A, 1024, None) == aq.AQ_ESIZE
+    assert L.aq_qgemm_fast(A, 4096, 4096, 2, 32, A, 0, 4096, aq.AQ_BF16, A, 4096, A, 1 << 24, None) == aq.AQ_EINVAL
     assert L.aq_qgemm_batch_plan(descs, n, 32, 7, buf, size) == aq.AQ_EINVAL          # unknown flags
 
 
@@ -280,18 +280,6 @@ def test_two_level_variant_validation_without_a_gpu(L):
     assert L.aq2_qgemm_batch_plan(gd, 2, 32, buf, size - 1) == aq.AQ_ESIZE
     gd[0].M = 0
     assert L.aq2_qgemm_batch_plan(gd, 2, 32, buf, size) == aq.AQ_EINVAL
-
-
-def test_mfma_probe_validation_without_a_gpu(L):
-    A = 1 << 20
-    flops = ctypes.c_int64(0)
-    f = ctypes.byref(flops)
-    assert L.aq_probe_mfma(2, A, 10, 1, A, f, None) == aq.AQ_EINVAL
-    assert L.aq_probe_mfma(0, A, 0, 1, A, f, None) == aq.AQ_EINVAL
-    assert L.aq_probe_mfma(0, A, 10, 3, A, f, None) == aq.AQ_EINVAL
-    assert L.aq_probe_mfma(0, None, 10, 1, A, f, None) == aq.AQ_ENULL
-    assert L.aq_probe_mfma(0, A, 10, 1, A, None, None) == aq.AQ_ENULL
-    assert L.aq_probe_mfma(0, A + 2, 10, 1, A, f, None) == aq.AQ_EALIGN
 
 
 def test_hsic_validation_without_a_gpu(L):

@@ -312,3 +312,53 @@ def test_workload_generators_are_seeded():
     xf = (x.astype(np.uint32) << 16).view(np.float32)
     assert abs(xf[:256].std() - 3.0) < 0.1 and abs(xf[256:].std() - 1.0) < 0.1
     assert wl.seeded_allocation([(4, 4)] * 10, 2.5) == wl.seeded_allocation([(4, 4)] * 10, 2.5)
+
+
+# ---------------------------------------------------------------- the acceptance measure and the row sampler
+def test_rel_l2_on_hand_computed_pairs(oracle):
+    """||Y - ref|| / ||ref|| on pairs worked by hand (Pythagorean triples, so every norm is an integer).
+    ref = (3, 4), Y = ref + (5, 12): numerator 13, denominator 5.  A dropped square root gives 169 / 25
+    or 13 / 25, the norms swapped 5 / 13, the norm of Y in the denominator 13 / sqrt(8^2 + 16^2)."""
+    ref = np.array([3.0, 4.0])
+    assert oracle.rel_l2(ref + np.array([5.0, 12.0]), ref) == pytest.approx(13.0 / 5.0, rel=1e-15)
+    # not symmetric in its arguments: the reference's norm divides
+    assert oracle.rel_l2(ref, ref + np.array([5.0, 12.0])) == pytest.approx(13.0 / np.sqrt(8.0 ** 2 + 16.0 ** 2), rel=1e-15)
+    # a 2-D pair, taken over the whole array: ref norm sqrt(1+4+4+16) = 5, difference (0, 0, 0, 0.5)
+    ref2 = np.array([[1.0, 2.0], [2.0, 4.0]])
+    y2 = ref2.copy()
+    y2[1, 1] += 0.5
+    assert oracle.rel_l2(y2, ref2) == pytest.approx(0.1, rel=1e-15)
+    assert oracle.rel_l2(ref2, ref2) == 0.0
+    # scale invariance and the 1e-3 bar itself: a uniform relative perturbation of 1e-3 measures 1e-3
+    big = np.arange(1.0, 101.0) * 1e6
+    assert oracle.rel_l2(big * (1 + 1e-3), big) == pytest.approx(1e-3, rel=1e-9)
+    # fp32 inputs are widened, not compared in fp32 (2^-30 survives next to 1)
+    a = np.array([1.0, 1.0], dtype=np.float32)
+    b = np.array([1.0, 1.0 + 2.0 ** -30], dtype=np.float64)
+    assert oracle.rel_l2(a, b) == pytest.approx(2.0 ** -30 / np.sqrt(1 + (1 + 2.0 ** -30) ** 2), rel=1e-12)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_qmatmul_rows_equals_the_matching_columns_of_qmatmul(oracle, bits):
+    """qmatmul_rows(rows) = the columns `rows` of the full product, in the order asked for, duplicates
+    included, on a ragged matrix (N = 37, K = 96) and for a single row; and against exact rationals for one
+    sampled row, so the sampler is pinned to the definition and not only to the function it wraps."""
+    N, K, M = 37, 96, 3
+    codes = wl.draw_codes(N, K, bits, 71, bits)
+    scales = wl.draw_scales(N, K, 72)
+    X = wl.draw_activations(M, K, "bf16", 73)
+    full = oracle.qmatmul(codes, scales, N, K, bits, X, "bf16")
+    rows = [36, 0, 5, 5, 17]
+    got = oracle.qmatmul_rows(codes, scales, rows, K, bits, X, "bf16")
+    assert got.shape == (M, len(rows))
+    assert np.array_equal(got, full[:, rows])
+    one = oracle.qmatmul_rows(codes, scales, [9], K, bits, X, "bf16")
+    assert np.array_equal(one[:, 0], full[:, 9])
+    # exact rationals for row 17, activation row 1
+    q = oracle.unpack(codes, N, K, bits)
+    d = scales.reshape(N, K // 32).view(np.float16)
+    xf = (X[1].astype(np.uint32) << 16).view(np.float32)
+    acc = Fraction(0)
+    for k in range(K):
+        acc += Fraction(float(xf[k])) * Fraction(float(d[17, k // 32])) * (int(q[17, k]) - (1 << (bits - 1)))
+    assert abs(got[1, 4] - float(acc)) <= 1e-13 * max(1.0, abs(float(acc)))
