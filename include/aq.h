@@ -86,7 +86,8 @@ int aq_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block,
  * Section 4.1 selects the code path per descriptor ("every matmul dispatches to one
  * dense kernel", Section 1); used for a whole backbone pass (7 matrices x L layers).
  * Step 1 (host only): aq_qgemv_batch_plan turns `count` descriptors into a plan image
- *   of aq_qgemv_batch_plan_size(count) bytes in HOST memory `plan_host`.
+ *   of aq_qgemv_batch_plan_size(descs, count, block) bytes in HOST memory `plan_host` (0: an invalid descriptor;
+ *   the image holds one record per product and one table entry per workgroup of the launch).
  * Step 2: the caller copies that image to 16-byte-aligned DEVICE memory `plan_dev`.
  * Step 3: aq_qgemv_batch(plan_host, plan_dev, stream) launches (one kernel launch); it may be
  *   repeated. */
@@ -99,7 +100,7 @@ typedef struct aq_gemv_desc {
     int32_t     x_dtype;  /* AQ_F16 or AQ_BF16 */
 } aq_gemv_desc;
 
-size_t aq_qgemv_batch_plan_size(int count);
+size_t aq_qgemv_batch_plan_size(const aq_gemv_desc* descs /*HOST*/, int count, int block);
 int aq_qgemv_batch_plan(const aq_gemv_desc* descs /*HOST*/, int count, int block,
                         void* plan_host, size_t plan_bytes);
 int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);

@@ -74,7 +74,7 @@ def lib() -> ctypes.CDLL:
         L.aq_pack_weights.argtypes = [_p, _p, _i64, _i64, _int, _int, _p, _sz, _p]
         L.aq_qgemv.argtypes = [_p, _i64, _i64, _int, _int, _p, _int, _p, _p]
         L.aq_qgemv_batch_plan_size.restype = _sz
-        L.aq_qgemv_batch_plan_size.argtypes = [_int]
+        L.aq_qgemv_batch_plan_size.argtypes = [ctypes.POINTER(aq_gemv_desc), _int, _int]
         L.aq_qgemv_batch_plan.argtypes = [ctypes.POINTER(aq_gemv_desc), _int, _int, _p, _sz]
         L.aq_qgemv_batch.argtypes = [_p, _p, _p]
         L.aq_qgemm_workspace_size.restype = _sz
@@ -179,8 +179,8 @@ class GemvBatch:
         for d, (packed, N, K, bits, x, y) in zip(descs, items):
             d.packed, d.x, d.y = packed.data_ptr(), x.data_ptr(), y.data_ptr()
             d.N, d.K, d.bits, d.x_dtype = N, K, bits, _dtype_code(x)
-        size = int(lib().aq_qgemv_batch_plan_size(n))
-        self.plan_host = torch.empty(size, dtype=torch.uint8)
+        size = int(lib().aq_qgemv_batch_plan_size(descs, n, block))      # 0: an invalid descriptor; the planner names it
+        self.plan_host = torch.empty(max(size, 64), dtype=torch.uint8)
         plan = lib().aq2_qgemv_batch_plan if two_level else lib().aq_qgemv_batch_plan
         _check(plan(descs, n, block, self.plan_host.data_ptr(), size), "aq_qgemv_batch_plan")
         self.plan_dev = self.plan_host.to(items[0][0].device)

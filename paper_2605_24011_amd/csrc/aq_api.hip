@@ -28,7 +28,7 @@ struct PlanHeader {
     int32_t reserved[9];
 };
 static_assert(sizeof(PlanHeader) == 64, "PlanHeader must stay 64 bytes");
-constexpr uint32_t PLAN_MAGIC = 0x41515031u;  // "AQP1"
+constexpr uint32_t PLAN_MAGIC = 0x41515034u;  // "AQP4"
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -266,38 +266,62 @@ int aq_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, cons
     if (!packed || !x || !y) return AQ_ENULL;
     if (!aligned16(packed) || !aligned16(x) || !aligned16(y)) return AQ_EALIGN;
     AqGemvTask t = make_task(packed, N, K, bits, x, x_dtype, y);
-    int rt = aqk_gemv_tiles_per_wg(N, false);
     t.wg_begin = 0;
-    t.wg_count = aqk_gemv_wg_count(N, rt);
-    return aqk_gemv(nullptr, 0, t, bits, rt, t.wg_count, (int)K, static_cast<hipStream_t>(stream)) == hipSuccess
+    aqk_gemv_shape(t, false);
+    return aqk_gemv(nullptr, nullptr, 0, t, bits, t.wg_count, (int)K, static_cast<hipStream_t>(stream)) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
 }
 
-size_t aq_qgemv_batch_plan_size(int count)
+// workgroups of the list in the given format, -1 if a descriptor is invalid
+static int64_t gemv_list_wgs(const aq_gemv_desc* descs, int count, int block, int format, int* status)
 {
-    if (count < 1) return 0;
-    return sizeof(PlanHeader) + (size_t)count * sizeof(AqGemvTask);
+    const int rt = aqk_gemv_tiles_per_wg(0, true);
+    int64_t wgs = 0;
+    for (int i = 0; i < count; ++i) {
+        const aq_gemv_desc& d = descs[i];
+        int rc = check_matrix(d.N, d.K, d.bits, block);
+        if (rc == AQ_OK) rc = check_dtype(d.x_dtype);
+        if (rc == AQ_OK && (!d.packed || !d.x || !d.y)) rc = AQ_ENULL;
+        if (rc == AQ_OK && (!aligned16(d.packed) || !aligned16(d.x) || !aligned16(d.y))) rc = AQ_EALIGN;
+        if (rc != AQ_OK) { if (status) *status = rc; return -1; }
+        if (format == 1) {
+            wgs += aqk_gemv_wg_count(d.N, rt);
+        } else {
+            AqGemvTask t = make_task(d.packed, d.N, d.K, d.bits, d.x, d.x_dtype, d.y);
+            aqk_gemv_shape(t, true);
+            wgs += t.wg_count;
+        }
+        if (wgs > 0x3FFFFFFF) { if (status) *status = AQ_EINVAL; return -1; }
+    }
+    return wgs;
+}
+
+static size_t gemv_plan_bytes(int count, int64_t wgs)
+{
+    return sizeof(PlanHeader) + (size_t)count * sizeof(AqGemvTask) + (((size_t)wgs * 4 + 15) & ~(size_t)15);
+}
+
+size_t aq_qgemv_batch_plan_size(const aq_gemv_desc* descs, int count, int block)
+{
+    if (count < 1 || !descs) return 0;
+    // the base format never needs fewer workgroups than the two-level variant: one size serves both planners
+    const int64_t a = gemv_list_wgs(descs, count, block, 0, nullptr), b = gemv_list_wgs(descs, count, block, 1, nullptr);
+    if (a < 0 || b < 0) return 0;
+    return gemv_plan_bytes(count, a > b ? a : b);
 }
 
 static int gemv_plan(const aq_gemv_desc* descs, int count, int block, void* plan_host, size_t plan_bytes, int format)
 {
     if (count < 1) return AQ_EINVAL;
     if (!descs || !plan_host) return AQ_ENULL;
-    if (plan_bytes < aq_qgemv_batch_plan_size(count)) return AQ_ESIZE;
     const int rt = aqk_gemv_tiles_per_wg(0, true);
-    int64_t wgs = 0;
+    int status = AQ_OK;
+    const int64_t wgs = gemv_list_wgs(descs, count, block, format, &status);
+    if (wgs < 0) return status;
+    if (plan_bytes < gemv_plan_bytes(count, wgs)) return AQ_ESIZE;
     int max_K = 0;
-    for (int i = 0; i < count; ++i) {
-        const aq_gemv_desc& d = descs[i];
-        int rc = check_matrix(d.N, d.K, d.bits, block);
-        if (rc != AQ_OK) return rc;
-        if ((rc = check_dtype(d.x_dtype)) != AQ_OK) return rc;
-        if (!d.packed || !d.x || !d.y) return AQ_ENULL;
-        if (!aligned16(d.packed) || !aligned16(d.x) || !aligned16(d.y)) return AQ_EALIGN;
-        wgs += aqk_gemv_wg_count(d.N, rt);
-        if (wgs > 0x7FFFFFFF) return AQ_EINVAL;
-        if (d.K > max_K) max_K = (int)d.K;
-    }
+    for (int i = 0; i < count; ++i)
+        if (descs[i].K > max_K) max_K = (int)descs[i].K;
     PlanHeader h;
     std::memset(&h, 0, sizeof(h));
     h.magic = PLAN_MAGIC;
@@ -306,6 +330,8 @@ static int gemv_plan(const aq_gemv_desc* descs, int count, int block, void* plan
     h.max_K = max_K;
     h.format = format;
     AqGemvTask* tasks = reinterpret_cast<AqGemvTask*>(static_cast<uint8_t*>(plan_host) + sizeof(PlanHeader));
+    int32_t* wg_task = reinterpret_cast<int32_t*>(static_cast<uint8_t*>(plan_host) + sizeof(PlanHeader) +
+                                                  (size_t)count * sizeof(AqGemvTask));
     int32_t begin = 0;
     h.bits = descs[0].bits;
     // The products of a list are independent, so their workgroups may run in any order.  A workgroup walks the
@@ -316,7 +342,9 @@ static int gemv_plan(const aq_gemv_desc* descs, int count, int block, void* plan
         if (d.bits != descs[0].bits) h.bits = 0;
         AqGemvTask t = make_task(d.packed, d.N, d.K, d.bits, d.x, d.x_dtype, d.y);
         t.wg_begin = begin;
-        t.wg_count = aqk_gemv_wg_count(d.N, rt);
+        if (format == 1) t.wg_count = aqk_gemv_wg_count(d.N, rt);
+        else aqk_gemv_shape(t, true);
+        for (int w = 0; w < t.wg_count; ++w) wg_task[begin + w] = j;
         begin += t.wg_count;
         std::memcpy(&tasks[j], &t, sizeof(t));
     }
@@ -398,15 +426,15 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream)
     if (h.magic != PLAN_MAGIC || h.count < 1 || h.total_wgs < 1 || (h.bits != 0 && (h.bits < 2 || h.bits > 4)) ||
         (h.format != 0 && h.format != 1))
         return AQ_EINVAL;
-    const AqGemvTask* tasks =
-        reinterpret_cast<const AqGemvTask*>(static_cast<const uint8_t*>(plan_dev) + sizeof(PlanHeader));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint8_t* dev = static_cast<const uint8_t*>(plan_dev);
+    const AqGemvTask* tasks = reinterpret_cast<const AqGemvTask*>(dev + sizeof(PlanHeader));
     AqGemvTask none;
     std::memset(&none, 0, sizeof(none));
     if (h.format == 1)
-        return aqk2_gemv(tasks, h.count, none, h.bits, h.tiles_per_wg, h.total_wgs, h.max_K,
-                         static_cast<hipStream_t>(stream)) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
-    return aqk_gemv(tasks, h.count, none, h.bits, h.tiles_per_wg, h.total_wgs, h.max_K,
-                    static_cast<hipStream_t>(stream)) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+        return aqk2_gemv(tasks, h.count, none, h.bits, h.tiles_per_wg, h.total_wgs, h.max_K, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    const int32_t* wg_task = reinterpret_cast<const int32_t*>(dev + sizeof(PlanHeader) + (size_t)h.count * sizeof(AqGemvTask));
+    return aqk_gemv(tasks, wg_task, h.count, none, h.bits, h.total_wgs, h.max_K, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
 }
 
 size_t aq_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits)

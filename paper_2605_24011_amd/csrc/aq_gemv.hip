@@ -1,32 +1,40 @@
-// Decode kernel: y[n] = sum_k x[k] * d[n, k/32] * (q[n, k] - 2^(bits-1))   (Eq. 1 fused into the product)
+// Decode kernels: y[n] = sum_k x[k] * d[n, k/32] * (q[n, k] - 2^(bits-1))   (Eq. 1 fused into the product)
 //
-// HBM-bound by design: each weight is read once (bits/8 + 1/16 bytes) and costs well under one
-// vector-ALU instruction, so the load stream, not the ALUs, sets the pace:
+// HBM-bound by design: each weight is read once (bits/8 + 1/16 bytes) and must cost well under one vector-ALU
+// instruction, so that the load stream, not the ALUs, sets the pace.  Two code paths:
 //
-//  * unpack: one AND-OR per TWO codes.  A 32-bit word of the blob carries the even element of a
-//    pair in its low half and the odd element in its high half at the same bit position, so
-//    (word & mask) | magic is a pair of fp16 numbers (2^e + q).  A few shifts per word bring all
-//    positions under masks that sit inside the fp16 mantissa.
-//  * multiply-accumulate: on the matrix cores.  One V_MFMA_F32_16X16X32_F16 takes 16 rows x 32
-//    k-slots of weights as A.  Its 32 k-slots are spread over the 8 blocks of a chunk (4 slots
-//    per block), and B holds x on a block diagonal: column c of B is x restricted to the slots of
-//    block c.  After 8 MFMAs D[row][c] is the complete 32-element sum of block c for that row,
-//    one useful number per lane and register, with no cross-lane reduction.
-//  * the -2^(bits-1) offset and the magic constants are linear in x: their contribution
-//    corr[block] = sum_t (magic_t + z) (x[2t] + x[2t+1]) depends on x only, is computed once per
-//    workgroup while x is staged in LDS, and enters as the C operand of the first MFMA.
-//  * the fp16 block scale multiplies the finished block sum in fp32 (one mixed-precision FMA per
-//    block and row), so every product is exact and only fp32 summation rounds.
+//  * 2-bit and 4-bit matrices: the codes go to the matrix cores as stored, as fp4 operands of the block-scaled
+//    V_MFMA_SCALE_F32_16X16X128_F8F6F4, against the activations as block-floating-point fp6 digits (aq_gemv_digit.h):
+//    3 vector-ALU instructions per 16 two-bit codes, one MFMA per 2048 (2-bit) or 1024 (4-bit) weights.
+//  * 3-bit matrices: unpack to fp16 pairs (one AND-OR per two codes against a magic exponent), V_MFMA_F32_16X16X32_F16
+//    against x on a block diagonal (aq_gemv_core.h).
 //
-// Work split: a workgroup of 4 wavefronts owns 4 or 8 tiles (16 rows each) of one 128-row group;
-// every wavefront walks the whole K extent of its own one or two tiles, sums stay in registers.
-// A batched launch runs many matrices (each with its own bit-width) in one grid.
+// In both, column c of an MFMA result is the finished sum of ONE block of 32 k for 16 rows, the fp16 block scale
+// multiplies it in fp32, and sums stay in registers until the end of the row's walk over K.
+//
+// Work split: a workgroup of 4 wavefronts; in a batched launch it owns one 128-row group (2 tiles per wavefront) and
+// walks the whole of K, every wavefront summing its own rows in registers; a lone matrix is cut into one tile per
+// workgroup with the 4 wavefronts splitting K.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include "aq_layout.h"
 #include "aq_kernels.h"
 #include "aq_codec.h"
 #include "aq_gemv_core.h"
+#include "aq_gemv_digit.h"
+#include <type_traits>
+
+#ifdef AQ_GEMV_TRACE
+// debug builds only: per-workgroup timestamps (start, after staging, end of loop, end) of the last launch
+__device__ unsigned long long aq_trace_buf[4 * 65536];
+extern "C" int aq_debug_trace_read(void* host, size_t bytes)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(aq_trace_buf), bytes);
+}
+#define AQ_TRACE(slot) do { if (threadIdx.x == 0 && blockIdx.x < 65536) aq_trace_buf[blockIdx.x * 4 + (slot)] = wall_clock64(); } while (0)
+#else
+#define AQ_TRACE(slot) do { } while (0)
+#endif
 
 namespace {
 
@@ -41,6 +49,26 @@ constexpr int THREADS = WAVES * 64;
 #ifndef AQ_GEMV_MIN_WAVES_B34
 #define AQ_GEMV_MIN_WAVES_B34 3
 #endif
+// chunks of packed units a wavefront keeps in flight on the fp4 x fp6 path
+#ifndef AQ_DG_DEPTH_B2
+#define AQ_DG_DEPTH_B2 2
+#endif
+#ifndef AQ_DG_DEPTH_B4
+#define AQ_DG_DEPTH_B4 2
+#endif
+#ifndef AQ_DG_TW
+#define AQ_DG_TW 2
+#endif
+// chunks of x staged in LDS at a time on the fp4 x fp6 path (a multiple of the ring depths)
+#ifndef AQ_GEMV_SEG_CHUNKS
+#define AQ_GEMV_SEG_CHUNKS 16
+#endif
+#ifndef AQ_DG_MIN_WAVES
+#define AQ_DG_MIN_WAVES 4
+#endif
+#ifndef AQ_DG_MIN_WAVES_B4
+#define AQ_DG_MIN_WAVES_B4 3
+#endif
 // chunks of packed units a wavefront of a lone matrix's launch requests ahead (the batched launches: 2)
 #ifndef AQ_GEMV_LONE_DEPTH
 #define AQ_GEMV_LONE_DEPTH 16
@@ -48,21 +76,17 @@ constexpr int THREADS = WAVES * 64;
 // Workgroup = 4 wavefronts x TW tiles (16 rows each) of one 128-row group; every wavefront walks
 // the whole K extent of its own tiles, so sums stay in registers and wavefronts never meet.  At
 // each chunk the 4 wavefronts together read one contiguous run of 4*TW units.
-// The task of this workgroup: `single` when count == 0, else the last record whose first workgroup
-// is not above blockIdx.x (binary search over uniform scalar loads).  A macro, so that the record
-// stays a kernel-local value in scalar registers.
+// The task of this workgroup: `single` when count == 0, else tasks[wg_task[blockIdx.x]] (a table with one entry per
+// workgroup of the launch, written by the host when the list is planned: two dependent scalar loads; a search over
+// the task records would be a chain of eight, microseconds before the workgroup's first weight load).  A macro, so
+// that the record stays a kernel-local value in scalar registers.
 #define AQ_FIND_TASK(t, wg)                                                       \
     AqGemvTask t;                                                                 \
     int wg = blockIdx.x;                                                          \
     if (count == 0) {                                                             \
         t = single;                                                               \
     } else {                                                                      \
-        int lo = 0, hi = count - 1;                                               \
-        while (lo < hi) {                                                         \
-            int mid = (lo + hi + 1) >> 1;                                         \
-            if (tasks[mid].wg_begin <= wg) lo = mid; else hi = mid - 1;           \
-        }                                                                         \
-        t = tasks[lo];                                                            \
+        t = tasks[wg_task[wg]];                                                   \
         wg -= t.wg_begin;                                                         \
     }                                                                             \
     if (wg >= t.wg_count) return
@@ -71,30 +95,46 @@ constexpr int THREADS = WAVES * 64;
 // TW == 1, may use the whole register file: its launches have few workgroups)
 template <int BITS, int TW>
 __global__ __launch_bounds__(THREADS, (TW == 1 ? 1 : BITS == 2 ? AQ_GEMV_MIN_WAVES_B2 : AQ_GEMV_MIN_WAVES_B34))
-void qgemv_kernel(const AqGemvTask* __restrict__ tasks, int count, AqGemvTask single)
+void qgemv_kernel(const AqGemvTask* __restrict__ tasks, const int32_t* __restrict__ wg_task, int count, AqGemvTask single)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     AQ_FIND_TASK(t, wg);
 #include "aq_gemv_body.inc"
 }
 
-// matrices of different bit-widths in one launch (a mixed-precision backbone pass): each workgroup
-// branches once on its matrix's bit-width; one launch has one tail instead of three
-template <int TW>
-__global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES_B34)
-void qgemv_mixed_kernel(const AqGemvTask* __restrict__ tasks, int count, AqGemvTask single)
+// the same for the fp4 x fp6 path (bits 2 and 4); lds_x = bytes of staged activations ahead of the zero record
+template <int BITS, int TW, bool KSPLIT>
+__global__ __launch_bounds__(THREADS, (BITS == 2 ? AQ_DG_MIN_WAVES : AQ_DG_MIN_WAVES_B4))
+void qgemv_digit_kernel(const AqGemvTask* __restrict__ tasks, const int32_t* __restrict__ wg_task, int count,
+                        AqGemvTask single, int lds_x)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     AQ_FIND_TASK(t, wg);
-    if (t.bits == 2) {
-        constexpr int BITS = 2;
-#include "aq_gemv_body.inc"
-    } else if (t.bits == 3) {
+#include "aq_gemv_digit_body.inc"
+}
+
+// matrices of different bit-widths in one launch (a mixed-precision backbone pass): each workgroup
+// branches once on its matrix's bit-width; one launch has one tail instead of three
+__global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES_B34)
+void qgemv_mixed_kernel(const AqGemvTask* __restrict__ tasks, const int32_t* __restrict__ wg_task, int count,
+                        AqGemvTask single, int lds_x)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    AQ_FIND_TASK(t, wg);
+    if (t.bits == 3) {
+        constexpr int TW = 2;
         constexpr int BITS = 3;
 #include "aq_gemv_body.inc"
     } else {
-        constexpr int BITS = 4;
-#include "aq_gemv_body.inc"
+        constexpr int TW = AQ_DG_TW;
+        constexpr bool KSPLIT = false;
+        if (t.bits == 2) {
+            constexpr int BITS = 2;
+#include "aq_gemv_digit_body.inc"
+        } else {
+            constexpr int BITS = 4;
+#include "aq_gemv_digit_body.inc"
+        }
     }
 }
 
@@ -104,10 +144,19 @@ size_t gemv_lds_bytes(int max_K)
     return (size_t)nch * 4 * X_PAIR_BYTES + (size_t)nch * 32 + 192 + 16;
 }
 
+// staged digits + the zero record + (lone launches) the 4 wavefronts' partial sums
+size_t digit_lds_bytes(int lds_x) { return (size_t)lds_x + 64 + 4 * 2 * 16 * sizeof(float); }
+
+template <class Kern> hipError_t allow_lds(Kern k, size_t lds)
+{
+    if (lds <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+}
+
 }  // namespace
 
-// tiles per workgroup: 8 (two per wavefront) in general, 4 for a lone small matrix so that it
-// spreads over more compute units
+// tiles per workgroup of the whole-K launches (3-bit matrices here, and the two-level variant's kernels): 8 (two per
+// wavefront) in general, 4 for a lone small matrix so that it spreads over more compute units
 int aqk_gemv_tiles_per_wg(int64_t N, bool batched)
 {
     if (batched) return 8;
@@ -119,22 +168,54 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg)
     return (int)(aq_num_groups(N) * (AQ_GROUP_TILES / tiles_per_wg));
 }
 
-// bits == 0: the tasks have different bit-widths (one mixed launch); else all tasks share `bits`
-hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
+void aqk_gemv_shape(AqGemvTask& t, bool batched)
+{
+    if (t.bits == 3) t.wg_count = aqk_gemv_wg_count(t.N, aqk_gemv_tiles_per_wg(t.N, batched));
+    else if (batched) t.wg_count = (int)aq_num_groups(t.N) * (AQ_GROUP_TILES / (WAVES * AQ_DG_TW));
+    else t.wg_count = (int)(aq_num_groups(t.N) * AQ_GROUP_TILES);          // one tile per workgroup
+}
+
+hipError_t aqk_gemv(const AqGemvTask* tasks_dev, const int32_t* wg_task, int count, const AqGemvTask& single, int bits,
                     int total_wgs, int max_K, hipStream_t s)
 {
-    // the grid was sized for `tiles_per_wg` tiles per workgroup: only the two shapes the kernels are built for
-    if ((tiles_per_wg != 4 && tiles_per_wg != 8) || (bits == 0 && tiles_per_wg != 8)) return hipErrorInvalidValue;
-    const size_t lds = gemv_lds_bytes(max_K);
     const dim3 grid((unsigned)total_wgs), block(THREADS);
-#define AQ_LAUNCH(BITS, TW) hipLaunchKernelGGL((qgemv_kernel<BITS, TW>), grid, block, lds, s, tasks_dev, count, single)
-    if (bits == 0) {
-        hipLaunchKernelGGL((qgemv_mixed_kernel<2>), grid, block, lds, s, tasks_dev, count, single);
-    } else if (tiles_per_wg == 8) {
-        if (bits == 2) AQ_LAUNCH(2, 2); else if (bits == 3) AQ_LAUNCH(3, 2); else AQ_LAUNCH(4, 2);
-    } else {
-        if (bits == 2) AQ_LAUNCH(2, 1); else if (bits == 3) AQ_LAUNCH(3, 1); else AQ_LAUNCH(4, 1);
+    const int max_nch = (max_K + AQ_CHUNK_K - 1) / AQ_CHUNK_K;
+    const int seg = max_nch < AQ_GEMV_SEG_CHUNKS ? max_nch : AQ_GEMV_SEG_CHUNKS;
+    if (count == 0) {                              // a lone matrix
+        if (bits == 3) {
+            const size_t lds = gemv_lds_bytes(max_K);
+            if (aqk_gemv_tiles_per_wg(single.N, false) == 8)
+                hipLaunchKernelGGL((qgemv_kernel<3, 2>), grid, block, lds, s, tasks_dev, wg_task, 0, single);
+            else
+                hipLaunchKernelGGL((qgemv_kernel<3, 1>), grid, block, lds, s, tasks_dev, wg_task, 0, single);
+            return hipGetLastError();
+        }
+        // every wavefront stages its own quarter of K, a segment at a time
+        const int per = (max_nch + WAVES - 1) / WAVES;
+        const int lds_x = WAVES * AQ_GEMV_SEG_CHUNKS * DG_CHUNK;
+        (void)per;
+        const size_t lds = digit_lds_bytes(lds_x);
+        hipError_t e = hipSuccess;
+        if (bits == 2) {
+            if ((e = allow_lds(qgemv_digit_kernel<2, 1, true>, lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((qgemv_digit_kernel<2, 1, true>), grid, block, lds, s, tasks_dev, wg_task, 0, single, lds_x);
+        } else {
+            if ((e = allow_lds(qgemv_digit_kernel<4, 1, true>, lds)) != hipSuccess) return e;
+            hipLaunchKernelGGL((qgemv_digit_kernel<4, 1, true>), grid, block, lds, s, tasks_dev, wg_task, 0, single, lds_x);
+        }
+        return hipGetLastError();
     }
-#undef AQ_LAUNCH
+    const int lds_x = seg * DG_CHUNK;
+    if (bits == 3) {
+        hipLaunchKernelGGL((qgemv_kernel<3, 2>), grid, block, gemv_lds_bytes(max_K), s, tasks_dev, wg_task, count, single);
+    } else if (bits == 2) {
+        hipLaunchKernelGGL((qgemv_digit_kernel<2, AQ_DG_TW, false>), grid, block, digit_lds_bytes(lds_x), s, tasks_dev, wg_task, count, single, lds_x);
+    } else if (bits == 4) {
+        hipLaunchKernelGGL((qgemv_digit_kernel<4, AQ_DG_TW, false>), grid, block, digit_lds_bytes(lds_x), s, tasks_dev, wg_task, count, single, lds_x);
+    } else {
+        // mixed: max_K counts for the 3-bit tasks' stage, a segment for the others
+        const size_t a = gemv_lds_bytes(max_K), b = digit_lds_bytes(lds_x);
+        hipLaunchKernelGGL(qgemv_mixed_kernel, grid, block, a > b ? a : b, s, tasks_dev, wg_task, count, single, lds_x);
+    }
     return hipGetLastError();
 }

@@ -24,13 +24,18 @@ hipError_t aqk_pack(const uint8_t* codes, const uint16_t* scales, int64_t N, int
 hipError_t aqk_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, uint8_t* out, hipStream_t s);
 hipError_t aqk_dequant(const void* blob, int64_t N, int64_t K, int bits, float* out, hipStream_t s);
 
-// tiles (of 16 rows) per workgroup used by the decode kernel for a matrix of N rows
+// Decode launches.  aqk_gemv_shape sets a task's wg_count:
+//   batched == true : workgroups of 4 wavefronts x 2 tiles = one 128-row group each
+//   batched == false: a lone matrix; bits 2 and 4: one tile per workgroup, its 4 wavefronts split K
+void aqk_gemv_shape(AqGemvTask& t, bool batched);
+// count == 0: run `single` (shaped with batched == false); else `count` tasks from device memory (shaped with
+// batched == true), `total_wgs` workgroups, wg_task (device) = the index of the task of every workgroup.
+// bits: the common bit-width of the tasks, 0 if they differ.  max_K: over the tasks.
+hipError_t aqk_gemv(const AqGemvTask* tasks_dev, const int32_t* wg_task, int count, const AqGemvTask& single, int bits,
+                    int total_wgs, int max_K, hipStream_t s);
+// The decode launcher of the two-level variant keeps whole-K workgroups of `tiles_per_wg` tiles.
 int aqk_gemv_tiles_per_wg(int64_t N, bool batched);
 int aqk_gemv_wg_count(int64_t N, int tiles_per_wg);
-// count == 0: run `single`; else run `count` tasks from device memory, `total_wgs` workgroups.
-// Every task of one launch has the same bit-width `bits`.
-hipError_t aqk_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
-                    int total_wgs, int max_K, hipStream_t s);
 
 // Two-level variant of the format (layout in aq_layout.h): same contracts as the three functions and the decode
 // launcher above, other blobs.

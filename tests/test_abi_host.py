@@ -73,8 +73,9 @@ def test_batch_plan_validation(L):
     descs = (aq.aq_gemv_desc * n)()
     for i, d in enumerate(descs):
         d.packed, d.x, d.y, d.N, d.K, d.bits, d.x_dtype = A, A, A, 256 * (i + 1), 512, 2 + i, aq.AQ_F16
-    size = L.aq_qgemv_batch_plan_size(n)
-    assert size >= n * 64
+    size = L.aq_qgemv_batch_plan_size(descs, n, 32)
+    assert size >= n * 80
+    assert L.aq_qgemv_batch_plan_size(descs, 0, 32) == 0 and L.aq_qgemv_batch_plan_size(None, n, 32) == 0
     buf = ctypes.create_string_buffer(size)
     assert L.aq_qgemv_batch_plan(descs, n, 32, buf, size) == aq.AQ_OK
     assert L.aq_qgemv_batch_plan(descs, n, 32, buf, size - 1) == aq.AQ_ESIZE
@@ -87,6 +88,7 @@ def test_batch_plan_validation(L):
     bad = ctypes.create_string_buffer(size)
     assert L.aq_qgemv_batch(bad, A, None) == aq.AQ_EINVAL     # not a plan image
     assert L.aq_qgemv_batch(buf, None, None) == aq.AQ_ENULL
+    assert L.aq_qgemv_batch(buf, A + 8, None) == aq.AQ_EALIGN
 
 
 def test_gemm_batch_plan_validation_and_workspace(L):
@@ -246,7 +248,7 @@ def test_two_level_variant_validation_without_a_gpu(L):
     descs = (aq.aq_gemv_desc * 2)()
     for d, (N, K, b) in zip(descs, [(256, 1024, 2), (128, 512, 3)]):
         d.packed, d.x, d.y, d.N, d.K, d.bits, d.x_dtype = A, A, A, N, K, b, aq.AQ_BF16
-    size = L.aq_qgemv_batch_plan_size(2)
+    size = L.aq_qgemv_batch_plan_size(descs, 2, 32)
     buf = (ctypes.c_uint8 * size)()
     assert L.aq2_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_OK
     import numpy as np
