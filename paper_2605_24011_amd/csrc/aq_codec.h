@@ -96,33 +96,47 @@ template <> struct Codec<4> {
 
 template <> struct Codec<3> {
     static constexpr int WORDS = 6;
-    __device__ static float offset(int t) {
-        const float o[5] = {128.f, 128.f, 16.f, 128.f, 16.f};
-        return t < 15 ? o[t % 5] : 16.f;
-    }
+    // Pair t = 8h + s of a block: its upper two bits sit at half-bits 2s, 2s+1 of word h, its lowest bit at half-bit
+    // p = 4 (s / 2) + 2h + (s % 2) of word 2.  The lowest bit keeps its position (moved down by 8 when p >= 8) and the
+    // upper bits are shifted next to it: the code then occupies mantissa bits b .. b+2, b = p % 8, of a binary16 number
+    // whose exponent makes bit b worth one: magic = 2^(10 - b).
+    __device__ static constexpr int lowbit(int t) { return (4 * ((t & 7) >> 1) + 2 * (t >> 3) + (t & 1)) & 7; }
+    __device__ static float offset(int t) { return (float)(1 << (10 - lowbit(t))); }
     __device__ static void load(const uint8_t* unit, int lane, uint32_t (&w)[WORDS]) {
         u32x2 v0 = __builtin_nontemporal_load(as_global<u32x2>(unit) + lane);
         u32x4 v1 = __builtin_nontemporal_load(as_global<u32x4>(unit + 512) + lane);
         w[0] = v0.x; w[1] = v0.y;
         w[2] = v1.x; w[3] = v1.y; w[4] = v1.z; w[5] = v1.w;
     }
-    struct Magic { uint32_t m128, m16; };
-    __device__ static Magic magic() { return {opaque_vgpr(0x58005800u), opaque_vgpr(0x4C004C00u)}; }
-    __device__ static void fence(Magic& k, float& a) { asm volatile("" : "+v"(k.m128), "+v"(k.m16), "+v"(a)); }
-    __device__ static void unpack(const uint32_t* w, const Magic& k, uint32_t (&a)[16]) {
+    struct Magic { uint32_t m[8]; };               // m[b] = the pair (2^(10-b), 2^(10-b)) as binary16 bit patterns
+    __device__ static Magic magic() {
+        Magic k;
 #pragma unroll
-        for (int h = 0; h < 3; ++h) {
-            uint32_t u0 = w[h], u1 = u0 >> 6, u2 = u0 << 3;
-            a[5 * h + 0] = and_or(u2, 0x00380038u, k.m128);
-            a[5 * h + 1] = and_or(u0, 0x00380038u, k.m128);
-            a[5 * h + 2] = and_or(u0, 0x01C001C0u, k.m16);
-            a[5 * h + 3] = and_or(u1, 0x00380038u, k.m128);
-            a[5 * h + 4] = and_or(u1, 0x01C001C0u, k.m16);
+        for (int b = 0; b < 8; ++b) k.m[b] = opaque_vgpr((uint32_t)(25 - b) * 0x04000400u);
+        return k;
+    }
+    __device__ static void fence(Magic& k, float& a) {
+        asm volatile("" : "+v"(k.m[0]), "+v"(k.m[1]), "+v"(k.m[2]), "+v"(k.m[3]), "+v"(k.m[4]), "+v"(k.m[5]), "+v"(k.m[6]),
+                     "+v"(k.m[7]), "+v"(a));
+    }
+    // words of one block (w[0], w[1]: the upper-bit plane, w[2]: the lowest bits) -> 16 pair registers
+    __device__ static void unpack(const uint32_t* w, const Magic& k, uint32_t (&a)[16]) {
+        const uint32_t l0 = w[2], l8 = w[2] >> 8;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // shifts of the upper-bit word that bring the field of pair s to bits b+1, b+2: s < 4: 2h + 1 - (s % 2),
+            // s >= 4: that minus 8
+            const int up = 2 * h + 1;
+            const uint32_t e0 = w[h] << up, o0 = up > 1 ? w[h] << (up - 1) : w[h];
+            const uint32_t e1 = w[h] >> (8 - up), o1 = w[h] >> (9 - up);
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int t = 8 * h + s, b = lowbit(t);
+                const uint32_t hv = s < 4 ? ((s & 1) ? o0 : e0) : ((s & 1) ? o1 : e1);
+                const uint32_t lv = s < 4 ? l0 : l8;
+                a[t] = and_or(lv, 0x00010001u << b, and_or(hv, 0x00060006u << b, k.m[b]));
+            }
         }
-        // pair 15: bit h of its codes sits in bit 15 of the halves of word h
-        uint32_t r = and_or(w[0] >> 9, 0x00400040u, k.m16);
-        r = and_or(w[1] >> 8, 0x00800080u, r);
-        a[15] = and_or(w[2] >> 7, 0x01000100u, r);
     }
 };
 

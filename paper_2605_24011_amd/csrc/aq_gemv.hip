@@ -1,16 +1,12 @@
 // Decode kernels: y[n] = sum_k x[k] * d[n, k/32] * (q[n, k] - 2^(bits-1))   (Eq. 1 fused into the product)
 //
 // HBM-bound by design: each weight is read once (bits/8 + 1/16 bytes) and must cost well under one vector-ALU
-// instruction, so that the load stream, not the ALUs, sets the pace.  Two code paths:
-//
-//  * 2-bit and 4-bit matrices: the codes go to the matrix cores as stored, as fp4 operands of the block-scaled
-//    V_MFMA_SCALE_F32_16X16X128_F8F6F4, against the activations as block-floating-point fp6 digits (aq_gemv_digit.h):
-//    3 vector-ALU instructions per 16 two-bit codes, one MFMA per 2048 (2-bit) or 1024 (4-bit) weights.
-//  * 3-bit matrices: unpack to fp16 pairs (one AND-OR per two codes against a magic exponent), V_MFMA_F32_16X16X32_F16
-//    against x on a block diagonal (aq_gemv_core.h).
-//
-// In both, column c of an MFMA result is the finished sum of ONE block of 32 k for 16 rows, the fp16 block scale
-// multiplies it in fp32, and sums stay in registers until the end of the row's walk over K.
+// instruction, so that the load stream, not the ALUs, sets the pace.  The codes go to the matrix cores as stored, as
+// fp4 operands of the block-scaled V_MFMA_SCALE_F32_16X16X128_F8F6F4, against the activations as block-floating-point
+// fp6 digits (aq_gemv_digit.h): 3 vector-ALU instructions per 16 two-bit codes, one MFMA per 2048 (2-bit) or 1024
+// (3-, 4-bit: two planes) weights.  Column c of an MFMA result is the finished sum of ONE block of 32 k (times one
+// digit of x) for 16 rows, the fp16 block scale multiplies it in fp32, and sums stay in registers until the end of
+// the row's walk over K.
 //
 // Work split: a workgroup of 4 wavefronts; in a batched launch it owns one 128-row group (2 tiles per wavefront) and
 // walks the whole of K, every wavefront summing its own rows in registers; a lone matrix is cut into one tile per
@@ -20,7 +16,6 @@
 #include "aq_layout.h"
 #include "aq_kernels.h"
 #include "aq_codec.h"
-#include "aq_gemv_core.h"
 #include "aq_gemv_digit.h"
 #include <type_traits>
 
@@ -43,12 +38,6 @@ using namespace aqdev;
 constexpr int WAVES = 4;
 constexpr int THREADS = WAVES * 64;
 
-#ifndef AQ_GEMV_MIN_WAVES_B2
-#define AQ_GEMV_MIN_WAVES_B2 4
-#endif
-#ifndef AQ_GEMV_MIN_WAVES_B34
-#define AQ_GEMV_MIN_WAVES_B34 3
-#endif
 // chunks of packed units a wavefront keeps in flight on the fp4 x fp6 path
 #ifndef AQ_DG_DEPTH_B2
 #define AQ_DG_DEPTH_B2 2
@@ -69,13 +58,6 @@ constexpr int THREADS = WAVES * 64;
 #ifndef AQ_DG_MIN_WAVES_B4
 #define AQ_DG_MIN_WAVES_B4 3
 #endif
-// chunks of packed units a wavefront of a lone matrix's launch requests ahead (the batched launches: 2)
-#ifndef AQ_GEMV_LONE_DEPTH
-#define AQ_GEMV_LONE_DEPTH 16
-#endif
-// Workgroup = 4 wavefronts x TW tiles (16 rows each) of one 128-row group; every wavefront walks
-// the whole K extent of its own tiles, so sums stay in registers and wavefronts never meet.  At
-// each chunk the 4 wavefronts together read one contiguous run of 4*TW units.
 // The task of this workgroup: `single` when count == 0, else tasks[wg_task[blockIdx.x]] (a table with one entry per
 // workgroup of the launch, written by the host when the list is planned: two dependent scalar loads; a search over
 // the task records would be a chain of eight, microseconds before the workgroup's first weight load).  A macro, so
@@ -91,18 +73,8 @@ constexpr int THREADS = WAVES * 64;
     }                                                                             \
     if (wg >= t.wg_count) return
 
-// one bit-width per launch: the registers, and with them the occupancy, fit that bit-width (the lone-matrix shape,
-// TW == 1, may use the whole register file: its launches have few workgroups)
-template <int BITS, int TW>
-__global__ __launch_bounds__(THREADS, (TW == 1 ? 1 : BITS == 2 ? AQ_GEMV_MIN_WAVES_B2 : AQ_GEMV_MIN_WAVES_B34))
-void qgemv_kernel(const AqGemvTask* __restrict__ tasks, const int32_t* __restrict__ wg_task, int count, AqGemvTask single)
-{
-    extern __shared__ __align__(16) uint8_t smem[];
-    AQ_FIND_TASK(t, wg);
-#include "aq_gemv_body.inc"
-}
-
-// the same for the fp4 x fp6 path (bits 2 and 4); lds_x = bytes of staged activations ahead of the zero record
+// one bit-width per launch: the registers, and with them the occupancy, fit that bit-width.
+// lds_x = bytes of staged activations ahead of the zero record
 template <int BITS, int TW, bool KSPLIT>
 __global__ __launch_bounds__(THREADS, (BITS == 2 ? AQ_DG_MIN_WAVES : AQ_DG_MIN_WAVES_B4))
 void qgemv_digit_kernel(const AqGemvTask* __restrict__ tasks, const int32_t* __restrict__ wg_task, int count,
@@ -115,33 +87,24 @@ void qgemv_digit_kernel(const AqGemvTask* __restrict__ tasks, const int32_t* __r
 
 // matrices of different bit-widths in one launch (a mixed-precision backbone pass): each workgroup
 // branches once on its matrix's bit-width; one launch has one tail instead of three
-__global__ __launch_bounds__(THREADS, AQ_GEMV_MIN_WAVES_B34)
+__global__ __launch_bounds__(THREADS, AQ_DG_MIN_WAVES_B4)
 void qgemv_mixed_kernel(const AqGemvTask* __restrict__ tasks, const int32_t* __restrict__ wg_task, int count,
                         AqGemvTask single, int lds_x)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     AQ_FIND_TASK(t, wg);
-    if (t.bits == 3) {
-        constexpr int TW = 2;
+    constexpr int TW = AQ_DG_TW;
+    constexpr bool KSPLIT = false;
+    if (t.bits == 2) {
+        constexpr int BITS = 2;
+#include "aq_gemv_digit_body.inc"
+    } else if (t.bits == 3) {
         constexpr int BITS = 3;
-#include "aq_gemv_body.inc"
+#include "aq_gemv_digit_body.inc"
     } else {
-        constexpr int TW = AQ_DG_TW;
-        constexpr bool KSPLIT = false;
-        if (t.bits == 2) {
-            constexpr int BITS = 2;
+        constexpr int BITS = 4;
 #include "aq_gemv_digit_body.inc"
-        } else {
-            constexpr int BITS = 4;
-#include "aq_gemv_digit_body.inc"
-        }
     }
-}
-
-size_t gemv_lds_bytes(int max_K)
-{
-    int nch = (max_K + AQ_CHUNK_K - 1) / AQ_CHUNK_K;
-    return (size_t)nch * 4 * X_PAIR_BYTES + (size_t)nch * 32 + 192 + 16;
 }
 
 // staged digits + the zero record + (lone launches) the 4 wavefronts' partial sums
@@ -155,8 +118,8 @@ template <class Kern> hipError_t allow_lds(Kern k, size_t lds)
 
 }  // namespace
 
-// tiles per workgroup of the whole-K launches (3-bit matrices here, and the two-level variant's kernels): 8 (two per
-// wavefront) in general, 4 for a lone small matrix so that it spreads over more compute units
+// tiles per workgroup of the two-level variant's kernels: 8 (two per wavefront) in general, 4 for a lone small matrix
+// so that it spreads over more compute units
 int aqk_gemv_tiles_per_wg(int64_t N, bool batched)
 {
     if (batched) return 8;
@@ -170,8 +133,7 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg)
 
 void aqk_gemv_shape(AqGemvTask& t, bool batched)
 {
-    if (t.bits == 3) t.wg_count = aqk_gemv_wg_count(t.N, aqk_gemv_tiles_per_wg(t.N, batched));
-    else if (batched) t.wg_count = (int)aq_num_groups(t.N) * (AQ_GROUP_TILES / (WAVES * AQ_DG_TW));
+    if (batched) t.wg_count = (int)aq_num_groups(t.N) * (AQ_GROUP_TILES / (WAVES * AQ_DG_TW));
     else t.wg_count = (int)(aq_num_groups(t.N) * AQ_GROUP_TILES);          // one tile per workgroup
 }
 
@@ -181,41 +143,26 @@ hipError_t aqk_gemv(const AqGemvTask* tasks_dev, const int32_t* wg_task, int cou
     const dim3 grid((unsigned)total_wgs), block(THREADS);
     const int max_nch = (max_K + AQ_CHUNK_K - 1) / AQ_CHUNK_K;
     const int seg = max_nch < AQ_GEMV_SEG_CHUNKS ? max_nch : AQ_GEMV_SEG_CHUNKS;
-    if (count == 0) {                              // a lone matrix
-        if (bits == 3) {
-            const size_t lds = gemv_lds_bytes(max_K);
-            if (aqk_gemv_tiles_per_wg(single.N, false) == 8)
-                hipLaunchKernelGGL((qgemv_kernel<3, 2>), grid, block, lds, s, tasks_dev, wg_task, 0, single);
-            else
-                hipLaunchKernelGGL((qgemv_kernel<3, 1>), grid, block, lds, s, tasks_dev, wg_task, 0, single);
-            return hipGetLastError();
-        }
-        // every wavefront stages its own quarter of K, a segment at a time
-        const int per = (max_nch + WAVES - 1) / WAVES;
+    hipError_t e = hipSuccess;
+#define AQ_GO(KERNEL, LDS_X)                                                                                  \
+    do {                                                                                                      \
+        const size_t lds = digit_lds_bytes(LDS_X);                                                            \
+        if ((e = allow_lds(KERNEL, lds)) != hipSuccess) return e;                                             \
+        hipLaunchKernelGGL(KERNEL, grid, block, lds, s, tasks_dev, wg_task, count, single, LDS_X);            \
+    } while (0)
+    if (count == 0) {
+        // a lone matrix: every wavefront stages its own quarter of K, a segment at a time
         const int lds_x = WAVES * AQ_GEMV_SEG_CHUNKS * DG_CHUNK;
-        (void)per;
-        const size_t lds = digit_lds_bytes(lds_x);
-        hipError_t e = hipSuccess;
-        if (bits == 2) {
-            if ((e = allow_lds(qgemv_digit_kernel<2, 1, true>, lds)) != hipSuccess) return e;
-            hipLaunchKernelGGL((qgemv_digit_kernel<2, 1, true>), grid, block, lds, s, tasks_dev, wg_task, 0, single, lds_x);
-        } else {
-            if ((e = allow_lds(qgemv_digit_kernel<4, 1, true>, lds)) != hipSuccess) return e;
-            hipLaunchKernelGGL((qgemv_digit_kernel<4, 1, true>), grid, block, lds, s, tasks_dev, wg_task, 0, single, lds_x);
-        }
+        if (bits == 2) AQ_GO((qgemv_digit_kernel<2, 1, true>), lds_x);
+        else if (bits == 3) AQ_GO((qgemv_digit_kernel<3, 1, true>), lds_x);
+        else AQ_GO((qgemv_digit_kernel<4, 1, true>), lds_x);
         return hipGetLastError();
     }
     const int lds_x = seg * DG_CHUNK;
-    if (bits == 3) {
-        hipLaunchKernelGGL((qgemv_kernel<3, 2>), grid, block, gemv_lds_bytes(max_K), s, tasks_dev, wg_task, count, single);
-    } else if (bits == 2) {
-        hipLaunchKernelGGL((qgemv_digit_kernel<2, AQ_DG_TW, false>), grid, block, digit_lds_bytes(lds_x), s, tasks_dev, wg_task, count, single, lds_x);
-    } else if (bits == 4) {
-        hipLaunchKernelGGL((qgemv_digit_kernel<4, AQ_DG_TW, false>), grid, block, digit_lds_bytes(lds_x), s, tasks_dev, wg_task, count, single, lds_x);
-    } else {
-        // mixed: max_K counts for the 3-bit tasks' stage, a segment for the others
-        const size_t a = gemv_lds_bytes(max_K), b = digit_lds_bytes(lds_x);
-        hipLaunchKernelGGL(qgemv_mixed_kernel, grid, block, a > b ? a : b, s, tasks_dev, wg_task, count, single, lds_x);
-    }
+    if (bits == 2) AQ_GO((qgemv_digit_kernel<2, AQ_DG_TW, false>), lds_x);
+    else if (bits == 3) AQ_GO((qgemv_digit_kernel<3, AQ_DG_TW, false>), lds_x);
+    else if (bits == 4) AQ_GO((qgemv_digit_kernel<4, AQ_DG_TW, false>), lds_x);
+    else AQ_GO(qgemv_mixed_kernel, lds_x);
+#undef AQ_GO
     return hipGetLastError();
 }

@@ -219,6 +219,19 @@ template <> struct DigitUnit<2> {
     }
 };
 
+template <> struct DigitUnit<3> {
+    // two planes: the upper two bits of every code (words 0, 1: 2-bit fields) and the lowest bit (word 2: one bit per
+    // 4-bit field after the shifts below); q = 2 hi + lo
+    __device__ static __forceinline__ float4v block(const uint32_t* w, const v8i& B, const float4v& C, int sb)
+    {
+        const uint32_t M = 0x33333333u, M1 = 0x11111111u;
+        const v4i hi = {(int)(w[0] & M), (int)((w[0] >> 2) & M), (int)(w[1] & M), (int)((w[1] >> 2) & M)};
+        const v4i lo = {(int)(w[2] & M1), (int)((w[2] >> 1) & M1), (int)((w[2] >> 2) & M1), (int)((w[2] >> 3) & M1)};
+        const float4v d = mfma_fp4_fp6(lo, B, C, SA_X2, sb);
+        return mfma_fp4_fp6(hi, B, d, SA_X4, sb);
+    }
+};
+
 template <> struct DigitUnit<4> {
     // two planes: the low and the high two bits of every code; q = lo + 4 hi
     __device__ static __forceinline__ float4v block(const uint32_t* w, const v8i& B, const float4v& C, int sb)

@@ -22,8 +22,11 @@
 // constant turns a word into two fp16 numbers (magic + code):
 //   bits = 2: word h (0..1) holds pairs t = 8h + s, s = 0..7, code at half-bit 2s
 //   bits = 4: word h (0..3) holds pairs t = 4h + s, s = 0..3, code at half-bit 4s
-//   bits = 3: word h (0..2) holds pairs t = 5h + s, s = 0..4, code at half-bit 3s; bit 15 of
-//             each half of word h holds bit h of pair 15's code
+//   bits = 3: two planes.  Words 0, 1 hold the upper two bits of every code (q >> 1) in the 2-bit format above; word 2
+//             holds the lowest bits: bit (q & 1) of element 16h + 4n + 2f + o (h, f, o in {0,1}, n in 0..3) sits at
+//             bit 16o + 4n + 2h + f, i.e. pair t = 8h + 2n + f has its two low bits at half-bit 4n + 2h + f.  (The decode
+//             kernel feeds each plane to the matrix cores as 4-bit fields: `(word >> j) & 0x11111111` must put
+//             element (register j = 2h + f, nibble n + 4o) where `(word_h >> 2f) & 0x33333333` puts its upper bits.)
 // The lane's 2*bits words are w[blk*bits + h] (blk = 0, 1).
 //   code area  : bits == 2: one plane of 16 B per lane (4 words)          -> 1024 B
 //                bits == 3: plane A 8 B per lane (words 0,1), plane B 16 B per lane (words 2..5) -> 512 + 1024 B
@@ -96,18 +99,19 @@ AQ_HD uint32_t aq_block_get(const uint32_t* w, int bits, int e)
     int t = e >> 1, sh = (e & 1) * 16;
     if (bits == 2) return (w[t >> 3] >> (sh + 2 * (t & 7))) & 3u;
     if (bits == 4) return (w[t >> 2] >> (sh + 4 * (t & 3))) & 15u;
-    if (t < 15) return (w[t / 5] >> (sh + 3 * (t % 5))) & 7u;
-    return ((w[0] >> (sh + 15)) & 1u) | (((w[1] >> (sh + 15)) & 1u) << 1) | (((w[2] >> (sh + 15)) & 1u) << 2);
+    // bits == 3: upper two bits in the 2-bit format, lowest bit in word 2
+    int h = t >> 3, s = t & 7, n = s >> 1, f = s & 1;
+    uint32_t hi = (w[h] >> (sh + 2 * s)) & 3u, lo = (w[2] >> (sh + 4 * n + 2 * h + f)) & 1u;
+    return 2u * hi + lo;
 }
 AQ_HD void aq_block_put(uint32_t* w, int bits, int e, uint32_t q)
 {
     int t = e >> 1, sh = (e & 1) * 16;
     if (bits == 2) w[t >> 3] |= q << (sh + 2 * (t & 7));
     else if (bits == 4) w[t >> 2] |= q << (sh + 4 * (t & 3));
-    else if (t < 15) w[t / 5] |= q << (sh + 3 * (t % 5));
     else {
-        w[0] |= (q & 1u) << (sh + 15);
-        w[1] |= ((q >> 1) & 1u) << (sh + 15);
-        w[2] |= ((q >> 2) & 1u) << (sh + 15);
+        int h = t >> 3, s = t & 7, n = s >> 1, f = s & 1;
+        w[h] |= (q >> 1) << (sh + 2 * s);
+        w[2] |= (q & 1u) << (sh + 4 * n + 2 * h + f);
     }
 }
