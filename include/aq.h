@@ -145,6 +145,18 @@ int aq_qgemm_fast(const void* packed, int64_t N, int64_t K, int bits, int block,
                   const void* X, int64_t M, int64_t ldx, int x_dtype,
                   float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): aq_qgemm with its workspace taken from a fixed array inside the library
+ * (AQ_NOALLOC_SCRATCH_BYTES of device memory per GPU, held until the process ends; the call itself allocates and frees
+ * nothing).  Same arithmetic, arguments and errors as aq_qgemm; AQ_ESIZE if aq_qgemm_workspace_size(M, N, K, bits)
+ * exceeds AQ_NOALLOC_SCRATCH_BYTES (M = 300 fits up to K = 16384).  Every call on one GPU uses that GPU's one array
+ * (its contents are rewritten by each call, nothing has to start at zero): calls that overlap on one GPU, on
+ * different streams, race; calls on one stream are ordered. */
+#define AQ_NOALLOC_SCRATCH_BYTES (12 * 1024 * 1024)
+int aq_qgemm_noalloc(const void* packed, int64_t N, int64_t K, int bits, int block,
+                     const void* X, int64_t M, int64_t ldx, int x_dtype,
+                     float* Y, int64_t ldy, void* stream);
+
 /* A list of independent prefill products in TWO launches (a whole backbone pass; a lone 4096-row
  * matrix fills only a quarter of the GPU): one that re-orders every distinct activation matrix of
  * the list into the workspace (descriptors with equal X, M, K and ldx share one copy), one for all

@@ -81,6 +81,7 @@ def lib() -> ctypes.CDLL:
         L.aq_qgemm_workspace_size.argtypes = [_i64, _i64, _i64, _int]
         L.aq_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
         L.aq_qgemm_fast.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
+        L.aq_qgemm_noalloc.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p]
         L.aq_qgemm_batch_plan_size.restype = _sz
         L.aq_qgemm_batch_plan_size.argtypes = [_int]
         L.aq_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _int, _p, _sz]
@@ -211,6 +212,14 @@ def aq_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block
     fn = lib().aq_qgemm_fast if fast else lib().aq_qgemm
     _check(fn(packed.data_ptr(), N, K, bits, block, X.data_ptr(), M, X.stride(0), _dtype_code(X),
               Y.data_ptr(), Y.stride(0), ws_ptr, ws_bytes, _stream(stream)), "aq_qgemm_fast" if fast else "aq_qgemm")
+    return Y
+
+
+def aq_qgemm_noalloc(packed, N: int, K: int, bits: int, X, Y, block: int = BLOCK, stream=None):
+    """The C entry point aq_qgemm_noalloc: aq_qgemm with the library's own fixed scratch array as workspace.  Y is the
+    caller's (this wrapper allocates nothing either)."""
+    _check(lib().aq_qgemm_noalloc(packed.data_ptr(), N, K, bits, block, X.data_ptr(), X.shape[0], X.stride(0), _dtype_code(X),
+                                  Y.data_ptr(), Y.stride(0), _stream(stream)), "aq_qgemm_noalloc")
     return Y
 
 

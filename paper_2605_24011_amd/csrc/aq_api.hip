@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 #include "../../include/aq.h"
 #include "aq_layout.h"
@@ -219,6 +220,33 @@ int decode_part_chunks(const int64_t* rows, int matrices, int nchunks)
         if (wgs <= DECODE_TARGET_WGS) break;
     }
     return p;
+}
+
+}  // namespace
+
+// Scratch of aq_qgemm_noalloc: a file-scope device array (every GPU the library runs on holds its own copy until the
+// process ends).  In host code the array's name is only a handle: the address kernels and copies can use comes from
+// hipGetSymbolAddress, asked for once per device with that device current.
+static __device__ __align__(256) unsigned char scratch[AQ_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[MAX_DEVICES] = {};
+
+int noalloc_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return AQ_ELAUNCH;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return AQ_ELAUNCH;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return AQ_OK;
 }
 
 }  // namespace
@@ -486,6 +514,18 @@ int aq_qgemm_fast(const void* packed, int64_t N, int64_t K, int bits, int block,
                   void* stream)
 {
     return qgemm_one(packed, N, K, bits, block, X, M, ldx, x_dtype, Y, ldy, AQ_GEMM_FAST, workspace, workspace_bytes,
+                     stream);
+}
+
+int aq_qgemm_noalloc(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M,
+                     int64_t ldx, int x_dtype, float* Y, int64_t ldy, void* stream)
+{
+    int rc = check_gemm(N, K, bits, block, M, ldx, ldy, x_dtype, packed, X, Y);
+    if (rc != AQ_OK) return rc;
+    if (aq_qgemm_workspace_size(M, N, K, bits) > (size_t)AQ_NOALLOC_SCRATCH_BYTES) return AQ_ESIZE;
+    void* ws = nullptr;
+    if ((rc = noalloc_scratch(&ws)) != AQ_OK) return rc;
+    return qgemm_one(packed, N, K, bits, block, X, M, ldx, x_dtype, Y, ldy, AQ_GEMM_EXACT, ws, AQ_NOALLOC_SCRATCH_BYTES,
                      stream);
 }
 
