@@ -53,6 +53,27 @@ def build_stream(aq, wl, torch, specs, x_dtype, seed_tag):
     return items
 
 
+def backbone_prefill_items(torch, wl, items, specs, M, dtype, seed_tag, image_rows=0, image_gain=1.0, shared=False):
+    """(packed, N, K, bits, X, Y) per product of a backbone pass.  As in a transformer block, the projections that read
+    the same hidden state share one X per layer (q/k/v; gate/up), o and down have their own, and every product has its
+    own Y.  shared=True is the cheaper stand-in (one X per K, one Y per N for the whole pass: outputs overwrite each
+    other in cache); it is kept as an option to show the difference."""
+    if shared:
+        Xs = {K: wl.draw_activations_torch(M, K, dtype, "cuda", seed_tag, K, image_rows=image_rows, image_gain=image_gain)
+              for K in sorted({m.K for m in specs})}
+        Ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({m.N for m in specs})}
+        return [(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in items]
+    out, cache = [], {}
+    for m, (packed, N, K, bits, _x, _y) in zip(specs, items):
+        group = {"q": "attn", "k": "attn", "v": "attn", "gate": "mlp", "up": "mlp"}.get(m.name, m.name)
+        key = (m.layer, group)
+        if key not in cache:
+            cache[key] = wl.draw_activations_torch(M, K, dtype, "cuda", seed_tag, m.layer, len(cache),
+                                                   image_rows=image_rows, image_gain=image_gain)
+        out.append((packed, N, K, bits, cache[key], torch.empty((M, N), dtype=torch.float32, device="cuda")))
+    return out
+
+
 def time_launches(torch, fn, steps, warmup):
     """Per-launch durations (ms) from HIP events on the launch stream, plus wall time of all steps."""
     for _ in range(warmup):
@@ -85,6 +106,8 @@ def main():
     ap.add_argument("--skip-two-level", action="store_true")
     ap.add_argument("--skip-hsic", action="store_true")
     ap.add_argument("--prefill-steps", type=int, default=5)
+    ap.add_argument("--prefill-shared-buffers", action="store_true",
+                    help="prefill sections: one X per K and one Y per N for the whole pass instead of a backbone pass's buffers")
     ap.add_argument("--prefill-only", action="store_true",
                     help="the timed decode stream with 2 steps, then only the M = 300 prefill (short run for rocprofv3 --pmc passes)")
     ap.add_argument("--decode-only", action="store_true",
@@ -132,14 +155,19 @@ def main():
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = step_bytes / (kernel_ms * 1e-3) / 1e9
 
-    # HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
-    # plain copy of known size); the committed summary carries the figure
-    traffic = None
+    # HBM bytes per launch: measured OFFLINE with two rocprofv3 --pmc passes over this same command (FETCH_SIZE, then
+    # WRITE_SIZE, scaled by a plain copy of known size); the committed summary carries the figure together with the
+    # algorithmic bytes it was taken against.  Reported only while those still are this run's.
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "qgemv_mixed_kernel__llama2-7b_mixed_decode__hbm_traffic.md")
     if os.path.exists(tpath):
         import re
-        m = re.search(r"hbm_bytes_per_launch\s*=\s*(\d+)", open(tpath).read())
-        traffic = int(m.group(1)) if m else None
+        text = open(tpath).read()
+        m = re.search(r"hbm_bytes_per_launch\s*=\s*(\d+)", text)
+        a = re.search(r"algorithmic_bytes_per_launch\s*=\s*(\d+)", text)
+        if m and a and int(a.group(1)) == step_bytes:
+            traffic = int(m.group(1))
+            traffic_source = "offline: rocprofv3 --pmc passes recorded in profiles/" + os.path.basename(tpath)
 
     out = {
         "metric": "qGEMV HBM GB/s (decode, batch 1, algorithmic bytes / time)",
@@ -173,6 +201,7 @@ def main():
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": traffic,
+            "traffic_source": traffic_source,
             "avg_launch_ms": round(kernel_ms, 4),
         },
     }
@@ -208,6 +237,27 @@ def main():
             "tokens_per_s": round(cpu_bytes / cpu_s / step_bytes, 3),
             "gpu_vs_oracle_max_rel_l2": float("%.3g" % worst),
         }
+        # the same oracle on ONE core, on the first 4096 x 4096 matrix of the stream
+        try:
+            import ctypes
+            gomp = ctypes.CDLL("libgomp.so.1")
+            threads = aq_oracle.num_threads()
+            gomp.omp_set_num_threads(1)
+            m = specs[0]
+            codes, scales = wl.draw_matrix_torch(m.N, m.K, m.bits, "cuda", 3, m.index)
+            c = codes.cpu().numpy()
+            sc = scales.view(torch.int16).cpu().numpy().view(np.uint16)
+            x = items[0][4].view(torch.int16).cpu().numpy().view(np.uint16)[None, :]
+            t0 = time.perf_counter()
+            aq_oracle.qmatmul(c, sc, m.N, m.K, m.bits, x, "f16")
+            one_s = time.perf_counter() - t0
+            gomp.omp_set_num_threads(threads)
+            out["cpu_baseline"]["single_thread"] = {
+                "value": round(gemv_bytes(m.N, m.K, m.bits) / one_s / 1e9, 4), "unit": "GB/s", "cores": 1,
+                "sample": "one %d x %d matrix at %d bits, %.2f s" % (m.N, m.K, m.bits, one_s)}
+            del codes, scales
+        except OSError:
+            pass
 
     # ---- the same pass at a uniform bit-width (cold: 2.0 / 2.8 / 3.6 GB per pass) ----------
     if not args.skip_by_bits:
@@ -278,17 +328,16 @@ def main():
     # ---- prefill: M = 300 over the same mixed stream -------------------------------------
     if not args.skip_prefill:
         M = wl.PREFILL_M
-        Xs = {}
-        for K in sorted({m.K for m in specs}):
-            Xs[K] = wl.draw_activations_torch(M, K, "bf16", "cuda", 4, K, image_rows=wl.PREFILL_IMAGE_ROWS,
-                                              image_gain=wl.PREFILL_IMAGE_GAIN)
-        # one output buffer per distinct N, shared by the matrices of that shape (outputs are not consumed)
-        Ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({m.N for m in specs})}
         flops = 2.0 * M * weights
-        pre = {"workload": "M=300 (256 image rows x3 + 44 text rows, bf16) over the same 224 matrices: one launch that "
-                           "re-orders X and one batched product launch"}
+        pre = {"workload": "M=300 (256 image rows x3 + 44 text rows, bf16) over the same 224 matrices as a backbone pass: one X "
+                           "per layer and input (q/k/v share, gate/up share, o and down their own), one Y per product; one "
+                           "launch that re-orders the distinct X and one batched product launch"}
+        pitems = backbone_prefill_items(torch, wl, items, specs, M, "bf16", 4, wl.PREFILL_IMAGE_ROWS, wl.PREFILL_IMAGE_GAIN,
+                                        shared=args.prefill_shared_buffers)
+        if args.prefill_shared_buffers:
+            pre["workload"] += " [--prefill-shared-buffers: ONE X per K and ONE Y per N for the whole pass]"
         for mode, fast in (("exact", False), ("fast", True)):
-            gbatch = aq.GemmBatch([(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in items], fast=fast)
+            gbatch = aq.GemmBatch(pitems, fast=fast)
             d, w = time_launches(torch, gbatch.run, args.prefill_steps, 1)
             ms = sum(d) / len(d)
             pre[mode] = {
@@ -323,6 +372,26 @@ def main():
                     probe["%s_%s_TFLOP/s" % (name, label)] = round(box.value / (min(d) * 1e-3) / 1e12, 1)
             pre["mfma_probe"] = probe
             pre["fast"]["frac_of_probe_16x16x32_random"] = round(pre["fast"]["TFLOP/s"] / probe["16x16x32_random_N01_TFLOP/s"], 4)
+        if not args.skip_cpu:
+            # the oracle on one 4096 x 4096 matrix at M = 300 (10 GFLOP in fp64), all host threads, checked against the
+            # exact-mode output of the same product
+            from oracle import aq_oracle
+            m = specs[0]
+            codes, scales = wl.draw_matrix_torch(m.N, m.K, m.bits, "cuda", 3, m.index)
+            c = codes.cpu().numpy()
+            sc = scales.view(torch.int16).cpu().numpy().view(np.uint16)
+            Xh = pitems[0][4].view(torch.int16).cpu().numpy().view(np.uint16)
+            t0 = time.perf_counter()
+            ref = aq_oracle.qmatmul(c, sc, m.N, m.K, m.bits, Xh, "bf16")
+            cpu_s = time.perf_counter() - t0
+            Yg = aq.aq_qgemm(items[0][0], m.N, m.K, m.bits, pitems[0][4]).cpu().numpy()
+            pre["cpu_oracle"] = {"TFLOP/s": round(2.0 * M * m.N * m.K / cpu_s / 1e12, 4), "cores": aq_oracle.num_threads(),
+                                 "kind": "oracle",
+                                 "sample": "one %d x %d matrix at %d bits, M = %d, %.2f s" % (m.N, m.K, m.bits, M, cpu_s),
+                                 "gpu_vs_oracle_rel_l2": float("%.3g" % aq_oracle.rel_l2(Yg, ref))}
+            del codes, scales
+        del pitems
+        torch.cuda.empty_cache()
         pre["modes"] = ("exact: integer codes on the matrix cores, fp16 block scale applied to each block's sum in fp32 "
                         "(no weight rounded); fast: d*(q-z) rounded to binary16 while unpacking (exact for 2 bits), "
                         "bf16 activations converted to binary16 with a power-of-two factor per row")
@@ -344,14 +413,13 @@ def main():
                           "pct_hbm_peak": round(100 * gbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
                           "ms": round(ms, 4), "tokens_per_s": round(1e3 / ms, 1), "bytes": gbytes}}
         for M in (16, 64, wl.PREFILL_M):
-            Xs = {K: wl.draw_activations_torch(M, K, "bf16", "cuda", 6, K, M) for K in sorted({m.K for m in gs})}
-            Ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({m.N for m in gs})}
+            gp = backbone_prefill_items(torch, wl, gitems, gs, M, "bf16", 6 + M, shared=args.prefill_shared_buffers)
             flops = 2.0 * M * gweights
             nbytes = sum(stored_bytes(m.N, m.K, m.bits) + 2 * M * m.K + 4 * M * m.N for m in gs)
             t_hbm, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
             cell = {"bound": "hbm" if t_hbm > t_mfma else "mfma"}
             for mode, fast in (("exact", False), ("fast", True)):
-                g2 = aq.GemmBatch([(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in gitems], fast=fast)
+                g2 = aq.GemmBatch(gp, fast=fast)
                 d, w = time_launches(torch, g2.run, args.prefill_steps, 1)
                 ms = sum(d) / len(d)
                 cell[mode] = {"ms": round(ms, 4), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
@@ -360,7 +428,7 @@ def main():
                               "tokens_per_s": round(M / (ms * 1e-3), 1)}
                 del g2
             gem["prefill_M%d" % M] = cell
-            del Xs, Ys
+            del gp
         out["gemma"] = gem
 
     # ---- block-level scale optimisation (the step that produces codes and scales), one 11008 x 4096 matrix ----
@@ -435,18 +503,16 @@ def main():
             if alloc == "mixed":
                 # prefill over the same blobs (aq2_qgemm semantics: weights formed in binary16), M = 300
                 M = wl.PREFILL_M
-                Xs = {K: wl.draw_activations_torch(M, K, "bf16", "cuda", 13, K, image_rows=wl.PREFILL_IMAGE_ROWS,
-                                                   image_gain=wl.PREFILL_IMAGE_GAIN) for K in sorted({m.K for m in specs})}
-                Ys = {N: torch.empty((M, N), dtype=torch.float32, device="cuda") for N in sorted({m.N for m in specs})}
-                gb = aq.GemmBatch([(packed, N, K, bits, Xs[K], Ys[N]) for (packed, N, K, bits, _x, _y) in items],
-                                  two_level=True)
+                tp = backbone_prefill_items(torch, wl, items, specs, M, "bf16", 13, wl.PREFILL_IMAGE_ROWS, wl.PREFILL_IMAGE_GAIN,
+                                            shared=args.prefill_shared_buffers)
+                gb = aq.GemmBatch(tp, two_level=True)
                 d, w = time_launches(torch, gb.run, args.prefill_steps, 1)
                 ms = sum(d) / len(d)
                 flops = 2.0 * M * weights
                 two["mixed_prefill_m300"] = {"ms": round(ms, 3), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
                                              "mfma_frac_of_bf16_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                                              "prefill_tokens_per_s": round(M / (ms * 1e-3), 1)}
-                del gb, Xs, Ys
+                del gb, tp
             del items
         out["two_level_format"] = two
 
@@ -502,7 +568,10 @@ def main():
                 quant["b%d_rounds%d" % (b, r)] = {
                     "ms": round(ms, 4), "Gweights/s": round(N * K / (ms * 1e-3) / 1e9, 1),
                     "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
-                    "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                    "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    # fp64 vector-ALU instructions per weight: 12 for the stored-code assignment (3 more with F) plus
+                    # 12.5 per round, against 39.3 T lane-instructions/s (78.6 TFLOP/s fp64 vector / 2)
+                    "frac_fp64_valu_peak": round(N * K * (15.0 + 12.5 * r) / (ms * 1e-3) / 39.3e12, 4)}
         if not args.skip_cpu:
             from oracle import aq_oracle
             rows = N                   # the whole matrix: about 1.5 s on one core

@@ -141,7 +141,10 @@ def test_decode_step_hand_worked_block(gpu, oracle, layer_oracle):
     step.run()
     torch.cuda.synchronize()
     want = np.tile(np.array([0.2330221489, 0.7860565783, -1.8448801077, 0.2330221489]), 8)
-    assert np.allclose(x.cpu().numpy(), want, rtol=0, atol=2e-3)       # h2 is rounded to 11 bits on the way
+    # h2 is rounded to 11 bits on the way: a relative bar on every element (the smallest is 0.23), and on the vector
+    got = x.cpu().numpy()
+    assert np.all(np.abs(got - want) <= 1e-3 * np.abs(want))
+    assert oracle.rel_l2(got, want) <= 1e-3
     v = np.tile(np.array([1.0, -1.0, 1.0, 1.0]), 8)
     assert np.array_equal(qkv.cpu().numpy()[0], np.concatenate([v, v, v]))
 

@@ -135,6 +135,34 @@ def test_qgemv_zero_activations_and_scaling(gpu, oracle):
         assert oracle.rel_l2(y, ref) <= REL_L2_EXPECTED
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_qgemv_wide_dynamic_range_inside_one_vector(gpu, oracle, bits, dtype):
+    """Activations whose magnitude differs by many binades from block to block of ONE vector (bf16: 2^-60 .. 2^40
+    over the blocks, f16: 2^-12 .. 2^12) and by 2^-12 inside blocks: the staging keeps one exponent per block of
+    32, so every block keeps 16 bits below its own largest element.  Lone call and batched launch."""
+    torch, aq = gpu
+    N, K = 272, 4096
+    codes, scales = wl.draw_matrix(N, K, bits, 17, bits)
+    rng = np.random.default_rng(171 + bits)
+    x = rng.standard_normal(K).astype(np.float32)
+    span = 100 if dtype == "bf16" else 24
+    block_exp = rng.integers(0, span + 1, size=K // 32) - (60 if dtype == "bf16" else 12)
+    x *= np.exp2(np.repeat(block_exp, 32)).astype(np.float32)
+    small = rng.random(K) < 0.25                    # a quarter of the elements sit 2^-12 below their block
+    x[small] *= np.float32(2.0 ** -12)
+    xb = (wl.f32_to_bf16_bits(x[None]) if dtype == "bf16" else wl.f32_to_f16_bits(x[None]))
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    ref = oracle.qmatmul(codes, scales, N, K, bits, xb, dtype)[0]
+    xd = _dev(torch, xb[0], dtype)
+    y = aq.aq_qgemv(packed, N, K, bits, xd).cpu().numpy()
+    assert np.isfinite(y).all()
+    assert oracle.rel_l2(y, ref) <= REL_L2_EXPECTED
+    yb = torch.empty(N, dtype=torch.float32, device="cuda")
+    aq.GemvBatch([(packed, N, K, bits, xd, yb)]).run()
+    assert oracle.rel_l2(yb.cpu().numpy(), ref) <= REL_L2_EXPECTED
+
+
 def test_qgemv_batch_matches_single_calls(gpu, oracle):
     """A mixed-bit stream in one launch gives what the per-matrix calls give, and the oracle's."""
     torch, aq = gpu
