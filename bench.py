@@ -320,6 +320,19 @@ def main():
                     ms1 = sum(d) / len(d) / copies
                     cell["per_call_us"] = round(ms1 * 1e3, 2)
                     cell["per_call_GB/s"] = round(per / (ms1 * 1e-3) / 1e9, 1)
+                    # the same calls replayed from a captured HIP graph (kernel nodes only): what the GPU needs per call
+                    # without the host's launch path
+                    side = torch.cuda.Stream()
+                    side.wait_stream(torch.cuda.current_stream())
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.stream(side):
+                        lone()
+                        with torch.cuda.graph(graph, stream=side):
+                            lone()
+                    torch.cuda.current_stream().wait_stream(side)
+                    d, w = time_launches(torch, graph.replay, 5, 1)
+                    cell["per_call_us_graph_replay"] = round(sum(d) / len(d) / copies * 1e3, 2)
+                    del graph
                 cells["%s_b%d" % (name, b)] = cell
                 del its, bt
                 torch.cuda.empty_cache()

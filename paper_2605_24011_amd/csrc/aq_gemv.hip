@@ -73,10 +73,11 @@ constexpr int THREADS = WAVES * 64;
     }                                                                             \
     if (wg >= t.wg_count) return
 
-// one bit-width per launch: the registers, and with them the occupancy, fit that bit-width.
+// one bit-width per launch: the registers, and with them the occupancy, fit that bit-width (the lone-matrix shape may
+// use the whole register file: its launches have about one workgroup per compute unit).
 // lds_x = bytes of staged activations ahead of the zero record
 template <int BITS, int TW, bool KSPLIT>
-__global__ __launch_bounds__(THREADS, (BITS == 2 ? AQ_DG_MIN_WAVES : AQ_DG_MIN_WAVES_B4))
+__global__ __launch_bounds__(THREADS, (KSPLIT ? 1 : BITS == 2 ? AQ_DG_MIN_WAVES : AQ_DG_MIN_WAVES_B4))
 void qgemv_digit_kernel(const AqGemvTask* __restrict__ tasks, const int32_t* __restrict__ wg_task, int count,
                         AqGemvTask single, int lds_x)
 {
