@@ -514,17 +514,21 @@ def main():
                           "tokens_per_s": round(1e3 / ms, 1)}
             del bt
             if alloc == "mixed":
-                # prefill over the same blobs (aq2_qgemm semantics: weights formed in binary16), M = 300
+                # prefill over the same blobs, M = 300: exact products (aq2_qgemm) and weights formed in binary16
+                # (aq2_qgemm_fast)
                 M = wl.PREFILL_M
                 tp = backbone_prefill_items(torch, wl, items, specs, M, "bf16", 13, wl.PREFILL_IMAGE_ROWS, wl.PREFILL_IMAGE_GAIN,
                                             shared=args.prefill_shared_buffers)
-                gb = aq.GemmBatch(tp, two_level=True)
-                d, w = time_launches(torch, gb.run, args.prefill_steps, 1)
-                ms = sum(d) / len(d)
                 flops = 2.0 * M * weights
-                two["mixed_prefill_m300"] = {"ms": round(ms, 3), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
-                                             "mfma_frac_of_bf16_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                                             "prefill_tokens_per_s": round(M / (ms * 1e-3), 1)}
+                two["mixed_prefill_m300"] = {}
+                for mode, fast in (("exact", False), ("fast", True)):
+                    gb = aq.GemmBatch(tp, two_level=True, fast=fast)
+                    d, w = time_launches(torch, gb.run, args.prefill_steps, 1)
+                    ms = sum(d) / len(d)
+                    two["mixed_prefill_m300"][mode] = {
+                        "ms": round(ms, 3), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
+                        "mfma_frac_of_bf16_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                        "prefill_tokens_per_s": round(M / (ms * 1e-3), 1)}
                 del gb, tp
             del items
         out["two_level_format"] = two

@@ -229,11 +229,16 @@ int aq_allocate_bits(const double* S, const int64_t* sizes, int L, int J, const 
  * fp32.  aq2_qgemv_batch_plan plans a list of such products (every blob of the list in this format); the plan is
  * launched with aq_qgemv_batch.  aq2_unpack_codes / aq2_dequant_f32 are the parity inverses (the latter returns
  * fp32(D a q - M c), rounded once).
- * aq2_qgemm is aq_qgemm_fast for such a blob, at any M in 1 .. AQ_MAX_M (there is no exact-product form of it): a weight meets X
- * as the binary16 number fp16(q * fp16(D a) - fp16(M c)), the subtraction fused (three roundings to 11 bits, against
- * one in the base format), X as in aq_qgemm_fast; the caller keeps 15 * (2^bits - 1) * |D| and 15 * |M| inside
- * binary16 (65504), there is no rescaling of such a matrix.  Workspace: aq_qgemm_workspace_size(M, N, K, bits) bytes.
- * aq2_qgemm_batch_plan plans a list of such products (plan of aq_qgemm_batch_plan_size(count) bytes; workspace from
+ * aq2_qgemm is aq_qgemm for such a blob (exact products, any M in 1 .. AQ_MAX_M): per block the matrix cores give
+ * P = sum_k q x on exact small integers and X_b = sum_k x, and the accumulators take (D a) P - (M c) X_b in fp32 (D a
+ * and M c are exact there); no weight is rounded and no magnitude limit applies beyond fp32's.
+ * aq2_qgemm_fast is aq_qgemm_fast for such a blob: a weight meets X as the binary16 number
+ * fp16(q * fp16(D a) - fp16(M c)), the subtraction fused (three roundings to 11 bits, against one in the base format),
+ * X as in aq_qgemm_fast.  LIMIT of this mode only: the caller keeps 15 * (2^bits - 1) * |D| and 15 * |M| inside
+ * binary16 (65504); such a matrix is not rescaled, and beyond the limit the result holds infinities or NaNs where
+ * aq2_qgemm, aq2_qgemv and aq2_dequant_f32 stay finite.  Workspace of both: aq_qgemm_workspace_size(M, N, K, bits) bytes.
+ * aq2_qgemm_batch_plan plans a list of such products in the mode `flags` names (AQ_GEMM_EXACT or AQ_GEMM_FAST; plan of
+ * aq_qgemm_batch_plan_size(count) bytes; workspace from
  * aq_qgemm_batch_workspace_size; launched with aq_qgemm_batch).  The decode step through the blocks takes the base
  * format.  Arguments, limits and errors as for the base functions. */
 size_t aq2_packed_size(int64_t N, int64_t K, int bits, int block);
@@ -245,7 +250,10 @@ int aq2_qgemv_batch_plan(const aq_gemv_desc* descs /*HOST*/, int count, int bloc
                          void* plan_host, size_t plan_bytes);
 int aq2_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M, int64_t ldx,
               int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
-int aq2_qgemm_batch_plan(const aq_gemm_desc* descs /*HOST*/, int count, int block, void* plan_host, size_t plan_bytes);
+int aq2_qgemm_fast(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M, int64_t ldx,
+                   int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream);
+int aq2_qgemm_batch_plan(const aq_gemm_desc* descs /*HOST*/, int count, int block, int flags,
+                         void* plan_host, size_t plan_bytes);
 int aq2_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream);
 int aq2_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int block, float* W, void* stream);
 

@@ -96,7 +96,8 @@ def lib() -> ctypes.CDLL:
         L.aq2_qgemv.argtypes = [_p, _i64, _i64, _int, _int, _p, _int, _p, _p]
         L.aq2_qgemv_batch_plan.argtypes = [ctypes.POINTER(aq_gemv_desc), _int, _int, _p, _sz]
         L.aq2_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
-        L.aq2_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _p, _sz]
+        L.aq2_qgemm_fast.argtypes = L.aq2_qgemm.argtypes
+        L.aq2_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _int, _p, _sz]
         L.aq2_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq2_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq_hsic_workspace_size.restype = _sz
@@ -233,7 +234,7 @@ class GemmBatch:
 
     def __init__(self, items: Sequence[tuple], block: int = BLOCK, fast: bool = False, two_level: bool = False):
         """items: (packed, N, K, bits, X, Y) per matrix; X [M, K] half/bfloat16, Y [M, N] float32.
-        two_level: every blob is in the two-level variant of the format (aq2_qgemm_batch_plan; fp16-weight mode)."""
+        two_level: every blob is in the two-level variant of the format (aq2_qgemm_batch_plan)."""
         import torch
         n = len(items)
         descs = (aq_gemm_desc * n)()
@@ -244,7 +245,8 @@ class GemmBatch:
         size = int(lib().aq_qgemm_batch_plan_size(n))
         self.plan_host = torch.empty(size, dtype=torch.uint8)
         if two_level:
-            _check(lib().aq2_qgemm_batch_plan(descs, n, block, self.plan_host.data_ptr(), size), "aq2_qgemm_batch_plan")
+            _check(lib().aq2_qgemm_batch_plan(descs, n, block, AQ_GEMM_FAST if fast else AQ_GEMM_EXACT,
+                                              self.plan_host.data_ptr(), size), "aq2_qgemm_batch_plan")
         else:
             _check(lib().aq_qgemm_batch_plan(descs, n, block, AQ_GEMM_FAST if fast else AQ_GEMM_EXACT,
                                              self.plan_host.data_ptr(), size), "aq_qgemm_batch_plan")
@@ -361,8 +363,10 @@ def aq2_qgemv(packed, N: int, K: int, bits: int, x, y=None, block: int = BLOCK, 
     return y
 
 
-def aq2_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None):
-    """X: cuda bfloat16/float16 [M, K] -> Y: cuda float32 [M, N], the blob in the two-level variant of the format."""
+def aq2_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None,
+              fast: bool = False):
+    """X: cuda bfloat16/float16 [M, K] -> Y: cuda float32 [M, N], the blob in the two-level variant of the format.
+    Exact products; fast=True calls aq2_qgemm_fast (fp16 weights)."""
     import torch
     M = X.shape[0]
     if Y is None:
@@ -372,9 +376,14 @@ def aq2_qgemm(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, bloc
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib().aq2_qgemm(packed.data_ptr(), N, K, bits, block, X.data_ptr(), M, X.stride(0), _dtype_code(X),
-                           Y.data_ptr(), Y.stride(0), ws_ptr, ws_bytes, _stream(stream)), "aq2_qgemm")
+    fn = lib().aq2_qgemm_fast if fast else lib().aq2_qgemm
+    _check(fn(packed.data_ptr(), N, K, bits, block, X.data_ptr(), M, X.stride(0), _dtype_code(X),
+              Y.data_ptr(), Y.stride(0), ws_ptr, ws_bytes, _stream(stream)), "aq2_qgemm_fast" if fast else "aq2_qgemm")
     return Y
+
+
+def aq2_qgemm_fast(packed, N: int, K: int, bits: int, X, Y=None, workspace=None, block: int = BLOCK, stream=None):
+    return aq2_qgemm(packed, N, K, bits, X, Y, workspace, block, stream, fast=True)
 
 
 def aq2_unpack_codes(packed, N: int, K: int, bits: int, block: int = BLOCK, stream=None):

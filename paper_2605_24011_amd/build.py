@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaq.so")
-SOURCES = ["aq_api.hip", "aq_pack.hip", "aq_gemv.hip", "aq_gemv2.hip", "aq_gemm.hip", "aq_gemm_small.hip", "aq_gemm_pc.hip", "aq_quant.hip",
+SOURCES = ["aq_api.hip", "aq_pack.hip", "aq_gemv.hip", "aq_gemv2.hip", "aq_gemm.hip", "aq_gemm2.hip", "aq_gemm_small.hip", "aq_gemm_pc.hip", "aq_quant.hip",
            "aq_layer.hip", "aq_hsic.hip"]
 
 HIPCC_FLAGS = [
@@ -22,6 +22,7 @@ SOURCE_FLAGS = {
     # prefill: MFMA results in ordinary VGPRs (no AGPR copies around the fp32 scaling of block sums).
     # Only here: the decode kernel is 8% slower with it.
     "aq_gemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "aq_gemm2.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 
@@ -48,7 +49,7 @@ def build(verbose: bool = False, extra: list[str] | None = None, out: str | None
             obj = os.path.join(tmp, src.replace(".hip", ".o"))
             jobs.append((obj, [hipcc] + HIPCC_FLAGS + SOURCE_FLAGS.get(src, []) + (extra or []) +
                          ["-I", CSRC, "-c", os.path.join(CSRC, src), "-o", obj]))
-        with concurrent.futures.ThreadPoolExecutor(max_workers=4) as pool:
+        with concurrent.futures.ThreadPoolExecutor(max_workers=6) as pool:
             log += list(pool.map(lambda j: _run(j[1], verbose), jobs))
         log.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + [j[0] for j in jobs], verbose))
     text = "\n".join(t for t in log if t.strip())

@@ -58,7 +58,7 @@ struct GemmPlanHeader {
     int32_t fast;            // fp16-weight mode
     int32_t small_mt;        // > 0: the small-M streaming kernel with that many m-tiles (fast mode, M <= 64)
     int32_t pc;              // the producer / consumer kernel (fast mode, prefill-sized M)
-    int32_t format;          // 0: base format, 1: two-level variant (always the producer / consumer kernel)
+    int32_t format;          // 0: base format, 1: two-level variant (fast: the producer / consumer kernel; exact: aq_gemm2.hip)
     int32_t reserved;
 };
 static_assert(sizeof(GemmPlanHeader) == 64, "GemmPlanHeader must stay 64 bytes");
@@ -529,8 +529,8 @@ int aq_qgemm_noalloc(const void* packed, int64_t N, int64_t K, int bits, int blo
                      stream);
 }
 
-int aq2_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M, int64_t ldx,
-              int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream)
+static int qgemm2_one(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M, int64_t ldx,
+                      int x_dtype, float* Y, int64_t ldy, int flags, void* workspace, size_t workspace_bytes, void* stream)
 {
     int rc = check_gemm(N, K, bits, block, M, ldx, ldy, x_dtype, packed, X, Y);
     if (rc != AQ_OK) return rc;
@@ -538,11 +538,28 @@ int aq2_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, con
     if (!aligned16(workspace)) return AQ_EALIGN;
     if (workspace_bytes < aq_qgemm_workspace_size(M, N, K, bits)) return AQ_ESIZE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int convert = x_dtype == AQ_BF16;
+    const int fast = flags == AQ_GEMM_FAST, convert = fast && x_dtype == AQ_BF16;
     const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
     if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
-    const AqGemmTask t = make_pc_task(packed, N, K, bits, M, 0, Y, ldy, 0);
-    return aqk_gemm_pc(nullptr, 0, t, bits, 1, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    if (fast) {
+        const AqGemmTask t = make_pc_task(packed, N, K, bits, M, 0, Y, ldy, 0);
+        return aqk_gemm_pc(nullptr, 0, t, bits, 1, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    }
+    const int A = aqk_gemm_mtiles(M, aq_num_groups(N));
+    const AqGemmTask t = make_gemm_task(packed, N, K, bits, M, 0, Y, ldy, A, 1, 0);
+    return aqk2_gemm(nullptr, 0, t, x_dtype, A, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+}
+
+int aq2_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M, int64_t ldx,
+              int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return qgemm2_one(packed, N, K, bits, block, X, M, ldx, x_dtype, Y, ldy, AQ_GEMM_EXACT, workspace, workspace_bytes, stream);
+}
+
+int aq2_qgemm_fast(const void* packed, int64_t N, int64_t K, int bits, int block, const void* X, int64_t M, int64_t ldx,
+                   int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return qgemm2_one(packed, N, K, bits, block, X, M, ldx, x_dtype, Y, ldy, AQ_GEMM_FAST, workspace, workspace_bytes, stream);
 }
 
 // plan image: header, `count` product tasks, then up to `count` re-tiling tasks
@@ -552,7 +569,8 @@ size_t aq_qgemm_batch_plan_size(int count)
     return sizeof(GemmPlanHeader) + (size_t)count * (sizeof(AqGemmTask) + sizeof(AqRetileTask));
 }
 
-// format 1 (two-level variant): fp16-weight mode through the producer / consumer kernel at every M
+// format 1 (two-level variant): the fp16-weight mode runs the producer / consumer kernel and the exact mode the
+// 8-wavefront kernel, both at every M
 static int gemm_plan(const aq_gemm_desc* descs, int count, int block, int flags, void* plan_host, size_t plan_bytes,
                      int format)
 {
@@ -576,11 +594,11 @@ static int gemm_plan(const aq_gemm_desc* descs, int count, int block, int flags,
     int64_t groups = 0;
     for (int i = 0; i < count; ++i) groups += aq_num_groups(descs[i].N);
     h.mtiles = aqk_gemm_mtiles(max_M, groups);
-    h.nsplit = aqk_gemm_nsplit(max_M);
+    h.nsplit = format ? 1 : aqk_gemm_nsplit(max_M);
     h.fast = flags == AQ_GEMM_FAST;
     h.format = format;
     h.small_mt = !format && max_M <= (h.fast ? SMALL_M : SMALL_M_EXACT) ? aqk_small_mtiles(max_M) : 0;
-    h.pc = 1;
+    h.pc = format ? h.fast : 1;
     for (int i = 0; i < count && !format; ++i) h.pc = h.pc && use_pc(h.fast, descs[i].M);      // every product of the list
     const int convert = h.fast && h.x_dtype == AQ_BF16;
     uint8_t* base = static_cast<uint8_t*>(plan_host);
@@ -630,9 +648,9 @@ int aq_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int fla
     return gemm_plan(descs, count, block, flags, plan_host, plan_bytes, 0);
 }
 
-int aq2_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, void* plan_host, size_t plan_bytes)
+int aq2_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int flags, void* plan_host, size_t plan_bytes)
 {
-    return gemm_plan(descs, count, block, AQ_GEMM_FAST, plan_host, plan_bytes, 1);
+    return gemm_plan(descs, count, block, flags, plan_host, plan_bytes, 1);
 }
 
 static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
@@ -645,7 +663,7 @@ static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
            (h.fast == 0 || h.fast == 1) &&
            (h.small_mt == 0 || h.small_mt == 1 || h.small_mt == 2 || (h.small_mt == 4 && h.fast == 1)) &&
            (h.pc == 0 || (h.pc == 1 && h.fast == 1 && h.small_mt == 0)) &&
-           (h.format == 0 || (h.format == 1 && h.pc == 1));
+           (h.format == 0 || (h.format == 1 && h.pc == h.fast && h.small_mt == 0));
 }
 
 size_t aq_qgemm_batch_workspace_size(const void* plan_host)
@@ -682,6 +700,9 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
         return AQ_ELAUNCH;
     if (h.pc)
         return aqk_gemm_pc(tasks, h.count, none, h.bits, h.format, h.total_wgs, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    if (h.format == 1)
+        return aqk2_gemm(tasks, h.count, none, h.x_dtype, h.mtiles, h.total_wgs, workspace, s) == hipSuccess
+                   ? AQ_OK : AQ_ELAUNCH;
     return aqk_gemm(tasks, h.count, none, h.bits, h.x_dtype, h.mtiles, h.nsplit, h.fast, h.total_wgs, workspace, s) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
 }

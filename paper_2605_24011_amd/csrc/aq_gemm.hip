@@ -19,129 +19,9 @@
 // once per product list into operand order (retile_kernel) and the main kernel's loads are 1 KiB
 // contiguous.  A batched launch runs a list of matrices in one grid (a lone 4096-row matrix gives only
 // 32 workgroups for 256 CUs).
-#include <hip/hip_runtime.h>
-#include <type_traits>
-#include "aq_layout.h"
-#include "aq_kernels.h"
-#include "aq_codec.h"
+#include "aq_gemm_kernel.h"
 
 namespace {
-
-using namespace aqdev;
-typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
-
-constexpr int GM_WAVES = 8;                        // all along m: each wavefront covers the workgroup's 128 n
-constexpr int GM_THREADS = GM_WAVES * 64;
-constexpr int GM_NT = AQ_GROUP_ROWS;               // n per workgroup = one 128-row group of the blob
-constexpr int W_ROW = AQ_CHUNK_K * 2 + 32;         // LDS row stride of the W chunk tile: 544 B.  A stride of 64j + 32 bytes
-                                                   // lets the b128 operand reads (16 rows x 4 quarters per instruction)
-                                                   // run at ~175 B/clk/CU; 64j + 16 gives ~125, 64j gives 33-66 (measured)
-
-// words of one block -> 16 registers, each a pair of exact (q - z) in fp16 or bf16
-template <int BITS, bool XBF>
-__device__ __forceinline__ void unpack_exact(const uint32_t* w, const typename Codec<BITS>::Magic& magic,
-                                             uint32_t (&o)[16])
-{
-    uint32_t a[16];
-    Codec<BITS>::unpack(w, magic, a);              // fp16 pairs (magic + q)
-    const float z = (float)(1 << (BITS - 1));
-#pragma unroll
-    for (int p = 0; p < 16; ++p) {
-        const _Float16 k = (_Float16)(Codec<BITS>::offset(p) + z);
-        const uint32_t ap = a[p];
-        const half2v h = __builtin_bit_cast(half2v, ap) - half2v{k, k};      // exact: small integers
-        if (XBF) {
-            const float lo = (float)h.x, hi = (float)h.y;                    // bf16 = upper half of the fp32
-            o[p] = (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
-        } else {
-            o[p] = __builtin_bit_cast(uint32_t, h);
-        }
-    }
-}
-
-template <bool XBF>
-__device__ __forceinline__ float4v mfma16(const u32x4& a, const u32x4& b, const float4v& c)
-{
-    if (XBF)
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a), __builtin_bit_cast(bf8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
-}
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory, which
-// costs a full drain of the vector-memory queue (vmcnt 0) and with it the X prefetch, once per chunk.
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-#define AQ_FIND_GEMM_TASK(t, wg)                                                  \
-    AqGemmTask t;                                                                 \
-    int wg = blockIdx.x;                                                          \
-    if (count == 0) {                                                             \
-        t = single;                                                               \
-    } else {                                                                      \
-        int lo = 0, hi = count - 1;                                               \
-        while (lo < hi) {                                                         \
-            int mid = (lo + hi + 1) >> 1;                                         \
-            if (tasks[mid].wg_begin <= wg) lo = mid; else hi = mid - 1;           \
-        }                                                                         \
-        t = tasks[lo];                                                            \
-        wg -= t.wg_begin;                                                         \
-    }                                                                             \
-    if (wg >= t.wg_count) return
-
-// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup.
-// FAST: fp16-weight mode.  Xt holds binary16 activations (XBF is false) with a power-of-two factor per row;
-// the workgroup forms w = d * (q - z) in binary16 while unpacking ("FOLD") and the MFMAs accumulate across
-// blocks with no per-block fp32 scaling.  d * (q - z) needs at most 14 significant bits: exact for 2 bits
-// (q - z is 0 or a power of two), rounded to 11 bits (relative error <= 2^-12) for some codes of 3 and 4
-// bits.  If the matrix holds a scale so large that the product could overflow binary16 (trailer word of
-// the blob), the workgroup takes the exact per-block path instead, on the same binary16 activations.
-template <int BITS_T, bool XBF, int A, int NW, bool FAST>
-__global__ __launch_bounds__(GM_THREADS) void qgemm_kernel(const AqGemmTask* __restrict__ tasks, int count,
-                                                           AqGemmTask single, const uint8_t* __restrict__ workspace)
-{
-    extern __shared__ __align__(16) uint8_t smem[];
-    static_assert(!(FAST && XBF), "the fp16-weight mode multiplies binary16 operands");
-    AQ_FIND_GEMM_TASK(t, wg);
-    bool fold = false;
-    if (FAST) {
-        const uint32_t max_d = *reinterpret_cast<const uint32_t*>(
-            t.blob + (int64_t)t.slabs * t.nchunks * AQ_GROUP_TILES * aq_unit_bytes(t.bits));
-        fold = max_d <= 0x7BFFu - (uint32_t)(t.bits - 1) * 0x400u;      // max|d| * 2^(bits-1) <= 65504
-    }
-    if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) {
-        constexpr int BITS = 2;
-        if (FAST && fold) {
-            constexpr bool FOLD = true;
-#include "aq_gemm_body.inc"
-        } else {
-            constexpr bool FOLD = false;
-#include "aq_gemm_body.inc"
-        }
-    } else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) {
-        constexpr int BITS = 3;
-        if (FAST && fold) {
-            constexpr bool FOLD = true;
-#include "aq_gemm_body.inc"
-        } else {
-            constexpr bool FOLD = false;
-#include "aq_gemm_body.inc"
-        }
-    } else {
-        constexpr int BITS = 4;
-        if (FAST && fold) {
-            constexpr bool FOLD = true;
-#include "aq_gemm_body.inc"
-        } else {
-            constexpr bool FOLD = false;
-#include "aq_gemm_body.inc"
-        }
-    }
-}
 
 // X[M][ldx] (16-bit elements) -> Xt in operand order.  Thread e handles the 16-byte piece j = e % (K/8)
 // of row e / (K/8): reads run along the rows of X, rows in [M, 16*ceil(M/16)) are written as zeros.
@@ -229,29 +109,6 @@ __global__ __launch_bounds__(256) void retile_convert_kernel(const AqRetileTask*
     if (tid == 0) rowexp[row] = -shift;
 }
 
-template <int BITS_T, bool XBF, bool FAST>
-void launch_a(int A, int NW, dim3 grid, size_t lds, hipStream_t s, const AqGemmTask* tasks, int count,
-              const AqGemmTask& single, const uint8_t* ws)
-{
-    dim3 block(GM_THREADS);
-#define AQ_LAUNCH(AA, NN)                                                                                      \
-    do {                                                                                                       \
-        auto k = qgemm_kernel<BITS_T, XBF, AA, NN, FAST>;                                                      \
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                  (int)lds);               /* more than the 64 KiB default */                  \
-        hipLaunchKernelGGL(k, grid, block, lds, s, tasks, count, single, ws);                                  \
-    } while (0)
-    switch (A * 16 + NW) {
-        case 1 * 16 + 8: AQ_LAUNCH(1, 8); break;
-        case 1 * 16 + 4: AQ_LAUNCH(1, 4); break;
-        case 1 * 16 + 2: AQ_LAUNCH(1, 2); break;
-        case 1 * 16 + 1: AQ_LAUNCH(1, 1); break;
-        case 2 * 16 + 1: AQ_LAUNCH(2, 1); break;
-        default: AQ_LAUNCH(3, 1); break;
-    }
-#undef AQ_LAUNCH
-}
-
 }  // namespace
 
 // Shape of the wavefront grid for M rows of activations.  mtiles = most m-tiles (16 rows) per wavefront;
@@ -316,15 +173,15 @@ hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTa
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
                     int nsplit, int fast, int total_wgs, const void* workspace, hipStream_t s)
 {
-    const size_t lds = 2 * ((size_t)GM_NT * W_ROW + GM_NT * 8 * sizeof(float));     // two chunk buffers
+    const size_t lds = gm_lds_bytes(0);
     const dim3 grid((unsigned)total_wgs);
     const bool bf = (x_dtype == 2) && !fast;         // the fp16-weight mode reads binary16 activations from Xt
     const uint8_t* ws = static_cast<const uint8_t*>(workspace);
 #define AQ_GO(B)                                                                                     \
     do {                                                                                             \
-        if (fast) launch_a<B, false, true>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);   \
-        else if (bf) launch_a<B, true, false>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws); \
-        else launch_a<B, false, false>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);       \
+        if (fast) launch_a<B, false, true, 0>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);   \
+        else if (bf) launch_a<B, true, false, 0>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws); \
+        else launch_a<B, false, false, 0>(A, nsplit, grid, lds, s, tasks_dev, count, single, ws);       \
     } while (0)
     if (bits == 2) AQ_GO(2);
     else if (bits == 3) AQ_GO(3);

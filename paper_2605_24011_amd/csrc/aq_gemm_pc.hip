@@ -284,8 +284,7 @@ hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask&
 #define AQ_PC(B)                                                                                                \
     do {                                                                                                        \
         auto k = two_level ? qgemm_pc_kernel<B, 1> : qgemm_pc_kernel<B, 0>;                                     \
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                  (int)lds);                                                                    \
+        if (aqk_allow_lds(reinterpret_cast<const void*>(k), lds) != hipSuccess) return hipErrorInvalidValue;    \
         hipLaunchKernelGGL(k, grid, block, lds, s, tasks_dev, count, single, ws);                               \
     } while (0)
     if (bits == 2) AQ_PC(2);

@@ -111,11 +111,7 @@ void qgemv_mixed_kernel(const AqGemvTask* __restrict__ tasks, const int32_t* __r
 // staged digits + the zero record + (lone launches) the 4 wavefronts' partial sums
 size_t digit_lds_bytes(int lds_x) { return (size_t)lds_x + 64 + 4 * 2 * 16 * sizeof(float); }
 
-template <class Kern> hipError_t allow_lds(Kern k, size_t lds)
-{
-    if (lds <= 64 * 1024) return hipSuccess;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-}
+template <class Kern> hipError_t allow_lds(Kern k, size_t lds) { return aqk_allow_lds(reinterpret_cast<const void*>(k), lds); }
 
 }  // namespace
 

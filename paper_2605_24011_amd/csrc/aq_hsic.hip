@@ -4,7 +4,10 @@
 // The dense part is the Gram matrix A A^T of K samples x d features (2 K^2 d flop): fp32 on the matrix cores
 // (V_MFMA_F32_32X32X2_F32), one 128 x 128 tile of the K x K result per workgroup, 4 wavefronts of 64 x 64 each,
 // A staged through a double-buffered LDS 32 features at a time.  The kernel value follows in the epilogue from the squared norms:
-// ||a_i - a_j||^2 = r_i + r_j - 2 a_i.a_j (clamped at 0).  Everything after that is O(K^2) streaming in fp64:
+// ||a_i - a_j||^2 = r_i + r_j - 2 a_i.a_j (clamped at 0).  The kernel is translation invariant, and that identity
+// cancels badly when the samples share a large offset (r far above the distances): every sample is therefore taken
+// relative to sample 0, a_i - a_0, in the squared norms and in the staging of the product alike (no extra pass, no
+// extra memory).  Everything after that is O(K^2) streaming in fp64:
 // with a_i, b_i the row sums of K_A, K_B,
 //     tr(K_A C K_B C) = sum_ij [K_A]_ij [K_B]_ij - (2/K) sum_i a_i b_i + (1/K^2) (sum_i a_i)(sum_i b_i),
 // (C K_A C written out), so the centering matrix is never formed and no K x K product is needed.
@@ -40,7 +43,7 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// r[i] = sum_k A[i][k]^2, one wavefront per row
+// r[i] = sum_k (A[i][k] - A[0][k])^2, one wavefront per row
 __global__ __launch_bounds__(256) void sqnorm_kernel(const float* __restrict__ A, int64_t K, int64_t d, int64_t lda,
                                                      float* __restrict__ r)
 {
@@ -49,7 +52,7 @@ __global__ __launch_bounds__(256) void sqnorm_kernel(const float* __restrict__ A
     const int lane = threadIdx.x & 63;
     float s = 0.f;
     for (int64_t k = lane; k < d; k += 64) {
-        const float v = A[row * lda + k];
+        const float v = A[row * lda + k] - A[k];
         s = fmaf(v, v, s);
     }
 #pragma unroll
@@ -100,10 +103,11 @@ __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float*
     const int srow = tid / LPR, sk = (tid % LPR) * 4;
     const bool vec = (lda & 3) == 0;                         // rows start 16-byte aligned: whole quads in one load
     f32x4 nxA[NH][2], nxB[NH][2];                            // [row group][i / j block], two stages in flight
+    f32x4 rfA, rfB;                                          // sample 0's quad of the same stages: the common shift
     // No lane-dependent branches around the loads (a join after a divergent branch makes the compiler wait for every
     // load in flight): rows beyond K re-read row K - 1 (their results are never stored), and the choice between whole
     // quads and guarded single elements (last stage of a d that is not a multiple of 32, unaligned rows) is uniform.
-    auto fetch = [&](f32x4 (&nx)[NH][2], int64_t k0) {
+    auto fetch = [&](f32x4 (&nx)[NH][2], f32x4& rf, int64_t k0) {
         const int64_t k = k0 + sk;
         const float* p[NH][2];
 #pragma unroll
@@ -118,7 +122,13 @@ __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float*
             for (int h = 0; h < NH; ++h)
 #pragma unroll
                 for (int blk = 0; blk < 2; ++blk) nx[h][blk] = *reinterpret_cast<const f32x4*>(p[h][blk] + k);
+            rf = *reinterpret_cast<const f32x4*>(A + k);
         } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float x = A[k + e < d ? k + e : 0];
+                rf[e] = k + e < d ? x : 0.f;
+            }
 #pragma unroll
             for (int h = 0; h < NH; ++h)
 #pragma unroll
@@ -133,11 +143,11 @@ __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float*
                 }
         }
     };
-    auto stash_piece = [&](float* buf, const f32x4 (&nx)[NH][2], int g) {    // g = 0 .. KC / 2 - 1 = 4 NH - 1
+    auto stash_piece = [&](float* buf, const f32x4 (&nx)[NH][2], const f32x4& rf, int g) {    // g = 0 .. KC / 2 - 1 = 4 NH - 1
         const int h = g >> 2, blk = (g >> 1) & 1, e = 2 * (g & 1);
         float* dst = buf + (blk * GT + srow + (GT / NH) * h) * LROW + sk + e;
-        dst[0] = nx[h][blk][e];
-        dst[1] = nx[h][blk][e + 1];
+        dst[0] = nx[h][blk][e] - rf[e];
+        dst[1] = nx[h][blk][e + 1] - rf[e + 1];
     };
     // operand layout of the 32x32x2 MFMA: lane l supplies A[row l % 32][k l / 32] and B[k l / 32][column l % 32]
     const int lr = lane & 31, lk = lane >> 5;
@@ -147,11 +157,11 @@ __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float*
     if (stages <= 0) return;                                                // uniform
     // one stage: `cur` holds stage s + 1 (requested a stage ago) and goes to the other LDS buffer piece by piece,
     // `nxt` receives stage s + 2, stage s is multiplied out of its buffer
-    auto stage = [&](int64_t s, const f32x4 (&cur)[NH][2], f32x4 (&nxt)[NH][2]) {
+    auto stage = [&](int64_t s, const f32x4 (&cur)[NH][2], const f32x4& rcur, f32x4 (&nxt)[NH][2], f32x4& rnxt) {
         const float* buf = gl + (s & 1) * GSTAGE;
         float* other = gl + ((s + 1) & 1) * GSTAGE;          // read last during stage s - 1, before the barrier
         const bool more = s + 1 < stages;
-        if (s + 2 < stages) fetch(nxt, (first + s + 2) * KC);
+        if (s + 2 < stages) fetch(nxt, rnxt, (first + s + 2) * KC);
         const float* ti = buf + (wi * 64 + lr) * LROW + lk;
         const float* tj = buf + (GT + wj * 64 + lr) * LROW + lk;
         // operands of feature pair kk + 2 are requested before the four MFMAs of pair kk
@@ -165,7 +175,7 @@ __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float*
 #pragma unroll
                 for (int a = 0; a < 2; ++a) { fa[cb ^ 1][a] = ti[a * 32 * LROW + kk + 2]; fb[cb ^ 1][a] = tj[a * 32 * LROW + kk + 2]; }
             }
-            if (more) stash_piece(other, cur, kk >> 1);
+            if (more) stash_piece(other, cur, rcur, kk >> 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int a = 0; a < 2; ++a)
@@ -176,14 +186,14 @@ __global__ __launch_bounds__(256, AQ_GRAM_WGS) void gram_rbf_kernel(const float*
         }
         lds_barrier();                                       // stage s read by everyone, stage s + 1 in place
     };
-    fetch(nxB, first * KC);
+    fetch(nxB, rfB, first * KC);
 #pragma unroll
-    for (int g = 0; g < KC / 2; ++g) stash_piece(gl, nxB, g);
-    if (stages > 1) fetch(nxA, (first + 1) * KC);
+    for (int g = 0; g < KC / 2; ++g) stash_piece(gl, nxB, rfB, g);
+    if (stages > 1) fetch(nxA, rfA, (first + 1) * KC);
     lds_barrier();
     for (int64_t s = 0; s < stages; s += 2) {
-        stage(s, nxA, nxB);
-        if (s + 1 < stages) stage(s + 1, nxB, nxA);
+        stage(s, nxA, rfA, nxB, rfB);
+        if (s + 1 < stages) stage(s + 1, nxB, rfB, nxA, rfA);
     }
 
     // result layout: register v of lane l is row 8 * (v / 4) + 4 * (l / 32) + v % 4, column l % 32 of the 32 x 32 tile
@@ -322,11 +332,11 @@ hipError_t aqk_rbf_gram(const float* A, int64_t K, int64_t d, int64_t lda, float
     const dim3 grid((unsigned)ntiles, (unsigned)split);
     if (split == 1) {
         auto k = gram_rbf_kernel<false>;
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)GRAM_LDS);
+        (void)aqk_allow_lds(reinterpret_cast<const void*>(k), GRAM_LDS);
         hipLaunchKernelGGL(k, grid, dim3(256), GRAM_LDS, s, A, K, d, lda, sq, gamma, G, 0);
     } else {
         auto k = gram_rbf_kernel<true>;
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)GRAM_LDS);
+        (void)aqk_allow_lds(reinterpret_cast<const void*>(k), GRAM_LDS);
         hipLaunchKernelGGL(gram_tile_pass_kernel<false>, dim3((unsigned)ntiles), dim3(256), 0, s, K, sq, gamma, G);
         hipLaunchKernelGGL(k, grid, dim3(256), GRAM_LDS, s, A, K, d, lda, sq, gamma, G, (int)((stages + split - 1) / split));
         hipLaunchKernelGGL(gram_tile_pass_kernel<true>, dim3((unsigned)ntiles), dim3(256), 0, s, K, sq, gamma, G);

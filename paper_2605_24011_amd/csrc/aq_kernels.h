@@ -2,6 +2,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <map>
+#include <mutex>
+#include <utility>
 
 // One decode product y = x W^T as the kernels see it (device-visible, 64 bytes).
 struct AqGemvTask {
@@ -18,6 +21,24 @@ struct AqGemvTask {
     int64_t pad;
 };
 static_assert(sizeof(AqGemvTask) == 64, "AqGemvTask must stay 64 bytes");
+
+// Kernels that need more than the default 64 KiB of dynamic LDS must be told so once per device and kernel.  This
+// remembers what has been granted, so that the launch path makes the runtime call the first time only.
+inline hipError_t aqk_allow_lds(const void* kernel, size_t lds)
+{
+    if (lds <= 64 * 1024) return hipSuccess;
+    static std::mutex mu;
+    static std::map<std::pair<int, const void*>, size_t> granted;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    size_t& have = granted[std::make_pair(dev, kernel)];
+    if (have >= lds) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) have = lds;
+    return e;
+}
 
 hipError_t aqk_pack(const uint8_t* codes, const uint16_t* scales, int64_t N, int64_t K, int bits,
                     void* blob, hipStream_t s);
@@ -110,6 +131,10 @@ hipError_t aqk_gemm_small(const AqGemmTask* tasks_dev, int count, const AqGemmTa
 // Prefill, fp16-weight mode, prefill-sized M: producer / consumer wavefronts (aq_gemm_pc.hip).  Reads the binary16
 // Xt + rowexp that aqk_retile writes; a task's wg_count = aqk_gemm_pc_wg_count (128-row groups x blocks of 320 rows).
 int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs);
+// exact products for blobs of the two-level variant (aq_gemm2.hip); tasks as for aqk_gemm with nsplit = 1, X re-tiled
+// without conversion
+hipError_t aqk2_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int x_dtype, int A,
+                     int total_wgs, const void* workspace, hipStream_t s);
 hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int two_level,
                        int total_wgs, const void* workspace, hipStream_t s);
 

@@ -61,7 +61,8 @@ int main()
             CHECK(aq_qgemm_batch_plan(d.data(), count, 32, flags, plan, bytes) == AQ_OK);
             CHECK(aq_qgemm_batch_workspace_size(plan) > 0);
         }
-        CHECK(aq2_qgemm_batch_plan(d.data(), count, 32, plan, bytes) == AQ_OK);
+        CHECK(aq2_qgemm_batch_plan(d.data(), count, 32, AQ_GEMM_EXACT, plan, bytes) == AQ_OK);
+        CHECK(aq2_qgemm_batch_plan(d.data(), count, 32, AQ_GEMM_FAST, plan, bytes) == AQ_OK);
         CHECK(aq_qgemm_batch_plan(d.data(), count, 32, 7, plan, bytes) == AQ_EINVAL);
         CHECK(aq_qgemm_batch_plan(d.data(), count, 32, AQ_GEMM_EXACT, plan, bytes - 1) == AQ_ESIZE);
         CHECK(aq_qgemm_batch(plan, nullptr, nullptr, 0, nullptr) == AQ_ENULL);

@@ -267,21 +267,29 @@ def test_two_level_variant_validation_without_a_gpu(L):
     assert L.aq2_qgemm(A, 64, 512, 4, 32, A, 0, 512, aq.AQ_F16, A, 64, A, ws, None) == aq.AQ_EINVAL
     assert L.aq2_qgemm(A, 64, 512, 4, 32, A, 40, 500, aq.AQ_F16, A, 64, A, ws, None) == aq.AQ_EINVAL     # ldx < K
     assert L.aq2_qgemm(A + 4, 64, 512, 4, 32, A, 40, 512, aq.AQ_F16, A, 64, A, ws, None) == aq.AQ_EALIGN
-    # planning launches nothing; the plan is marked two-level and takes the producer / consumer kernel at any M
+    assert L.aq2_qgemm_fast(A, 64, 512, 4, 32, A, 40, 512, aq.AQ_F16, A, 64, A, ws - 1, None) == aq.AQ_ESIZE
+    assert L.aq2_qgemm_fast(A, 64, 512, 7, 32, A, 40, 512, aq.AQ_F16, A, 64, A, ws, None) == aq.AQ_EINVAL
+    # planning launches nothing; the plan is marked two-level; its fp16-weight mode takes the producer / consumer
+    # kernel at any M, its exact mode the 8-wavefront kernel
     gd = (aq.aq_gemm_desc * 2)()
     for d, (N, K, b, M) in zip(gd, [(256, 1024, 2, 5), (128, 512, 3, 300)]):
         d.packed, d.X, d.Y, d.N, d.K, d.M, d.ldx, d.ldy, d.bits, d.x_dtype = A, A, A, N, K, M, K, N, b, aq.AQ_BF16
     size = L.aq_qgemm_batch_plan_size(2)
     buf = (ctypes.c_uint8 * size)()
-    assert L.aq2_qgemm_batch_plan(gd, 2, 32, buf, size) == aq.AQ_OK
+    assert L.aq2_qgemm_batch_plan(gd, 2, 32, aq.AQ_GEMM_FAST, buf, size) == aq.AQ_OK
     head = np.frombuffer(bytes(buf[:64]), dtype=np.int32)
     assert head[1] == 2 and head[2] == 0 and head[11] == 1 and head[12] == 0 and head[13] == 1 and head[14] == 1
+    assert L.aq2_qgemm_batch_plan(gd, 2, 32, aq.AQ_GEMM_EXACT, buf, size) == aq.AQ_OK
+    head = np.frombuffer(bytes(buf[:64]), dtype=np.int32)
+    assert head[11] == 0 and head[12] == 0 and head[13] == 0 and head[14] == 1       # exact, not small, not pc, two-level
+    assert L.aq_qgemm_batch_workspace_size(buf) > 0
+    assert L.aq2_qgemm_batch_plan(gd, 2, 32, 5, buf, size) == aq.AQ_EINVAL
     assert L.aq_qgemm_batch_workspace_size(buf) > 0
     assert L.aq_qgemm_batch_plan(gd, 2, 32, aq.AQ_GEMM_FAST, buf, size) == aq.AQ_OK
     assert np.frombuffer(bytes(buf[:64]), dtype=np.int32)[14] == 0
-    assert L.aq2_qgemm_batch_plan(gd, 2, 32, buf, size - 1) == aq.AQ_ESIZE
+    assert L.aq2_qgemm_batch_plan(gd, 2, 32, aq.AQ_GEMM_FAST, buf, size - 1) == aq.AQ_ESIZE
     gd[0].M = 0
-    assert L.aq2_qgemm_batch_plan(gd, 2, 32, buf, size) == aq.AQ_EINVAL
+    assert L.aq2_qgemm_batch_plan(gd, 2, 32, aq.AQ_GEMM_EXACT, buf, size) == aq.AQ_EINVAL
 
 
 def test_hsic_validation_without_a_gpu(L):

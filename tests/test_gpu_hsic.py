@@ -36,6 +36,34 @@ def test_rbf_gram_matches_oracle(gpu, ho, K, d):
     assert np.array_equal(np.diag(G), np.ones(K))
 
 
+@pytest.mark.parametrize("K,d,offset", [(130, 40, 20.0), (257, 1000, 20.0), (300, 129, -300.0)])
+def test_rbf_gram_with_a_common_offset_on_every_feature(gpu, ho, K, d, offset):
+    """Activations share a mean offset; the kernel depends on differences only.  r_i + r_j - 2 a_i.a_j on the raw
+    samples would lose about eps * d * offset^2 of the squared distance (1000 features at +20: 0.05 absolute, against
+    distances of order d); relative to sample 0 the offset is gone before anything is squared."""
+    torch, aq = gpu
+    X, _, _ = wl.draw_hsic_inputs(K, d, 4, 2, 95, K, d)
+    gamma = ho.median_gamma(X)
+    Xo = (X + np.float32(offset)).astype(np.float32)
+    G = aq.aq_rbf_gram(torch.from_numpy(Xo).cuda(), gamma).cpu().numpy().astype(np.float64)
+    want = ho.rbf_gram(Xo.astype(np.float64), gamma)          # the oracle on the very floats the GPU was given
+    assert np.abs(G - want).max() <= 2e-5
+    assert np.array_equal(np.diag(G), np.ones(K))
+
+
+def test_sensitivity_with_offsets(gpu, ho):
+    torch, aq = gpu
+    K = 200
+    X, Z, Y = wl.draw_hsic_inputs(K, 96, 64, 7, 96, K)
+    gx, gz, gy = ho.median_gamma(X), ho.median_gamma(Z), ho.median_gamma(Y)
+    Xo, Zo = (X + np.float32(20.0)).astype(np.float32), (Z - np.float32(35.0)).astype(np.float32)
+    out = aq.aq_hsic_sensitivity(torch.from_numpy(Xo).cuda(), gx, torch.from_numpy(Zo).cuda(), gz,
+                                 torch.from_numpy(Y).cuda(), gy, 0.5, 3.0).cpu().numpy()
+    h_xz, h_zy = ho.hsic(Xo.astype(np.float64), gx, Zo.astype(np.float64), gz), ho.hsic(Zo.astype(np.float64), gz, Y, gy)
+    assert abs(out[0] - h_xz) <= 1e-4 * abs(h_xz) + 1e-9
+    assert abs(out[1] - h_zy) <= 1e-4 * abs(h_zy) + 1e-9
+
+
 @pytest.mark.parametrize("K,dx,dz,dy", [(2, 1, 1, 1), (64, 32, 48, 7), (200, 96, 64, 7), (513, 300, 260, 14),
                                         (1500, 160, 224, 7)])      # 12 x 12 tiles, fp64 reductions over many workgroups
 def test_sensitivity_matches_oracle(gpu, ho, K, dx, dz, dy):
