@@ -299,6 +299,26 @@ def draw_hsic_inputs(K: int, d_in: int, d_out: int, d_act: int, *key: int, noise
 
 
 # ----------------------------------------------------------------------------
+# non-uniform codebook variant of the format: tables of 2^bits levels
+def draw_levels(kind: str, bits: int, *key: int) -> np.ndarray:
+    """float32 [2^bits].  'quantile': the standard normal's quantiles at (q + 1/2) / 2^bits (dense near zero, the shape
+    of tables fitted to bell-shaped weights); 'random': seeded N(0, 1) draws in no order (with a repeated value);
+    'dyadic': seeded multiples of 1/8 in [-5, 5] (exact arithmetic); 'uniform': q - 2^(bits-1), the base format."""
+    n = 1 << bits
+    if kind == "quantile":
+        from scipy.stats import norm
+        return norm.ppf((np.arange(n) + 0.5) / n).astype(np.float32)
+    if kind == "random":
+        t = _rng(31, bits, *key).normal(size=n).astype(np.float32)
+        t[n - 1] = t[0]
+        return t
+    if kind == "dyadic":
+        return (_rng(32, bits, *key).integers(-40, 41, size=n) / 8.0).astype(np.float32)
+    if kind == "uniform":
+        return (np.arange(n) - n // 2).astype(np.float32)
+    raise ValueError(kind)
+
+
 # two-level variant of the format: 4-bit scale and offset codes per block, two fp16 numbers per super-block
 # ----------------------------------------------------------------------------
 def draw_affine_params(N: int, K: int, bits: int, *key: int) -> Tuple[np.ndarray, np.ndarray]:

@@ -257,6 +257,47 @@ int aq2_qgemm_batch_plan(const aq_gemm_desc* descs /*HOST*/, int count, int bloc
 int aq2_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, uint8_t* codes_u8, void* stream);
 int aq2_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int block, float* W, void* stream);
 
+/* Non-uniform codebook variant of the format (Section 3, "Weight quantization": the codes of a format come from a
+ * format-specific codebook of representable values, uniform or non-uniform): a block of 32 consecutive weights of a
+ * row has one binary16 scale d, and a code q of `bits` bits selects one of 2^bits levels of a table that belongs to
+ * the matrix,
+ *         w_hat[n][k] = d[n][k/32] * levels[q[n][k]].
+ * The base format is the table levels[q] = q - 2^(bits-1).  `levels` is a HOST array of 2^bits finite floats; the
+ * caller passes the SAME table to aqc_pack_weights and to every later call on that blob (the blob does not carry it).
+ * Canonical inputs of aqc_pack_weights: codes and scales as for aq_pack_weights; the blob has aq_packed_size(N, K,
+ * bits, block) bytes and the base format's layout.
+ * How a table reaches the matrix cores (aqc_table_info reports it; results do not depend on it beyond fp32 rounding):
+ *   native = 1  (bits = 4 and levels = alpha * the sixteen E2M1 numbers 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives,
+ *               in any order, each to within float rounding): the codes are re-numbered at packing so that a stored
+ *               nibble is the fp4 bit pattern of its level, and the decode kernel multiplies the stored words as they are;
+ *   native = 0  (any other table): the table is written as a multilinear polynomial of the code's bits,
+ *               levels[q] = sum over subsets S of the bit positions set in q of coef[S], and the kernel runs one
+ *               one-bit plane per non-empty S (3 / 7 / 15 planes for 2 / 3 / 4 bits: 4-bit tables other than E2M1 are slow).
+ * aqc_table_info: native (HOST int, may be NULL), coef (HOST float[16], may be NULL: the coefficients indexed by S,
+ *   coef[0] the constant term; for a native table coef[0] = alpha and the rest is 0).
+ * aqc_qgemv / aqc_unpack_codes / aqc_dequant_f32 are aq_qgemv / aq_unpack_codes / aq_dequant_f32 for such a blob
+ * (aqc_unpack_codes returns the caller's codes, whatever the stored numbering).  A list of products runs in one launch:
+ * aqc_qgemv_batch_plan_size / aqc_qgemv_batch_plan (HOST) / copy the image to 16-byte-aligned DEVICE memory /
+ * aqc_qgemv_batch, as for aq_qgemv_batch; the tables are read when the plan is made.  K has no upper limit here
+ * beyond 2^24.  There is no prefill entry point for this variant.  Arguments, ownership and errors otherwise as for the
+ * base functions; AQ_EINVAL also for a table with an infinity or a NaN. */
+typedef struct aqc_gemv_desc {
+    aq_gemv_desc product;  /* packed: a blob from aqc_pack_weights */
+    const float* levels;   /* HOST float [2^bits] */
+} aqc_gemv_desc;
+int aqc_table_info(const float* levels /*HOST*/, int bits, int* native /*HOST*/, float* coef /*HOST*/);
+int aqc_pack_weights(const uint8_t* codes, const uint16_t* scales, const float* levels /*HOST*/, int64_t N, int64_t K,
+                     int bits, int block, void* packed, size_t packed_bytes, void* stream);
+int aqc_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, const float* levels /*HOST*/,
+              const void* x, int x_dtype, float* y, void* stream);
+size_t aqc_qgemv_batch_plan_size(const aqc_gemv_desc* descs /*HOST*/, int count, int block);
+int aqc_qgemv_batch_plan(const aqc_gemv_desc* descs /*HOST*/, int count, int block, void* plan_host, size_t plan_bytes);
+int aqc_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
+int aqc_unpack_codes(const void* packed, int64_t N, int64_t K, int bits, int block, const float* levels /*HOST*/,
+                     uint8_t* codes_u8, void* stream);
+int aqc_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int block, const float* levels /*HOST*/,
+                    float* W, void* stream);
+
 /* One decode step (M = 1) through a stack of transformer blocks, layer by layer, with what sits between the
  * matrices fused into the matrix-vector kernels.  Section 3 ("Vision-Language-Action models") names a block's
  * matrices: the attention projections W_Q, W_K, W_V, W_O and the MLP's W_gate, W_up, W_down; the rest is the

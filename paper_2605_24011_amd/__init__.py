@@ -37,6 +37,10 @@ class aq_gemv_desc(ctypes.Structure):
                 ("bits", ctypes.c_int32), ("x_dtype", ctypes.c_int32)]
 
 
+class aqc_gemv_desc(ctypes.Structure):
+    _fields_ = [("product", aq_gemv_desc), ("levels", _p)]
+
+
 class aq_block_shape(ctypes.Structure):
     _fields_ = [("d_model", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("d_ff", ctypes.c_int32), ("act", ctypes.c_int32), ("eps", ctypes.c_float)]
@@ -100,6 +104,16 @@ def lib() -> ctypes.CDLL:
         L.aq2_qgemm_batch_plan.argtypes = [ctypes.POINTER(aq_gemm_desc), _int, _int, _int, _p, _sz]
         L.aq2_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
         L.aq2_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _p, _p]
+        _pf = ctypes.POINTER(ctypes.c_float)
+        L.aqc_table_info.argtypes = [_pf, _int, ctypes.POINTER(ctypes.c_int), _pf]
+        L.aqc_pack_weights.argtypes = [_p, _p, _pf, _i64, _i64, _int, _int, _p, _sz, _p]
+        L.aqc_qgemv.argtypes = [_p, _i64, _i64, _int, _int, _pf, _p, _int, _p, _p]
+        L.aqc_qgemv_batch_plan_size.restype = _sz
+        L.aqc_qgemv_batch_plan_size.argtypes = [ctypes.POINTER(aqc_gemv_desc), _int, _int]
+        L.aqc_qgemv_batch_plan.argtypes = [ctypes.POINTER(aqc_gemv_desc), _int, _int, _p, _sz]
+        L.aqc_qgemv_batch.argtypes = [_p, _p, _p]
+        L.aqc_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _pf, _p, _p]
+        L.aqc_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _pf, _p, _p]
         L.aq_hsic_workspace_size.restype = _sz
         L.aq_hsic_workspace_size.argtypes = [_i64]
         L.aq_rbf_gram.argtypes = [_p, _i64, _i64, _i64, ctypes.c_float, _p, _p, _sz, _p]
@@ -399,6 +413,85 @@ def aq2_dequant_f32(packed, N: int, K: int, bits: int, block: int = BLOCK, strea
     out = torch.empty((N, K), dtype=torch.float32, device=packed.device)
     _check(lib().aq2_dequant_f32(packed.data_ptr(), N, K, bits, block, out.data_ptr(), _stream(stream)),
            "aq2_dequant_f32")
+    return out
+
+
+# ---- non-uniform codebook variant of the format ----
+def _levels(levels, bits: int):
+    vals = [float(v) for v in levels]
+    if len(vals) != (1 << bits):
+        raise AqError(AQ_EINVAL, "levels")
+    return (ctypes.c_float * len(vals))(*vals)
+
+
+def aqc_table_info(levels, bits: int):
+    """-> (native: bool, coef: list of 16 floats); see aq.h."""
+    native = ctypes.c_int(0)
+    coef = (ctypes.c_float * 16)()
+    _check(lib().aqc_table_info(_levels(levels, bits), bits, ctypes.byref(native), coef), "aqc_table_info")
+    return bool(native.value), list(coef)
+
+
+def aqc_pack_weights(codes, scales, levels, N: int, K: int, bits: int, block: int = BLOCK, stream=None):
+    import torch
+    size = aq_packed_size(N, K, bits, block)
+    if size == 0:
+        raise AqError(AQ_EINVAL, "aq_packed_size")
+    packed = torch.empty(size, dtype=torch.uint8, device=codes.device)
+    _check(lib().aqc_pack_weights(codes.data_ptr(), scales.data_ptr(), _levels(levels, bits), N, K, bits, block,
+                                  packed.data_ptr(), size, _stream(stream)), "aqc_pack_weights")
+    return packed
+
+
+def aqc_qgemv(packed, N: int, K: int, bits: int, levels, x, y=None, block: int = BLOCK, stream=None):
+    """x: cuda float16/bfloat16 [K] -> y: cuda float32 [N], the blob packed with aqc_pack_weights and the same levels."""
+    import torch
+    if y is None:
+        y = torch.empty(N, dtype=torch.float32, device=x.device)
+    _check(lib().aqc_qgemv(packed.data_ptr(), N, K, bits, block, _levels(levels, bits), x.data_ptr(), _dtype_code(x),
+                           y.data_ptr(), _stream(stream)), "aqc_qgemv")
+    return y
+
+
+class CbGemvBatch:
+    """A planned stream of decode products over codebook blobs (one launch).  Holds references to every tensor."""
+
+    def __init__(self, items: Sequence[tuple], block: int = BLOCK):
+        """items: (packed, N, K, bits, levels, x, y) per matrix."""
+        import torch
+        n = len(items)
+        descs = (aqc_gemv_desc * n)()
+        self._tables = []
+        for d, (packed, N, K, bits, levels, x, y) in zip(descs, items):
+            d.product.packed, d.product.x, d.product.y = packed.data_ptr(), x.data_ptr(), y.data_ptr()
+            d.product.N, d.product.K, d.product.bits, d.product.x_dtype = N, K, bits, _dtype_code(x)
+            tab = _levels(levels, bits)
+            self._tables.append(tab)
+            d.levels = ctypes.cast(tab, _p)
+        size = int(lib().aqc_qgemv_batch_plan_size(descs, n, block))
+        self.plan_host = torch.empty(max(size, 64), dtype=torch.uint8)
+        _check(lib().aqc_qgemv_batch_plan(descs, n, block, self.plan_host.data_ptr(), size), "aqc_qgemv_batch_plan")
+        self.plan_dev = self.plan_host.to(items[0][0].device)
+        self.items = list(items)
+
+    def run(self, stream=None) -> None:
+        _check(lib().aqc_qgemv_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), _stream(stream)),
+               "aqc_qgemv_batch")
+
+
+def aqc_unpack_codes(packed, N: int, K: int, bits: int, levels, block: int = BLOCK, stream=None):
+    import torch
+    out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(lib().aqc_unpack_codes(packed.data_ptr(), N, K, bits, block, _levels(levels, bits), out.data_ptr(),
+                                  _stream(stream)), "aqc_unpack_codes")
+    return out
+
+
+def aqc_dequant_f32(packed, N: int, K: int, bits: int, levels, block: int = BLOCK, stream=None):
+    import torch
+    out = torch.empty((N, K), dtype=torch.float32, device=packed.device)
+    _check(lib().aqc_dequant_f32(packed.data_ptr(), N, K, bits, block, _levels(levels, bits), out.data_ptr(),
+                                 _stream(stream)), "aqc_dequant_f32")
     return out
 
 

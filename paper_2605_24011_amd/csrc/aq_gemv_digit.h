@@ -78,11 +78,13 @@ __device__ __forceinline__ StageLoad stage_load(const uint16_t* x, int K, int bl
 // +-7.5): digit 0 = fp6(x / 2^(e-1)) with 2^e <= max|x| < 2^(e+1), so |x| / 2^(e-1) < 4; the residual x - digit is exact
 // in binary16, at most 1/8 of the scale, and is converted again at a scale 16 times smaller; four rounds leave a
 // residual below 2^-17 of the block's largest magnitude.  Digits are signed (a residual can have either sign).
+// `z`: the constant the block's sum is multiplied by (negated) for digit 0's C operand: the zero point 2^(BITS-1) of the
+// base format; the codebook variant passes minus its table's constant term.
 template <int BITS>
-__device__ __forceinline__ void stage_convert(const StageLoad& ld, int x_dtype, int nblk, uint8_t* xl, int it)
+__device__ __forceinline__ void stage_convert(const StageLoad& ld, int x_dtype, int nblk, uint8_t* xl, int it,
+                                              const float z = (float)(1 << (BITS - 1)))
 {
     if (it >= nblk) return;
-    const float z = (float)(1 << (BITS - 1));
     uint32_t w[16];
 #pragma unroll
     for (int i = 0; i < 4; ++i) { w[4 * i] = ld.v[i].x; w[4 * i + 1] = ld.v[i].y; w[4 * i + 2] = ld.v[i].z; w[4 * i + 3] = ld.v[i].w; }
@@ -166,11 +168,12 @@ __device__ __forceinline__ void stage_convert(const StageLoad& ld, int x_dtype, 
 // Stage the blocks [blk0, blk0 + nblk) of x (blocks at or beyond K/32 are zero) into `xl`, one block per thread, `T`
 // threads with indices tid = 0 .. T-1.  The caller orders the LDS writes against the later reads (barrier).
 template <int BITS, int T>
-__device__ __forceinline__ void stage_digits(const uint16_t* x, int x_dtype, int K, int blk0, int nblk, uint8_t* xl, int tid)
+__device__ __forceinline__ void stage_digits(const uint16_t* x, int x_dtype, int K, int blk0, int nblk, uint8_t* xl, int tid,
+                                             const float z = (float)(1 << (BITS - 1)))
 {
     for (int it = tid; it < nblk; it += T) {
         const StageLoad ld = stage_load(x, K, blk0, nblk, it);
-        stage_convert<BITS>(ld, x_dtype, nblk, xl, it);
+        stage_convert<BITS>(ld, x_dtype, nblk, xl, it, z);
     }
 }
 

@@ -22,6 +22,18 @@ struct AqGemvTask {
 };
 static_assert(sizeof(AqGemvTask) == 64, "AqGemvTask must stay 64 bytes");
 
+// A decode product of the non-uniform codebook variant (device-visible, 192 bytes): the base record, then how the
+// table reaches the matrix cores.  native: the stored nibbles are fp4 bit patterns and alpha scales the result;
+// else coef[S] is the coefficient of the monomial of the code bits in S (coef[0]: the constant term) and alpha is 1.
+struct AqCbTask {
+    AqGemvTask g;
+    float coef[16];
+    float alpha;
+    int32_t native;
+    int32_t pad[14];
+};
+static_assert(sizeof(AqCbTask) == 192, "AqCbTask must stay 192 bytes");
+
 // Kernels that need more than the default 64 KiB of dynamic LDS must be told so once per device and kernel.  This
 // remembers what has been granted, so that the launch path makes the runtime call the first time only.
 inline hipError_t aqk_allow_lds(const void* kernel, size_t lds)
@@ -60,6 +72,19 @@ int aqk_gemv_wg_count(int64_t N, int tiles_per_wg);
 
 // Two-level variant of the format (layout in aq_layout.h): same contracts as the three functions and the decode
 // launcher above, other blobs.
+// ---- non-uniform codebook variant (aq_gemv_cb.hip; blobs in the base layout) ----
+// remap: sixteen nibbles, stored code of canonical code q = (remap >> 4q) & 15 (identity: 0xFEDCBA9876543210)
+hipError_t aqk_pack_remap(const uint8_t* codes, const uint16_t* scales, int64_t N, int64_t K, int bits, uint64_t remap,
+                          void* blob, hipStream_t s);
+struct AqCbTable { float level[16]; };      // level of every STORED code
+hipError_t aqk_cb_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, uint64_t inverse_remap, uint8_t* out,
+                               hipStream_t s);
+hipError_t aqk_cb_dequant(const void* blob, int64_t N, int64_t K, int bits, const AqCbTable& stored_levels, float* out,
+                          hipStream_t s);
+void aqk_cb_gemv_shape(AqCbTask& t);
+hipError_t aqk_cb_gemv(const AqCbTask* tasks_dev, const int32_t* wg_task, int count, const AqCbTask& single, int mode,
+                       int total_wgs, int max_K, hipStream_t s);      // mode: 1 native, 2 / 3 / 4 planes at that width, 0 mixed
+
 hipError_t aqk2_pack(const uint8_t* codes, const uint8_t* sub, const uint16_t* sup, int64_t N, int64_t K, int bits,
                      void* blob, hipStream_t s);
 hipError_t aqk2_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, uint8_t* out, hipStream_t s);

@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ c
                                                    const uint16_t* __restrict__ scales,
                                                    int64_t N, int64_t K, int bits,
                                                    uint8_t* __restrict__ blob, int64_t n_units,
-                                                   uint32_t* __restrict__ trailer)
+                                                   uint32_t* __restrict__ trailer, uint64_t remap)
 {
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t unit = gid >> 6;
@@ -42,7 +42,8 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint8_t* __restrict__ c
         int64_t j = chunk * AQ_CHUNK_BLOCKS + 2 * g + blk;
         if (row < N && j < nb) {
             const uint8_t* src = codes + (row * nb + j) * (4 * bits);
-            for (int e = 0; e < 32; ++e) aq_block_put(w, bits, e, canon_code(src, bits, e));
+            for (int e = 0; e < 32; ++e)
+                aq_block_put(w, bits, e, (uint32_t)(remap >> (4 * canon_code(src, bits, e))) & 15u);
         }
         for (int h = 0; h < bits; ++h)
             *reinterpret_cast<uint32_t*>(u + aq_word_offset(bits, l, blk * bits + h)) = w[h];
@@ -72,11 +73,12 @@ __global__ void clear_trailer_kernel(uint32_t* trailer)
     if (threadIdx.x < AQ_TRAILER_BYTES / 4) trailer[threadIdx.x] = 0u;
 }
 
-// one thread per (row, block): writes 32 codes or 32 dequantised weights
-template <bool DEQUANT>
+// one thread per (row, block): writes 32 codes or 32 dequantised weights.  TABLE (codebook variant): a stored code c
+// is reported as (remap >> 4c) & 15 and dequantised as d * table.level[c]
+template <bool DEQUANT, bool TABLE = false>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ blob, int64_t N, int64_t K,
                                                      int bits, uint8_t* __restrict__ out_codes,
-                                                     float* __restrict__ out_w)
+                                                     float* __restrict__ out_w, uint64_t remap, AqCbTable table)
 {
     int64_t nb = K / AQ_BLOCK;
     int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -98,10 +100,13 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
         float d = __half2float(__ushort_as_half(sb));
         int z = 1 << (bits - 1);
         for (int e = 0; e < 32; ++e)
-            out_w[row * K + j * AQ_BLOCK + e] = d * (float)((int)aq_block_get(w, bits, e) - z);
+            out_w[row * K + j * AQ_BLOCK + e] = TABLE ? d * table.level[aq_block_get(w, bits, e)]
+                                                      : d * (float)((int)aq_block_get(w, bits, e) - z);
     } else {
-        for (int e = 0; e < 32; ++e)
-            out_codes[row * K + j * AQ_BLOCK + e] = (uint8_t)aq_block_get(w, bits, e);
+        for (int e = 0; e < 32; ++e) {
+            const uint32_t c = aq_block_get(w, bits, e);
+            out_codes[row * K + j * AQ_BLOCK + e] = TABLE ? (uint8_t)((remap >> (4 * c)) & 15u) : (uint8_t)c;
+        }
     }
 }
 
@@ -190,13 +195,37 @@ __global__ __launch_bounds__(256) void decode2_kernel(const uint8_t* __restrict_
 hipError_t aqk_pack(const uint8_t* codes, const uint16_t* scales, int64_t N, int64_t K, int bits,
                     void* blob, hipStream_t s)
 {
+    return aqk_pack_remap(codes, scales, N, K, bits, 0xFEDCBA9876543210ull, blob, s);
+}
+
+hipError_t aqk_pack_remap(const uint8_t* codes, const uint16_t* scales, int64_t N, int64_t K, int bits, uint64_t remap,
+                          void* blob, hipStream_t s)
+{
     int64_t n_units = aq_num_groups(N) * aq_num_chunks(K) * AQ_GROUP_TILES;
     int64_t threads = n_units * 64;
     unsigned grid = (unsigned)((threads + 255) / 256);
     uint32_t* trailer = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(blob) + aq_trailer_offset(N, K, bits));
     hipLaunchKernelGGL(clear_trailer_kernel, dim3(1), dim3(64), 0, s, trailer);
     hipLaunchKernelGGL(pack_kernel, dim3(grid), dim3(256), 0, s, codes, scales, N, K, bits,
-                       static_cast<uint8_t*>(blob), n_units, trailer);
+                       static_cast<uint8_t*>(blob), n_units, trailer, remap);
+    return hipGetLastError();
+}
+
+hipError_t aqk_cb_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, uint64_t inverse_remap, uint8_t* out,
+                               hipStream_t s)
+{
+    unsigned grid = (unsigned)((N * (K / AQ_BLOCK) + 255) / 256);
+    hipLaunchKernelGGL((decode_kernel<false, true>), dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(blob),
+                       N, K, bits, out, (float*)nullptr, inverse_remap, AqCbTable{});
+    return hipGetLastError();
+}
+
+hipError_t aqk_cb_dequant(const void* blob, int64_t N, int64_t K, int bits, const AqCbTable& stored_levels, float* out,
+                          hipStream_t s)
+{
+    unsigned grid = (unsigned)((N * (K / AQ_BLOCK) + 255) / 256);
+    hipLaunchKernelGGL((decode_kernel<true, true>), dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(blob),
+                       N, K, bits, (uint8_t*)nullptr, out, (uint64_t)0, stored_levels);
     return hipGetLastError();
 }
 
@@ -204,8 +233,8 @@ hipError_t aqk_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, ui
 {
     int64_t threads = N * (K / AQ_BLOCK);
     unsigned grid = (unsigned)((threads + 255) / 256);
-    hipLaunchKernelGGL(decode_kernel<false>, dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(blob),
-                       N, K, bits, out, (float*)nullptr);
+    hipLaunchKernelGGL((decode_kernel<false, false>), dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(blob),
+                       N, K, bits, out, (float*)nullptr, (uint64_t)0, AqCbTable{});
     return hipGetLastError();
 }
 
@@ -213,8 +242,8 @@ hipError_t aqk_dequant(const void* blob, int64_t N, int64_t K, int bits, float* 
 {
     int64_t threads = N * (K / AQ_BLOCK);
     unsigned grid = (unsigned)((threads + 255) / 256);
-    hipLaunchKernelGGL(decode_kernel<true>, dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(blob),
-                       N, K, bits, (uint8_t*)nullptr, out);
+    hipLaunchKernelGGL((decode_kernel<true, false>), dim3(grid), dim3(256), 0, s, static_cast<const uint8_t*>(blob),
+                       N, K, bits, (uint8_t*)nullptr, out, (uint64_t)0, AqCbTable{});
     return hipGetLastError();
 }
 

@@ -25,8 +25,9 @@ def L():
 
 def test_every_declared_symbol_is_exported(L):
     header = open(os.path.join(ROOT, "include", "aq.h")).read()
-    names = set(re.findall(r"\b(aq_[a-z0-9_]+)\s*\(", header))
-    assert {"aq_pack_weights", "aq_qgemv", "aq_qgemm", "aq_packed_size", "aq_qgemv_batch"} <= names
+    names = set(re.findall(r"\b(aq[2c]?_[a-z0-9_]+)\s*\(", header))
+    assert {"aq_pack_weights", "aq_qgemv", "aq_qgemm", "aq_packed_size", "aq_qgemv_batch", "aq2_qgemm", "aq2_qgemm_fast",
+            "aqc_qgemv", "aqc_table_info", "aqc_qgemv_batch"} <= names
     for n in names:
         assert hasattr(L, n), n
 
@@ -290,6 +291,65 @@ def test_two_level_variant_validation_without_a_gpu(L):
     assert L.aq2_qgemm_batch_plan(gd, 2, 32, aq.AQ_GEMM_FAST, buf, size - 1) == aq.AQ_ESIZE
     gd[0].M = 0
     assert L.aq2_qgemm_batch_plan(gd, 2, 32, aq.AQ_GEMM_EXACT, buf, size) == aq.AQ_EINVAL
+
+
+def test_codebook_variant_table_analysis_and_validation_without_a_gpu(L):
+    """The table analysis is host arithmetic: the multilinear coefficients must reproduce the table (sum of coef[S] over
+    the subsets S of a code's set bits), the E2M1 grid is recognised in any order and at any factor, and every
+    launching call below is rejected before anything is launched."""
+    import numpy as np
+    rng = np.random.default_rng(3)
+    for bits in (2, 3, 4):
+        n = 1 << bits
+        for T in (rng.normal(size=n), np.arange(n) - n / 2, rng.integers(-40, 41, size=n) / 8.0):
+            native, coef = aq.aqc_table_info(T.astype(np.float32), bits)
+            assert not native
+            rec = np.array([sum(coef[S] for S in range(n) if (S & q) == S) for q in range(n)])
+            assert np.abs(rec - T.astype(np.float32)).max() <= 1e-6 * max(1.0, np.abs(T).max())
+            if bits == 2:                       # closed form: a_0 = L0, a_1 = L1 - L0, a_2 = L2 - L0, a_3 = L3 - L2 - L1 + L0
+                Tf = T.astype(np.float32).astype(np.float64)
+                assert np.allclose(coef[:4], [Tf[0], Tf[1] - Tf[0], Tf[2] - Tf[0], Tf[3] - Tf[2] - Tf[1] + Tf[0]], atol=1e-6)
+    e2m1 = np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -0., -.5, -1, -1.5, -2, -3, -4, -6], dtype=np.float32)
+    for alpha in (1.0, 0.37, 1e-3, 4096.0):
+        native, coef = aq.aqc_table_info((e2m1 * np.float32(alpha))[rng.permutation(16)], 4)
+        assert native and abs(coef[0] - np.float32(alpha)) <= 1e-6 * alpha
+    assert not aq.aqc_table_info(np.abs(e2m1), 4)[0]                    # every magnitude twice: not a permutation
+    assert not aq.aqc_table_info(np.zeros(16, dtype=np.float32), 4)[0]
+    A = 1 << 20
+    lv = (ctypes.c_float * 4)(-1.5, -0.25, 0.25, 1.5)
+    bad = (ctypes.c_float * 4)(0.0, float("inf"), 1.0, 2.0)
+    assert L.aqc_table_info(lv, 5, None, None) == aq.AQ_EINVAL
+    assert L.aqc_table_info(None, 2, None, None) == aq.AQ_ENULL
+    assert L.aqc_table_info(bad, 2, None, None) == aq.AQ_EINVAL
+    assert L.aqc_pack_weights(A, A, lv, 16, 64, 2, 32, A, 10, None) == aq.AQ_ESIZE
+    assert L.aqc_pack_weights(A, A, None, 16, 64, 2, 32, A, 1 << 20, None) == aq.AQ_ENULL
+    assert L.aqc_pack_weights(A, A, bad, 16, 64, 2, 32, A, 1 << 20, None) == aq.AQ_EINVAL
+    assert L.aqc_qgemv(A, 16, 64, 2, 32, lv, A, 7, A, None) == aq.AQ_EDTYPE
+    assert L.aqc_qgemv(A, 16, 65, 2, 32, lv, A, aq.AQ_F16, A, None) == aq.AQ_EINVAL
+    assert L.aqc_qgemv(A + 8, 16, 64, 2, 32, lv, A, aq.AQ_F16, A, None) == aq.AQ_EALIGN
+    assert L.aqc_qgemv(A, 16, 64, 2, 32, lv, None, aq.AQ_F16, A, None) == aq.AQ_ENULL
+    assert L.aqc_unpack_codes(A, 16, 64, 2, 32, lv, None, None) == aq.AQ_ENULL
+    assert L.aqc_dequant_f32(A, 16, 64, 6, 32, lv, A, None) == aq.AQ_EINVAL
+    # list plans: made on the host, nothing launched
+    descs = (aq.aqc_gemv_desc * 2)()
+    lv4 = (ctypes.c_float * 16)(*[float(v) for v in e2m1])
+    for d, (N, K, b, tab) in zip(descs, [(256, 1024, 2, lv), (300, 11008, 4, lv4)]):
+        d.product.packed, d.product.x, d.product.y = A, A, A
+        d.product.N, d.product.K, d.product.bits, d.product.x_dtype = N, K, b, aq.AQ_BF16
+        d.levels = ctypes.cast(tab, ctypes.c_void_p)
+    size = L.aqc_qgemv_batch_plan_size(descs, 2, 32)
+    assert size == 64 + 2 * 192 + 16 * ((4 * (2 + 3) + 15) // 16)
+    buf = (ctypes.c_uint8 * size)()
+    assert L.aqc_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_OK
+    head = np.frombuffer(bytes(buf[:64]), dtype=np.int32)
+    assert head[1] == 2 and head[2] == 11008 and head[3] == 5 and head[4] == 0          # count, max K, workgroups, mixed
+    assert L.aqc_qgemv_batch_plan(descs, 2, 32, buf, size - 1) == aq.AQ_ESIZE
+    assert L.aqc_qgemv_batch(buf, None, None) == aq.AQ_ENULL
+    assert L.aqc_qgemv_batch(buf, A + 4, None) == aq.AQ_EALIGN
+    descs[1].levels = None
+    assert L.aqc_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_ENULL
+    zero = (ctypes.c_uint8 * size)()
+    assert L.aqc_qgemv_batch(zero, A, None) == aq.AQ_EINVAL
 
 
 def test_hsic_validation_without_a_gpu(L):
