@@ -533,6 +533,35 @@ def main():
             del items
         out["two_level_format"] = two
 
+    if not args.skip_two_level:
+        # the decode pass over the same shapes in the non-uniform codebook variant (w = d * levels[q], same bytes as the
+        # base format): normal-quantile tables at 2 and 3 bits (one-bit planes on the matrix cores), the E2M1 grid at 4
+        # bits (multiplied natively), and the seeded mixed allocation with those tables
+        from scipy.stats import norm
+        tabs = {b: [float(v) for v in norm.ppf((np.arange(1 << b) + 0.5) / (1 << b))] for b in (2, 3)}
+        tabs[4] = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0, -0.0, -0.5, -1.0, -1.5, -2.0, -3.0, -4.0, -6.0]
+        cbk = {"format": "w = d * levels[q]: quantile tables at 2 and 3 bits (planes), E2M1 at 4 bits (native)"}
+        for alloc in ("b2", "b3", "b4", "mixed"):
+            torch.cuda.empty_cache()
+            specs = wl.backbone_stream("llama2-7b", alloc)
+            items, nbytes = [], 0
+            for m in specs:
+                codes, scales = wl.draw_matrix_torch(m.N, m.K, m.bits, "cuda", 14, m.index)
+                packed = aq.aqc_pack_weights(codes, scales, tabs[m.bits], m.N, m.K, m.bits)
+                x = wl.draw_activations_torch(1, m.K, "bf16", "cuda", 14, m.index)[0].contiguous()
+                y = torch.empty(m.N, dtype=torch.float32, device="cuda")
+                items.append((packed, m.N, m.K, m.bits, tabs[m.bits], x, y))
+                nbytes += m.N * m.K * m.bits // 8 + m.N * (m.K // 32) * 2 + 2 * m.K + 4 * m.N
+                del codes, scales
+            bt = aq.CbGemvBatch(items)
+            d, w = time_launches(torch, bt.run, max(10, args.steps // 2), 3)
+            ms = sum(d) / len(d)
+            cbk[alloc] = {"bytes": nbytes, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                          "pct_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),
+                          "tokens_per_s": round(1e3 / ms, 1)}
+            del bt, items
+        out["codebook_format"] = cbk
+
     if not args.skip_hsic:
         # Eq. 5 for one weight matrix: K calibration samples of input hidden states, of the matrix's output hidden
         # states and of 7-dimensional action labels; the cost is the three Gram products (fp32 on the matrix cores)
