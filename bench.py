@@ -267,7 +267,7 @@ def main():
             its = build_stream(aq, wl, torch, sp, "f16", 20 + b)
             bt = aq.GemvBatch(its)
             nbytes = sum(gemv_bytes(m.N, m.K, m.bits) for m in sp)
-            d, w = time_launches(torch, bt.run, max(10, args.steps // 2), 3)
+            d, w = time_launches(torch, bt.run, max(20, args.steps), 10)
             ms = sum(d) / len(d)
             by_bits[str(b)] = {"GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
                                "pct_hbm_peak": round(100 * nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
@@ -285,7 +285,7 @@ def main():
         its = build_stream(aq, wl, torch, sp, "f16", 30)
         bt = aq.GemvBatch(its)
         nbytes = sum(gemv_bytes(m.N, m.K, m.bits) for m in sp)
-        d, w = time_launches(torch, bt.run, max(10, args.steps // 2), 3)
+        d, w = time_launches(torch, bt.run, max(20, args.steps), 10)
         ms = sum(d) / len(d)
         out["greedy_allocation"] = {
             "bits_histogram": {str(b): sum(1 for m in sp if m.bits == b) for b in (2, 3, 4)},
@@ -505,7 +505,7 @@ def main():
                 nbytes += m.N * m.K * m.bits // 8 + m.N * (m.K // 32) + m.N * ((m.K + 255) // 256) * 4 + 2 * m.K + 4 * m.N
                 del codes, sub, sup
             bt = aq.GemvBatch(items, two_level=True)
-            d, w = time_launches(torch, bt.run, max(10, args.steps // 2), 3)
+            d, w = time_launches(torch, bt.run, max(20, args.steps), 10)
             ms = sum(d) / len(d)
             weights = sum(m.N * m.K for m in specs)
             two[alloc] = {"stored_bits_per_weight": round(8.0 * sum(it[0].numel() for it in items) / weights, 4),
@@ -554,7 +554,7 @@ def main():
                 nbytes += m.N * m.K * m.bits // 8 + m.N * (m.K // 32) * 2 + 2 * m.K + 4 * m.N
                 del codes, scales
             bt = aq.CbGemvBatch(items)
-            d, w = time_launches(torch, bt.run, max(10, args.steps // 2), 3)
+            d, w = time_launches(torch, bt.run, max(20, args.steps), 10)
             ms = sum(d) / len(d)
             cbk[alloc] = {"bytes": nbytes, "ms": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
                           "pct_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS * 100, 2),

@@ -300,10 +300,9 @@ int aq_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, cons
                ? AQ_OK : AQ_ELAUNCH;
 }
 
-// workgroups of the list in the given format, -1 if a descriptor is invalid
-static int64_t gemv_list_wgs(const aq_gemv_desc* descs, int count, int block, int format, int* status)
+// workgroups of the list (both formats use the same launch shape), -1 if a descriptor is invalid
+static int64_t gemv_list_wgs(const aq_gemv_desc* descs, int count, int block, int* status)
 {
-    const int rt = aqk_gemv_tiles_per_wg(0, true);
     int64_t wgs = 0;
     for (int i = 0; i < count; ++i) {
         const aq_gemv_desc& d = descs[i];
@@ -312,13 +311,9 @@ static int64_t gemv_list_wgs(const aq_gemv_desc* descs, int count, int block, in
         if (rc == AQ_OK && (!d.packed || !d.x || !d.y)) rc = AQ_ENULL;
         if (rc == AQ_OK && (!aligned16(d.packed) || !aligned16(d.x) || !aligned16(d.y))) rc = AQ_EALIGN;
         if (rc != AQ_OK) { if (status) *status = rc; return -1; }
-        if (format == 1) {
-            wgs += aqk_gemv_wg_count(d.N, rt);
-        } else {
-            AqGemvTask t = make_task(d.packed, d.N, d.K, d.bits, d.x, d.x_dtype, d.y);
-            aqk_gemv_shape(t, true);
-            wgs += t.wg_count;
-        }
+        AqGemvTask t = make_task(d.packed, d.N, d.K, d.bits, d.x, d.x_dtype, d.y);
+        aqk_gemv_shape(t, true);
+        wgs += t.wg_count;
         if (wgs > 0x3FFFFFFF) { if (status) *status = AQ_EINVAL; return -1; }
     }
     return wgs;
@@ -332,19 +327,17 @@ static size_t gemv_plan_bytes(int count, int64_t wgs)
 size_t aq_qgemv_batch_plan_size(const aq_gemv_desc* descs, int count, int block)
 {
     if (count < 1 || !descs) return 0;
-    // the base format never needs fewer workgroups than the two-level variant: one size serves both planners
-    const int64_t a = gemv_list_wgs(descs, count, block, 0, nullptr), b = gemv_list_wgs(descs, count, block, 1, nullptr);
-    if (a < 0 || b < 0) return 0;
-    return gemv_plan_bytes(count, a > b ? a : b);
+    const int64_t wgs = gemv_list_wgs(descs, count, block, nullptr);      // one size serves both planners
+    if (wgs < 0) return 0;
+    return gemv_plan_bytes(count, wgs);
 }
 
 static int gemv_plan(const aq_gemv_desc* descs, int count, int block, void* plan_host, size_t plan_bytes, int format)
 {
     if (count < 1) return AQ_EINVAL;
     if (!descs || !plan_host) return AQ_ENULL;
-    const int rt = aqk_gemv_tiles_per_wg(0, true);
     int status = AQ_OK;
-    const int64_t wgs = gemv_list_wgs(descs, count, block, format, &status);
+    const int64_t wgs = gemv_list_wgs(descs, count, block, &status);
     if (wgs < 0) return status;
     if (plan_bytes < gemv_plan_bytes(count, wgs)) return AQ_ESIZE;
     int max_K = 0;
@@ -354,7 +347,7 @@ static int gemv_plan(const aq_gemv_desc* descs, int count, int block, void* plan
     std::memset(&h, 0, sizeof(h));
     h.magic = PLAN_MAGIC;
     h.count = count;
-    h.tiles_per_wg = rt;
+    h.tiles_per_wg = 8;
     h.max_K = max_K;
     h.format = format;
     AqGemvTask* tasks = reinterpret_cast<AqGemvTask*>(static_cast<uint8_t*>(plan_host) + sizeof(PlanHeader));
@@ -370,8 +363,7 @@ static int gemv_plan(const aq_gemv_desc* descs, int count, int block, void* plan
         if (d.bits != descs[0].bits) h.bits = 0;
         AqGemvTask t = make_task(d.packed, d.N, d.K, d.bits, d.x, d.x_dtype, d.y);
         t.wg_begin = begin;
-        if (format == 1) t.wg_count = aqk_gemv_wg_count(d.N, rt);
-        else aqk_gemv_shape(t, true);
+        aqk_gemv_shape(t, true);
         for (int w = 0; w < t.wg_count; ++w) wg_task[begin + w] = j;
         begin += t.wg_count;
         std::memcpy(&tasks[j], &t, sizeof(t));
@@ -418,10 +410,9 @@ int aq2_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, con
     if (!packed || !x || !y) return AQ_ENULL;
     if (!aligned16(packed) || !aligned16(x) || !aligned16(y)) return AQ_EALIGN;
     AqGemvTask t = make_task(packed, N, K, bits, x, x_dtype, y);
-    int rt = aqk_gemv_tiles_per_wg(N, false);
     t.wg_begin = 0;
-    t.wg_count = aqk_gemv_wg_count(N, rt);
-    return aqk2_gemv(nullptr, 0, t, bits, rt, t.wg_count, (int)K, static_cast<hipStream_t>(stream)) == hipSuccess
+    aqk_gemv_shape(t, false);
+    return aqk2_gemv(nullptr, nullptr, 0, t, bits, t.wg_count, (int)K, static_cast<hipStream_t>(stream)) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
 }
 
@@ -459,9 +450,9 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream)
     const AqGemvTask* tasks = reinterpret_cast<const AqGemvTask*>(dev + sizeof(PlanHeader));
     AqGemvTask none;
     std::memset(&none, 0, sizeof(none));
-    if (h.format == 1)
-        return aqk2_gemv(tasks, h.count, none, h.bits, h.tiles_per_wg, h.total_wgs, h.max_K, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     const int32_t* wg_task = reinterpret_cast<const int32_t*>(dev + sizeof(PlanHeader) + (size_t)h.count * sizeof(AqGemvTask));
+    if (h.format == 1)
+        return aqk2_gemv(tasks, wg_task, h.count, none, h.bits, h.total_wgs, h.max_K, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     return aqk_gemv(tasks, wg_task, h.count, none, h.bits, h.total_wgs, h.max_K, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
 }
 

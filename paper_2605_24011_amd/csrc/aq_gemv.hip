@@ -115,19 +115,6 @@ template <class Kern> hipError_t allow_lds(Kern k, size_t lds) { return aqk_allo
 
 }  // namespace
 
-// tiles per workgroup of the two-level variant's kernels: 8 (two per wavefront) in general, 4 for a lone small matrix
-// so that it spreads over more compute units
-int aqk_gemv_tiles_per_wg(int64_t N, bool batched)
-{
-    if (batched) return 8;
-    return N >= 128 * 1024 ? 8 : 4;
-}
-
-int aqk_gemv_wg_count(int64_t N, int tiles_per_wg)
-{
-    return (int)(aq_num_groups(N) * (AQ_GROUP_TILES / tiles_per_wg));
-}
-
 void aqk_gemv_shape(AqGemvTask& t, bool batched)
 {
     if (batched) t.wg_count = (int)aq_num_groups(t.N) * (AQ_GROUP_TILES / (WAVES * AQ_DG_TW));

@@ -79,10 +79,11 @@ __device__ __forceinline__ StageLoad stage_load(const uint16_t* x, int K, int bl
 // in binary16, at most 1/8 of the scale, and is converted again at a scale 16 times smaller; four rounds leave a
 // residual below 2^-17 of the block's largest magnitude.  Digits are signed (a residual can have either sign).
 // `z`: the constant the block's sum is multiplied by (negated) for digit 0's C operand: the zero point 2^(BITS-1) of the
-// base format; the codebook variant passes minus its table's constant term.
+// base format; the codebook variant passes minus its table's constant term.  `all_digits`: write that value into every
+// digit's record (the two-level variant reads it in all four lanes of a block).
 template <int BITS>
 __device__ __forceinline__ void stage_convert(const StageLoad& ld, int x_dtype, int nblk, uint8_t* xl, int it,
-                                              const float z = (float)(1 << (BITS - 1)))
+                                              const float z = (float)(1 << (BITS - 1)), const bool all_digits = false)
 {
     if (it >= nblk) return;
     uint32_t w[16];
@@ -160,7 +161,7 @@ __device__ __forceinline__ void stage_convert(const StageLoad& ld, int x_dtype, 
         const int sb = special ? 255 : 127 + e - 1 - 4 * j;
         *reinterpret_cast<u32x4*>(rec + 16) = u32x4{p[4], p[5], (uint32_t)sb, 0u};
         // the zero point of the whole block rides in digit 0's column: -z * (sum of the block)
-        const float cz = j == 0 ? -z * (x_dtype == 1 ? sum : ldexpf(sum, e)) : 0.f;
+        const float cz = (j == 0 || all_digits) ? -z * (x_dtype == 1 ? sum : ldexpf(sum, e)) : 0.f;
         *reinterpret_cast<float4v*>(rec + 32) = float4v{cz, cz, cz, cz};
     }
 }
@@ -169,11 +170,11 @@ __device__ __forceinline__ void stage_convert(const StageLoad& ld, int x_dtype, 
 // threads with indices tid = 0 .. T-1.  The caller orders the LDS writes against the later reads (barrier).
 template <int BITS, int T>
 __device__ __forceinline__ void stage_digits(const uint16_t* x, int x_dtype, int K, int blk0, int nblk, uint8_t* xl, int tid,
-                                             const float z = (float)(1 << (BITS - 1)))
+                                             const float z = (float)(1 << (BITS - 1)), const bool all_digits = false)
 {
     for (int it = tid; it < nblk; it += T) {
         const StageLoad ld = stage_load(x, K, blk0, nblk, it);
-        stage_convert<BITS>(ld, x_dtype, nblk, xl, it, z);
+        stage_convert<BITS>(ld, x_dtype, nblk, xl, it, z, all_digits);
     }
 }
 

@@ -66,9 +66,6 @@ void aqk_gemv_shape(AqGemvTask& t, bool batched);
 // bits: the common bit-width of the tasks, 0 if they differ.  max_K: over the tasks.
 hipError_t aqk_gemv(const AqGemvTask* tasks_dev, const int32_t* wg_task, int count, const AqGemvTask& single, int bits,
                     int total_wgs, int max_K, hipStream_t s);
-// The decode launcher of the two-level variant keeps whole-K workgroups of `tiles_per_wg` tiles.
-int aqk_gemv_tiles_per_wg(int64_t N, bool batched);
-int aqk_gemv_wg_count(int64_t N, int tiles_per_wg);
 
 // Two-level variant of the format (layout in aq_layout.h): same contracts as the three functions and the decode
 // launcher above, other blobs.
@@ -89,7 +86,7 @@ hipError_t aqk2_pack(const uint8_t* codes, const uint8_t* sub, const uint16_t* s
                      void* blob, hipStream_t s);
 hipError_t aqk2_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, uint8_t* out, hipStream_t s);
 hipError_t aqk2_dequant(const void* blob, int64_t N, int64_t K, int bits, float* out, hipStream_t s);
-hipError_t aqk2_gemv(const AqGemvTask* tasks_dev, int count, const AqGemvTask& single, int bits, int tiles_per_wg,
+hipError_t aqk2_gemv(const AqGemvTask* tasks_dev, const int32_t* wg_task, int count, const AqGemvTask& single, int bits,
                      int total_wgs, int max_K, hipStream_t s);
 
 // Prefill.  The activations are first re-tiled into the order the matrix cores read them ("Xt"):
