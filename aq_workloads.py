@@ -303,7 +303,8 @@ def draw_hsic_inputs(K: int, d_in: int, d_out: int, d_act: int, *key: int, noise
 def draw_levels(kind: str, bits: int, *key: int) -> np.ndarray:
     """float32 [2^bits].  'quantile': the standard normal's quantiles at (q + 1/2) / 2^bits (dense near zero, the shape
     of tables fitted to bell-shaped weights); 'random': seeded N(0, 1) draws in no order (with a repeated value);
-    'dyadic': seeded multiples of 1/8 in [-5, 5] (exact arithmetic); 'uniform': q - 2^(bits-1), the base format."""
+    'dyadic': seeded multiples of 1/8 in [-5, 5] (exact arithmetic); 'signed_dyadic': such multiples in pairs +v, -v;
+    'uniform': q - 2^(bits-1), the base format."""
     n = 1 << bits
     if kind == "quantile":
         from scipy.stats import norm
@@ -316,6 +317,11 @@ def draw_levels(kind: str, bits: int, *key: int) -> np.ndarray:
         return (_rng(32, bits, *key).integers(-40, 41, size=n) / 8.0).astype(np.float32)
     if kind == "uniform":
         return (np.arange(n) - n // 2).astype(np.float32)
+    if kind == "signed_dyadic":                  # pairs +v, -v of multiples of 1/8 (one pair of zeros), in no order
+        r = _rng(33, bits, *key)
+        mags = (r.integers(1, 41, size=n // 2) / 8.0).astype(np.float32)
+        mags[0] = 0.0
+        return np.concatenate([mags, -mags])[r.permutation(n)].astype(np.float32)
     raise ValueError(kind)
 
 

@@ -267,13 +267,17 @@ int aq2_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int bloc
  * Canonical inputs of aqc_pack_weights: codes and scales as for aq_pack_weights; the blob has aq_packed_size(N, K,
  * bits, block) bytes and the base format's layout.
  * How a table reaches the matrix cores (aqc_table_info reports it; results do not depend on it beyond fp32 rounding):
- *   native = 1  (bits = 4 and levels = alpha * the sixteen E2M1 numbers 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives,
- *               in any order, each to within float rounding): the codes are re-numbered at packing so that a stored
- *               nibble is the fp4 bit pattern of its level, and the decode kernel multiplies the stored words as they are;
- *   native = 0  (any other table): the table is written as a multilinear polynomial of the code's bits,
- *               levels[q] = sum over subsets S of the bit positions set in q of coef[S], and the kernel runs one
- *               one-bit plane per non-empty S (3 / 7 / 15 planes for 2 / 3 / 4 bits: 4-bit tables other than E2M1 are slow).
- * aqc_table_info: native (HOST int, may be NULL), coef (HOST float[16], may be NULL: the coefficients indexed by S,
+ *   AQC_FORM_NATIVE  (bits = 4 and levels = alpha * the sixteen E2M1 numbers 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their
+ *               negatives, in any order, each to within float rounding): the codes are re-numbered at packing so that a
+ *               stored nibble is the fp4 bit pattern of its level, and the decode kernel multiplies the stored words as
+ *               they are;
+ *   AQC_FORM_SIGNED  (the levels come in pairs +v, -v, zeros pairing with zeros): the codes are re-numbered to a sign
+ *               bit and the index m of the magnitude in ascending order; the magnitude table is written as a multilinear
+ *               polynomial of m's bits, mag[m] = sum over subsets S of the bits set in m of coef[S], and the kernel runs
+ *               one signed one-bit plane per S (2 / 4 / 8 planes for 2 / 3 / 4 bits);
+ *   AQC_FORM_PLANES  (any other table): levels[q] = sum over subsets S of the bits set in q of coef[S], one one-bit
+ *               plane per non-empty S (3 / 7 / 15 planes: 4-bit tables of this form are slow).
+ * aqc_table_info: form (HOST int, may be NULL), coef (HOST float[16], may be NULL: the coefficients indexed by S,
  *   coef[0] the constant term; for a native table coef[0] = alpha and the rest is 0).
  * aqc_qgemv / aqc_unpack_codes / aqc_dequant_f32 are aq_qgemv / aq_unpack_codes / aq_dequant_f32 for such a blob
  * (aqc_unpack_codes returns the caller's codes, whatever the stored numbering).  A list of products runs in one launch:
@@ -285,7 +289,10 @@ typedef struct aqc_gemv_desc {
     aq_gemv_desc product;  /* packed: a blob from aqc_pack_weights */
     const float* levels;   /* HOST float [2^bits] */
 } aqc_gemv_desc;
-int aqc_table_info(const float* levels /*HOST*/, int bits, int* native /*HOST*/, float* coef /*HOST*/);
+#define AQC_FORM_PLANES 0
+#define AQC_FORM_NATIVE 1
+#define AQC_FORM_SIGNED 2
+int aqc_table_info(const float* levels /*HOST*/, int bits, int* form /*HOST*/, float* coef /*HOST*/);
 int aqc_pack_weights(const uint8_t* codes, const uint16_t* scales, const float* levels /*HOST*/, int64_t N, int64_t K,
                      int bits, int block, void* packed, size_t packed_bytes, void* stream);
 int aqc_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, const float* levels /*HOST*/,

@@ -424,12 +424,15 @@ def _levels(levels, bits: int):
     return (ctypes.c_float * len(vals))(*vals)
 
 
+AQC_FORM_PLANES, AQC_FORM_NATIVE, AQC_FORM_SIGNED = 0, 1, 2
+
+
 def aqc_table_info(levels, bits: int):
-    """-> (native: bool, coef: list of 16 floats); see aq.h."""
-    native = ctypes.c_int(0)
+    """-> (form: AQC_FORM_*, coef: list of 16 floats); see aq.h."""
+    form = ctypes.c_int(0)
     coef = (ctypes.c_float * 16)()
-    _check(lib().aqc_table_info(_levels(levels, bits), bits, ctypes.byref(native), coef), "aqc_table_info")
-    return bool(native.value), list(coef)
+    _check(lib().aqc_table_info(_levels(levels, bits), bits, ctypes.byref(form), coef), "aqc_table_info")
+    return int(form.value), list(coef)
 
 
 def aqc_pack_weights(codes, scales, levels, N: int, K: int, bits: int, block: int = BLOCK, stream=None):

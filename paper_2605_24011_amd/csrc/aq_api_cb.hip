@@ -22,7 +22,8 @@ struct CbPlanHeader {
     int32_t count;
     int32_t max_K;
     int32_t total_wgs;
-    int32_t mode;            // 1: every table native; 2, 3, 4: every product in planes at that bit-width; 0: mixed
+    int32_t mode;            // 4 * form + bits if every product of the list has that form and bit-width; mixed lists:
+                             // 1 if every product fits the light mixed kernel, else 0
     int32_t reserved[11];
 };
 static_assert(sizeof(CbPlanHeader) == 64, "CbPlanHeader must stay 64 bytes");
@@ -48,10 +49,11 @@ double e2m1(int p)
 
 // What the kernels need to know of a table.
 struct CbInfo {
-    int native;            // 1: stored nibble = fp4 pattern of its level / alpha
+    int form;              // AQC_FORM_PLANES, AQC_FORM_NATIVE (stored nibble = fp4 pattern of its level / alpha) or
+                           // AQC_FORM_SIGNED (stored code = sign bit, then the index into the magnitude table)
     uint64_t remap;        // stored code of canonical code q: (remap >> 4q) & 15
     uint64_t inverse;      // canonical code of stored code c
-    float coef[16];        // planes: coefficient of the monomial of the code bits in S; coef[0] the constant term
+    float coef[16];        // plane forms: coefficient of the monomial of the (magnitude) bits in S; coef[0] the constant term
     float alpha;
     float stored_level[16];// level of every stored code
 };
@@ -86,7 +88,7 @@ int analyse(const float* levels, int bits, CbInfo& info)
             else { used[found] = true; pattern_of[q] = found; }
         }
         if (ok) {
-            info.native = 1;
+            info.form = AQC_FORM_NATIVE;
             info.alpha = (float)alpha;
             info.remap = info.inverse = 0;
             for (int q = 0; q < 16; ++q) {
@@ -94,6 +96,47 @@ int analyse(const float* levels, int bits, CbInfo& info)
                 info.inverse |= (uint64_t)q << (4 * pattern_of[q]);
                 info.stored_level[pattern_of[q]] = levels[q];
             }
+            return AQ_OK;
+        }
+    }
+    // Do the levels come in pairs +v, -v (zeros pair with zeros)?  Then the stored code is (sign, index of the magnitude
+    // in ascending order) and only the magnitudes are expanded.
+    {
+        const int half = n / 2;
+        bool used[16] = {};
+        int pos[8], neg[8], pairs = 0;
+        bool ok = true;
+        for (int q = 0; q < n && ok; ++q) {
+            if (used[q]) continue;
+            int r = -1;
+            for (int c = q + 1; c < n && r < 0; ++c)
+                if (!used[c] && levels[c] == -levels[q]) r = c;
+            if (r < 0) { ok = false; break; }
+            used[q] = used[r] = true;
+            const bool q_is_pos = levels[q] > 0.f || (levels[q] == 0.f && !std::signbit(levels[q]));
+            pos[pairs] = q_is_pos ? q : r;
+            neg[pairs] = q_is_pos ? r : q;
+            ++pairs;
+        }
+        if (ok && pairs == half) {
+            int order[8];
+            for (int i = 0; i < half; ++i) order[i] = i;
+            std::stable_sort(order, order + half, [&](int a, int b) { return std::fabs(levels[pos[a]]) < std::fabs(levels[pos[b]]); });
+            info.form = AQC_FORM_SIGNED;
+            info.remap = info.inverse = 0;
+            double a[8];
+            for (int m = 0; m < half; ++m) {
+                const int P = pos[order[m]], Ng = neg[order[m]], sp = m, sn = half | m;
+                info.remap |= ((uint64_t)sp << (4 * P)) | ((uint64_t)sn << (4 * Ng));
+                info.inverse |= ((uint64_t)P << (4 * sp)) | ((uint64_t)Ng << (4 * sn));
+                info.stored_level[sp] = levels[P];
+                info.stored_level[sn] = levels[Ng];
+                a[m] = std::fabs((double)levels[P]);
+            }
+            for (int j = 0; j < bits - 1; ++j)
+                for (int S = 0; S < half; ++S)
+                    if (S & (1 << j)) a[S] -= a[S ^ (1 << j)];
+            for (int S = 0; S < half; ++S) info.coef[S] = (float)a[S];
             return AQ_OK;
         }
     }
@@ -137,7 +180,7 @@ int make_cb_task(const void* packed, int64_t N, int64_t K, int bits, int block, 
     t.g.nchunks = (int32_t)aq_num_chunks(K);
     std::memcpy(t.coef, info.coef, sizeof(t.coef));
     t.alpha = info.alpha;
-    t.native = info.native;
+    t.form = info.form;
     aqk_cb_gemv_shape(t);
     return AQ_OK;
 }
@@ -151,17 +194,17 @@ size_t cb_plan_bytes(int count, int64_t wgs)
 
 extern "C" {
 
-int aqc_table_info(const float* levels, int bits, int* native, float* coef)
+int aqc_table_info(const float* levels, int bits, int* form, float* coef)
 {
     if (bits != 2 && bits != 3 && bits != 4) return AQ_EINVAL;
     if (!levels) return AQ_ENULL;
     CbInfo info;
     int rc = analyse(levels, bits, info);
     if (rc != AQ_OK) return rc;
-    if (native) *native = info.native;
+    if (form) *form = info.form;
     if (coef) {
         std::memcpy(coef, info.coef, sizeof(info.coef));
-        if (info.native) coef[0] = info.alpha;
+        if (info.form == AQC_FORM_NATIVE) coef[0] = info.alpha;
     }
     return AQ_OK;
 }
@@ -211,7 +254,7 @@ int aqc_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, con
     AqCbTask t;
     int rc = make_cb_task(packed, N, K, bits, block, levels, x, x_dtype, y, t);
     if (rc != AQ_OK) return rc;
-    return aqk_cb_gemv(nullptr, nullptr, 0, t, t.native ? 1 : bits, t.g.wg_count, (int)K, static_cast<hipStream_t>(stream)) == hipSuccess
+    return aqk_cb_gemv(nullptr, nullptr, 0, t, 4 * t.form + bits, t.g.wg_count, (int)K, static_cast<hipStream_t>(stream)) == hipSuccess
                ? AQ_OK : AQ_ELAUNCH;
 }
 
@@ -239,6 +282,7 @@ int aqc_qgemv_batch_plan(const aqc_gemv_desc* descs, int count, int block, void*
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return descs[a].product.K > descs[b].product.K; });
     int64_t wgs = 0;
     int max_K = 0, mode = 0;
+    bool light = true;
     for (int j = 0; j < count; ++j) {
         const aqc_gemv_desc& c = descs[order[j]];
         const aq_gemv_desc& d = c.product;
@@ -248,9 +292,11 @@ int aqc_qgemv_batch_plan(const aqc_gemv_desc* descs, int count, int block, void*
         wgs += tasks[j].g.wg_count;
         if (wgs > 0x3FFFFFFF) return AQ_EINVAL;
         if (d.K > max_K) max_K = (int)d.K;
-        const int m = tasks[j].native ? 1 : d.bits;
+        const int m = 4 * tasks[j].form + d.bits;
         mode = j == 0 ? m : (mode == m ? m : 0);
+        light = light && aqk_cb_light(tasks[j].form, d.bits);
     }
+    if (mode == 0 && light) mode = 1;
     if (plan_bytes < cb_plan_bytes(count, wgs)) return AQ_ESIZE;
     CbPlanHeader h;
     std::memset(&h, 0, sizeof(h));
@@ -274,7 +320,7 @@ int aqc_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream)
     if (!aligned16(plan_dev)) return AQ_EALIGN;
     CbPlanHeader h;
     std::memcpy(&h, plan_host, sizeof(h));
-    if (h.magic != CB_PLAN_MAGIC || h.count < 1 || h.total_wgs < 1 || h.max_K < AQ_BLOCK || h.mode < 0 || h.mode > 4)
+    if (h.magic != CB_PLAN_MAGIC || h.count < 1 || h.total_wgs < 1 || h.max_K < AQ_BLOCK || h.mode < 0 || h.mode > 12)
         return AQ_EINVAL;
     const uint8_t* dev = static_cast<const uint8_t*>(plan_dev);
     const AqCbTask* tasks = reinterpret_cast<const AqCbTask*>(dev + sizeof(CbPlanHeader));

@@ -23,13 +23,15 @@ struct AqGemvTask {
 static_assert(sizeof(AqGemvTask) == 64, "AqGemvTask must stay 64 bytes");
 
 // A decode product of the non-uniform codebook variant (device-visible, 192 bytes): the base record, then how the
-// table reaches the matrix cores.  native: the stored nibbles are fp4 bit patterns and alpha scales the result;
-// else coef[S] is the coefficient of the monomial of the code bits in S (coef[0]: the constant term) and alpha is 1.
+// table reaches the matrix cores.  form 1 (native): the stored nibbles are fp4 bit patterns and alpha scales the
+// result; form 0 (planes): coef[S] is the coefficient of the monomial of the code bits in S (coef[0]: the constant
+// term); form 2 (signed planes): the top bit of a stored code is the sign and coef[S] expands the magnitude table over
+// the lower bits; alpha is 1 for both plane forms.
 struct AqCbTask {
     AqGemvTask g;
     float coef[16];
     float alpha;
-    int32_t native;
+    int32_t form;
     int32_t pad[14];
 };
 static_assert(sizeof(AqCbTask) == 192, "AqCbTask must stay 192 bytes");
@@ -79,8 +81,9 @@ hipError_t aqk_cb_unpack_codes(const void* blob, int64_t N, int64_t K, int bits,
 hipError_t aqk_cb_dequant(const void* blob, int64_t N, int64_t K, int bits, const AqCbTable& stored_levels, float* out,
                           hipStream_t s);
 void aqk_cb_gemv_shape(AqCbTask& t);
+bool aqk_cb_light(int form, int bits);
 hipError_t aqk_cb_gemv(const AqCbTask* tasks_dev, const int32_t* wg_task, int count, const AqCbTask& single, int mode,
-                       int total_wgs, int max_K, hipStream_t s);      // mode: 1 native, 2 / 3 / 4 planes at that width, 0 mixed
+                       int total_wgs, int max_K, hipStream_t s);      // mode: 4 * form + bits for a uniform launch; mixed: 1 if aqk_cb_light holds for every task, else 0
 
 hipError_t aqk2_pack(const uint8_t* codes, const uint8_t* sub, const uint16_t* sup, int64_t N, int64_t K, int bits,
                      void* blob, hipStream_t s);

@@ -302,8 +302,8 @@ def test_codebook_variant_table_analysis_and_validation_without_a_gpu(L):
     for bits in (2, 3, 4):
         n = 1 << bits
         for T in (rng.normal(size=n), np.arange(n) - n / 2, rng.integers(-40, 41, size=n) / 8.0):
-            native, coef = aq.aqc_table_info(T.astype(np.float32), bits)
-            assert not native
+            form, coef = aq.aqc_table_info(T.astype(np.float32), bits)
+            assert form == aq.AQC_FORM_PLANES
             rec = np.array([sum(coef[S] for S in range(n) if (S & q) == S) for q in range(n)])
             assert np.abs(rec - T.astype(np.float32)).max() <= 1e-6 * max(1.0, np.abs(T).max())
             if bits == 2:                       # closed form: a_0 = L0, a_1 = L1 - L0, a_2 = L2 - L0, a_3 = L3 - L2 - L1 + L0
@@ -311,10 +311,21 @@ def test_codebook_variant_table_analysis_and_validation_without_a_gpu(L):
                 assert np.allclose(coef[:4], [Tf[0], Tf[1] - Tf[0], Tf[2] - Tf[0], Tf[3] - Tf[2] - Tf[1] + Tf[0]], atol=1e-6)
     e2m1 = np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -0., -.5, -1, -1.5, -2, -3, -4, -6], dtype=np.float32)
     for alpha in (1.0, 0.37, 1e-3, 4096.0):
-        native, coef = aq.aqc_table_info((e2m1 * np.float32(alpha))[rng.permutation(16)], 4)
-        assert native and abs(coef[0] - np.float32(alpha)) <= 1e-6 * alpha
-    assert not aq.aqc_table_info(np.abs(e2m1), 4)[0]                    # every magnitude twice: not a permutation
-    assert not aq.aqc_table_info(np.zeros(16, dtype=np.float32), 4)[0]
+        form, coef = aq.aqc_table_info((e2m1 * np.float32(alpha))[rng.permutation(16)], 4)
+        assert form == aq.AQC_FORM_NATIVE and abs(coef[0] - np.float32(alpha)) <= 1e-6 * alpha
+    assert aq.aqc_table_info(np.abs(e2m1), 4)[0] == aq.AQC_FORM_PLANES   # every magnitude twice: no permutation, no pairs
+    assert aq.aqc_table_info(np.zeros(16, dtype=np.float32), 4)[0] == aq.AQC_FORM_SIGNED
+    # pairs +v, -v in any order: the coefficients expand the ascending magnitudes over the index bits
+    for bits in (2, 3, 4):
+        half = 1 << (bits - 1)
+        mags = np.sort(np.abs(rng.normal(size=half))).astype(np.float32)
+        T = np.concatenate([mags, -mags])[rng.permutation(2 * half)]
+        form, coef = aq.aqc_table_info(T, bits)
+        assert form == aq.AQC_FORM_SIGNED
+        rec = np.array([sum(coef[S] for S in range(half) if (S & m) == S) for m in range(half)])
+        assert np.abs(rec - mags).max() <= 1e-6
+    off = np.array([-1.5, -0.5, 0.5, 1.25], dtype=np.float32)            # one magnitude without its partner
+    assert aq.aqc_table_info(off, 2)[0] == aq.AQC_FORM_PLANES
     A = 1 << 20
     lv = (ctypes.c_float * 4)(-1.5, -0.25, 0.25, 1.5)
     bad = (ctypes.c_float * 4)(0.0, float("inf"), 1.0, 2.0)
@@ -342,7 +353,16 @@ def test_codebook_variant_table_analysis_and_validation_without_a_gpu(L):
     buf = (ctypes.c_uint8 * size)()
     assert L.aqc_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_OK
     head = np.frombuffer(bytes(buf[:64]), dtype=np.int32)
-    assert head[1] == 2 and head[2] == 11008 and head[3] == 5 and head[4] == 0          # count, max K, workgroups, mixed
+    assert head[1] == 2 and head[2] == 11008 and head[3] == 5 and head[4] == 1          # count, max K, workgroups, light mixed
+    heavy = (ctypes.c_float * 16)(*[float(v) for v in np.random.default_rng(4).normal(size=16)])     # 15 planes
+    descs[1].levels = ctypes.cast(heavy, ctypes.c_void_p)
+    assert L.aqc_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_OK
+    assert np.frombuffer(bytes(buf[:64]), dtype=np.int32)[4] == 0
+    descs[0].levels = ctypes.cast(heavy, ctypes.c_void_p); descs[0].product.bits = 4
+    assert L.aqc_qgemv_batch_plan(descs, 2, 32, buf, size) == aq.AQ_OK
+    assert np.frombuffer(bytes(buf[:64]), dtype=np.int32)[4] == 4                       # uniform: planes at 4 bits
+    descs[0].levels = ctypes.cast(lv, ctypes.c_void_p); descs[0].product.bits = 2
+    descs[1].levels = ctypes.cast(lv4, ctypes.c_void_p)
     assert L.aqc_qgemv_batch_plan(descs, 2, 32, buf, size - 1) == aq.AQ_ESIZE
     assert L.aqc_qgemv_batch(buf, None, None) == aq.AQ_ENULL
     assert L.aqc_qgemv_batch(buf, A + 4, None) == aq.AQ_EALIGN

@@ -45,7 +45,7 @@ def dev(torch, a, kind=None):
 
 def tables(cb, bits):
     """(name, levels) the bit-width is tested with; the 4-bit list holds native tables as well."""
-    out = [(k, wl.draw_levels(k, bits, 1)) for k in ("quantile", "random", "dyadic", "uniform")]
+    out = [(k, wl.draw_levels(k, bits, 1)) for k in ("quantile", "random", "dyadic", "uniform", "signed_dyadic")]
     if bits == 4:
         e = cb.e2m1_levels().astype(np.float32)
         perm = np.random.default_rng(5).permutation(16)
@@ -76,9 +76,9 @@ def test_native_tables_are_recognised_and_stored_as_fp4_patterns(gpu, cb, oracle
     N, K = 40, 512
     codes, scales = wl.draw_matrix(N, K, 4, 82)
     e = cb.e2m1_levels().astype(np.float32)
-    assert aq.aqc_table_info(e, 4)[0] and aq.aqc_table_info(e * 3.0, 4)[0]
-    assert not aq.aqc_table_info(wl.draw_levels("quantile", 4, 1), 4)[0]
-    assert not aq.aqc_table_info(np.where(np.arange(16) == 3, 1.6, e).astype(np.float32), 4)[0]      # one level off the grid
+    assert aq.aqc_table_info(e, 4)[0] == aq.AQC_FORM_NATIVE and aq.aqc_table_info(e * 3.0, 4)[0] == aq.AQC_FORM_NATIVE
+    assert aq.aqc_table_info(wl.draw_levels("quantile", 4, 1), 4)[0] == aq.AQC_FORM_SIGNED
+    assert aq.aqc_table_info(np.where(np.arange(16) == 3, 1.6, e).astype(np.float32), 4)[0] == aq.AQC_FORM_PLANES   # one level off the grid
     base = aq.aq_pack_weights(dev(torch, codes), dev(torch, scales), N, K, 4)
     own = aq.aqc_pack_weights(dev(torch, codes), dev(torch, scales), e, N, K, 4)
     assert torch.equal(base, own)
@@ -125,7 +125,7 @@ def test_qgemv_bit_exact_on_exact_arithmetic_inputs(gpu, cb, oracle, bits):
     codes = wl.draw_codes(N, K, bits, 85, bits)
     scales = wl.draw_pow2_scales(N, K, 85, bits)
     x = wl.draw_int_activations(1, K, "f16", 85, bits)
-    tabs = [wl.draw_levels("dyadic", bits, 2)]
+    tabs = [wl.draw_levels("dyadic", bits, 2), wl.draw_levels("signed_dyadic", bits, 2)]
     if bits == 4:
         tabs.append((cb.e2m1_levels() * 0.25).astype(np.float32))
     for levels in tabs:
@@ -139,7 +139,8 @@ def test_mixed_batch_matches_single_calls_and_oracle(gpu, cb, oracle):
     e = cb.e2m1_levels().astype(np.float32)
     specs = [(256, 1024, 2, wl.draw_levels("quantile", 2, 1)), (384, 4096, 4, e), (130, 544, 3, wl.draw_levels("quantile", 3, 1)),
              (512, 11008, 4, (e * np.float32(1.7))[::-1].copy()), (128, 2048, 4, wl.draw_levels("quantile", 4, 1)),
-             (640, 4096, 3, wl.draw_levels("random", 3, 2))]
+             (640, 4096, 3, wl.draw_levels("random", 3, 2)), (256, 2048, 2, wl.draw_levels("random", 2, 2)),
+             (384, 1024, 4, wl.draw_levels("random", 4, 2))]
     items, refs, singles = [], [], []
     for i, (N, K, bits, levels) in enumerate(specs):
         codes, scales = wl.draw_matrix(N, K, bits, 86, i)
@@ -155,8 +156,8 @@ def test_mixed_batch_matches_single_calls_and_oracle(gpu, cb, oracle):
     for it, ref, one in zip(items, refs, singles):
         assert oracle.rel_l2(it[6].cpu().numpy(), ref) <= REL_L2_EXPECTED
         assert oracle.rel_l2(it[6].cpu().numpy(), one.cpu().numpy()) <= 1e-5
-    # uniform lists take the kernel built for their form: all native, and all 3-bit planes
-    for sel in ([1, 3], [2, 5]):
+    # uniform lists take the kernel built for their form: all native, all signed 3-bit planes, all general 3-bit planes
+    for sel in ([1, 3], [2], [5]):
         sub = [items[i] for i in sel]
         for it in sub:
             it[6].fill_(float("nan"))
