@@ -307,7 +307,7 @@ def main():
                 sp = [wl.MatrixSpec(i, 0, name, N, K, b) for i in range(copies)]
                 its = build_stream(aq, wl, torch, sp, "f16", 40 + b)
                 bt = aq.GemvBatch(its)
-                d, w = time_launches(torch, bt.run, 20, 3)
+                d, w = time_launches(torch, bt.run, max(20, args.steps), 20)      # short launches: the clocks need the warm-up
                 ms = sum(d) / len(d)
                 cell = {"copies": copies, "batched_GB/s": round(copies * per / (ms * 1e-3) / 1e9, 1),
                         "batched_pct_hbm_peak": round(100 * copies * per / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)}
@@ -316,7 +316,7 @@ def main():
                     def lone():
                         for (packed, N_, K_, b_, x, y) in its:
                             aq.aq_qgemv(packed, N_, K_, b_, x, y)
-                    d, w = time_launches(torch, lone, 5, 1)
+                    d, w = time_launches(torch, lone, 10, 3)
                     ms1 = sum(d) / len(d) / copies
                     cell["per_call_us"] = round(ms1 * 1e3, 2)
                     cell["per_call_GB/s"] = round(per / (ms1 * 1e-3) / 1e9, 1)
@@ -330,7 +330,7 @@ def main():
                         with torch.cuda.graph(graph, stream=side):
                             lone()
                     torch.cuda.current_stream().wait_stream(side)
-                    d, w = time_launches(torch, graph.replay, 5, 1)
+                    d, w = time_launches(torch, graph.replay, 10, 3)
                     cell["per_call_us_graph_replay"] = round(sum(d) / len(d) / copies * 1e3, 2)
                     del graph
                 cells["%s_b%d" % (name, b)] = cell
@@ -351,7 +351,7 @@ def main():
             pre["workload"] += " [--prefill-shared-buffers: ONE X per K and ONE Y per N for the whole pass]"
         for mode, fast in (("exact", False), ("fast", True)):
             gbatch = aq.GemmBatch(pitems, fast=fast)
-            d, w = time_launches(torch, gbatch.run, args.prefill_steps, 1)
+            d, w = time_launches(torch, gbatch.run, args.prefill_steps, 2)
             ms = sum(d) / len(d)
             pre[mode] = {
                 "ms": round(ms, 3),
@@ -419,7 +419,7 @@ def main():
         gweights = sum(m.weights for m in gs)
         gb = aq.GemvBatch(gitems)
         gbytes = sum(gemv_bytes(m.N, m.K, m.bits) for m in gs)
-        d, w = time_launches(torch, gb.run, max(10, args.steps // 2), 3)
+        d, w = time_launches(torch, gb.run, max(20, args.steps), 20)
         ms = sum(d) / len(d)
         gem = {"workload": "gemma-2b-shaped stream, 126 matrices, 3 bits (3.5 bits/weight stored), bf16 activations",
                "decode": {"GB/s": round(gbytes / (ms * 1e-3) / 1e9, 1),
@@ -433,7 +433,7 @@ def main():
             cell = {"bound": "hbm" if t_hbm > t_mfma else "mfma"}
             for mode, fast in (("exact", False), ("fast", True)):
                 g2 = aq.GemmBatch(gp, fast=fast)
-                d, w = time_launches(torch, g2.run, args.prefill_steps, 1)
+                d, w = time_launches(torch, g2.run, args.prefill_steps, 2)
                 ms = sum(d) / len(d)
                 cell[mode] = {"ms": round(ms, 4), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
                               "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
@@ -476,7 +476,7 @@ def main():
             def one_token():
                 x.copy_(x0, non_blocking=True)
                 step.run()
-            d, w = time_launches(torch, one_token, max(10, args.steps // 2), 3)
+            d, w = time_launches(torch, one_token, max(10, args.steps // 2), 5)
             ms = sum(d) / len(d)
             step_out[model] = {
                 "allocation": alloc, "layers": n_layers, "launches_per_token": 4 * n_layers + 2,
@@ -523,7 +523,7 @@ def main():
                 two["mixed_prefill_m300"] = {}
                 for mode, fast in (("exact", False), ("fast", True)):
                     gb = aq.GemmBatch(tp, two_level=True, fast=fast)
-                    d, w = time_launches(torch, gb.run, args.prefill_steps, 1)
+                    d, w = time_launches(torch, gb.run, args.prefill_steps, 2)
                     ms = sum(d) / len(d)
                     two["mixed_prefill_m300"][mode] = {
                         "ms": round(ms, 3), "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 2),
