@@ -23,28 +23,6 @@ constexpr int W_ROW = AQ_CHUNK_K * 2 + 32;         // LDS row stride of the W ch
 // variant: and offsets)
 inline size_t gm_lds_bytes(int fmt) { return 2 * ((size_t)GM_NT * W_ROW + GM_NT * (fmt ? 16 : 8) * sizeof(float)); }
 
-// words of one block -> 16 registers, each a pair of exact (q - z) in fp16 or bf16 (RAWQ: the codes q themselves)
-template <int BITS, bool XBF, bool RAWQ = false>
-__device__ __forceinline__ void unpack_exact(const uint32_t* w, const typename Codec<BITS>::Magic& magic,
-                                             uint32_t (&o)[16])
-{
-    uint32_t a[16];
-    Codec<BITS>::unpack(w, magic, a);              // fp16 pairs (magic + q)
-    const float z = RAWQ ? 0.f : (float)(1 << (BITS - 1));
-#pragma unroll
-    for (int p = 0; p < 16; ++p) {
-        const _Float16 k = (_Float16)(Codec<BITS>::offset(p) + z);
-        const uint32_t ap = a[p];
-        const half2v h = __builtin_bit_cast(half2v, ap) - half2v{k, k};      // exact: small integers
-        if (XBF) {
-            const float lo = (float)h.x, hi = (float)h.y;                    // bf16 = upper half of the fp32
-            o[p] = (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
-        } else {
-            o[p] = __builtin_bit_cast(uint32_t, h);
-        }
-    }
-}
-
 template <bool XBF>
 __device__ __forceinline__ float4v mfma16(const u32x4& a, const u32x4& b, const float4v& c)
 {
