@@ -19,17 +19,7 @@
 #include "aq_gemv_digit.h"
 #include <type_traits>
 
-#ifdef AQ_GEMV_TRACE
-// debug builds only: per-workgroup timestamps (start, after staging, end of loop, end) of the last launch
-__device__ unsigned long long aq_trace_buf[4 * 65536];
-extern "C" int aq_debug_trace_read(void* host, size_t bytes)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(aq_trace_buf), bytes);
-}
-#define AQ_TRACE(slot) do { if (threadIdx.x == 0 && blockIdx.x < 65536) aq_trace_buf[blockIdx.x * 4 + (slot)] = wall_clock64(); } while (0)
-#else
-#define AQ_TRACE(slot) do { } while (0)
-#endif
+#define AQ_TRACE(slot) do { } while (0)      // hook of the shared body for timestamp experiments; unused
 
 namespace {
 
