@@ -694,3 +694,30 @@ def test_qgemm_fast_producer_consumer_shapes(gpu, oracle, bits, N, K, M):
     Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
     assert np.isfinite(Y).all()
     assert oracle.rel_l2(Y, oracle.qmatmul(codes, big, N, K, bits, X, "bf16")) <= FAST_EXPECTED[bits]
+
+
+def test_qgemv_seeded_sweep_of_shapes_around_the_kernel_boundaries(gpu, oracle):
+    """Shapes drawn around what the decode kernel's structure makes special: K at and next to multiples of a chunk
+    (256), of a staged segment (4096) and of a lone call's four-way split of K; N at and next to multiples of a tile
+    (16) and of a group (128); every bit-width and both activation types; lone calls and one listed launch of all."""
+    torch, aq = gpu
+    rng = np.random.default_rng(2024)
+    ks = [32, 224, 256, 288, 1024 - 32, 1024 + 32, 4096 - 32, 4096, 4096 + 32, 8192, 8192 + 256 + 32, 12288 - 32, 16384]
+    ns = [1, 15, 16, 17, 127, 128, 129, 255, 300]
+    cases = [(int(rng.choice(ns)), int(k), int(rng.integers(2, 5)), str(rng.choice(["f16", "bf16"]))) for k in ks for _ in range(2)]
+    items, refs = [], []
+    for i, (N, K, bits, dtype) in enumerate(cases):
+        codes, scales = wl.draw_matrix(N, K, bits, 97, i)
+        x = wl.draw_activations(1, K, dtype, 97, i)
+        packed = _pack(torch, aq, codes, scales, N, K, bits)
+        xd = _dev(torch, x[0], dtype)
+        ref = oracle.qmatmul(codes, scales, N, K, bits, x, dtype)[0]
+        y = aq.aq_qgemv(packed, N, K, bits, xd).cpu().numpy()
+        assert oracle.rel_l2(y, ref) <= REL_L2_EXPECTED, (N, K, bits, dtype)
+        yb = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, xd, yb))
+        refs.append(ref)
+    aq.GemvBatch(items).run()
+    torch.cuda.synchronize()
+    for it, ref, case in zip(items, refs, cases):
+        assert oracle.rel_l2(it[5].cpu().numpy(), ref) <= REL_L2_EXPECTED, case

@@ -257,3 +257,30 @@ def test_qgemm_full_size_sampled_columns(gpu, oracle, af, fast):
     torch.cuda.synchronize()
     for it, (rows, ref) in zip(items, checks):
         assert oracle.rel_l2(it[5].cpu().numpy()[:, rows], ref) <= (1e-3 if fast else 2e-5)
+
+
+def test_qgemv_seeded_sweep_of_shapes_around_the_kernel_boundaries(gpu, oracle, af):
+    """As in the base format's sweep: K around chunk, segment and K-split boundaries, N around tile and group
+    boundaries, lone calls and one listed launch."""
+    torch, aq = gpu
+    rng = np.random.default_rng(2025)
+    ks = [32, 224, 256, 288, 1024 + 32, 4096 - 32, 4096, 4096 + 32, 8192 + 256 + 32, 16384]
+    ns = [1, 15, 16, 17, 127, 128, 129, 300]
+    cases = [(int(rng.choice(ns)), int(k), int(rng.integers(2, 5)), str(rng.choice(["f16", "bf16"]))) for k in ks for _ in range(2)]
+    items, refs = [], []
+    for i, (N, K, bits, dtype) in enumerate(cases):
+        codes = wl.draw_codes(N, K, bits, 98, i)
+        sub, sup = wl.draw_affine_params(N, K, bits, 98, i)
+        x = wl.draw_activations(1, K, dtype, 98, i)
+        packed = pack(torch, aq, codes, sub, sup, N, K, bits)
+        xd = dev(torch, x, dtype)[0].contiguous()
+        ref = af.qmatvec(codes, sub, sup, N, K, bits, x[0], dtype)
+        y = aq.aq2_qgemv(packed, N, K, bits, xd).cpu().numpy()
+        assert oracle.rel_l2(y, ref) <= 2e-4, (N, K, bits, dtype)
+        yb = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, xd, yb))
+        refs.append(ref)
+    aq.GemvBatch(items, two_level=True).run()
+    torch.cuda.synchronize()
+    for it, ref, case in zip(items, refs, cases):
+        assert oracle.rel_l2(it[5].cpu().numpy(), ref) <= 2e-4, case
