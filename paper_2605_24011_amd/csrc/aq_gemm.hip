@@ -23,90 +23,109 @@
 
 namespace {
 
-// X[M][ldx] (16-bit elements) -> Xt in operand order.  Thread e handles the 16-byte piece j = e % (K/8)
-// of row e / (K/8): reads run along the rows of X, rows in [M, 16*ceil(M/16)) are written as zeros.
+// X[M][ldx] (16-bit elements) -> Xt in operand order: Xt[m-tile][32-k step][lane (g, c)] = the 16 bytes
+// X[16 m-tile + c][32 step + 8g .. + 8].  One wavefront writes whole 1 KiB fragments (contiguous, coalesced stores) and
+// reads, per fragment, 64 bytes of each of the tile's 16 rows; its four fragments are four consecutive steps, so the
+// 16 rows' reads cover whole 256-byte runs.  A workgroup = one m-tile x 16 steps.  Rows in [M, 16 ceil(M/16)) are
+// written as zeros.
+constexpr int RT_STEPS = 4;                                    // steps per wavefront
 __global__ __launch_bounds__(256) void retile_kernel(const AqRetileTask* __restrict__ tasks, int count,
                                                      AqRetileTask single, uint8_t* __restrict__ workspace)
 {
     AqRetileTask t;
     if (count == 0) t = single; else t = tasks[blockIdx.y];
     if ((int)blockIdx.x >= t.blocks) return;
-    const int pieces = t.K >> 3;                               // 16-byte pieces per row
-    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t row = e / pieces;
-    const int j = (int)(e - row * pieces);
+    const int ksteps = t.K >> 5;
+    const int per_tile = (ksteps + 4 * RT_STEPS - 1) / (4 * RT_STEPS);       // workgroups per m-tile
+    const int64_t mtile = blockIdx.x / per_tile;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+    const int step0 = ((blockIdx.x % per_tile) * 4 + wave) * RT_STEPS;
+    const int64_t row = mtile * 16 + c;
     const int64_t mpad = (t.M + 15) & ~(int64_t)15;
-    if (row >= mpad) return;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (row < t.M) v = *as_global<u32x4>(t.X + row * t.ldx + (int64_t)j * 8);
-    const int64_t mtile = row >> 4;
-    const int c = (int)(row & 15), step = j >> 2, g = j & 3;
-    const int64_t ksteps = t.K >> 5;
-    u32x4* dst = reinterpret_cast<u32x4*>(workspace + t.xt_offset);
-    dst[(mtile * ksteps + step) * 64 + g * 16 + c] = v;
-    if (j == 0) reinterpret_cast<int32_t*>(workspace + t.xt_offset + mpad * t.K * 2)[row] = 0;       // rowexp
+    u32x4 v[RT_STEPS];
+#pragma unroll
+    for (int s = 0; s < RT_STEPS; ++s) {
+        v[s] = u32x4{0u, 0u, 0u, 0u};
+        if (row < t.M && step0 + s < ksteps) v[s] = *as_global<u32x4>(t.X + row * t.ldx + (int64_t)(step0 + s) * 32 + g * 8);
+    }
+    u32x4* dst = reinterpret_cast<u32x4*>(workspace + t.xt_offset) + (mtile * ksteps + step0) * 64 + lane;
+#pragma unroll
+    for (int s = 0; s < RT_STEPS; ++s)
+        if (step0 + s < ksteps) dst[s * 64] = v[s];
+    if (step0 == 0 && g == 0) reinterpret_cast<int32_t*>(workspace + t.xt_offset + mpad * t.K * 2)[row] = 0;       // rowexp
 }
 
-// bf16 X[M][ldx] -> binary16 Xt with one power-of-two factor per row.  One workgroup per padded row:
-// pass 1 finds the row's largest magnitude, pass 2 scales, converts (round to nearest even) and scatters
-// the 16-byte pieces into operand order; rowexp[row] = the exponent the product kernel adds back.
+// bf16 X[M][ldx] -> binary16 Xt with one power-of-two factor per row.  One workgroup per m-tile (16 rows): pass 1 finds
+// every row's largest magnitude (wavefront w takes rows 4w .. 4w+3, reading along the rows), pass 2 walks the tile's
+// fragments as retile_kernel does (second read of the tile: from L2), scales, converts (round to nearest even) and
+// stores whole fragments; rowexp[row] = the exponent the product kernel adds back.
 __global__ __launch_bounds__(256) void retile_convert_kernel(const AqRetileTask* __restrict__ tasks, int count,
                                                              AqRetileTask single, uint8_t* __restrict__ workspace)
 {
-    __shared__ uint32_t wave_max[4];
+    __shared__ int row_shift[16];
     AqRetileTask t;
     if (count == 0) t = single; else t = tasks[blockIdx.y];
-    const int64_t row = blockIdx.x;
+    const int64_t mtile = blockIdx.x;
     const int64_t mpad = (t.M + 15) & ~(int64_t)15;
-    if (row >= mpad) return;                                   // uniform per workgroup
-    const int pieces = t.K >> 3, tid = threadIdx.x;
-    const int64_t ksteps = t.K >> 5;
-    u32x4* dst = reinterpret_cast<u32x4*>(workspace + t.xt_offset);
+    if (mtile * 16 >= mpad) return;                            // uniform per workgroup
+    const int pieces = t.K >> 3, ksteps = t.K >> 5;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
     int32_t* rowexp = reinterpret_cast<int32_t*>(workspace + t.xt_offset + mpad * t.K * 2);
-    const int64_t base = ((row >> 4) * ksteps) * 64 + (row & 15);
-    if (row >= t.M) {
-        for (int j = tid; j < pieces; j += 256) dst[base + (int64_t)(j >> 2) * 64 + (j & 3) * 16] = u32x4{0u, 0u, 0u, 0u};
-        if (tid == 0) rowexp[row] = 0;
-        return;
-    }
-    const AQ_GLOBAL u32x4* src = as_global<u32x4>(t.X + row * t.ldx);
-    uint32_t mx = 0;                                           // bf16 magnitudes order like unsigned integers
-    for (int j = tid; j < pieces; j += 256) {
-        const u32x4 v = src[j];
+    // pass 1: bf16 magnitudes order like unsigned integers
+    for (int r = 0; r < 4; ++r) {
+        const int64_t row = mtile * 16 + wave * 4 + r;
+        uint32_t mx = 0;
+        if (row < t.M) {
+            const AQ_GLOBAL u32x4* src = as_global<u32x4>(t.X + row * t.ldx);
+            for (int j = lane; j < pieces; j += 64) {
+                const u32x4 v = src[j];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t lo = v[i] & 0x7FFFu, hi = (v[i] >> 16) & 0x7FFFu;
-            mx = lo > mx ? lo : mx;
-            mx = hi > mx ? hi : mx;
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t lo = v[i] & 0x7FFFu, hi = (v[i] >> 16) & 0x7FFFu;
+                    mx = lo > mx ? lo : mx;
+                    mx = hi > mx ? hi : mx;
+                }
+            }
+        }
+        for (int o = 32; o >= 1; o >>= 1) {
+            const uint32_t other = (uint32_t)__shfl_xor((int)mx, o);
+            mx = other > mx ? other : mx;
+        }
+        if (lane == 0) {
+            int shift = 0;                                     // x * 2^shift has its largest magnitude in [2^14, 2^15)
+            if (mx != 0) {
+                const int field = (int)(mx >> 7);              // biased exponent; 0 = bf16 subnormal, 255 = inf / NaN
+                shift = 14 - ((field ? field : 1) - 127);
+            }
+            row_shift[wave * 4 + r] = shift;
+            rowexp[row] = -shift;                              // padded rows: 0
         }
     }
-    for (int o = 32; o >= 1; o >>= 1) {
-        const uint32_t other = (uint32_t)__shfl_xor((int)mx, o);
-        mx = other > mx ? other : mx;
-    }
-    if ((tid & 63) == 0) wave_max[tid >> 6] = mx;
     __syncthreads();
-    mx = wave_max[0];
+    // pass 2
+    const int64_t row = mtile * 16 + c;
+    const int shift = row_shift[c];
+    u32x4* dst = reinterpret_cast<u32x4*>(workspace + t.xt_offset) + mtile * ksteps * 64 + lane;
+    for (int step0 = wave * RT_STEPS; step0 < ksteps; step0 += 4 * RT_STEPS) {
+        u32x4 v[RT_STEPS];
 #pragma unroll
-    for (int i = 1; i < 4; ++i) mx = wave_max[i] > mx ? wave_max[i] : mx;
-    int shift = 0;                                             // x * 2^shift has its largest magnitude in [2^14, 2^15)
-    if (mx != 0) {
-        const int field = (int)(mx >> 7);                      // biased exponent; 0 = bf16 subnormal, 255 = inf / NaN
-        shift = 14 - ((field ? field : 1) - 127);
-    }
-    for (int j = tid; j < pieces; j += 256) {
-        const u32x4 v = src[j];
-        u32x4 o;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float lo = ldexpf(__uint_as_float(v[i] << 16), shift);
-            const float hi = ldexpf(__uint_as_float(v[i] & 0xFFFF0000u), shift);
-            const half2v h = {(_Float16)lo, (_Float16)hi};
-            o[i] = __builtin_bit_cast(uint32_t, h);
+        for (int s = 0; s < RT_STEPS; ++s) {
+            v[s] = u32x4{0u, 0u, 0u, 0u};
+            if (row < t.M && step0 + s < ksteps) v[s] = *as_global<u32x4>(t.X + row * t.ldx + (int64_t)(step0 + s) * 32 + g * 8);
         }
-        dst[base + (int64_t)(j >> 2) * 64 + (j & 3) * 16] = o;
+#pragma unroll
+        for (int s = 0; s < RT_STEPS; ++s) {
+            u32x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float lo = ldexpf(__uint_as_float(v[s][i] << 16), shift);
+                const float hi = ldexpf(__uint_as_float(v[s][i] & 0xFFFF0000u), shift);
+                const half2v h = {(_Float16)lo, (_Float16)hi};
+                o[i] = __builtin_bit_cast(uint32_t, h);
+            }
+            if (step0 + s < ksteps) dst[(int64_t)(step0 + s) * 64] = o;
+        }
     }
-    if (tid == 0) rowexp[row] = -shift;
 }
 
 }  // namespace
@@ -151,10 +170,11 @@ size_t aqk_retile_bytes(int64_t M, int64_t K)
     return (size_t)(mpad * K * 2 + ((mpad * 4 + 1023) / 1024) * 1024);
 }
 
+// workgroups of a re-tiling task: one per m-tile (converting), one per m-tile and 16 steps of 32 k (plain)
 int aqk_retile_blocks(int64_t M, int64_t K, int convert)
 {
-    const int64_t mpad = ((M + 15) / 16) * 16;
-    return convert ? (int)mpad : (int)((mpad * (K / 8) + 255) / 256);
+    const int64_t mtiles = (M + 15) / 16, ksteps = K / 32;
+    return convert ? (int)mtiles : (int)(mtiles * ((ksteps + 15) / 16));
 }
 
 hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int max_blocks,

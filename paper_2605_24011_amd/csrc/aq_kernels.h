@@ -105,7 +105,7 @@ struct AqRetileTask {
     int64_t M, ldx;
     int64_t xt_offset;  // bytes from the workspace base, multiple of 1024
     int32_t K;
-    int32_t blocks;     // workgroups of 256 threads: one 16-byte piece per thread, or one row per workgroup
+    int32_t blocks;     // workgroups of 256 threads (aqk_retile_blocks)
     int32_t convert;
     int32_t pad;        // small-M layout: m-tiles of the launch (1, 2, 4); else 0
 };
