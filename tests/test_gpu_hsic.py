@@ -65,7 +65,8 @@ def test_sensitivity_with_offsets(gpu, ho):
 
 
 @pytest.mark.parametrize("K,dx,dz,dy", [(2, 1, 1, 1), (64, 32, 48, 7), (200, 96, 64, 7), (513, 300, 260, 14),
-                                        (1500, 160, 224, 7)])      # 12 x 12 tiles, fp64 reductions over many workgroups
+                                        (1500, 160, 224, 7),       # 12 x 12 tiles, fp64 reductions over many workgroups
+                                        (4096, 64, 48, 7)])        # the bench's sample count (528 tiles), few features
 def test_sensitivity_matches_oracle(gpu, ho, K, dx, dz, dy):
     torch, aq = gpu
     X, Z, Y = wl.draw_hsic_inputs(K, dx, dz, dy, 92, K)

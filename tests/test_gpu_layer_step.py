@@ -1,11 +1,10 @@
 """Parity of the layer-by-layer decode step (aq_decode_plan / aq_decode_step, through the C ABI) against the
 fp64 layer oracle on the same seeded inputs.
 
-Bar: relative L2 <= 1e-3 for q, k, v and the residual stream of every stack of up to 4 layers.  The inputs of every
+Bar: relative L2 <= 1e-3 for q, k, v and the residual stream at every depth, up to 32 layers.  The inputs of every
 product are rounded to binary16 times a power of two (relative error <= 2^-12, rms 1.4e-4 of the vector); a layer
-has four such roundings and they add in quadrature along the residual stream, so a stack of L layers is held to
-1e-3 * max(1, sqrt(L / 4)) (measured on the CPU with the same roundings planted in the oracle: 1.2e-4 at one
-layer, 7.7e-4 at 32)."""
+has four such roundings and they add in quadrature along the residual stream (measured on the CPU with the same
+roundings planted in the oracle: 1.2e-4 at one layer, 7.7e-4 at 32; on the GPU 7.6e-4 at 32)."""
 import numpy as np
 import pytest
 
@@ -30,7 +29,9 @@ def layer_oracle():
 
 
 def bar(layers: int) -> float:
-    return 1e-3 * max(1.0, (layers / 4.0) ** 0.5)
+    """Relative L2 <= 1e-3 at every depth (measured on the GPU: 2.2e-4 .. 3.7e-4 after 1 to 6 layers, 7.6e-4 after 32:
+    four independent roundings of the products' inputs to 11 significant bits per layer)."""
+    return 1e-3
 
 
 def build_step(torch, aq, shape: wl.BlockShape, layers, x0):

@@ -55,10 +55,19 @@ def test_properties():
     assert abs(h - ho.hsic(X + 3.0, gx, Z - 1.0, gz)) < 1e-12           # the RBF kernel sees differences only
     perm = np.random.default_rng(0).permutation(96)
     assert abs(h - ho.hsic(X[perm], gx, Z[perm], gz)) < 1e-14           # the order of the paired samples is free
-    # dependence: Z is a noisy linear map of X; an independent redraw of Z is not
+    # dependence, by the permutation test built on this statistic (re-pairing the samples at random draws from the
+    # null distribution of independence; the empirical estimator is what Section 3, "HSIC", defines): Z is a noisy
+    # linear map of X, so the statistic of the true pairing lies above that of every one of 50 random re-pairings
+    # (level 1/51); for an independent redraw of Z the true pairing is exchangeable with the re-pairings and does not
+    rng = np.random.default_rng(1)
+    null = [ho.hsic(X, gx, Z[rng.permutation(96)], gz) for _ in range(50)]
+    assert h > max(null)
     _, Z2, _ = wl.draw_hsic_inputs(96, 16, 16, 4, 84)
-    h_ind = ho.hsic(X, gx, Z2, ho.median_gamma(Z2))
-    assert h > 2.0 * h_ind > 0.0                                        # (the estimator has a bias of order 1/K)
+    Z2 = Z2.astype(np.float64)
+    g2 = ho.median_gamma(Z2)
+    h_ind = ho.hsic(X, gx, Z2, g2)
+    null2 = [ho.hsic(X, gx, Z2[rng.permutation(96)], g2) for _ in range(50)]
+    assert 0.0 < h_ind < max(null2)                                     # (the estimator has a bias of order 1/K)
     assert ho.hsic(X, gx, X, gx) > h
     # constant variable: its centred kernel matrix vanishes
     assert abs(ho.hsic(X, gx, np.ones((96, 2)), 1.0)) < 1e-15
