@@ -112,6 +112,9 @@ def lib() -> ctypes.CDLL:
         L.aqc_qgemv_batch_plan_size.argtypes = [ctypes.POINTER(aqc_gemv_desc), _int, _int]
         L.aqc_qgemv_batch_plan.argtypes = [ctypes.POINTER(aqc_gemv_desc), _int, _int, _p, _sz]
         L.aqc_qgemv_batch.argtypes = [_p, _p, _p]
+        L.aqc_qgemm_workspace_size.restype = _sz
+        L.aqc_qgemm_workspace_size.argtypes = [_i64, _i64, _i64, _int]
+        L.aqc_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _pf, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
         L.aqc_unpack_codes.argtypes = [_p, _i64, _i64, _int, _int, _pf, _p, _p]
         L.aqc_dequant_f32.argtypes = [_p, _i64, _i64, _int, _int, _pf, _p, _p]
         L.aq_hsic_workspace_size.restype = _sz
@@ -480,6 +483,22 @@ class CbGemvBatch:
     def run(self, stream=None) -> None:
         _check(lib().aqc_qgemv_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), _stream(stream)),
                "aqc_qgemv_batch")
+
+
+def aqc_qgemm(packed, N: int, K: int, bits: int, levels, X, Y=None, workspace=None, block: int = BLOCK, stream=None):
+    """X: cuda bfloat16/float16 [M, K] -> Y: cuda float32 [M, N], weights fp16(d * levels[q]) (see aq.h)."""
+    import torch
+    M = X.shape[0]
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    need = int(lib().aqc_qgemm_workspace_size(M, N, K, bits))
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().aqc_qgemm(packed.data_ptr(), N, K, bits, block, _levels(levels, bits), X.data_ptr(), M, X.stride(0),
+                           _dtype_code(X), Y.data_ptr(), Y.stride(0), ws_ptr, ws_bytes, _stream(stream)), "aqc_qgemm")
+    return Y
 
 
 def aqc_unpack_codes(packed, N: int, K: int, bits: int, levels, block: int = BLOCK, stream=None):

@@ -553,6 +553,35 @@ int aq2_qgemm_fast(const void* packed, int64_t N, int64_t K, int bits, int block
     return qgemm2_one(packed, N, K, bits, block, X, M, ldx, x_dtype, Y, ldy, AQ_GEMM_FAST, workspace, workspace_bytes, stream);
 }
 
+// Codebook variant, fp16-weight prefill: the producer / consumer kernel with the table-lookup producer at every M; the
+// table (level of every stored code) goes to the last 64 bytes of the workspace first.
+size_t aqc_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits)
+{
+    const size_t base = aq_qgemm_workspace_size(M, N, K, bits);
+    return base ? base + 64 : 0;
+}
+
+int aqc_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const float* levels, const void* X, int64_t M,
+              int64_t ldx, int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = check_gemm(N, K, bits, block, M, ldx, ldy, x_dtype, packed, X, Y);
+    if (rc != AQ_OK) return rc;
+    if (!workspace || !levels) return AQ_ENULL;
+    if (!aligned16(workspace)) return AQ_EALIGN;
+    const size_t base = aq_qgemm_workspace_size(M, N, K, bits);
+    if (workspace_bytes < base + 64) return AQ_ESIZE;
+    AqCbTable table;
+    if ((rc = aqk_cb_stored_levels(levels, bits, &table)) != AQ_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* table_dev = reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + base);
+    if (aqk_cb_write_table(table, table_dev, s) != hipSuccess) return AQ_ELAUNCH;
+    const int convert = x_dtype == AQ_BF16;
+    const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
+    if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
+    const AqGemmTask t = make_pc_task(packed, N, K, bits, M, 0, Y, ldy, 0);
+    return aqk_gemm_pc(nullptr, 0, t, bits, 2, t.wg_count, workspace, s, table_dev) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+}
+
 // plan image: header, `count` product tasks, then up to `count` re-tiling tasks
 size_t aq_qgemm_batch_plan_size(int count)
 {

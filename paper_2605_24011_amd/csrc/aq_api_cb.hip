@@ -192,6 +192,15 @@ size_t cb_plan_bytes(int count, int64_t wgs)
 
 }  // namespace
 
+int aqk_cb_stored_levels(const float* levels, int bits, AqCbTable* out)
+{
+    CbInfo info;
+    int rc = analyse(levels, bits, info);
+    if (rc != AQ_OK) return rc;
+    std::memcpy(out->level, info.stored_level, sizeof(out->level));
+    return AQ_OK;
+}
+
 extern "C" {
 
 int aqc_table_info(const float* levels, int bits, int* form, float* coef)

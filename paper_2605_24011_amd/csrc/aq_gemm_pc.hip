@@ -41,12 +41,15 @@ __device__ __forceinline__ void lds_barrier()
 
 // Producer: tiles 2p, 2p+1 of the group, all chunks.  Executes nch + 1 barriers.
 // FMT 0: the base format, w = fp16(d * (q - z)).  FMT 1: the two-level variant, w = fp16(q * fp16(D a) - fp16(M c))
-// (three roundings to 11 bits instead of one: D a and M c have up to 15 significant bits).
+// (three roundings to 11 bits instead of one: D a and M c have up to 15 significant bits).  FMT 2: the codebook
+// variant, w = fp16(d * level[stored code]), the product formed in fp32 and rounded once; the table of 16 levels sits
+// in the lanes of the wavefront (lane l holds level[l % 16]) and a lookup is one cross-lane read (DS_BPERMUTE_B32).
 template <int BITS, int FMT>
-__device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, int lane, uint8_t* smem, _Float16 down)
+__device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, int lane, uint8_t* smem, _Float16 down,
+                                        const float* __restrict__ cb_table)
 {
     constexpr int WORDS = Codec<BITS>::WORDS;
-    constexpr int UNIT = 512 * BITS + (FMT ? AQ2_PARAM_BYTES : 256);
+    constexpr int UNIT = 512 * BITS + (FMT == 1 ? AQ2_PARAM_BYTES : 256);
     const int g = lane >> 4, c = lane & 15;
     const int nch = t.nchunks;
     const uint8_t* ubase = t.blob + (((int64_t)group * nch) * AQ_GROUP_TILES + 2 * p) * UNIT;
@@ -59,7 +62,7 @@ __device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, i
         for (int w = 0; w < 2; ++w) {
             const uint8_t* u = ubase + ch * chunk_stride + w * UNIT;
             Codec<BITS>::load(u, lane, raw[w]);
-            if (FMT) {
+            if (FMT == 1) {
                 const AQ_GLOBAL uint8_t* bp = as_global<uint8_t>(u + aq2_sub_offset(BITS, c >> 2, 2 * g, c & 3));
                 sc[w][0] = (uint32_t)bp[0] | ((uint32_t)bp[4] << 8);           // next block: 4 bytes on
                 sc[w][1] = *as_global<uint32_t>(u + aq2_sup_offset(BITS, c >> 2, c & 3));
@@ -71,16 +74,38 @@ __device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, i
         }
     };
     typename Codec<BITS>::Magic magic = Codec<BITS>::magic();
+    int level_bits = 0;                               // FMT 2: this lane's entry of the table
+    if (FMT == 2) level_bits = __float_as_int(cb_table[lane & 15]);
     auto unpack_to = [&](uint8_t* buf) {
         const float z = (float)(1 << (BITS - 1));
 #pragma unroll
         for (int w = 0; w < 2; ++w)
 #pragma unroll
             for (int b2 = 0; b2 < 2; ++b2) {
+                if (FMT == 2) {
+                    const float df = (float)__builtin_bit_cast(_Float16, (uint16_t)sc[w][b2]);
+                    uint8_t* dst = buf + ((2 * p + w) * 16 + c) * PC_W_ROW + (2 * g + b2) * 64;
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        uint32_t o[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int e = 2 * (4 * q4 + i);            // elements e, e + 1 of the block
+                            const int c0 = (int)aq_block_get(&raw[w][b2 * BITS], BITS, e);
+                            const int c1 = (int)aq_block_get(&raw[w][b2 * BITS], BITS, e + 1);
+                            const float l0 = __int_as_float(__builtin_amdgcn_ds_bpermute(c0 << 2, level_bits));
+                            const float l1 = __int_as_float(__builtin_amdgcn_ds_bpermute(c1 << 2, level_bits));
+                            const half2v h = {(_Float16)(l0 * df), (_Float16)(l1 * df)};
+                            o[i] = __builtin_bit_cast(uint32_t, h);
+                        }
+                        *reinterpret_cast<u32x4*>(dst + 16 * q4) = u32x4{o[0], o[1], o[2], o[3]};
+                    }
+                    continue;
+                }
                 uint32_t a[16];
                 Codec<BITS>::unpack(&raw[w][b2 * BITS], magic, a);         // fp16 pairs (magic + q)
                 _Float16 d, off = (_Float16)0.0f;
-                if (FMT) {
+                if (FMT == 1) {
                     const uint32_t ac = (sc[w][0] >> (8 * b2)) & 0xFFu, dm = sc[w][1];
                     d = (_Float16)((float)__builtin_bit_cast(_Float16, (uint16_t)(dm & 0xFFFFu)) * (float)(ac & 15u));
                     off = (_Float16)((float)__builtin_bit_cast(_Float16, (uint16_t)(dm >> 16)) * (float)(ac >> 4));
@@ -121,7 +146,8 @@ __device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, i
 // BITS_T == 0: the tasks' bit-widths differ, branch per workgroup.  FMT: see produce().
 template <int BITS_T, int FMT>
 __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* __restrict__ tasks, int count,
-                                                              AqGemmTask single, const uint8_t* __restrict__ workspace)
+                                                              AqGemmTask single, const uint8_t* __restrict__ workspace,
+                                                              const float* __restrict__ cb_table)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     AqGemmTask t;
@@ -147,7 +173,7 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
     // largest scale of the matrix (blob trailer) -> power-of-two shift that keeps d * (q - z) inside binary16
     // (blobs of the two-level variant carry no such word: their D * 15 * (2^bits - 1) must stay inside binary16)
     int sh = 0;
-    if (!FMT) {
+    if (FMT == 0) {
         const uint32_t max_d = *reinterpret_cast<const uint32_t*>(
             t.blob + (int64_t)t.slabs * nch * AQ_GROUP_TILES * aq_unit_bytes(t.bits));
         const int max_exp = (int)(max_d >> 10) - 15 + (t.bits - 1) + 1;
@@ -157,9 +183,9 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
     if (wave >= PC_CONSUMERS) {
         const _Float16 down = (_Float16)__builtin_ldexpf(1.f, -(sh < 24 ? sh : 24));
         const int p = wave - PC_CONSUMERS;
-        if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) produce<2, FMT>(t, group, p, lane, smem, down);
-        else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) produce<3, FMT>(t, group, p, lane, smem, down);
-        else produce<4, FMT>(t, group, p, lane, smem, down);
+        if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) produce<2, FMT>(t, group, p, lane, smem, down, cb_table);
+        else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) produce<3, FMT>(t, group, p, lane, smem, down, cb_table);
+        else produce<4, FMT>(t, group, p, lane, smem, down, cb_table);
         return;
     }
 
@@ -274,23 +300,36 @@ int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs)
 }
 
 // bits == 0: mixed bit-widths.  Xt: binary16, the re-tiled layout of the shared-role kernel.
-// two_level: the blobs are in the two-level variant of the format.
-hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int two_level,
-                       int total_wgs, const void* workspace, hipStream_t s)
+// format: 0 the base format, 1 the two-level variant, 2 the codebook variant (uniform bit-width only; cb_table: DEVICE,
+// 16 floats, the level of every stored code).
+hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int format,
+                       int total_wgs, const void* workspace, hipStream_t s, const float* cb_table)
 {
+    if (format == 2 && (bits < 2 || bits > 4 || !cb_table)) return hipErrorInvalidValue;
     const size_t lds = 2 * (size_t)PC_WBUF;
     const dim3 grid((unsigned)total_wgs), block(PC_THREADS);
     const uint8_t* ws = static_cast<const uint8_t*>(workspace);
 #define AQ_PC(B)                                                                                                \
     do {                                                                                                        \
-        auto k = two_level ? qgemm_pc_kernel<B, 1> : qgemm_pc_kernel<B, 0>;                                     \
+        auto k = format == 1 ? qgemm_pc_kernel<B, 1> : qgemm_pc_kernel<B, 0>;                                   \
         if (aqk_allow_lds(reinterpret_cast<const void*>(k), lds) != hipSuccess) return hipErrorInvalidValue;    \
-        hipLaunchKernelGGL(k, grid, block, lds, s, tasks_dev, count, single, ws);                               \
+        hipLaunchKernelGGL(k, grid, block, lds, s, tasks_dev, count, single, ws, cb_table);                     \
     } while (0)
+#define AQ_PC_CB(B)                                                                                             \
+    do {                                                                                                        \
+        auto k = qgemm_pc_kernel<B, 2>;                                                                         \
+        if (aqk_allow_lds(reinterpret_cast<const void*>(k), lds) != hipSuccess) return hipErrorInvalidValue;    \
+        hipLaunchKernelGGL(k, grid, block, lds, s, tasks_dev, count, single, ws, cb_table);                     \
+    } while (0)
+    if (format == 2) {
+        if (bits == 2) AQ_PC_CB(2); else if (bits == 3) AQ_PC_CB(3); else AQ_PC_CB(4);
+        return hipGetLastError();
+    }
     if (bits == 2) AQ_PC(2);
     else if (bits == 3) AQ_PC(3);
     else if (bits == 4) AQ_PC(4);
     else AQ_PC(0);
 #undef AQ_PC
+#undef AQ_PC_CB
     return hipGetLastError();
 }

@@ -80,6 +80,9 @@ hipError_t aqk_cb_unpack_codes(const void* blob, int64_t N, int64_t K, int bits,
                                hipStream_t s);
 hipError_t aqk_cb_dequant(const void* blob, int64_t N, int64_t K, int bits, const AqCbTable& stored_levels, float* out,
                           hipStream_t s);
+// the table of a codebook blob (host analysis, aq_api_cb.hip): the level of every STORED code; AQ_* status
+int aqk_cb_stored_levels(const float* levels, int bits, AqCbTable* out);
+hipError_t aqk_cb_write_table(const AqCbTable& table, float* dst, hipStream_t s);      // 16 floats to device memory
 void aqk_cb_gemv_shape(AqCbTask& t);
 bool aqk_cb_light(int form, int bits);
 hipError_t aqk_cb_gemv(const AqCbTask* tasks_dev, const int32_t* wg_task, int count, const AqCbTask& single, int mode,
@@ -160,8 +163,8 @@ int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs);
 // without conversion
 hipError_t aqk2_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int x_dtype, int A,
                      int total_wgs, const void* workspace, hipStream_t s);
-hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int two_level,
-                       int total_wgs, const void* workspace, hipStream_t s);
+hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int format,
+                       int total_wgs, const void* workspace, hipStream_t s, const float* cb_table = nullptr);
 
 // Layer-by-layer decode step.  One matrix of one stage as the kernel sees it (device-visible, 96 bytes):
 // y[n] += sum over the k of a workgroup's part of W[n][k] * f(in)[k], with f chosen by `prologue`:

@@ -211,6 +211,21 @@ hipError_t aqk_pack_remap(const uint8_t* codes, const uint16_t* scales, int64_t 
     return hipGetLastError();
 }
 
+namespace {
+
+__global__ void write_table_kernel(AqCbTable table, float* dst)
+{
+    if (threadIdx.x < 16) dst[threadIdx.x] = table.level[threadIdx.x];
+}
+
+}  // namespace
+
+hipError_t aqk_cb_write_table(const AqCbTable& table, float* dst, hipStream_t s)
+{
+    hipLaunchKernelGGL(write_table_kernel, dim3(1), dim3(64), 0, s, table, dst);
+    return hipGetLastError();
+}
+
 hipError_t aqk_cb_unpack_codes(const void* blob, int64_t N, int64_t K, int bits, uint64_t inverse_remap, uint8_t* out,
                                hipStream_t s)
 {

@@ -340,6 +340,15 @@ def test_codebook_variant_table_analysis_and_validation_without_a_gpu(L):
     assert L.aqc_qgemv(A + 8, 16, 64, 2, 32, lv, A, aq.AQ_F16, A, None) == aq.AQ_EALIGN
     assert L.aqc_qgemv(A, 16, 64, 2, 32, lv, None, aq.AQ_F16, A, None) == aq.AQ_ENULL
     assert L.aqc_unpack_codes(A, 16, 64, 2, 32, lv, None, None) == aq.AQ_ENULL
+    L.aqc_qgemm_workspace_size.restype = ctypes.c_size_t
+    L.aq_qgemm_workspace_size.restype = ctypes.c_size_t
+    wsz = L.aqc_qgemm_workspace_size(40, 64, 512, 2)
+    assert wsz == L.aq_qgemm_workspace_size(40, 64, 512, 2) + 64 and L.aqc_qgemm_workspace_size(40, 64, 500, 2) == 0
+    assert L.aqc_qgemm(A, 64, 512, 2, 32, lv, A, 40, 512, aq.AQ_F16, A, 64, A, wsz - 1, None) == aq.AQ_ESIZE
+    assert L.aqc_qgemm(A, 64, 512, 2, 32, None, A, 40, 512, aq.AQ_F16, A, 64, A, wsz, None) == aq.AQ_ENULL
+    assert L.aqc_qgemm(A, 64, 512, 2, 32, bad, A, 40, 512, aq.AQ_F16, A, 64, A, wsz, None) == aq.AQ_EINVAL
+    assert L.aqc_qgemm(A, 64, 512, 2, 32, lv, A, 40, 500, aq.AQ_F16, A, 64, A, wsz, None) == aq.AQ_EINVAL      # ldx < K
+    assert L.aqc_qgemm(A, 64, 512, 2, 32, lv, A, 40, 512, 3, A, 64, A, wsz, None) == aq.AQ_EDTYPE
     assert L.aqc_dequant_f32(A, 16, 64, 6, 32, lv, A, None) == aq.AQ_EINVAL
     # list plans: made on the host, nothing launched
     descs = (aq.aqc_gemv_desc * 2)()

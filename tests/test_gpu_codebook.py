@@ -207,3 +207,50 @@ def test_errors(gpu, cb):
     with pytest.raises(aq.AqError) as e:
         aq.aqc_qgemv(packed, N, K, 2, levels, x.float())
     assert e.value.status == aq.AQ_EDTYPE
+
+
+# ---- prefill over codebook blobs (aqc_qgemm: weights fp16(d * levels[q])) ----
+GEMM_CASES = [(8, 32, 1), (17, 96, 7), (200, 1056, 65), (128, 512, 320), (300, 4096, 300), (131, 2048, 333)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("bits", [2, 3, 4])
+@pytest.mark.parametrize("N,K,M", GEMM_CASES)
+def test_qgemm_matches_oracle(gpu, cb, oracle, bits, N, K, M, dtype):
+    torch, aq = gpu
+    codes, scales = wl.draw_matrix(N, K, bits, 89, N, K)
+    X = wl.draw_activations(M, K, dtype, 89, N, K)
+    for name, levels in tables(cb, bits):
+        packed = aq.aqc_pack_weights(dev(torch, codes), dev(torch, scales), levels, N, K, bits)
+        Y = aq.aqc_qgemm(packed, N, K, bits, levels, dev(torch, X, dtype)).cpu().numpy()
+        err = oracle.rel_l2(Y, cb.qmatmul(codes, scales, levels, N, K, bits, X, dtype))
+        assert err <= REL_L2_BAR, (name, err)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_qgemm_is_exact_when_the_binary16_weights_are(gpu, cb, oracle, bits):
+    """Levels that are multiples of 1/8, power-of-two scales, small integer activations: d * level is a binary16 number
+    and every fp32 sum is exact."""
+    torch, aq = gpu
+    N, K, M = 144, 800, 70
+    codes = wl.draw_codes(N, K, bits, 90, bits)
+    scales = wl.draw_pow2_scales(N, K, 90, bits)
+    X = wl.draw_int_activations(M, K, "f16", 90, bits)
+    for levels in (wl.draw_levels("dyadic", bits, 3), wl.draw_levels("signed_dyadic", bits, 3)):
+        packed = aq.aqc_pack_weights(dev(torch, codes), dev(torch, scales), levels, N, K, bits)
+        Y = aq.aqc_qgemm(packed, N, K, bits, levels, dev(torch, X, "f16")).cpu().numpy()
+        assert np.array_equal(Y.astype(np.float64), cb.qmatmul(codes, scales, levels, N, K, bits, X, "f16"))
+
+
+def test_qgemm_agrees_with_qgemv_row_by_row(gpu, cb, oracle):
+    torch, aq = gpu
+    N, K, M, bits = 256, 2048, 5, 4
+    codes, scales = wl.draw_matrix(N, K, bits, 91)
+    levels = cb.e2m1_levels().astype(np.float32)[::-1].copy()
+    X = wl.draw_activations(M, K, "f16", 91)
+    packed = aq.aqc_pack_weights(dev(torch, codes), dev(torch, scales), levels, N, K, bits)
+    Xd = dev(torch, X, "f16")
+    Y = aq.aqc_qgemm(packed, N, K, bits, levels, Xd).cpu().numpy()
+    for m in range(M):
+        y = aq.aqc_qgemv(packed, N, K, bits, levels, Xd[m].contiguous()).cpu().numpy()
+        assert oracle.rel_l2(Y[m], y) <= 5e-4
