@@ -117,13 +117,12 @@ std::vector<int> longest_k_first(int count, KeyFn key)
 }
 
 constexpr int64_t SMALL_M = 64;      // fast-mode products with M up to this run the streaming kernel
-// The producer / consumer kernel computes blocks of 20 m-tiles (320 rows of X) whole: used when at least 4 of 5
-// of them are real rows.
+// The producer / consumer kernel's consumers compute whole m-tile slots (2 or 3 per wavefront): used when at least 4
+// of 5 of them hold real rows.
 bool use_pc(int fast, int64_t M)
 {
     if (!fast || M <= 64) return false;
-    const int64_t tiles = (M + 15) / 16, blocks = (tiles + 19) / 20;
-    return tiles * 5 >= blocks * 20 * 4;
+    return ((M + 15) / 16) * 5 >= aqk_gemm_pc_tile_slots(M) * 4;
 }
 
 AqGemmTask make_pc_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset, float* Y,

@@ -1,22 +1,24 @@
 // Prefill, fp16-weight mode, prefill-sized M: producer and consumer wavefronts.
 //
-// The shared-role kernel (aq_gemm.hip: 8 wavefronts that all unpack and all multiply, m split 8 ways) reads the
-// whole unpacked weight tile from LDS once per wavefront: 3 MFMAs per 1 KiB LDS read, which puts LDS traffic at
-// two thirds of its peak when the matrix pipe is full -- in practice both end up half busy.  Here the 8 wavefronts
-// of a workgroup split the ROLES, one of each per SIMD:
-//   * wavefronts 0-3 (consumers) own 5 m-tiles x all 8 n-tiles each (20 m-tiles = 320 rows of X per workgroup;
-//     160 accumulator registers).  Per 32-k step a consumer reads 8 weight operands from LDS and 5 activation
-//     operands from the re-tiled X in global memory (two steps ahead) and issues 40 MFMAs: 5 MFMAs per LDS read,
-//     half the LDS traffic of the shared-role kernel, and nothing else competes for the wavefront's issue slots.
-//   * wavefronts 4-7 (producers) own 2 of the group's 8 tiles each: load the packed units two chunks ahead,
-//     unpack, multiply by the block scale in binary16 (w = d * (q - z)) and write the next chunk's tile to the
-//     other LDS buffer.  About a quarter of a chunk's time; their vector-ALU work runs under the consumers' MFMAs.
+// The shared-role kernel (aq_gemm.hip: 8 wavefronts that all unpack and all multiply) spends the issue slots of the
+// wavefronts that feed the matrix pipe on unpacking.  Here the 12 wavefronts of a workgroup split the ROLES:
+//   * wavefronts 0-7 (consumers, two per SIMD: one wavefront alone cannot issue 16x16x32 MFMAs back to back fast
+//     enough, 1.25 against 1.5 PFLOP/s in the probe) own 2 or 3 m-tiles x all 8 n-tiles each (up to 24 m-tiles =
+//     384 rows of X per workgroup; 19 tiles are dealt 3,3,3,2,2,2,2,2, so that every SIMD works through at most 5;
+//     96 accumulator registers).  Per 32-k step a consumer reads 8 weight operands from LDS and its activation
+//     operands from the re-tiled X in global memory (two steps ahead) and issues 16 or 24 MFMAs; nothing else
+//     competes for its issue slots.  The tile count is a compile-time constant of the loop instance it runs.
+//   * wavefronts 8-11 (producers, one per SIMD) own 2 of the group's 8 tiles each: load the packed units two chunks
+//     ahead, unpack, multiply by the block scale in binary16 (w = d * (q - z)) and write the next chunk's tile to the
+//     other LDS buffer.  Their vector-ALU work runs under the consumers' MFMAs.
 // One LDS-only barrier per chunk (256 k) orders "next tile written" and "current tile read".
+// (Four consumers of 5 m-tiles each, one per SIMD, 8 wavefronts in all: 3.43 ms for the M = 300 pass against 3.25 ms.)
 //
 // A matrix whose largest scale could overflow binary16 has every scale multiplied by 2^-sh first and the result by
 // 2^sh (as in the small-M kernel).  Activations: the re-tiled binary16 copy Xt with one power-of-two factor per
 // row (aq_gemm.hip's pre-pass).
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include "aq_layout.h"
 #include "aq_kernels.h"
 #include "aq_codec.h"
@@ -25,9 +27,18 @@ namespace {
 
 using namespace aqdev;
 
-constexpr int PC_THREADS = 512;
-constexpr int PC_CONSUMERS = 4;
-constexpr int PC_MT = 5;                              // m-tiles per consumer
+#ifndef AQ_PC_CONSUMERS
+#define AQ_PC_CONSUMERS 8
+#define AQ_PC_MT 3
+#define AQ_PC_MT_LOW 2
+#endif
+constexpr int PC_CONSUMERS = AQ_PC_CONSUMERS;
+constexpr int PC_THREADS = (PC_CONSUMERS + 4) * 64;
+constexpr int PC_MT = AQ_PC_MT;                       // most m-tiles per consumer
+#ifndef AQ_PC_MT_LOW
+#define AQ_PC_MT_LOW AQ_PC_MT
+#endif
+constexpr int PC_MT_LOW = AQ_PC_MT_LOW;               // the loop instance of a consumer that owns at most this many
 constexpr int PC_MBLOCK = PC_CONSUMERS * PC_MT;       // m-tiles per workgroup
 constexpr int PC_W_ROW = AQ_CHUNK_K * 2 + 32;         // LDS row stride of the weight tile: 544 B (64 j + 32: conflict-free b128 reads)
 constexpr int PC_WBUF = AQ_GROUP_ROWS * PC_W_ROW;     // one chunk's tile: 128 rows
@@ -192,7 +203,7 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
     // the consumers' MFMAs go ahead of the producers' vector-ALU work whenever both are ready to issue
     __builtin_amdgcn_s_setprio(3);
 
-    // ---- consumer `wave`: m-tiles mt0 .. mt0 + cnt - 1 (the workgroup's T <= 20 tiles dealt as evenly as they go)
+    // ---- consumer `wave`: m-tiles mt0 .. mt0 + cnt - 1 (the workgroup's T <= PC_MBLOCK tiles dealt as evenly as they go)
     const int g = lane >> 4, c = lane & 15;
     const int K = t.K, ksteps = K / AQ_BLOCK;
     const int64_t M = t.M;
@@ -202,96 +213,120 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
     const int cnt = T / PC_CONSUMERS + (wave < T % PC_CONSUMERS ? 1 : 0);
     const int mt0 = wg_first + wave * (T / PC_CONSUMERS) + (wave < T % PC_CONSUMERS ? wave : T % PC_CONSUMERS);
 
-    // X operands straight from the re-tiled copy Xt[m-tile][step][lane] (1 KiB per load), two steps ahead.  A tile
-    // the wavefront does not own re-reads its first tile (or tile 0) and is never stored; a step beyond K re-reads
-    // step 0 and is never used: no branches in the loop.
-    const AQ_GLOBAL u32x4* xp[PC_MT];
+    // The loop is compiled for a wavefront that owns PC_MT m-tiles and (PC_MT_LOW < PC_MT) for one that owns fewer: the
+    // tile count is a compile-time constant of the instance a wavefront runs (chosen once, no branch in the loop), so a
+    // wavefront with fewer tiles issues fewer MFMAs instead of recomputing a tile it does not own.
+    auto consume = [&](auto mtc) {
+        constexpr int MTC = decltype(mtc)::value;
+        // X operands straight from the re-tiled copy Xt[m-tile][step][lane] (1 KiB per load), two steps ahead.  A tile
+        // the wavefront does not own re-reads its first tile (or tile 0) and is never stored; a step beyond K re-reads
+        // step 0 and is never used: no branches in the loop.
+        const AQ_GLOBAL u32x4* xp[MTC];
 #pragma unroll
-    for (int mt = 0; mt < PC_MT; ++mt)
-        xp[mt] = as_global<u32x4>(workspace + t.xt_offset) + (int64_t)(mt < cnt ? mt0 + mt : 0) * ksteps * 64 + lane;
-    u32x4 xr[2][PC_MT];
-    auto load_x = [&](int mt, int step, u32x4& dst) {
-        const int st = step < ksteps ? step : 0;
-        dst = xp[mt][st * 64];
-    };
+        for (int mt = 0; mt < MTC; ++mt)
+            xp[mt] = as_global<u32x4>(workspace + t.xt_offset) + (int64_t)(mt < cnt ? mt0 + mt : 0) * ksteps * 64 + lane;
+        u32x4 xr[2][MTC];
+        auto load_x = [&](int mt, int step, u32x4& dst) {
+            const int st = step < ksteps ? step : 0;
+            dst = xp[mt][st * 64];
+        };
 #pragma unroll
-    for (int mt = 0; mt < PC_MT; ++mt) {
-        load_x(mt, 0, xr[0][mt]);
-        load_x(mt, 1, xr[1][mt]);
-    }
+        for (int mt = 0; mt < MTC; ++mt) {
+            load_x(mt, 0, xr[0][mt]);
+            load_x(mt, 1, xr[1][mt]);
+        }
 
-    float4v acc[PC_MT][8];
+        float4v acc[MTC][8];
 #pragma unroll
-    for (int mt = 0; mt < PC_MT; ++mt)
+        for (int mt = 0; mt < MTC; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) acc[mt][nt] = float4v{0.f, 0.f, 0.f, 0.f};
+            for (int nt = 0; nt < 8; ++nt) acc[mt][nt] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    // weight operand of n-tile nt, block blk: lane (g, c) = row nt*16 + c, k = 8g .. 8g+7 of the block
-    const int lane_off = c * PC_W_ROW + g * 16;
-    // A step is four quarters of 2 n-tiles (10 MFMAs each).  Four weight operands live in registers: the two the
-    // current quarter multiplies and the two of the next quarter, requested when the current one starts, so an LDS
-    // read has 10 MFMAs (160 cycles) to arrive.
-    u32x4 bw[2][2];
-    lds_barrier();                                    // chunk 0 is in buffer 0
+        // weight operand of n-tile nt, block blk: lane (g, c) = row nt*16 + c, k = 8g .. 8g+7 of the block
+        const int lane_off = c * PC_W_ROW + g * 16;
+        // A step is four quarters of 2 n-tiles (2 MTC MFMAs each).  Four weight operands live in registers: the two the
+        // current quarter multiplies and the two of the next quarter, requested when the current one starts, so an LDS
+        // read has a quarter's MFMAs to arrive.
+        u32x4 bw[2][2];
+        lds_barrier();                                    // chunk 0 is in buffer 0
 #pragma unroll 1
-    for (int ch = 0; ch < nch; ++ch) {
-        const uint8_t* cur = smem + (ch & 1) * PC_WBUF + lane_off;
+        for (int ch = 0; ch < nch; ++ch) {
+            const uint8_t* cur = smem + (ch & 1) * PC_WBUF + lane_off;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) bw[0][j] = *reinterpret_cast<const u32x4*>(cur + j * 16 * PC_W_ROW);
+            for (int j = 0; j < 2; ++j) bw[0][j] = *reinterpret_cast<const u32x4*>(cur + j * 16 * PC_W_ROW);
 #pragma unroll
-        for (int qs = 0; qs < 32; ++qs) {             // quarter-steps: step qs / 4, n-tiles 2 * (qs % 4), + 1
-            const int s = qs >> 2, qt = qs & 3, par = s & 1, set = qs & 1;
-            if (qs < 31) {
-                const int s2 = (qs + 1) >> 2, q2 = (qs + 1) & 3;
+            for (int qs = 0; qs < 32; ++qs) {             // quarter-steps: step qs / 4, n-tiles 2 * (qs % 4), + 1
+                const int s = qs >> 2, qt = qs & 3, par = s & 1, set = qs & 1;
+                if (qs < 31) {
+                    const int s2 = (qs + 1) >> 2, q2 = (qs + 1) & 3;
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    bw[set ^ 1][j] = *reinterpret_cast<const u32x4*>(cur + (2 * q2 + j) * 16 * PC_W_ROW + s2 * 64);
-            }
-            __builtin_amdgcn_sched_barrier(0);        // keep the reads up here, ahead of the MFMAs they overlap with
+                    for (int j = 0; j < 2; ++j)
+                        bw[set ^ 1][j] = *reinterpret_cast<const u32x4*>(cur + (2 * q2 + j) * 16 * PC_W_ROW + s2 * 64);
+                }
+                __builtin_amdgcn_sched_barrier(0);        // keep the reads up here, ahead of the MFMAs they overlap with
 #pragma unroll
-            for (int mt = 0; mt < PC_MT; ++mt) {
+                for (int mt = 0; mt < MTC; ++mt) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[mt][2 * qt + j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xr[par][mt]),
-                                                                                  __builtin_bit_cast(half8, bw[set][j]),
-                                                                                  acc[mt][2 * qt + j], 0, 0, 0);
-                // the step's last quarter has used this m-tile's activation operand: request step s + 2's (from
-                // L2: as early as possible)
-                if (qt == 3) {
-                    load_x(mt, ch * 8 + s + 2, xr[par][mt]);
-                    __builtin_amdgcn_sched_barrier(0);
+                    for (int j = 0; j < 2; ++j)
+                        acc[mt][2 * qt + j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xr[par][mt]),
+                                                                                      __builtin_bit_cast(half8, bw[set][j]),
+                                                                                      acc[mt][2 * qt + j], 0, 0, 0);
+                    // the step's last quarter has used this m-tile's activation operand: request step s + 2's (from
+                    // L2: as early as possible)
+                    if (qt == 3) {
+                        load_x(mt, ch * 8 + s + 2, xr[par][mt]);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
+            lds_barrier();                                // chunk ch read, chunk ch + 1 written
         }
-        lds_barrier();                                // chunk ch read, chunk ch + 1 written
-    }
 
-    // D[m][n]: lane (g, c) holds rows 4g .. 4g+3 of the m-tile for column c of the n-tile
-    AQ_GLOBAL float* Y = (AQ_GLOBAL float*)(uintptr_t)t.Y;
-    const int32_t* rowexp = reinterpret_cast<const int32_t*>(workspace + t.xt_offset + (int64_t)mtiles16 * 16 * K * 2);
+        // D[m][n]: lane (g, c) holds rows 4g .. 4g+3 of the m-tile for column c of the n-tile
+        AQ_GLOBAL float* Y = (AQ_GLOBAL float*)(uintptr_t)t.Y;
+        const int32_t* rowexp = reinterpret_cast<const int32_t*>(workspace + t.xt_offset + (int64_t)mtiles16 * 16 * K * 2);
 #pragma unroll
-    for (int mt = 0; mt < PC_MT; ++mt) {
-        if (mt < cnt) {
-            int e[4];
+        for (int mt = 0; mt < MTC; ++mt) {
+            if (mt < cnt) {
+                int e[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) e[r] = rowexp[(mt0 + mt) * 16 + 4 * g + r] + sh;
+                for (int r = 0; r < 4; ++r) e[r] = rowexp[(mt0 + mt) * 16 + 4 * g + r] + sh;
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt) {
-                const int64_t n = (int64_t)group * AQ_GROUP_ROWS + nt * 16 + c;
+                for (int nt = 0; nt < 8; ++nt) {
+                    const int64_t n = (int64_t)group * AQ_GROUP_ROWS + nt * 16 + c;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int64_t m = (int64_t)(mt0 + mt) * 16 + 4 * g + r;
-                    if (m < M && n < t.N) Y[m * t.ldy + n] = ldexpf(acc[mt][nt][r], e[r]);
+                    for (int r = 0; r < 4; ++r) {
+                        const int64_t m = (int64_t)(mt0 + mt) * 16 + 4 * g + r;
+                        if (m < M && n < t.N) Y[m * t.ldy + n] = ldexpf(acc[mt][nt][r], e[r]);
+                    }
                 }
             }
         }
-    }
+    };
+    if (PC_MT_LOW < PC_MT && cnt <= PC_MT_LOW) consume(std::integral_constant<int, PC_MT_LOW>{});
+    else consume(std::integral_constant<int, PC_MT>{});
 }
 
 }  // namespace
 
 
-// workgroups of a product: 128-row groups of W x blocks of 320 rows of X
+// m-tile slots the consumers of a product's workgroups compute (each runs the loop instance for PC_MT or PC_MT_LOW
+// tiles), per 128-row group: against ceil(M / 16) it says how much of the matrix-core work is spent on real rows
+int64_t aqk_gemm_pc_tile_slots(int64_t M)
+{
+    const int64_t tiles = (M + 15) / 16;
+    int64_t slots = 0;
+    for (int64_t first = 0; first < tiles; first += PC_MBLOCK) {
+        const int T = (int)(tiles - first < PC_MBLOCK ? tiles - first : PC_MBLOCK);
+        for (int w = 0; w < PC_CONSUMERS; ++w) {
+            const int cnt = T / PC_CONSUMERS + (w < T % PC_CONSUMERS ? 1 : 0);
+            slots += (PC_MT_LOW < PC_MT && cnt <= PC_MT_LOW) ? PC_MT_LOW : PC_MT;
+        }
+    }
+    return slots;
+}
+
+// workgroups of a product: 128-row groups of W x blocks of PC_MBLOCK m-tiles of X
 int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs)
 {
     const int sl = (int)aq_num_groups(N);
