@@ -38,6 +38,9 @@ constexpr int PC_MT = AQ_PC_MT;                       // most m-tiles per consum
 #ifndef AQ_PC_MT_LOW
 #define AQ_PC_MT_LOW AQ_PC_MT
 #endif
+#ifndef AQ_PC_NJ
+#define AQ_PC_NJ 2
+#endif
 constexpr int PC_MT_LOW = AQ_PC_MT_LOW;               // the loop instance of a consumer that owns at most this many
 constexpr int PC_MBLOCK = PC_CONSUMERS * PC_MT;       // m-tiles per workgroup
 constexpr int PC_W_ROW = AQ_CHUNK_K * 2 + 32;         // LDS row stride of the weight tile: 544 B (64 j + 32: conflict-free b128 reads)
@@ -247,33 +250,35 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
         // A step is four quarters of 2 n-tiles (2 MTC MFMAs each).  Four weight operands live in registers: the two the
         // current quarter multiplies and the two of the next quarter, requested when the current one starts, so an LDS
         // read has a quarter's MFMAs to arrive.
-        u32x4 bw[2][2];
+        constexpr int NJ = AQ_PC_NJ;                      // n-tiles per batch of LDS reads
+        constexpr int BPS = 8 / NJ;                       // batches per step
+        u32x4 bw[2][NJ];
         lds_barrier();                                    // chunk 0 is in buffer 0
 #pragma unroll 1
         for (int ch = 0; ch < nch; ++ch) {
             const uint8_t* cur = smem + (ch & 1) * PC_WBUF + lane_off;
 #pragma unroll
-            for (int j = 0; j < 2; ++j) bw[0][j] = *reinterpret_cast<const u32x4*>(cur + j * 16 * PC_W_ROW);
+            for (int j = 0; j < NJ; ++j) bw[0][j] = *reinterpret_cast<const u32x4*>(cur + j * 16 * PC_W_ROW);
 #pragma unroll
-            for (int qs = 0; qs < 32; ++qs) {             // quarter-steps: step qs / 4, n-tiles 2 * (qs % 4), + 1
-                const int s = qs >> 2, qt = qs & 3, par = s & 1, set = qs & 1;
-                if (qs < 31) {
-                    const int s2 = (qs + 1) >> 2, q2 = (qs + 1) & 3;
+            for (int qs = 0; qs < 8 * BPS; ++qs) {        // batches: step qs / BPS, n-tiles NJ * (qs % BPS) .. + NJ - 1
+                const int s = qs / BPS, qt = qs % BPS, par = s & 1, set = qs & 1;
+                if (qs < 8 * BPS - 1) {
+                    const int s2 = (qs + 1) / BPS, q2 = (qs + 1) % BPS;
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        bw[set ^ 1][j] = *reinterpret_cast<const u32x4*>(cur + (2 * q2 + j) * 16 * PC_W_ROW + s2 * 64);
+                    for (int j = 0; j < NJ; ++j)
+                        bw[set ^ 1][j] = *reinterpret_cast<const u32x4*>(cur + (NJ * q2 + j) * 16 * PC_W_ROW + s2 * 64);
                 }
                 __builtin_amdgcn_sched_barrier(0);        // keep the reads up here, ahead of the MFMAs they overlap with
 #pragma unroll
                 for (int mt = 0; mt < MTC; ++mt) {
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        acc[mt][2 * qt + j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xr[par][mt]),
+                    for (int j = 0; j < NJ; ++j)
+                        acc[mt][NJ * qt + j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, xr[par][mt]),
                                                                                       __builtin_bit_cast(half8, bw[set][j]),
-                                                                                      acc[mt][2 * qt + j], 0, 0, 0);
-                    // the step's last quarter has used this m-tile's activation operand: request step s + 2's (from
+                                                                                      acc[mt][NJ * qt + j], 0, 0, 0);
+                    // the step's last batch has used this m-tile's activation operand: request step s + 2's (from
                     // L2: as early as possible)
-                    if (qt == 3) {
+                    if (qt == BPS - 1) {
                         load_x(mt, ch * 8 + s + 2, xr[par][mt]);
                         __builtin_amdgcn_sched_barrier(0);
                     }
