@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaq.so")
-SOURCES = ["aq_api.hip", "aq_api_cb.hip", "aq_pack.hip", "aq_gemv.hip", "aq_gemv_cb.hip", "aq_gemv2.hip", "aq_gemm.hip", "aq_gemm2.hip", "aq_gemm_small.hip", "aq_gemm_pc.hip", "aq_quant.hip",
+SOURCES = ["aq_api.hip", "aq_api_cb.hip", "aq_pack.hip", "aq_gemv.hip", "aq_gemv_cb.hip", "aq_gemv2.hip", "aq_gemm.hip", "aq_gemm2.hip", "aq_gemm_small.hip", "aq_gemm_pc.hip", "aq_gemm_pcx.hip", "aq_quant.hip",
            "aq_layer.hip", "aq_hsic.hip"]
 
 HIPCC_FLAGS = [

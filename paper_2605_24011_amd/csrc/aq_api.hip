@@ -57,7 +57,7 @@ struct GemmPlanHeader {
     int32_t nsplit;          // wavefronts along n, from the largest M
     int32_t fast;            // fp16-weight mode
     int32_t small_mt;        // > 0: the small-M streaming kernel with that many m-tiles (fast mode, M <= 64)
-    int32_t pc;              // the producer / consumer kernel (fast mode, prefill-sized M)
+    int32_t pc;              // a producer / consumer kernel (prefill-sized M; fast: aq_gemm_pc.hip, exact: aq_gemm_pcx.hip)
     int32_t format;          // 0: base format, 1: two-level variant (fast: the producer / consumer kernel; exact: aq_gemm2.hip)
     int32_t reserved;
 };
@@ -121,8 +121,8 @@ constexpr int64_t SMALL_M = 64;      // fast-mode products with M up to this run
 // of 5 of them hold real rows.
 bool use_pc(int fast, int64_t M)
 {
-    if (!fast || M <= 64) return false;
-    return ((M + 15) / 16) * 5 >= aqk_gemm_pc_tile_slots(M) * 4;
+    if (M <= 64) return false;
+    return ((M + 15) / 16) * 5 >= (fast ? aqk_gemm_pc_tile_slots(M) : aqk_gemm_pcx_tile_slots(M)) * 4;
 }
 
 AqGemmTask make_pc_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset, float* Y,
@@ -139,6 +139,15 @@ AqGemmTask make_pc_task(const void* packed, int64_t N, int64_t K, int bits, int6
     t.wg_begin = wg_begin;
     t.wg_count = aqk_gemm_pc_wg_count(N, M, &slabs);
     t.slabs = slabs;
+    return t;
+}
+
+AqGemmTask make_pcx_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset, float* Y,
+                         int64_t ldy, int wg_begin)
+{
+    AqGemmTask t = make_pc_task(packed, N, K, bits, M, xt_offset, Y, ldy, wg_begin);
+    int slabs = 0;
+    t.wg_count = aqk_gemm_pcx_wg_count(N, M, &slabs);
     return t;
 }
 
@@ -483,6 +492,10 @@ static int qgemm_one(const void* packed, int64_t N, int64_t K, int bits, int blo
     const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
     if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
     if (use_pc(fast, M)) {
+        if (!fast) {
+            const AqGemmTask t = make_pcx_task(packed, N, K, bits, M, 0, Y, ldy, 0);
+            return aqk_gemm_pcx(nullptr, 0, t, bits, x_dtype, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+        }
         const AqGemmTask t = make_pc_task(packed, N, K, bits, M, 0, Y, ldy, 0);
         return aqk_gemm_pc(nullptr, 0, t, bits, 0, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     }
@@ -646,6 +659,7 @@ static int gemm_plan(const aq_gemm_desc* descs, int count, int block, int flags,
             if (rt.back().blocks > h.retile_max_blocks) h.retile_max_blocks = rt.back().blocks;
         }
         AqGemmTask t = h.small_mt ? make_small_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, (int)begin)
+                       : (h.pc && !h.fast) ? make_pcx_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, (int)begin)
                        : h.pc ? make_pc_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, (int)begin)
                                   : make_gemm_task(d.packed, d.N, d.K, d.bits, d.M, off, d.Y, d.ldy, h.mtiles, h.nsplit, (int)begin);
         begin += t.wg_count;
@@ -681,7 +695,7 @@ static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
            (h.nsplit == 1 || ((h.nsplit == 2 || h.nsplit == 4 || h.nsplit == 8) && h.mtiles == 1)) &&
            (h.fast == 0 || h.fast == 1) &&
            (h.small_mt == 0 || h.small_mt == 1 || h.small_mt == 2 || (h.small_mt == 4 && h.fast == 1)) &&
-           (h.pc == 0 || (h.pc == 1 && h.fast == 1 && h.small_mt == 0)) &&
+           (h.pc == 0 || (h.pc == 1 && h.small_mt == 0)) &&
            (h.format == 0 || (h.format == 1 && h.pc == h.fast && h.small_mt == 0));
 }
 
@@ -717,6 +731,8 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
     }
     if (aqk_retile(rtasks, h.retile_count, rnone, h.retile_max_blocks, convert, workspace, s) != hipSuccess)
         return AQ_ELAUNCH;
+    if (h.pc && !h.fast)
+        return aqk_gemm_pcx(tasks, h.count, none, h.bits, h.x_dtype, h.total_wgs, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     if (h.pc)
         return aqk_gemm_pc(tasks, h.count, none, h.bits, h.format, h.total_wgs, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     if (h.format == 1)

@@ -160,6 +160,11 @@ hipError_t aqk_gemm_small(const AqGemmTask* tasks_dev, int count, const AqGemmTa
 // Xt + rowexp that aqk_retile writes; a task's wg_count = aqk_gemm_pc_wg_count (128-row groups x blocks of 320 rows).
 int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs);
 int64_t aqk_gemm_pc_tile_slots(int64_t M);
+// exact products, producer / consumer wavefronts (aq_gemm_pcx.hip); tasks as for aqk_gemm_pc with the counts below
+int64_t aqk_gemm_pcx_tile_slots(int64_t M);
+int aqk_gemm_pcx_wg_count(int64_t N, int64_t M, int* slabs);
+hipError_t aqk_gemm_pcx(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype,
+                        int total_wgs, const void* workspace, hipStream_t s);
 // exact products for blobs of the two-level variant (aq_gemm2.hip); tasks as for aqk_gemm with nsplit = 1, X re-tiled
 // without conversion
 hipError_t aqk2_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int x_dtype, int A,
