@@ -107,6 +107,38 @@ int main()
         for (int b : bits) CHECK(b == 4);
     }
 
+    // codebook variant: table analysis for every form, list plans with exact-size buffers
+    {
+        const float e2m1[16] = {0.f, .5f, 1.f, 1.5f, 2.f, 3.f, 4.f, 6.f, -0.f, -.5f, -1.f, -1.5f, -2.f, -3.f, -4.f, -6.f};
+        const float sym3[8] = {-2.1f, -1.3f, -.7f, -.2f, .2f, .7f, 1.3f, 2.1f};
+        const float gen2[4] = {-1.f, .1f, .2f, 5.f};
+        int form = -1;
+        float coef[16];
+        CHECK(aqc_table_info(e2m1, 4, &form, coef) == AQ_OK && form == AQC_FORM_NATIVE);
+        CHECK(aqc_table_info(sym3, 3, &form, coef) == AQ_OK && form == AQC_FORM_SIGNED);
+        CHECK(aqc_table_info(gen2, 2, &form, coef) == AQ_OK && form == AQC_FORM_PLANES);
+        CHECK(aqc_table_info(gen2, 2, nullptr, nullptr) == AQ_OK);
+        std::vector<aqc_gemv_desc> d(5);
+        const float* tabs[5] = {e2m1, sym3, gen2, e2m1, sym3};
+        const int bits[5] = {4, 3, 2, 4, 3};
+        for (int i = 0; i < 5; ++i) {
+            d[i].product.packed = dev(3 * i); d[i].product.x = dev(3 * i + 1); d[i].product.y = (float*)dev(3 * i + 2);
+            d[i].product.N = 1 + 300 * i; d[i].product.K = 32 * (1 + 100 * i); d[i].product.bits = bits[i];
+            d[i].product.x_dtype = AQ_F16;
+            d[i].levels = tabs[i];
+        }
+        const size_t bytes = aqc_qgemv_batch_plan_size(d.data(), 5, 32);
+        CHECK(bytes > 0);
+        void* plan = std::malloc(bytes);
+        CHECK(aqc_qgemv_batch_plan(d.data(), 5, 32, plan, bytes) == AQ_OK);
+        CHECK(aqc_qgemv_batch_plan(d.data(), 5, 32, plan, bytes - 1) == AQ_ESIZE);
+        CHECK(aqc_qgemv_batch(plan, nullptr, nullptr) == AQ_ENULL);
+        std::free(plan);
+        CHECK(aqc_qgemm_workspace_size(300, 4096, 4096, 4) > aq_qgemm_workspace_size(300, 4096, 4096, 4));
+        CHECK(aqc_qgemm(dev(0), 64, 512, 2, 32, gen2, dev(1), 40, 512, AQ_F16, (float*)dev(2), 64, dev(3), 16, nullptr) == AQ_ESIZE);
+        CHECK(aqc_qgemv(dev(0), 16, 64, 2, 32, nullptr, dev(1), AQ_F16, (float*)dev(2), nullptr) == AQ_ENULL);
+    }
+
     // argument checks of the launching entry points: every call below must be turned away on the host
     CHECK(aq_qgemv(nullptr, 16, 32, 2, 32, dev(1), AQ_F16, (float*)dev(2), nullptr) == AQ_ENULL);
     CHECK(aq_qgemv(dev(0), 16, 33, 2, 32, dev(1), AQ_F16, (float*)dev(2), nullptr) == AQ_EINVAL);
