@@ -282,8 +282,7 @@ int aq2_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int bloc
  * aqc_qgemv / aqc_unpack_codes / aqc_dequant_f32 are aq_qgemv / aq_unpack_codes / aq_dequant_f32 for such a blob
  * (aqc_unpack_codes returns the caller's codes, whatever the stored numbering).  A list of products runs in one launch:
  * aqc_qgemv_batch_plan_size / aqc_qgemv_batch_plan (HOST) / copy the image to 16-byte-aligned DEVICE memory /
- * aqc_qgemv_batch, as for aq_qgemv_batch; the tables are read when the plan is made.  K has no upper limit here
- * beyond 2^24 in the decode calls.
+ * aqc_qgemv_batch, as for aq_qgemv_batch; the tables are read when the plan is made.
  * aqc_qgemm is aq_qgemm_fast for such a blob, at any M in 1 .. AQ_MAX_M: a weight meets X as the binary16 number
  * fp16(d * levels[q]), the product formed in fp32 and rounded once (the caller keeps |d * levels[q]| inside binary16's
  * range, 65504: there is no rescaling), X as in aq_qgemm_fast; there is no exact-product form and no list form of it.
