@@ -19,8 +19,6 @@
 #include "aq_gemv_digit.h"
 #include <type_traits>
 
-#define AQ_TRACE(slot) do { } while (0)      // hook of the shared body for timestamp experiments; unused
-
 namespace {
 
 using namespace aqdev;

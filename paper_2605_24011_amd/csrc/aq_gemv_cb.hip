@@ -24,8 +24,6 @@
 #include "aq_codec.h"
 #include "aq_gemv_digit.h"
 
-#define AQ_TRACE(slot) do { } while (0)
-
 namespace {
 
 using namespace aqdev;
