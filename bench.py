@@ -360,6 +360,21 @@ def main():
                 "prefill_tokens_per_s": round(M / (ms * 1e-3), 1),
             }
             del gbatch
+        # a lone product (one 4096 x 4096 matrix at 4 bits, M = 300: 32 row groups for 256 compute units; the library
+        # cuts m into more workgroups for such a call)
+        codes1, scales1 = wl.draw_matrix_torch(4096, 4096, 4, "cuda", 21)
+        packed1 = aq.aq_pack_weights(codes1, scales1, 4096, 4096, 4)
+        X1 = wl.draw_activations_torch(M, 4096, "bf16", "cuda", 21)
+        Y1 = torch.empty((M, 4096), dtype=torch.float32, device="cuda")
+        ws1 = torch.empty(aq.aq_qgemm_workspace_size(M, 4096, 4096, 4), dtype=torch.uint8, device="cuda")
+        lone = {}
+        for mode, fast in (("exact", False), ("fast", True)):
+            fn = lambda: aq.aq_qgemm(packed1, 4096, 4096, 4, X1, Y1, ws1, fast=fast)
+            d, w = time_launches(torch, fn, 30, 5)
+            us = sum(d) / len(d) * 1e3
+            lone[mode] = {"per_call_us": round(us, 1), "TFLOP/s": round(2.0 * M * 4096 * 4096 / (us * 1e-6) / 1e12, 1)}
+        pre["lone_4096x4096_b4"] = lone
+        del codes1, scales1, packed1, X1, Y1, ws1
         # calibration: what the matrix cores sustain on THIS part for the two binary16 MFMA shapes with random operand
         # data and nothing else running (the part clocks down under such data; with constant data it nearly reaches the
         # published rate) -- the ceiling the fp16-weight kernels work against.  The probe is a bench-only library of

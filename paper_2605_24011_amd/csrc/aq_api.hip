@@ -117,16 +117,16 @@ std::vector<int> longest_k_first(int count, KeyFn key)
 }
 
 constexpr int64_t SMALL_M = 64;      // fast-mode products with M up to this run the streaming kernel
-// The producer / consumer kernel's consumers compute whole m-tile slots (2 or 3 per wavefront): used when at least 4
-// of 5 of them hold real rows.
-bool use_pc(int fast, int64_t M)
+// The producer / consumer kernels' consumers compute whole m-tile slots (1, 2 or 3 per wavefront): used when at least 3
+// of 4 of them hold real rows.
+bool use_pc(int fast, int64_t M, int per = 0)
 {
     if (M <= 64) return false;
-    return ((M + 15) / 16) * 5 >= (fast ? aqk_gemm_pc_tile_slots(M) : aqk_gemm_pcx_tile_slots(M)) * 4;
+    return ((M + 15) / 16) * 4 >= (fast ? aqk_gemm_pc_tile_slots(M, per) : aqk_gemm_pcx_tile_slots(M, per)) * 3;
 }
 
 AqGemmTask make_pc_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset, float* Y,
-                        int64_t ldy, int wg_begin)
+                        int64_t ldy, int wg_begin, int per = 0)
 {
     AqGemmTask t;
     std::memset(&t, 0, sizeof(t));
@@ -137,17 +137,18 @@ AqGemmTask make_pc_task(const void* packed, int64_t N, int64_t K, int bits, int6
     t.K = (int32_t)K; t.bits = bits; t.nchunks = (int32_t)aq_num_chunks(K);
     int slabs = 0;
     t.wg_begin = wg_begin;
-    t.wg_count = aqk_gemm_pc_wg_count(N, M, &slabs);
+    t.wg_count = aqk_gemm_pc_wg_count(N, M, per, &slabs);
     t.slabs = slabs;
+    t.pad[0] = per;
     return t;
 }
 
 AqGemmTask make_pcx_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset, float* Y,
-                         int64_t ldy, int wg_begin)
+                         int64_t ldy, int wg_begin, int per = 0)
 {
-    AqGemmTask t = make_pc_task(packed, N, K, bits, M, xt_offset, Y, ldy, wg_begin);
+    AqGemmTask t = make_pc_task(packed, N, K, bits, M, xt_offset, Y, ldy, wg_begin, per);
     int slabs = 0;
-    t.wg_count = aqk_gemm_pcx_wg_count(N, M, &slabs);
+    t.wg_count = aqk_gemm_pcx_wg_count(N, M, per, &slabs);
     return t;
 }
 
@@ -491,12 +492,13 @@ static int qgemm_one(const void* packed, int64_t N, int64_t K, int bits, int blo
     }
     const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
     if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
-    if (use_pc(fast, M)) {
+    const int per = aqk_gemm_pc_tiles_per_wg(M, aq_num_groups(N));      // a lone matrix: fewer m-tiles per workgroup
+    if (use_pc(fast, M, per)) {
         if (!fast) {
-            const AqGemmTask t = make_pcx_task(packed, N, K, bits, M, 0, Y, ldy, 0);
+            const AqGemmTask t = make_pcx_task(packed, N, K, bits, M, 0, Y, ldy, 0, per);
             return aqk_gemm_pcx(nullptr, 0, t, bits, x_dtype, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
         }
-        const AqGemmTask t = make_pc_task(packed, N, K, bits, M, 0, Y, ldy, 0);
+        const AqGemmTask t = make_pc_task(packed, N, K, bits, M, 0, Y, ldy, 0, per);
         return aqk_gemm_pc(nullptr, 0, t, bits, 0, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     }
     const int A = aqk_gemm_mtiles(M, aq_num_groups(N)), nsplit = aqk_gemm_nsplit(M);

@@ -211,8 +211,9 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
     const int K = t.K, ksteps = K / AQ_BLOCK;
     const int64_t M = t.M;
     const int mtiles16 = (int)((M + 15) >> 4);
-    const int wg_first = mblock * PC_MBLOCK;
-    const int T = mtiles16 - wg_first < PC_MBLOCK ? mtiles16 - wg_first : PC_MBLOCK;
+    const int per = t.pad[0] ? (int)t.pad[0] : PC_MBLOCK;       // m-tiles per workgroup (fewer than the most for a lone matrix)
+    const int wg_first = mblock * per;
+    const int T = mtiles16 - wg_first < per ? mtiles16 - wg_first : per;
     const int cnt = T / PC_CONSUMERS + (wave < T % PC_CONSUMERS ? 1 : 0);
     const int mt0 = wg_first + wave * (T / PC_CONSUMERS) + (wave < T % PC_CONSUMERS ? wave : T % PC_CONSUMERS);
 
@@ -308,7 +309,8 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
             }
         }
     };
-    if (PC_MT_LOW < PC_MT && cnt <= PC_MT_LOW) consume(std::integral_constant<int, PC_MT_LOW>{});
+    if (cnt <= 1) consume(std::integral_constant<int, 1>{});
+    else if (PC_MT_LOW < PC_MT && cnt <= PC_MT_LOW) consume(std::integral_constant<int, PC_MT_LOW>{});
     else consume(std::integral_constant<int, PC_MT>{});
 }
 
@@ -317,26 +319,38 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
 
 // m-tile slots the consumers of a product's workgroups compute (each runs the loop instance for PC_MT or PC_MT_LOW
 // tiles), per 128-row group: against ceil(M / 16) it says how much of the matrix-core work is spent on real rows
-int64_t aqk_gemm_pc_tile_slots(int64_t M)
+int64_t aqk_gemm_pc_tile_slots(int64_t M, int per)
 {
     const int64_t tiles = (M + 15) / 16;
+    if (per <= 0 || per > PC_MBLOCK) per = PC_MBLOCK;
     int64_t slots = 0;
-    for (int64_t first = 0; first < tiles; first += PC_MBLOCK) {
-        const int T = (int)(tiles - first < PC_MBLOCK ? tiles - first : PC_MBLOCK);
+    for (int64_t first = 0; first < tiles; first += per) {
+        const int T = (int)(tiles - first < per ? tiles - first : per);
         for (int w = 0; w < PC_CONSUMERS; ++w) {
             const int cnt = T / PC_CONSUMERS + (w < T % PC_CONSUMERS ? 1 : 0);
-            slots += (PC_MT_LOW < PC_MT && cnt <= PC_MT_LOW) ? PC_MT_LOW : PC_MT;
+            slots += cnt <= 1 ? 1 : (PC_MT_LOW < PC_MT && cnt <= PC_MT_LOW) ? PC_MT_LOW : PC_MT;
         }
     }
     return slots;
 }
 
+// m-tiles per workgroup for a launch with `groups` 128-row groups in all: the most (24), unless that leaves most of the
+// chip idle (a lone matrix): then 16 or 8, each workgroup unpacking the weights again
+int aqk_gemm_pc_tiles_per_wg(int64_t M, int64_t groups)
+{
+    const int64_t tiles = (M + 15) / 16;
+    for (int per = PC_MBLOCK; per > 8; per -= 8)
+        if (groups * ((tiles + per - 1) / per) >= 192) return per;
+    return 8;
+}
+
 // workgroups of a product: 128-row groups of W x blocks of PC_MBLOCK m-tiles of X
-int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs)
+int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int per, int* slabs)
 {
     const int sl = (int)aq_num_groups(N);
     if (slabs) *slabs = sl;
-    return sl * (int)((M + PC_MBLOCK * 16 - 1) / (PC_MBLOCK * 16));
+    if (per <= 0 || per > PC_MBLOCK) per = PC_MBLOCK;
+    return sl * (int)(((M + 15) / 16 + per - 1) / per);
 }
 
 // bits == 0: mixed bit-widths.  Xt: binary16, the re-tiled layout of the shared-role kernel.

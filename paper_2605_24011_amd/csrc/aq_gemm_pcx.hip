@@ -146,8 +146,9 @@ __global__ __launch_bounds__(PX_THREADS) void qgemm_pcx_kernel(const AqGemmTask*
     const int K = t.K, ksteps = K / AQ_BLOCK;
     const int64_t M = t.M;
     const int mtiles16 = (int)((M + 15) >> 4);
-    const int wg_first = mblock * PX_MBLOCK;
-    const int T = mtiles16 - wg_first < PX_MBLOCK ? mtiles16 - wg_first : PX_MBLOCK;
+    const int per = t.pad[0] ? (int)t.pad[0] : PX_MBLOCK;       // m-tiles per workgroup (fewer than the most for a lone matrix)
+    const int wg_first = mblock * per;
+    const int T = mtiles16 - wg_first < per ? mtiles16 - wg_first : per;
     const int cnt = T / PX_CONSUMERS + (wave < T % PX_CONSUMERS ? 1 : 0);
     const int mt0 = wg_first + wave * (T / PX_CONSUMERS) + (wave < T % PX_CONSUMERS ? wave : T % PX_CONSUMERS);
 
@@ -249,33 +250,36 @@ __global__ __launch_bounds__(PX_THREADS) void qgemm_pcx_kernel(const AqGemmTask*
             }
         }
     };
-    if (cnt <= PX_MT_LOW) consume(std::integral_constant<int, PX_MT_LOW>{});
+    if (cnt <= 1) consume(std::integral_constant<int, 1>{});
+    else if (cnt <= PX_MT_LOW) consume(std::integral_constant<int, PX_MT_LOW>{});
     else consume(std::integral_constant<int, PX_MT>{});
 }
 
 }  // namespace
 
 // m-tile slots the consumers of a product's workgroups compute, per 128-row group (see aqk_gemm_pc_tile_slots)
-int64_t aqk_gemm_pcx_tile_slots(int64_t M)
+int64_t aqk_gemm_pcx_tile_slots(int64_t M, int per)
 {
     const int64_t tiles = (M + 15) / 16;
+    if (per <= 0 || per > PX_MBLOCK) per = PX_MBLOCK;
     int64_t slots = 0;
-    for (int64_t first = 0; first < tiles; first += PX_MBLOCK) {
-        const int T = (int)(tiles - first < PX_MBLOCK ? tiles - first : PX_MBLOCK);
+    for (int64_t first = 0; first < tiles; first += per) {
+        const int T = (int)(tiles - first < per ? tiles - first : per);
         for (int w = 0; w < PX_CONSUMERS; ++w) {
             const int cnt = T / PX_CONSUMERS + (w < T % PX_CONSUMERS ? 1 : 0);
-            slots += cnt <= PX_MT_LOW ? PX_MT_LOW : PX_MT;
+            slots += cnt <= 1 ? 1 : cnt <= PX_MT_LOW ? PX_MT_LOW : PX_MT;
         }
     }
     return slots;
 }
 
 // workgroups of a product: 128-row groups of W x blocks of PX_MBLOCK m-tiles of X
-int aqk_gemm_pcx_wg_count(int64_t N, int64_t M, int* slabs)
+int aqk_gemm_pcx_wg_count(int64_t N, int64_t M, int per, int* slabs)
 {
     const int sl = (int)aq_num_groups(N);
     if (slabs) *slabs = sl;
-    return sl * (int)((M + PX_MBLOCK * 16 - 1) / (PX_MBLOCK * 16));
+    if (per <= 0 || per > PX_MBLOCK) per = PX_MBLOCK;
+    return sl * (int)(((M + 15) / 16 + per - 1) / per);
 }
 
 // bits == 0: mixed bit-widths.  Xt: the activations as given (binary16 or bf16), the re-tiled layout of aq_gemm.hip.

@@ -158,11 +158,13 @@ hipError_t aqk_gemm_small(const AqGemmTask* tasks_dev, int count, const AqGemmTa
 
 // Prefill, fp16-weight mode, prefill-sized M: producer / consumer wavefronts (aq_gemm_pc.hip).  Reads the binary16
 // Xt + rowexp that aqk_retile writes; a task's wg_count = aqk_gemm_pc_wg_count (128-row groups x blocks of 320 rows).
-int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int* slabs);
-int64_t aqk_gemm_pc_tile_slots(int64_t M);
+// per = m-tiles per workgroup (0: the most, 24), carried by a task in pad[0]; both producer / consumer kernels alike
+int aqk_gemm_pc_tiles_per_wg(int64_t M, int64_t groups);   // groups = 128-row groups over all products of the launch
+int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int per, int* slabs);
+int64_t aqk_gemm_pc_tile_slots(int64_t M, int per);
 // exact products, producer / consumer wavefronts (aq_gemm_pcx.hip); tasks as for aqk_gemm_pc with the counts below
-int64_t aqk_gemm_pcx_tile_slots(int64_t M);
-int aqk_gemm_pcx_wg_count(int64_t N, int64_t M, int* slabs);
+int64_t aqk_gemm_pcx_tile_slots(int64_t M, int per);
+int aqk_gemm_pcx_wg_count(int64_t N, int64_t M, int per, int* slabs);
 hipError_t aqk_gemm_pcx(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype,
                         int total_wgs, const void* workspace, hipStream_t s);
 // exact products for blobs of the two-level variant (aq_gemm2.hip); tasks as for aqk_gemm with nsplit = 1, X re-tiled

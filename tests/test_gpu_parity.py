@@ -458,9 +458,10 @@ def test_qgemm_fast_row_factors_and_large_scales(gpu, oracle):
     big = wl.f32_to_f16_bits(np.ldexp(wl.f16_bits_to_f32(scales), 19))
     assert wl.f16_bits_to_f32(big).max() > 8192 and np.isfinite(wl.f16_bits_to_f32(big)).all()
     packed = _pack(torch, aq, codes, big, N, K, bits)
-    # M > 64: the workgroups take the exact path (no weight is rounded); M <= 64 runs the streaming kernel, which
-    # scales every d by a power of two before the binary16 product instead
-    for M2, bar in ((100, 2e-5), (M, FAST_EXPECTED[bits])):
+    # 64 < M with too few m-tiles for the producer / consumer kernel (M = 70: 5 tiles): the shared-role kernel, whose
+    # workgroups take the exact path for such a matrix (no weight is rounded); the producer / consumer kernel (M = 100)
+    # and the streaming kernel (M <= 64) scale every d by a power of two before the binary16 product instead
+    for M2, bar in ((70, 2e-5), (100, FAST_EXPECTED[bits]), (M, FAST_EXPECTED[bits])):
         X = wl.draw_activations(M2, K, "bf16", 21, M2)
         Y = aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, "bf16"), fast=True).cpu().numpy()
         ref = oracle.qmatmul(codes, big, N, K, bits, X, "bf16")
