@@ -285,8 +285,11 @@ int aq2_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int bloc
  * aqc_qgemv_batch, as for aq_qgemv_batch; the tables are read when the plan is made.
  * aqc_qgemm is aq_qgemm_fast for such a blob, at any M in 1 .. AQ_MAX_M: a weight meets X as the binary16 number
  * fp16(d * levels[q]), the product formed in fp32 and rounded once (the caller keeps |d * levels[q]| inside binary16's
- * range, 65504: there is no rescaling), X as in aq_qgemm_fast; there is no exact-product form and no list form of it.
- * Workspace: aqc_qgemm_workspace_size(M, N, K, bits) bytes (the re-ordered X and the table).
+ * range, 65504: there is no rescaling), X as in aq_qgemm_fast; there is no exact-product form of it.
+ * Workspace: aqc_qgemm_workspace_size(M, N, K, bits) bytes (the re-ordered X and the table).  A list of such products
+ * runs like a list of the base format's: aqc_qgemm_batch_plan writes aqc_qgemm_batch_plan_size(count) bytes on the HOST
+ * (the base plan image followed by the tables), the caller copies the image to 16-byte-aligned DEVICE memory, provides
+ * aq_qgemm_batch_workspace_size(plan_host) bytes of workspace and launches with aq_qgemm_batch.
  * Arguments, ownership and errors otherwise as for the base functions; AQ_EINVAL also for a table with an infinity or
  * a NaN. */
 typedef struct aqc_gemv_desc {
@@ -304,6 +307,12 @@ int aqc_qgemv(const void* packed, int64_t N, int64_t K, int bits, int block, con
 size_t aqc_qgemv_batch_plan_size(const aqc_gemv_desc* descs /*HOST*/, int count, int block);
 int aqc_qgemv_batch_plan(const aqc_gemv_desc* descs /*HOST*/, int count, int block, void* plan_host, size_t plan_bytes);
 int aqc_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
+typedef struct aqc_gemm_desc {
+    aq_gemm_desc product;  /* packed: a blob from aqc_pack_weights */
+    const float* levels;   /* HOST float [2^bits] */
+} aqc_gemm_desc;
+size_t aqc_qgemm_batch_plan_size(int count);
+int aqc_qgemm_batch_plan(const aqc_gemm_desc* descs /*HOST*/, int count, int block, void* plan_host, size_t plan_bytes);
 size_t aqc_qgemm_workspace_size(int64_t M, int64_t N, int64_t K, int bits);
 int aqc_qgemm(const void* packed, int64_t N, int64_t K, int bits, int block, const float* levels /*HOST*/, const void* X,
               int64_t M, int64_t ldx, int x_dtype, float* Y, int64_t ldy, void* workspace, size_t workspace_bytes,

@@ -55,6 +55,10 @@ class aq_gemm_desc(ctypes.Structure):
                 ("ldy", _i64), ("bits", ctypes.c_int32), ("x_dtype", ctypes.c_int32)]
 
 
+class aqc_gemm_desc(ctypes.Structure):
+    _fields_ = [("product", aq_gemm_desc), ("levels", _p)]
+
+
 def lib() -> ctypes.CDLL:
     """The loaded C library; raises if it has not been built."""
     global _lib
@@ -112,6 +116,9 @@ def lib() -> ctypes.CDLL:
         L.aqc_qgemv_batch_plan_size.argtypes = [ctypes.POINTER(aqc_gemv_desc), _int, _int]
         L.aqc_qgemv_batch_plan.argtypes = [ctypes.POINTER(aqc_gemv_desc), _int, _int, _p, _sz]
         L.aqc_qgemv_batch.argtypes = [_p, _p, _p]
+        L.aqc_qgemm_batch_plan_size.restype = _sz
+        L.aqc_qgemm_batch_plan_size.argtypes = [_int]
+        L.aqc_qgemm_batch_plan.argtypes = [ctypes.POINTER(aqc_gemm_desc), _int, _int, _p, _sz]
         L.aqc_qgemm_workspace_size.restype = _sz
         L.aqc_qgemm_workspace_size.argtypes = [_i64, _i64, _i64, _int]
         L.aqc_qgemm.argtypes = [_p, _i64, _i64, _int, _int, _pf, _p, _i64, _i64, _int, _p, _i64, _p, _sz, _p]
@@ -499,6 +506,36 @@ def aqc_qgemm(packed, N: int, K: int, bits: int, levels, X, Y=None, workspace=No
     _check(lib().aqc_qgemm(packed.data_ptr(), N, K, bits, block, _levels(levels, bits), X.data_ptr(), M, X.stride(0),
                            _dtype_code(X), Y.data_ptr(), Y.stride(0), ws_ptr, ws_bytes, _stream(stream)), "aqc_qgemm")
     return Y
+
+
+class CbGemmBatch:
+    """A planned list of prefill products over codebook blobs (two launches).  Holds references to every tensor."""
+
+    def __init__(self, items: Sequence[tuple], block: int = BLOCK):
+        """items: (packed, N, K, bits, levels, X, Y) per matrix; X [M, K] half/bfloat16, Y [M, N] float32."""
+        import torch
+        n = len(items)
+        descs = (aqc_gemm_desc * n)()
+        self._tables = []
+        for d, (packed, N, K, bits, levels, X, Y) in zip(descs, items):
+            p = d.product
+            p.packed, p.X, p.Y = packed.data_ptr(), X.data_ptr(), Y.data_ptr()
+            p.N, p.K, p.M, p.ldx, p.ldy = N, K, X.shape[0], X.stride(0), Y.stride(0)
+            p.bits, p.x_dtype = bits, _dtype_code(X)
+            tab = _levels(levels, bits)
+            self._tables.append(tab)
+            d.levels = ctypes.cast(tab, _p)
+        size = int(lib().aqc_qgemm_batch_plan_size(n))
+        self.plan_host = torch.empty(size, dtype=torch.uint8)
+        _check(lib().aqc_qgemm_batch_plan(descs, n, block, self.plan_host.data_ptr(), size), "aqc_qgemm_batch_plan")
+        self.plan_dev = self.plan_host.to(items[0][0].device)
+        self.workspace_bytes = int(lib().aq_qgemm_batch_workspace_size(self.plan_host.data_ptr()))
+        self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=items[0][0].device)
+        self.items = list(items)
+
+    def run(self, stream=None) -> None:
+        _check(lib().aq_qgemm_batch(self.plan_host.data_ptr(), self.plan_dev.data_ptr(), self.workspace.data_ptr(),
+                                    self.workspace_bytes, _stream(stream)), "aq_qgemm_batch")
 
 
 def aqc_unpack_codes(packed, N: int, K: int, bits: int, levels, block: int = BLOCK, stream=None):

@@ -632,7 +632,7 @@ static int gemm_plan(const aq_gemm_desc* descs, int count, int block, int flags,
     h.fast = flags == AQ_GEMM_FAST;
     h.format = format;
     h.small_mt = !format && max_M <= (h.fast ? SMALL_M : SMALL_M_EXACT) ? aqk_small_mtiles(max_M) : 0;
-    h.pc = format ? h.fast : 1;
+    h.pc = format ? h.fast : 1;                       // format 1: fast -> pc; format 2: always fast, always pc
     for (int i = 0; i < count && !format; ++i) h.pc = h.pc && use_pc(h.fast, descs[i].M);      // every product of the list
     const int convert = h.fast && h.x_dtype == AQ_BF16;
     uint8_t* base = static_cast<uint8_t*>(plan_host);
@@ -688,6 +688,36 @@ int aq2_qgemm_batch_plan(const aq_gemm_desc* descs, int count, int block, int fl
     return gemm_plan(descs, count, block, flags, plan_host, plan_bytes, 1);
 }
 
+// Codebook variant: the base plan image (format 2: the fp16-weight producer / consumer kernel at every M) followed by
+// one table of 16 floats per task, in the plan's task order (longest K first, ties in the caller's order).
+size_t aqc_qgemm_batch_plan_size(int count)
+{
+    if (count < 1) return 0;
+    return aq_qgemm_batch_plan_size(count) + (size_t)count * 64;
+}
+
+int aqc_qgemm_batch_plan(const aqc_gemm_desc* descs, int count, int block, void* plan_host, size_t plan_bytes)
+{
+    if (count < 1) return AQ_EINVAL;
+    if (!descs || !plan_host) return AQ_ENULL;
+    if (plan_bytes < aqc_qgemm_batch_plan_size(count)) return AQ_ESIZE;
+    std::vector<aq_gemm_desc> plain((size_t)count);
+    for (int i = 0; i < count; ++i) {
+        plain[i] = descs[i].product;
+        if (!descs[i].levels) return AQ_ENULL;
+    }
+    int rc = gemm_plan(plain.data(), count, block, AQ_GEMM_FAST, plan_host, aq_qgemm_batch_plan_size(count), 2);
+    if (rc != AQ_OK) return rc;
+    std::vector<int> order = longest_k_first(count, [&](int i) { return plain[i].K; });
+    uint8_t* tables = static_cast<uint8_t*>(plan_host) + aq_qgemm_batch_plan_size(count);
+    for (int j = 0; j < count; ++j) {
+        AqCbTable table;
+        if ((rc = aqk_cb_stored_levels(descs[order[j]].levels, plain[order[j]].bits, &table)) != AQ_OK) return rc;
+        std::memcpy(tables + (size_t)j * 64, table.level, 64);
+    }
+    return AQ_OK;
+}
+
 static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
 {
     std::memcpy(&h, plan_host, sizeof(h));
@@ -698,7 +728,8 @@ static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
            (h.fast == 0 || h.fast == 1) &&
            (h.small_mt == 0 || h.small_mt == 1 || h.small_mt == 2 || (h.small_mt == 4 && h.fast == 1)) &&
            (h.pc == 0 || (h.pc == 1 && h.small_mt == 0)) &&
-           (h.format == 0 || (h.format == 1 && h.pc == h.fast && h.small_mt == 0));
+           (h.format == 0 || (h.format == 1 && h.pc == h.fast && h.small_mt == 0) ||
+            (h.format == 2 && h.pc == 1 && h.fast == 1 && h.small_mt == 0));
 }
 
 size_t aq_qgemm_batch_workspace_size(const void* plan_host)
@@ -735,8 +766,12 @@ int aq_qgemm_batch(const void* plan_host, const void* plan_dev, void* workspace,
         return AQ_ELAUNCH;
     if (h.pc && !h.fast)
         return aqk_gemm_pcx(tasks, h.count, none, h.bits, h.x_dtype, h.total_wgs, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
-    if (h.pc)
-        return aqk_gemm_pc(tasks, h.count, none, h.bits, h.format, h.total_wgs, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+    if (h.pc) {
+        // format 2: the tables follow the re-tiling tasks in the plan image
+        const float* tables = h.format == 2 ? reinterpret_cast<const float*>(dev + aq_qgemm_batch_plan_size(h.count)) : nullptr;
+        return aqk_gemm_pc(tasks, h.count, none, h.bits, h.format, h.total_wgs, workspace, s, tables) == hipSuccess
+                   ? AQ_OK : AQ_ELAUNCH;
+    }
     if (h.format == 1)
         return aqk2_gemm(tasks, h.count, none, h.x_dtype, h.mtiles, h.total_wgs, workspace, s) == hipSuccess
                    ? AQ_OK : AQ_ELAUNCH;

@@ -176,6 +176,7 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
         }
         t = tasks[lo];
         wg -= t.wg_begin;
+        if (FMT == 2) cb_table += 16 * lo;            // a list carries one table of 16 levels per task
     }
     if (wg >= t.wg_count) return;
 
@@ -354,12 +355,12 @@ int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int per, int* slabs)
 }
 
 // bits == 0: mixed bit-widths.  Xt: binary16, the re-tiled layout of the shared-role kernel.
-// format: 0 the base format, 1 the two-level variant, 2 the codebook variant (uniform bit-width only; cb_table: DEVICE,
-// 16 floats, the level of every stored code).
+// format: 0 the base format, 1 the two-level variant, 2 the codebook variant (cb_table: DEVICE, 16 floats per task (one
+// table for `single`): the level of every stored code).
 hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int format,
                        int total_wgs, const void* workspace, hipStream_t s, const float* cb_table)
 {
-    if (format == 2 && (bits < 2 || bits > 4 || !cb_table)) return hipErrorInvalidValue;
+    if (format == 2 && !cb_table) return hipErrorInvalidValue;
     const size_t lds = 2 * (size_t)PC_WBUF;
     const dim3 grid((unsigned)total_wgs), block(PC_THREADS);
     const uint8_t* ws = static_cast<const uint8_t*>(workspace);
@@ -376,7 +377,7 @@ hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask&
         hipLaunchKernelGGL(k, grid, block, lds, s, tasks_dev, count, single, ws, cb_table);                     \
     } while (0)
     if (format == 2) {
-        if (bits == 2) AQ_PC_CB(2); else if (bits == 3) AQ_PC_CB(3); else AQ_PC_CB(4);
+        if (bits == 2) AQ_PC_CB(2); else if (bits == 3) AQ_PC_CB(3); else if (bits == 4) AQ_PC_CB(4); else AQ_PC_CB(0);
         return hipGetLastError();
     }
     if (bits == 2) AQ_PC(2);

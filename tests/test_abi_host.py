@@ -350,6 +350,28 @@ def test_codebook_variant_table_analysis_and_validation_without_a_gpu(L):
     assert L.aqc_qgemm(A, 64, 512, 2, 32, lv, A, 40, 500, aq.AQ_F16, A, 64, A, wsz, None) == aq.AQ_EINVAL      # ldx < K
     assert L.aqc_qgemm(A, 64, 512, 2, 32, lv, A, 40, 512, 3, A, 64, A, wsz, None) == aq.AQ_EDTYPE
     assert L.aqc_dequant_f32(A, 16, 64, 6, 32, lv, A, None) == aq.AQ_EINVAL
+    # prefill list plans: the base plan image, then one table per task in plan order (longest K first)
+    gd = (aq.aqc_gemm_desc * 2)()
+    lv4q = (ctypes.c_float * 16)(*[float(v) for v in range(-8, 8)])
+    for d, (N, K, b, tab) in zip(gd, [(256, 512, 2, lv), (128, 1024, 4, lv4q)]):
+        p = d.product
+        p.packed, p.X, p.Y, p.N, p.K, p.M, p.ldx, p.ldy, p.bits, p.x_dtype = A, A, A, N, K, 300, K, N, b, aq.AQ_BF16
+        d.levels = ctypes.cast(tab, ctypes.c_void_p)
+    L.aqc_qgemm_batch_plan_size.restype = ctypes.c_size_t
+    L.aq_qgemm_batch_plan_size.restype = ctypes.c_size_t
+    psz = L.aqc_qgemm_batch_plan_size(2)
+    assert psz == L.aq_qgemm_batch_plan_size(2) + 128
+    pbuf = (ctypes.c_uint8 * psz)()
+    assert L.aqc_qgemm_batch_plan(gd, 2, 32, pbuf, psz) == aq.AQ_OK
+    head = np.frombuffer(bytes(pbuf[:64]), dtype=np.int32)
+    assert head[1] == 2 and head[2] == 0 and head[11] == 1 and head[13] == 1 and head[14] == 2      # mixed, fast, pc, codebook
+    tabs = np.frombuffer(bytes(pbuf[psz - 128:]), dtype=np.float32).reshape(2, 16)
+    assert tabs[0].tolist() == [float(v) for v in range(-8, 8)]        # K = 1024 first; planes: stored = canonical codes
+    assert sorted(tabs[1, :4].tolist()) == [-1.5, -0.25, 0.25, 1.5] and not tabs[1, 4:].any()
+    assert L.aq_qgemm_batch_workspace_size(pbuf) > 0
+    assert L.aqc_qgemm_batch_plan(gd, 2, 32, pbuf, psz - 1) == aq.AQ_ESIZE
+    gd[1].levels = None
+    assert L.aqc_qgemm_batch_plan(gd, 2, 32, pbuf, psz) == aq.AQ_ENULL
     # list plans: made on the host, nothing launched
     descs = (aq.aqc_gemv_desc * 2)()
     lv4 = (ctypes.c_float * 16)(*[float(v) for v in e2m1])

@@ -254,3 +254,23 @@ def test_qgemm_agrees_with_qgemv_row_by_row(gpu, cb, oracle):
     for m in range(M):
         y = aq.aqc_qgemv(packed, N, K, bits, levels, Xd[m].contiguous()).cpu().numpy()
         assert oracle.rel_l2(Y[m], y) <= 5e-4
+
+
+def test_qgemm_list_matches_single_calls(gpu, cb, oracle):
+    torch, aq = gpu
+    e = cb.e2m1_levels().astype(np.float32)
+    shapes = [(256, 1024, 2, wl.draw_levels("quantile", 2, 1), 300), (384, 2048, 4, e, 300),
+              (130, 544, 3, wl.draw_levels("random", 3, 2), 20), (512, 1024, 4, wl.draw_levels("quantile", 4, 1), 300)]
+    items, singles, Xs = [], [], {}
+    for i, (N, K, bits, levels, M) in enumerate(shapes):
+        codes, scales = wl.draw_matrix(N, K, bits, 93, i)
+        if (M, K) not in Xs:
+            Xs[(M, K)] = dev(torch, wl.draw_activations(M, K, "bf16", 93, M, K), "bf16")
+        packed = aq.aqc_pack_weights(dev(torch, codes), dev(torch, scales), levels, N, K, bits)
+        Y = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+        items.append((packed, N, K, bits, levels, Xs[(M, K)], Y))
+        singles.append(aq.aqc_qgemm(packed, N, K, bits, levels, Xs[(M, K)]))
+    aq.CbGemmBatch(items).run()
+    torch.cuda.synchronize()
+    for it, one in zip(items, singles):
+        assert torch.equal(it[6], one)
