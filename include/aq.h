@@ -127,7 +127,9 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
  *       never pass through LDS); there such a matrix has every scale multiplied by one power of two
  *       2^-s first (s <= 4) and the result by 2^s, same error bound unless d < 2^(s-14).
  *   X   DEVICE uint16 [M][ldx], ldx >= K and ldx % 8 == 0, x_dtype = AQ_BF16 or AQ_F16
- *   Y   DEVICE float  [M][ldy], ldy >= N, overwritten for m < M, n < N
+ *   Y   DEVICE float  [M][ldy], ldy >= N, overwritten for m < M, n < N (a call on a matrix with few rows and a deep K
+ *       clears these elements in its first launch and adds two partial sums over halves of K to each with fp32
+ *       atomics: the same bits on every call, since two terms sum alike in either order)
  *   workspace DEVICE, 16-byte aligned, workspace_bytes >= aq_qgemm_workspace_size(M, N, K, bits)
  *       (2 bytes per element of X with M rounded up to 16, plus 4 bytes per row).  The call first copies
  *       X into it in the order the matrix cores read their operands, then runs the product from that

@@ -491,16 +491,24 @@ static int qgemm_one(const void* packed, int64_t N, int64_t K, int bits, int blo
         return aqk_gemm_small(nullptr, 0, t, bits, MT, !fast, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     }
     const AqRetileTask r = make_retile_task(X, M, K, ldx, 0, convert);
-    if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
     const int per = aqk_gemm_pc_tiles_per_wg(M, aq_num_groups(N));      // a lone matrix: fewer m-tiles per workgroup
     if (use_pc(fast, M, per)) {
-        if (!fast) {
-            const AqGemmTask t = make_pcx_task(packed, N, K, bits, M, 0, Y, ldy, 0, per);
-            return aqk_gemm_pcx(nullptr, 0, t, bits, x_dtype, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
+        AqGemmTask t = fast ? make_pc_task(packed, N, K, bits, M, 0, Y, ldy, 0, per)
+                            : make_pcx_task(packed, N, K, bits, M, 0, Y, ldy, 0, per);
+        // still under half of the chip's compute units: two workgroups per (group, m-block), each half of K, their
+        // parts added into Y, which the re-tiling launch clears
+        const int kparts = t.wg_count * 2 <= 256 && t.nchunks >= 8 ? 2 : 1;
+        if (kparts > 1) {
+            t.pad[1] = kparts;
+            t.wg_count *= kparts;
         }
-        const AqGemmTask t = make_pc_task(packed, N, K, bits, M, 0, Y, ldy, 0, per);
+        if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s, kparts > 1 ? Y : nullptr, N, ldy) != hipSuccess)
+            return AQ_ELAUNCH;
+        if (!fast)
+            return aqk_gemm_pcx(nullptr, 0, t, bits, x_dtype, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
         return aqk_gemm_pc(nullptr, 0, t, bits, 0, t.wg_count, workspace, s) == hipSuccess ? AQ_OK : AQ_ELAUNCH;
     }
+    if (aqk_retile(nullptr, 0, r, r.blocks, convert, workspace, s) != hipSuccess) return AQ_ELAUNCH;
     const int A = aqk_gemm_mtiles(M, aq_num_groups(N)), nsplit = aqk_gemm_nsplit(M);
     AqGemmTask t = make_gemm_task(packed, N, K, bits, M, 0, Y, ldy, A, nsplit, 0);
     return aqk_gemm(nullptr, 0, t, bits, x_dtype, A, nsplit, fast, t.wg_count, workspace, s) == hipSuccess

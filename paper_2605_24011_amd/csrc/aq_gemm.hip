@@ -28,9 +28,26 @@ namespace {
 // reads, per fragment, 64 bytes of each of the tile's 16 rows; its four fragments are four consecutive steps, so the
 // 16 rows' reads cover whole 256-byte runs.  A workgroup = one m-tile x 16 steps.  Rows in [M, 16 ceil(M/16)) are
 // written as zeros.
+// Rows [16 mtile, 16 mtile + 16) of Y, columns of share `part` of `parts`, = 0: folded into the re-tiling launch of a
+// lone product whose workgroups add their parts of K into Y.
+struct AqZeroY {
+    float* Y;           // null: nothing to clear
+    int64_t M, N, ldy;
+};
+__device__ __forceinline__ void zero_y_share(const AqZeroY& z, int64_t mtile, int part, int parts)
+{
+    if (!z.Y) return;
+    const int64_t per = (z.N + parts - 1) / parts, n0 = part * per, n1 = n0 + per < z.N ? n0 + per : z.N;
+    for (int r = 0; r < 16; ++r) {
+        const int64_t m = mtile * 16 + r;
+        if (m >= z.M) break;
+        for (int64_t n = n0 + threadIdx.x; n < n1; n += 256) z.Y[m * z.ldy + n] = 0.f;
+    }
+}
+
 constexpr int RT_STEPS = 4;                                    // steps per wavefront
 __global__ __launch_bounds__(256) void retile_kernel(const AqRetileTask* __restrict__ tasks, int count,
-                                                     AqRetileTask single, uint8_t* __restrict__ workspace)
+                                                     AqRetileTask single, uint8_t* __restrict__ workspace, AqZeroY zero)
 {
     AqRetileTask t;
     if (count == 0) t = single; else t = tasks[blockIdx.y];
@@ -38,6 +55,7 @@ __global__ __launch_bounds__(256) void retile_kernel(const AqRetileTask* __restr
     const int ksteps = t.K >> 5;
     const int per_tile = (ksteps + 4 * RT_STEPS - 1) / (4 * RT_STEPS);       // workgroups per m-tile
     const int64_t mtile = blockIdx.x / per_tile;
+    zero_y_share(zero, mtile, blockIdx.x % per_tile, per_tile);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
     const int step0 = ((blockIdx.x % per_tile) * 4 + wave) * RT_STEPS;
     const int64_t row = mtile * 16 + c;
@@ -55,12 +73,15 @@ __global__ __launch_bounds__(256) void retile_kernel(const AqRetileTask* __restr
     if (step0 == 0 && g == 0) reinterpret_cast<int32_t*>(workspace + t.xt_offset + mpad * t.K * 2)[row] = 0;       // rowexp
 }
 
-// bf16 X[M][ldx] -> binary16 Xt with one power-of-two factor per row.  One workgroup per m-tile (16 rows): pass 1 finds
-// every row's largest magnitude (wavefront w takes rows 4w .. 4w+3, reading along the rows), pass 2 walks the tile's
-// fragments as retile_kernel does (second read of the tile: from L2), scales, converts (round to nearest even) and
-// stores whole fragments; rowexp[row] = the exponent the product kernel adds back.
+// bf16 X[M][ldx] -> binary16 Xt with one power-of-two factor per row.  A workgroup = one m-tile (16 rows) x one of
+// gridDim.z slices of its steps (one slice in a list; a lone product cuts the steps into slices so that more than
+// ceil(M / 16) compute units take part): pass 1 finds every row's largest magnitude (wavefront w takes rows 4w .. 4w+3,
+// reading along the rows, the four rows' loads in flight together), pass 2 walks the slice's fragments as retile_kernel
+// does (second read of the tile: from L2), scales, converts (round to nearest even) and stores whole fragments;
+// rowexp[row] = the exponent the product kernel adds back.
 __global__ __launch_bounds__(256) void retile_convert_kernel(const AqRetileTask* __restrict__ tasks, int count,
-                                                             AqRetileTask single, uint8_t* __restrict__ workspace)
+                                                             AqRetileTask single, uint8_t* __restrict__ workspace,
+                                                             AqZeroY zero)
 {
     __shared__ int row_shift[16];
     AqRetileTask t;
@@ -68,37 +89,48 @@ __global__ __launch_bounds__(256) void retile_convert_kernel(const AqRetileTask*
     const int64_t mtile = blockIdx.x;
     const int64_t mpad = (t.M + 15) & ~(int64_t)15;
     if (mtile * 16 >= mpad) return;                            // uniform per workgroup
+    const int slice = blockIdx.z, slices = gridDim.z;
+    zero_y_share(zero, mtile, slice, slices);
     const int pieces = t.K >> 3, ksteps = t.K >> 5;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
     int32_t* rowexp = reinterpret_cast<int32_t*>(workspace + t.xt_offset + mpad * t.K * 2);
     // pass 1: bf16 magnitudes order like unsigned integers
-    for (int r = 0; r < 4; ++r) {
-        const int64_t row = mtile * 16 + wave * 4 + r;
-        uint32_t mx = 0;
-        if (row < t.M) {
-            const AQ_GLOBAL u32x4* src = as_global<u32x4>(t.X + row * t.ldx);
-            for (int j = lane; j < pieces; j += 64) {
-                const u32x4 v = src[j];
+    {
+        uint32_t mx[4] = {0u, 0u, 0u, 0u};
+#pragma unroll 4
+        for (int j = lane; j < pieces; j += 64) {
+            u32x4 v[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t row = mtile * 16 + wave * 4 + r;
+                v[r] = u32x4{0u, 0u, 0u, 0u};
+                if (row < t.M) v[r] = as_global<u32x4>(t.X + row * t.ldx)[j];
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const uint32_t lo = v[i] & 0x7FFFu, hi = (v[i] >> 16) & 0x7FFFu;
-                    mx = lo > mx ? lo : mx;
-                    mx = hi > mx ? hi : mx;
+                    const uint32_t lo = v[r][i] & 0x7FFFu, hi = (v[r][i] >> 16) & 0x7FFFu;
+                    mx[r] = lo > mx[r] ? lo : mx[r];
+                    mx[r] = hi > mx[r] ? hi : mx[r];
                 }
-            }
         }
-        for (int o = 32; o >= 1; o >>= 1) {
-            const uint32_t other = (uint32_t)__shfl_xor((int)mx, o);
-            mx = other > mx ? other : mx;
-        }
-        if (lane == 0) {
-            int shift = 0;                                     // x * 2^shift has its largest magnitude in [2^14, 2^15)
-            if (mx != 0) {
-                const int field = (int)(mx >> 7);              // biased exponent; 0 = bf16 subnormal, 255 = inf / NaN
-                shift = 14 - ((field ? field : 1) - 127);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            uint32_t m = mx[r];
+            for (int o = 32; o >= 1; o >>= 1) {
+                const uint32_t other = (uint32_t)__shfl_xor((int)m, o);
+                m = other > m ? other : m;
             }
-            row_shift[wave * 4 + r] = shift;
-            rowexp[row] = -shift;                              // padded rows: 0
+            if (lane == 0) {
+                int shift = 0;                                 // x * 2^shift has its largest magnitude in [2^14, 2^15)
+                if (m != 0) {
+                    const int field = (int)(m >> 7);           // biased exponent; 0 = bf16 subnormal, 255 = inf / NaN
+                    shift = 14 - ((field ? field : 1) - 127);
+                }
+                row_shift[wave * 4 + r] = shift;
+                if (slice == 0) rowexp[mtile * 16 + wave * 4 + r] = -shift;      // padded rows: 0
+            }
         }
     }
     __syncthreads();
@@ -106,7 +138,11 @@ __global__ __launch_bounds__(256) void retile_convert_kernel(const AqRetileTask*
     const int64_t row = mtile * 16 + c;
     const int shift = row_shift[c];
     u32x4* dst = reinterpret_cast<u32x4*>(workspace + t.xt_offset) + mtile * ksteps * 64 + lane;
-    for (int step0 = wave * RT_STEPS; step0 < ksteps; step0 += 4 * RT_STEPS) {
+    const int groups = (ksteps + 4 * RT_STEPS - 1) / (4 * RT_STEPS);          // runs of 16 steps (4 wavefronts x RT_STEPS)
+    const int gper = (groups + slices - 1) / slices;
+    const int gend = (slice + 1) * gper < groups ? (slice + 1) * gper : groups;
+    for (int gi = slice * gper; gi < gend; ++gi) {
+        const int step0 = (gi * 4 + wave) * RT_STEPS;
         u32x4 v[RT_STEPS];
 #pragma unroll
         for (int s = 0; s < RT_STEPS; ++s) {
@@ -178,14 +214,21 @@ int aqk_retile_blocks(int64_t M, int64_t K, int convert)
 }
 
 hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int max_blocks,
-                      int convert, void* workspace, hipStream_t s)
+                      int convert, void* workspace, hipStream_t s, float* zero_Y, int64_t zero_N, int64_t zero_ldy)
 {
-    const dim3 grid((unsigned)max_blocks, (unsigned)(count == 0 ? 1 : count));
-    if (convert)
+    AqZeroY zero = {nullptr, 0, 0, 0};
+    if (zero_Y && count == 0) zero = AqZeroY{zero_Y, single.M, zero_N, zero_ldy};
+    if (convert) {
+        // a lone product: the steps of an m-tile in slices of at least 16, up to 8 of them
+        const int runs = count == 0 ? (int)((single.K / 32 + 4 * RT_STEPS - 1) / (4 * RT_STEPS)) : 1;
+        const dim3 grid((unsigned)max_blocks, (unsigned)(count == 0 ? 1 : count), (unsigned)(runs < 8 ? runs : 8));
         hipLaunchKernelGGL(retile_convert_kernel, grid, dim3(256), 0, s, tasks_dev, count, single,
-                           static_cast<uint8_t*>(workspace));
-    else
-        hipLaunchKernelGGL(retile_kernel, grid, dim3(256), 0, s, tasks_dev, count, single, static_cast<uint8_t*>(workspace));
+                           static_cast<uint8_t*>(workspace), zero);
+    } else {
+        const dim3 grid((unsigned)max_blocks, (unsigned)(count == 0 ? 1 : count));
+        hipLaunchKernelGGL(retile_kernel, grid, dim3(256), 0, s, tasks_dev, count, single, static_cast<uint8_t*>(workspace),
+                           zero);
+    }
     return hipGetLastError();
 }
 

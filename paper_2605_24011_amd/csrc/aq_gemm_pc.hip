@@ -60,13 +60,14 @@ __device__ __forceinline__ void lds_barrier()
 // in the lanes of the wavefront (lane l holds level[l % 16]) and a lookup is one cross-lane read (DS_BPERMUTE_B32).
 template <int BITS, int FMT>
 __device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, int lane, uint8_t* smem, _Float16 down,
-                                        const float* __restrict__ cb_table)
+                                        const float* __restrict__ cb_table, int ch0, int nloc)
 {
     constexpr int WORDS = Codec<BITS>::WORDS;
     constexpr int UNIT = 512 * BITS + (FMT == 1 ? AQ2_PARAM_BYTES : 256);
     const int g = lane >> 4, c = lane & 15;
-    const int nch = t.nchunks;
-    const uint8_t* ubase = t.blob + (((int64_t)group * nch) * AQ_GROUP_TILES + 2 * p) * UNIT;
+    // the workgroup's part of K: chunks ch0 .. ch0 + nloc - 1 of the matrix's t.nchunks (all of them unless K is split)
+    const int nch = nloc;
+    const uint8_t* ubase = t.blob + (((int64_t)group * t.nchunks + ch0) * AQ_GROUP_TILES + 2 * p) * UNIT;
     const int64_t chunk_stride = (int64_t)AQ_GROUP_TILES * UNIT;
     uint32_t raw[2][WORDS];
     uint32_t sc[2][2];                                // FMT 0: scales of row c, blocks 2g and 2g + 1
@@ -182,15 +183,21 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // a lone matrix may split K over kparts workgroups per (group, m-block): each adds its part into Y (zeroed before)
+    const int kparts = t.pad[1] > 1 ? (int)t.pad[1] : 1;
+    const int wg_part = t.wg_count / kparts, kpart = wg / wg_part;
+    wg -= kpart * wg_part;
     const int group = wg % t.slabs, mblock = wg / t.slabs;
-    const int nch = t.nchunks;
+    const int cpp = (t.nchunks + kparts - 1) / kparts;
+    const int ch0 = kpart * cpp;
+    const int nch = t.nchunks - ch0 < cpp ? t.nchunks - ch0 : cpp;      // this workgroup's chunks: ch0 .. ch0 + nch - 1
 
     // largest scale of the matrix (blob trailer) -> power-of-two shift that keeps d * (q - z) inside binary16
     // (blobs of the two-level variant carry no such word: their D * 15 * (2^bits - 1) must stay inside binary16)
     int sh = 0;
     if (FMT == 0) {
         const uint32_t max_d = *reinterpret_cast<const uint32_t*>(
-            t.blob + (int64_t)t.slabs * nch * AQ_GROUP_TILES * aq_unit_bytes(t.bits));
+            t.blob + (int64_t)t.slabs * t.nchunks * AQ_GROUP_TILES * aq_unit_bytes(t.bits));
         const int max_exp = (int)(max_d >> 10) - 15 + (t.bits - 1) + 1;
         sh = max_exp > 15 ? max_exp - 15 : 0;
     }
@@ -198,9 +205,9 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
     if (wave >= PC_CONSUMERS) {
         const _Float16 down = (_Float16)__builtin_ldexpf(1.f, -(sh < 24 ? sh : 24));
         const int p = wave - PC_CONSUMERS;
-        if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) produce<2, FMT>(t, group, p, lane, smem, down, cb_table);
-        else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) produce<3, FMT>(t, group, p, lane, smem, down, cb_table);
-        else produce<4, FMT>(t, group, p, lane, smem, down, cb_table);
+        if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) produce<2, FMT>(t, group, p, lane, smem, down, cb_table, ch0, nch);
+        else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) produce<3, FMT>(t, group, p, lane, smem, down, cb_table, ch0, nch);
+        else produce<4, FMT>(t, group, p, lane, smem, down, cb_table, ch0, nch);
         return;
     }
 
@@ -237,8 +244,8 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
         };
 #pragma unroll
         for (int mt = 0; mt < MTC; ++mt) {
-            load_x(mt, 0, xr[0][mt]);
-            load_x(mt, 1, xr[1][mt]);
+            load_x(mt, ch0 * 8, xr[0][mt]);
+            load_x(mt, ch0 * 8 + 1, xr[1][mt]);
         }
 
         float4v acc[MTC][8];
@@ -281,7 +288,7 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
                     // the step's last batch has used this m-tile's activation operand: request step s + 2's (from
                     // L2: as early as possible)
                     if (qt == BPS - 1) {
-                        load_x(mt, ch * 8 + s + 2, xr[par][mt]);
+                        load_x(mt, (ch0 + ch) * 8 + s + 2, xr[par][mt]);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -304,7 +311,11 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int64_t m = (int64_t)(mt0 + mt) * 16 + 4 * g + r;
-                        if (m < M && n < t.N) Y[m * t.ldy + n] = ldexpf(acc[mt][nt][r], e[r]);
+                        if (m < M && n < t.N) {
+                            const float v = ldexpf(acc[mt][nt][r], e[r]);
+                            if (kparts > 1) unsafeAtomicAdd((float*)(uintptr_t)(Y + m * t.ldy + n), v);
+                            else Y[m * t.ldy + n] = v;
+                        }
                     }
                 }
             }

@@ -53,13 +53,15 @@ __device__ __forceinline__ float4v mfma16(const u32x4& a, const u32x4& b, const 
 
 // Producer: tiles 2p, 2p+1 of the group, all chunks.  Executes nch + 1 barriers.
 template <int BITS, bool XBF>
-__device__ __forceinline__ void produce_exact(const AqGemmTask& t, int group, int p, int lane, uint8_t* smem)
+__device__ __forceinline__ void produce_exact(const AqGemmTask& t, int group, int p, int lane, uint8_t* smem, int ch0,
+                                              int nloc)
 {
     constexpr int WORDS = Codec<BITS>::WORDS;
     constexpr int UNIT = 512 * BITS + 256;
     const int g = lane >> 4, c = lane & 15;
-    const int nch = t.nchunks;
-    const uint8_t* ubase = t.blob + (((int64_t)group * nch) * AQ_GROUP_TILES + 2 * p) * UNIT;
+    // the workgroup's part of K: chunks ch0 .. ch0 + nloc - 1 of the matrix's t.nchunks (all of them unless K is split)
+    const int nch = nloc;
+    const uint8_t* ubase = t.blob + (((int64_t)group * t.nchunks + ch0) * AQ_GROUP_TILES + 2 * p) * UNIT;
     const int64_t chunk_stride = (int64_t)AQ_GROUP_TILES * UNIT;
     uint32_t raw[2][WORDS];
     uint32_t sc[2][2];                                // scales of row c, blocks 2g and 2g + 1
@@ -127,14 +129,20 @@ __global__ __launch_bounds__(PX_THREADS) void qgemm_pcx_kernel(const AqGemmTask*
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // a lone matrix may split K over kparts workgroups per (group, m-block): each adds its part into Y (zeroed before)
+    const int kparts = t.pad[1] > 1 ? (int)t.pad[1] : 1;
+    const int wg_part = t.wg_count / kparts, kpart = wg / wg_part;
+    wg -= kpart * wg_part;
     const int group = wg % t.slabs, mblock = wg / t.slabs;
-    const int nch = t.nchunks;
+    const int cpp = (t.nchunks + kparts - 1) / kparts;
+    const int ch0 = kpart * cpp;
+    const int nch = t.nchunks - ch0 < cpp ? t.nchunks - ch0 : cpp;      // this workgroup's chunks: ch0 .. ch0 + nch - 1
 
     if (wave >= PX_CONSUMERS) {
         const int p = wave - PX_CONSUMERS;
-        if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) produce_exact<2, XBF>(t, group, p, lane, smem);
-        else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) produce_exact<3, XBF>(t, group, p, lane, smem);
-        else produce_exact<4, XBF>(t, group, p, lane, smem);
+        if (BITS_T == 2 || (BITS_T == 0 && t.bits == 2)) produce_exact<2, XBF>(t, group, p, lane, smem, ch0, nch);
+        else if (BITS_T == 3 || (BITS_T == 0 && t.bits == 3)) produce_exact<3, XBF>(t, group, p, lane, smem, ch0, nch);
+        else produce_exact<4, XBF>(t, group, p, lane, smem, ch0, nch);
         return;
     }
 
@@ -168,8 +176,8 @@ __global__ __launch_bounds__(PX_THREADS) void qgemm_pcx_kernel(const AqGemmTask*
         };
 #pragma unroll
         for (int mt = 0; mt < MTC; ++mt) {
-            load_x(mt, 0, xr[0][mt]);
-            load_x(mt, 1, xr[1][mt]);
+            load_x(mt, ch0 * 8, xr[0][mt]);
+            load_x(mt, ch0 * 8 + 1, xr[1][mt]);
         }
 
         float4v acc[MTC][8];
@@ -225,7 +233,7 @@ __global__ __launch_bounds__(PX_THREADS) void qgemm_pcx_kernel(const AqGemmTask*
 #pragma unroll
                     for (int j = 0; j < 2; ++j) D[mt & 1][j] = mfma16<XBF>(xr[par][mt], bw[set][j], zero);
                     // the step's last quarter has used this m-tile's activation operand: request step s + 2's
-                    if (qt == 3) load_x(mt, ch * 8 + s + 2, xr[par][mt]);
+                    if (qt == 3) load_x(mt, (ch0 + ch) * 8 + s + 2, xr[par][mt]);
                     if (mt > 0) fold(mt - 1, D[(mt - 1) & 1]);
                 }
                 fold(MTC - 1, D[(MTC - 1) & 1]);
@@ -244,7 +252,10 @@ __global__ __launch_bounds__(PX_THREADS) void qgemm_pcx_kernel(const AqGemmTask*
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int64_t m = (int64_t)(mt0 + mt) * 16 + 4 * g + r;
-                        if (m < M && n < t.N) Y[m * t.ldy + n] = acc[mt][nt][r];
+                        if (m < M && n < t.N) {
+                            if (kparts > 1) unsafeAtomicAdd((float*)(uintptr_t)(Y + m * t.ldy + n), acc[mt][nt][r]);
+                            else Y[m * t.ldy + n] = acc[mt][nt][r];
+                        }
                     }
                 }
             }

@@ -136,9 +136,11 @@ int aqk_gemm_wg_count(int64_t N, int64_t M, int A, int nsplit, int* slabs);
 size_t aqk_retile_bytes(int64_t M, int64_t K);
 int aqk_retile_blocks(int64_t M, int64_t K, int convert);
 // count == 0: run `single`; else `count` tasks from device memory; grid = (max_blocks, tasks); every task
-// of a launch has the same `convert`
+// of a launch has the same `convert`.  zero_Y (lone products, count == 0, only): rows [0, single.M) x columns [0, zero_N)
+// of that matrix (row stride zero_ldy) are cleared by the same launch
 hipError_t aqk_retile(const AqRetileTask* tasks_dev, int count, const AqRetileTask& single, int max_blocks,
-                      int convert, void* workspace, hipStream_t s);
+                      int convert, void* workspace, hipStream_t s, float* zero_Y = nullptr, int64_t zero_N = 0,
+                      int64_t zero_ldy = 0);
 // count == 0: run `single`; bits == 0: the tasks' bit-widths differ; x_dtype, A, nsplit and fast are per
 // launch.  fast != 0: weights are formed as binary16 d * (q - z) and the activations in Xt are binary16.
 hipError_t aqk_gemm(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int x_dtype, int A,
@@ -158,7 +160,9 @@ hipError_t aqk_gemm_small(const AqGemmTask* tasks_dev, int count, const AqGemmTa
 
 // Prefill, fp16-weight mode, prefill-sized M: producer / consumer wavefronts (aq_gemm_pc.hip).  Reads the binary16
 // Xt + rowexp that aqk_retile writes; a task's wg_count = aqk_gemm_pc_wg_count (128-row groups x blocks of 320 rows).
-// per = m-tiles per workgroup (0: the most, 24), carried by a task in pad[0]; both producer / consumer kernels alike
+// per = m-tiles per workgroup (0: the most, 24), carried by a task in pad[0]; both producer / consumer kernels alike.
+// pad[1] = kparts (0 or 1: none): K split over that many workgroups per (group, m-block), wg_count multiplied by it, the
+// parts ADDED into Y with fp32 atomics (the caller zeroes Y first; two parts give the same sum in either order)
 int aqk_gemm_pc_tiles_per_wg(int64_t M, int64_t groups);   // groups = 128-row groups over all products of the launch
 int aqk_gemm_pc_wg_count(int64_t N, int64_t M, int per, int* slabs);
 int64_t aqk_gemm_pc_tile_slots(int64_t M, int per);

@@ -697,6 +697,38 @@ def test_qgemm_fast_producer_consumer_shapes(gpu, oracle, bits, N, K, M):
     assert oracle.rel_l2(Y, oracle.qmatmul(codes, big, N, K, bits, X, "bf16")) <= FAST_EXPECTED[bits]
 
 
+@pytest.mark.parametrize("fast", [False, True])
+@pytest.mark.parametrize("N,K,M,bits", [(300, 2208, 300, 3), (136, 4096, 257, 4), (512, 2336, 130, 2)])
+def test_qgemm_lone_call_that_splits_k(gpu, oracle, N, K, M, bits, fast):
+    """A lone product with few 128-row groups and at least 8 chunks of K runs two workgroups per (group, m-block), each
+    half of the chunks (9 chunks: 5 + 4), which add their sums into an output the re-tiling launch cleared: the output
+    buffer starts as NaN, has a row stride beyond N whose extra columns must stay untouched, and a second call must give
+    the same bits (two parts sum to the same fp32 number in either order)."""
+    torch, aq = gpu
+    codes, scales = wl.draw_matrix(N, K, bits, 58, N, K)
+    X = wl.draw_activations(M, K, "bf16", 58, N, K, image_rows=min(256, M), image_gain=3.0)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    Xd = _dev(torch, X, "bf16")
+    big = torch.full((M, N + 24), float("nan"), dtype=torch.float32, device="cuda")
+    Y = big[:, :N]
+    aq.aq_qgemm(packed, N, K, bits, Xd, Y=Y, fast=fast)
+    first = Y.cpu().numpy().copy()
+    assert torch.isnan(big[:, N:]).all()
+    ref = oracle.qmatmul(codes, scales, N, K, bits, X, "bf16")
+    assert oracle.rel_l2(first, ref) <= (FAST_EXPECTED[bits] if fast else 2e-6)
+    for m in range(0, M, 11):
+        assert oracle.rel_l2(first[m], ref[m]) <= REL_L2_BAR
+    aq.aq_qgemm(packed, N, K, bits, Xd, Y=Y, fast=fast)
+    assert np.array_equal(Y.cpu().numpy(), first)
+    assert torch.isnan(big[:, N:]).all()
+    # integer activations, power-of-two scales: every order of summation gives the same fp32 bits
+    scales2 = wl.draw_pow2_scales(N, K, 58, bits)
+    Xi = wl.draw_int_activations(M, K, "f16", 58, bits)
+    packed = _pack(torch, aq, codes, scales2, N, K, bits)
+    Yi = aq.aq_qgemm(packed, N, K, bits, _dev(torch, Xi, "f16"), fast=fast).cpu().numpy()
+    assert np.array_equal(Yi.astype(np.float64), oracle.qmatmul(codes, scales2, N, K, bits, Xi, "f16"))
+
+
 def test_qgemv_seeded_sweep_of_shapes_around_the_kernel_boundaries(gpu, oracle):
     """Shapes drawn around what the decode kernel's structure makes special: K at and next to multiples of a chunk
     (256), of a staged segment (4096) and of a lone call's four-way split of K; N at and next to multiples of a tile
