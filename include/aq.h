@@ -111,7 +111,7 @@ int aq_qgemv_batch(const void* plan_host, const void* plan_dev, void* stream);
  *   aq_qgemm       code tiles are unpacked to the exact small integers (q - 2^(bits-1)) in LDS and the fp16
  *       block scale d multiplies each block's partial sum in fp32 (Eq. 1 with the factor d taken out of
  *       the block's sum): no weight is ever rounded, only fp32 summation rounds (rel-L2 ~1e-7).  One fp32
- *       multiply-add per 32 matrix-core multiply-adds: the vector ALU bounds the speed.  For M <= 32, where the
+ *       multiply-add per 32 matrix-core multiply-adds: the vector ALU bounds the speed.  For M <= 64, where the
  *       weight stream bounds the speed, the same precision is reached another way: d * (q - 2^(bits-1)) goes to the
  *       matrix cores as the exact sum of two binary16 numbers (two multiply-adds per weight) in the streaming
  *       kernel described under aq_qgemm_fast; bf16 activations are converted to binary16 per row as there.

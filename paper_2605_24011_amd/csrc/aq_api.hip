@@ -152,7 +152,7 @@ AqGemmTask make_pcx_task(const void* packed, int64_t N, int64_t K, int bits, int
     return t;
 }
 
-constexpr int64_t SMALL_M_EXACT = 32;  // exact-mode products with M up to this run it too, weights as two binary16 terms
+constexpr int64_t SMALL_M_EXACT = 64;  // exact-mode products with M up to this run it too, weights as two binary16 terms
 
 AqGemmTask make_small_task(const void* packed, int64_t N, int64_t K, int bits, int64_t M, int64_t xt_offset,
                            float* Y, int64_t ldy, int wg_begin)
@@ -734,7 +734,7 @@ static bool read_gemm_plan(const void* plan_host, GemmPlanHeader& h)
            h.retile_max_blocks >= 1 && h.workspace_bytes >= 1024 &&
            (h.nsplit == 1 || ((h.nsplit == 2 || h.nsplit == 4 || h.nsplit == 8) && h.mtiles == 1)) &&
            (h.fast == 0 || h.fast == 1) &&
-           (h.small_mt == 0 || h.small_mt == 1 || h.small_mt == 2 || (h.small_mt == 4 && h.fast == 1)) &&
+           (h.small_mt == 0 || h.small_mt == 1 || h.small_mt == 2 || h.small_mt == 4) &&
            (h.pc == 0 || (h.pc == 1 && h.small_mt == 0)) &&
            (h.format == 0 || (h.format == 1 && h.pc == h.fast && h.small_mt == 0) ||
             (h.format == 2 && h.pc == 1 && h.fast == 1 && h.small_mt == 0));

@@ -43,7 +43,7 @@ constexpr int SM_THREADS = SM_WAVES * 64;
 // SPLIT: the exact mode.  d * (q - z) is fed to the matrix cores as the sum of two binary16 numbers (its rounding
 // and the remainder, which the fused multiply-add delivers exactly), so that no weight is rounded: every product
 // with a binary16 x is exact in fp32 and only the fp32 sums round, as in the block-scaled exact kernel.  Twice the
-// MFMAs, which a weight-stream-bound product has to spare up to M = 32.
+// MFMAs; up to M = 64 that is cheaper than scaling every block's sum on the vector ALU.
 template <int BITS_T, int MT, bool SPLIT>
 __global__ __launch_bounds__(SM_THREADS) void qgemm_small_kernel(const AqGemmTask* __restrict__ tasks, int count,
                                                                  AqGemmTask single, const uint8_t* __restrict__ workspace)
@@ -144,7 +144,7 @@ void launch_small(int MT, bool split, dim3 grid, hipStream_t s, const AqGemmTask
     const size_t lds = (size_t)2 * 8 * MT * 1024;              // two chunk slots of X
 #define AQ_SMALL(MT_, SP_) hipLaunchKernelGGL((qgemm_small_kernel<BITS_T, MT_, SP_>), grid, block, lds, s, tasks, count, single, ws)
     if (split) {
-        if (MT == 1) AQ_SMALL(1, true); else AQ_SMALL(2, true);
+        if (MT == 1) AQ_SMALL(1, true); else if (MT == 2) AQ_SMALL(2, true); else AQ_SMALL(4, true);
     } else {
         if (MT == 1) AQ_SMALL(1, false); else if (MT == 2) AQ_SMALL(2, false); else AQ_SMALL(4, false);
     }
@@ -176,12 +176,11 @@ hipError_t aqk_small_retile(const AqRetileTask* tasks_dev, int count, const AqRe
 }
 
 // bits == 0: mixed bit-widths.  Every task: M <= 16 * MT, wg_count = its number of 128-row groups.
-// split: the exact mode (MT <= 2).
+// split: the exact mode.
 hipError_t aqk_gemm_small(const AqGemmTask* tasks_dev, int count, const AqGemmTask& single, int bits, int MT,
                           bool split, int total_wgs, const void* workspace, hipStream_t s)
 {
     if (MT != 1 && MT != 2 && MT != 4) return hipErrorInvalidValue;
-    if (split && MT == 4) return hipErrorInvalidValue;
     const dim3 grid((unsigned)total_wgs);
     const uint8_t* ws = static_cast<const uint8_t*>(workspace);
     if (bits == 2) launch_small<2>(MT, split, grid, s, tasks_dev, count, single, ws);
