@@ -96,6 +96,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--seed", type=int, default=0, help="seed of the headline stream's bit allocation (0: the recorded runs')")
+    ap.add_argument("--reading", choices=["A", "B"], default="B",
+                    help="what '2.5 bits per weight' means for the headline stream: A = 2.5 bits stored per weight, scales "
+                         "included (every matrix at 2 bits); B = a mean of 2.5 code bits (mixed 2/3/4-bit matrices, 3.0 "
+                         "bits stored per weight)")
+    ap.add_argument("--config", type=int, choices=[1, 2, 3, 4, 5], default=None,
+                    help="only the sections of one workload of the baseline list: 1 lone 4096 x 4096 4-bit decode call, 2 "
+                         "decode per bit-width and layer shape, 3 the backbone decode stream, 4 prefill at M = 300, 5 the "
+                         "Gemma-2B-shaped stream (the headline stream is timed in every case)")
     ap.add_argument("--skip-by-bits", action="store_true")
     ap.add_argument("--skip-prefill", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
@@ -122,6 +131,14 @@ def main():
     if args.decode_only:
         args.skip_by_bits = args.skip_prefill = args.skip_cpu = args.skip_gemma = args.skip_quant = args.skip_cells = True
         args.skip_layer_step = args.skip_two_level = args.skip_hsic = True
+    if args.config is not None:
+        keep = {1: {"cells"}, 2: {"by_bits", "cells"}, 3: {"by_bits", "cpu"}, 4: {"prefill"}, 5: {"gemma"}}[args.config]
+        args.skip_by_bits |= "by_bits" not in keep
+        args.skip_cells |= "cells" not in keep
+        args.skip_cpu |= "cpu" not in keep
+        args.skip_prefill |= "prefill" not in keep
+        args.skip_gemma |= "gemma" not in keep
+        args.skip_quant = args.skip_layer_step = args.skip_two_level = args.skip_hsic = True
     if args.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists).", file=sys.stderr)
         sys.exit(2)
@@ -144,7 +161,7 @@ def main():
         return
 
     # ---- the timed workload: mixed-bit LLaMA-2-7B-shaped decode stream -----------------
-    specs = wl.backbone_stream("llama2-7b", "mixed")
+    specs = wl.backbone_stream("llama2-7b", "mixed" if args.reading == "B" else "floor", seed=args.seed)
     items = build_stream(aq, wl, torch, specs, "f16", 3)
     batch = aq.GemvBatch(items)
     step_bytes = sum(gemv_bytes(m.N, m.K, m.bits) for m in specs)
@@ -183,9 +200,14 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": "llama2-7b-shaped decode stream, 224 matrices, seeded mixed {2,3,4}-bit allocation "
-                        "(mean 2.5 code bits = %.3f bits/weight stored), fp16 activations, one batched launch per token"
+            "workload": ("llama2-7b-shaped decode stream, 224 matrices, seeded mixed {2,3,4}-bit allocation "
+                         "(mean 2.5 code bits = %.3f bits/weight stored), fp16 activations, one batched launch per token"
+                         if args.reading == "B" else
+                         "llama2-7b-shaped decode stream, 224 matrices, every matrix at 2 bits (%.3f bits/weight stored, "
+                         "scales included), fp16 activations, one batched launch per token")
                         % wl.stored_bits_per_weight(specs),
+            "reading": args.reading,
+            "allocation_seed": args.seed,
             "matrices": len(specs),
             "weights": weights,
             "bytes_per_step": step_bytes,
@@ -194,7 +216,8 @@ def main():
         "tokens_per_s": round(1e3 / ms_per_step, 1),
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "roofline": {
-            "kernel": "qgemv_mixed_kernel (one batched launch per token)",
+            "kernel": ("qgemv_mixed_kernel" if args.reading == "B" else "qgemv_digit_kernel<2, 2, false>")
+                      + " (one batched launch per token)",
             "bound": "hbm",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS,
