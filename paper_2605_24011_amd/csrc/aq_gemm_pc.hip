@@ -158,8 +158,9 @@ __device__ __forceinline__ void produce(const AqGemmTask& t, int group, int p, i
     }
 }
 
-// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup.  FMT: see produce().
-template <int BITS_T, int FMT>
+// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup.  FMT: see produce().  KSPLIT: the instance for a
+// lone product that splits K (the list kernels carry none of its code).
+template <int BITS_T, int FMT, bool KSPLIT = false>
 __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* __restrict__ tasks, int count,
                                                               AqGemmTask single, const uint8_t* __restrict__ workspace,
                                                               const float* __restrict__ cb_table)
@@ -184,13 +185,13 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // a lone matrix may split K over kparts workgroups per (group, m-block): each adds its part into Y (zeroed before)
-    const int kparts = t.pad[1] > 1 ? (int)t.pad[1] : 1;
-    const int wg_part = t.wg_count / kparts, kpart = wg / wg_part;
+    const int kparts = KSPLIT && t.pad[1] > 1 ? (int)t.pad[1] : 1;
+    const int wg_part = t.wg_count / kparts, kpart = KSPLIT ? wg / wg_part : 0;
     wg -= kpart * wg_part;
     const int group = wg % t.slabs, mblock = wg / t.slabs;
     const int cpp = (t.nchunks + kparts - 1) / kparts;
     const int ch0 = kpart * cpp;
-    const int nch = t.nchunks - ch0 < cpp ? t.nchunks - ch0 : cpp;      // this workgroup's chunks: ch0 .. ch0 + nch - 1
+    const int nch = KSPLIT ? (t.nchunks - ch0 < cpp ? t.nchunks - ch0 : cpp) : t.nchunks;      // this workgroup's chunks: ch0 .. ch0 + nch - 1
 
     // largest scale of the matrix (blob trailer) -> power-of-two shift that keeps d * (q - z) inside binary16
     // (blobs of the two-level variant carry no such word: their D * 15 * (2^bits - 1) must stay inside binary16)
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(PC_THREADS) void qgemm_pc_kernel(const AqGemmTask* 
                         const int64_t m = (int64_t)(mt0 + mt) * 16 + 4 * g + r;
                         if (m < M && n < t.N) {
                             const float v = ldexpf(acc[mt][nt][r], e[r]);
-                            if (kparts > 1) unsafeAtomicAdd((float*)(uintptr_t)(Y + m * t.ldy + n), v);
+                            if (KSPLIT && kparts > 1) unsafeAtomicAdd((float*)(uintptr_t)(Y + m * t.ldy + n), v);
                             else Y[m * t.ldy + n] = v;
                         }
                     }
@@ -375,9 +376,10 @@ hipError_t aqk_gemm_pc(const AqGemmTask* tasks_dev, int count, const AqGemmTask&
     const size_t lds = 2 * (size_t)PC_WBUF;
     const dim3 grid((unsigned)total_wgs), block(PC_THREADS);
     const uint8_t* ws = static_cast<const uint8_t*>(workspace);
+    const bool ksplit = count == 0 && format == 0 && bits != 0 && single.pad[1] > 1;      // a lone product that splits K
 #define AQ_PC(B)                                                                                                \
     do {                                                                                                        \
-        auto k = format == 1 ? qgemm_pc_kernel<B, 1> : qgemm_pc_kernel<B, 0>;                                   \
+        auto k = format == 1 ? qgemm_pc_kernel<B, 1> : ksplit ? qgemm_pc_kernel<B ? B : 2, 0, true> : qgemm_pc_kernel<B, 0>; \
         if (aqk_allow_lds(reinterpret_cast<const void*>(k), lds) != hipSuccess) return hipErrorInvalidValue;    \
         hipLaunchKernelGGL(k, grid, block, lds, s, tasks_dev, count, single, ws, cb_table);                     \
     } while (0)

@@ -106,8 +106,9 @@ __device__ __forceinline__ void produce_exact(const AqGemmTask& t, int group, in
     }
 }
 
-// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup.  XBF: the activations are bf16.
-template <int BITS_T, bool XBF>
+// BITS_T == 0: the tasks' bit-widths differ, branch per workgroup.  XBF: the activations are bf16.  KSPLIT: the instance
+// for a lone product that splits K (the list kernels carry none of its code).
+template <int BITS_T, bool XBF, bool KSPLIT = false>
 __global__ __launch_bounds__(PX_THREADS) void qgemm_pcx_kernel(const AqGemmTask* __restrict__ tasks, int count,
                                                                AqGemmTask single, const uint8_t* __restrict__ workspace)
 {
@@ -130,13 +131,13 @@ __global__ __launch_bounds__(PX_THREADS) void qgemm_pcx_kernel(const AqGemmTask*
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // a lone matrix may split K over kparts workgroups per (group, m-block): each adds its part into Y (zeroed before)
-    const int kparts = t.pad[1] > 1 ? (int)t.pad[1] : 1;
-    const int wg_part = t.wg_count / kparts, kpart = wg / wg_part;
+    const int kparts = KSPLIT && t.pad[1] > 1 ? (int)t.pad[1] : 1;
+    const int wg_part = t.wg_count / kparts, kpart = KSPLIT ? wg / wg_part : 0;
     wg -= kpart * wg_part;
     const int group = wg % t.slabs, mblock = wg / t.slabs;
     const int cpp = (t.nchunks + kparts - 1) / kparts;
     const int ch0 = kpart * cpp;
-    const int nch = t.nchunks - ch0 < cpp ? t.nchunks - ch0 : cpp;      // this workgroup's chunks: ch0 .. ch0 + nch - 1
+    const int nch = KSPLIT ? (t.nchunks - ch0 < cpp ? t.nchunks - ch0 : cpp) : t.nchunks;      // this workgroup's chunks: ch0 .. ch0 + nch - 1
 
     if (wave >= PX_CONSUMERS) {
         const int p = wave - PX_CONSUMERS;
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(PX_THREADS) void qgemm_pcx_kernel(const AqGemmTask*
                     for (int r = 0; r < 4; ++r) {
                         const int64_t m = (int64_t)(mt0 + mt) * 16 + 4 * g + r;
                         if (m < M && n < t.N) {
-                            if (kparts > 1) unsafeAtomicAdd((float*)(uintptr_t)(Y + m * t.ldy + n), acc[mt][nt][r]);
+                            if (KSPLIT && kparts > 1) unsafeAtomicAdd((float*)(uintptr_t)(Y + m * t.ldy + n), acc[mt][nt][r]);
                             else Y[m * t.ldy + n] = acc[mt][nt][r];
                         }
                     }
@@ -300,9 +301,11 @@ hipError_t aqk_gemm_pcx(const AqGemmTask* tasks_dev, int count, const AqGemmTask
     const size_t lds = 2 * (size_t)PX_WBUF;
     const dim3 grid((unsigned)total_wgs), block(PX_THREADS);
     const uint8_t* ws = static_cast<const uint8_t*>(workspace);
+    const bool ksplit = count == 0 && bits != 0 && single.pad[1] > 1;      // a lone product that splits K
 #define AQ_PX(B)                                                                                                \
     do {                                                                                                        \
-        auto k = x_dtype == 2 ? qgemm_pcx_kernel<B, true> : qgemm_pcx_kernel<B, false>;                         \
+        auto k = ksplit ? (x_dtype == 2 ? qgemm_pcx_kernel<B ? B : 2, true, true> : qgemm_pcx_kernel<B ? B : 2, false, true>) \
+                        : (x_dtype == 2 ? qgemm_pcx_kernel<B, true> : qgemm_pcx_kernel<B, false>);              \
         if (aqk_allow_lds(reinterpret_cast<const void*>(k), lds) != hipSuccess) return hipErrorInvalidValue;    \
         hipLaunchKernelGGL(k, grid, block, lds, s, tasks_dev, count, single, ws);                               \
     } while (0)
