@@ -46,7 +46,7 @@ extern "C" {
 #endif
 
 #define AQ_OK        0
-#define AQ_EINVAL   (-1)  /* bits not in {2,3,4}; block != 32; N, K or M < 1; K % 32 != 0; ld too small; count < 1; unknown flags */
+#define AQ_EINVAL   (-1)  /* bits not in {2,3,4}; block != 32; N, K or M < 1; K % 32 != 0; K > 65536; ld too small; count < 1; unknown flags */
 #define AQ_ENULL    (-2)  /* a required pointer is NULL */
 #define AQ_EALIGN   (-3)  /* a device pointer is not 16-byte aligned */
 #define AQ_ESIZE    (-4)  /* a caller-provided buffer is too small */
@@ -341,7 +341,7 @@ int aqc_dequant_f32(const void* packed, int64_t N, int64_t K, int bits, int bloc
  * additions, so the last bits of a result can differ between runs.
  * One launch per stage (4 per layer, each taking its matrices' records as kernel arguments) plus one that clears
  * qkv; consecutive launches on one stream are the barriers between dependent stages.
- *   shape      HOST; d_model, d_ff, n_heads * head_dim multiples of 32 and <= 16384 (the K limit of aq_pack_weights), head_dim a multiple of 8,
+ *   shape      HOST; d_model, d_ff, n_heads * head_dim multiples of 32 and <= 16384 (this call's own limit), head_dim a multiple of 8,
  *              n_heads a multiple of n_kv_heads, act = AQ_ACT_SILU or AQ_ACT_GELU_TANH, eps >= 0
  *   blocks     HOST array of `layers` records: w[0..6] = DEVICE blobs (aq_pack_weights) of q, k, v, o, gate, up,
  *              down with the shapes the block shape implies and bit-widths bits[0..6]; norm_attn, norm_mlp =

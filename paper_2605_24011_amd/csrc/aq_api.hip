@@ -13,7 +13,8 @@
 
 namespace {
 
-constexpr int64_t AQ_MAX_K = 16384;          // x (fp16) must fit the decode kernel's LDS stage
+constexpr int64_t AQ_MAX_K = 65536;          // no kernel's LDS or registers grow with K: a bound on index arithmetic
+constexpr int64_t AQ_LAYER_MAX_K = 16384;    // the decode step's stage planner (parts of at most 8 chunks, one round of workgroups)
 constexpr int64_t AQ_MAX_N = (int64_t)1 << 24;
 constexpr int64_t AQ_MAX_M = (int64_t)1 << 20;
 
@@ -266,7 +267,7 @@ const char* aq_status_string(int status)
 {
     switch (status) {
         case AQ_OK: return "ok";
-        case AQ_EINVAL: return "invalid argument (bits must be 2, 3 or 4; block 32; K a multiple of 32 and <= 16384; sizes >= 1)";
+        case AQ_EINVAL: return "invalid argument (bits must be 2, 3 or 4; block 32; K a multiple of 32 and <= 65536; sizes >= 1)";
         case AQ_ENULL: return "null pointer";
         case AQ_EALIGN: return "device pointer not 16-byte aligned";
         case AQ_ESIZE: return "buffer too small";
@@ -866,12 +867,12 @@ int aq_decode_plan(const aq_block_shape* shape, const aq_block_desc* blocks, int
     if (!shape || !blocks || !x || !qkv || !workspace || !plan_host) return AQ_ENULL;
     if (layers < 1 || block != AQ_BLOCK) return AQ_EINVAL;
     const aq_block_shape& sh = *shape;
-    if (sh.d_model < 32 || sh.d_ff < 32 || sh.d_model % 32 || sh.d_ff % 32 || sh.d_model > AQ_MAX_K || sh.d_ff > AQ_MAX_K)
+    if (sh.d_model < 32 || sh.d_ff < 32 || sh.d_model % 32 || sh.d_ff % 32 || sh.d_model > AQ_LAYER_MAX_K || sh.d_ff > AQ_LAYER_MAX_K)
         return AQ_EINVAL;
     if (sh.n_heads < 1 || sh.n_kv_heads < 1 || sh.n_heads % sh.n_kv_heads || sh.head_dim < 8 || sh.head_dim % 8)
         return AQ_EINVAL;
     const int64_t dq = (int64_t)sh.n_heads * sh.head_dim, dkv = (int64_t)sh.n_kv_heads * sh.head_dim;
-    if (dq % 32 || dkv % 32 || dq > AQ_MAX_K) return AQ_EINVAL;      // every K of a block must be one aq_pack_weights takes
+    if (dq % 32 || dkv % 32 || dq > AQ_LAYER_MAX_K) return AQ_EINVAL;
     if (sh.act != AQ_ACT_SILU && sh.act != AQ_ACT_GELU_TANH) return AQ_EINVAL;
     if (!(sh.eps >= 0.f)) return AQ_EINVAL;
     if (!aligned16(x) || !aligned16(qkv) || !aligned16(workspace)) return AQ_EALIGN;

@@ -12,7 +12,7 @@
 
 namespace {
 
-constexpr int64_t CB_MAX_K = 16384;                 // the base format's limit (blobs share aq_packed_size)
+constexpr int64_t CB_MAX_K = 65536;                 // the base format's limit (blobs share aq_packed_size)
 constexpr int64_t CB_MAX_N = (int64_t)1 << 24;
 constexpr uint64_t IDENTITY_REMAP = 0xFEDCBA9876543210ull;
 constexpr uint32_t CB_PLAN_MAGIC = 0x41514331u;     // "AQC1"

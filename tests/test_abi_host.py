@@ -43,7 +43,7 @@ def test_packed_size_is_canonical_bytes_on_aligned_shapes(L):
     # padded shapes are never smaller than the canonical form
     assert aq.aq_packed_size(17, 96, 3) >= 17 * 96 * 3 // 8 + 17 * 3 * 2
     # invalid arguments give 0
-    for bad in ((0, 32, 4, 32), (4, 33, 4, 32), (4, 32, 5, 32), (4, 32, 4, 64), (4, 32768, 4, 32)):
+    for bad in ((0, 32, 4, 32), (4, 33, 4, 32), (4, 32, 5, 32), (4, 32, 4, 64), (4, 65536 + 32, 4, 32)):
         assert aq.aq_packed_size(*bad) == 0
 
 

@@ -191,6 +191,23 @@ def test_full_size_layer_sampled_rows(gpu, cb, oracle):
         assert oracle.rel_l2(it[6].cpu().numpy()[rows], ref) <= REL_L2_EXPECTED
 
 
+def test_qgemv_at_deep_k(gpu, cb, oracle):
+    """The decode kernel stages x a segment at a time, so its LDS does not grow with K: 32768 columns, lone and listed."""
+    torch, aq = gpu
+    N, K, bits = 70, 32768, 4
+    levels = cb.e2m1_levels().astype(np.float32)
+    codes, scales = wl.draw_matrix(N, K, bits, 92)
+    xh = wl.draw_activations(1, K, "bf16", 92)
+    packed = aq.aqc_pack_weights(dev(torch, codes), dev(torch, scales), levels, N, K, bits)
+    x = dev(torch, xh, "bf16")[0].contiguous()
+    ref = cb.qmatmul(codes, scales, levels, N, K, bits, xh, "bf16")[0]
+    assert oracle.rel_l2(aq.aqc_qgemv(packed, N, K, bits, levels, x).cpu().numpy(), ref) <= REL_L2_EXPECTED
+    y = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+    aq.CbGemvBatch([(packed, N, K, bits, levels, x, y)]).run()
+    torch.cuda.synchronize()
+    assert oracle.rel_l2(y.cpu().numpy(), ref) <= REL_L2_EXPECTED
+
+
 def test_errors(gpu, cb):
     torch, aq = gpu
     N, K = 16, 64

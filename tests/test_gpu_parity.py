@@ -729,13 +729,41 @@ def test_qgemm_lone_call_that_splits_k(gpu, oracle, N, K, M, bits, fast):
     assert np.array_equal(Yi.astype(np.float64), oracle.qmatmul(codes, scales2, N, K, bits, Xi, "f16"))
 
 
+@pytest.mark.parametrize("K,bits", [(32768, 3), (32768 + 4096 + 32, 2), (65536, 4)])
+def test_deep_k_codecs_and_prefill(gpu, oracle, K, bits):
+    """K far beyond the layer shapes (no kernel's LDS or registers grow with K): codes and dequantised weights
+    bit-exact, then prefill products of the streaming kernel (M = 20), the shared-role kernel (M = 130) and the producer
+    / consumer kernels (M = 300, which also splits K for so few rows), both modes, against rows of one oracle product."""
+    torch, aq = gpu
+    N, M = 70, 300
+    codes, scales = wl.draw_matrix(N, K, bits, 59, K)
+    packed = _pack(torch, aq, codes, scales, N, K, bits)
+    assert np.array_equal(aq.aq_unpack_codes(packed, N, K, bits).cpu().numpy(), oracle.unpack(codes, N, K, bits))
+    W = aq.aq_dequant_f32(packed, N, K, bits).cpu().numpy().astype(np.float64)
+    assert np.array_equal(W, oracle.dequant(codes, scales, N, K, bits))
+    X = wl.draw_activations(M, K, "bf16", 59, K, image_rows=256, image_gain=3.0)
+    ref = oracle.qmatmul(codes, scales, N, K, bits, X, "bf16")
+    # exact products, fp32 sums: the rounding error of a sum grows with the square root of its length; 2e-6 is the bar of
+    # the other exact-mode cases (K up to 16384)
+    exact_bar = 2e-6 * max(1.0, (K / 16384) ** 0.5)
+    for m in (20, 130, 300):
+        Xd = _dev(torch, X[:m], "bf16")
+        Y = aq.aq_qgemm(packed, N, K, bits, Xd).cpu().numpy()
+        assert oracle.rel_l2(Y, ref[:m]) <= exact_bar, (m, "exact")
+        Yf = aq.aq_qgemm(packed, N, K, bits, Xd, fast=True).cpu().numpy()
+        assert oracle.rel_l2(Yf, ref[:m]) <= FAST_EXPECTED[bits], (m, "fast")
+        for r in range(0, m, 13):
+            assert oracle.rel_l2(Y[r], ref[r]) <= REL_L2_BAR and oracle.rel_l2(Yf[r], ref[r]) <= REL_L2_BAR
+
+
 def test_qgemv_seeded_sweep_of_shapes_around_the_kernel_boundaries(gpu, oracle):
     """Shapes drawn around what the decode kernel's structure makes special: K at and next to multiples of a chunk
     (256), of a staged segment (4096) and of a lone call's four-way split of K; N at and next to multiples of a tile
     (16) and of a group (128); every bit-width and both activation types; lone calls and one listed launch of all."""
     torch, aq = gpu
     rng = np.random.default_rng(2024)
-    ks = [32, 224, 256, 288, 1024 - 32, 1024 + 32, 4096 - 32, 4096, 4096 + 32, 8192, 8192 + 256 + 32, 12288 - 32, 16384]
+    ks = [32, 224, 256, 288, 1024 - 32, 1024 + 32, 4096 - 32, 4096, 4096 + 32, 8192, 8192 + 256 + 32, 12288 - 32, 16384,
+          32768 - 32, 32768 + 256, 65536]
     ns = [1, 15, 16, 17, 127, 128, 129, 255, 300]
     cases = [(int(rng.choice(ns)), int(k), int(rng.integers(2, 5)), str(rng.choice(["f16", "bf16"]))) for k in ks for _ in range(2)]
     items, refs = [], []

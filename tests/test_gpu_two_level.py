@@ -264,7 +264,7 @@ def test_qgemv_seeded_sweep_of_shapes_around_the_kernel_boundaries(gpu, oracle, 
     boundaries, lone calls and one listed launch."""
     torch, aq = gpu
     rng = np.random.default_rng(2025)
-    ks = [32, 224, 256, 288, 1024 + 32, 4096 - 32, 4096, 4096 + 32, 8192 + 256 + 32, 16384]
+    ks = [32, 224, 256, 288, 1024 + 32, 4096 - 32, 4096, 4096 + 32, 8192 + 256 + 32, 16384, 32768 + 256 + 32]
     ns = [1, 15, 16, 17, 127, 128, 129, 300]
     cases = [(int(rng.choice(ns)), int(k), int(rng.integers(2, 5)), str(rng.choice(["f16", "bf16"]))) for k in ks for _ in range(2)]
     items, refs = [], []
