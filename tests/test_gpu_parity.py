@@ -782,3 +782,71 @@ def test_qgemv_seeded_sweep_of_shapes_around_the_kernel_boundaries(gpu, oracle):
     torch.cuda.synchronize()
     for it, ref, case in zip(items, refs, cases):
         assert oracle.rel_l2(it[5].cpu().numpy(), ref) <= REL_L2_EXPECTED, case
+
+
+def test_entry_points_replayed_from_a_captured_graph(gpu, oracle):
+    """The library launches kernels only (no memset nodes, no allocation, no synchronisation), so a caller may capture
+    its calls in a HIP graph: a lone decode call, a listed decode launch, a lone prefill call that splits K (its
+    pre-pass clears Y) in both modes, the entry point that allocates nothing and a listed prefill launch are recorded
+    once and replayed three times with new activations copied in between (the program's own eager work between replays);
+    every replay must match the oracle and the eager results bit for bit."""
+    torch, aq = gpu
+    N, K, M = 300, 2336, 130
+    mats = []
+    for bits in (2, 3, 4):
+        codes, scales = wl.draw_matrix(N, K, bits, 63, bits)
+        mats.append((bits, codes, scales, _pack(torch, aq, codes, scales, N, K, bits)))
+    x = torch.empty(K, dtype=torch.float16, device="cuda")
+    X = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+    ys = [torch.empty(N, dtype=torch.float32, device="cuda") for _ in range(4)]
+    Ys = [torch.empty((M, N), dtype=torch.float32, device="cuda") for _ in range(6)]
+    ws = torch.empty(aq.aq_qgemm_workspace_size(M, N, K, 4), dtype=torch.uint8, device="cuda")
+    gv = aq.GemvBatch([(m[3], N, K, m[0], x, ys[1 + i]) for i, m in enumerate(mats)])
+    gm = aq.GemmBatch([(m[3], N, K, m[0], X, Ys[3 + i]) for i, m in enumerate(mats)], fast=True)
+
+    def calls():
+        aq.aq_qgemv(mats[2][3], N, K, 4, x, ys[0])
+        gv.run()
+        aq.aq_qgemm(mats[1][3], N, K, 3, X, Y=Ys[0], workspace=ws)
+        aq.aq_qgemm(mats[1][3], N, K, 3, X, Y=Ys[1], workspace=ws, fast=True)
+        aq.aq_qgemm_noalloc(mats[0][3], N, K, 2, X, Ys[2])
+        gm.run()
+
+    def fill(seed):
+        xh = wl.draw_activations(1, K, "f16", 63, seed)
+        Xh = wl.draw_activations(M, K, "bf16", 63, seed, image_rows=100, image_gain=3.0)
+        x.copy_(_dev(torch, xh[0], "f16"))
+        X.copy_(_dev(torch, Xh, "bf16"))
+        return xh, Xh
+
+    side = torch.cuda.Stream()
+    fill(0)
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        calls()                                           # warm-up: per-kernel attributes are set outside the capture
+        with torch.cuda.graph(graph, stream=side):
+            calls()
+    torch.cuda.current_stream().wait_stream(side)
+    for seed in (1, 2, 3):
+        xh, Xh = fill(seed)
+        for t in ys + Ys:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got_y = [t.cpu().numpy().copy() for t in ys]
+        got_Y = [t.cpu().numpy().copy() for t in Ys]
+        refs = {m[0]: oracle.qmatmul(m[1], m[2], N, K, m[0], Xh, "bf16") for m in mats}
+        assert oracle.rel_l2(got_y[0], oracle.qmatmul(mats[2][1], mats[2][2], N, K, 4, xh, "f16")[0]) <= REL_L2_EXPECTED
+        for i, m in enumerate(mats):
+            assert oracle.rel_l2(got_y[1 + i], oracle.qmatmul(m[1], m[2], N, K, m[0], xh, "f16")[0]) <= REL_L2_EXPECTED
+            assert oracle.rel_l2(got_Y[3 + i], refs[m[0]]) <= FAST_EXPECTED[m[0]]
+        assert oracle.rel_l2(got_Y[0], refs[3]) <= 2e-6
+        assert oracle.rel_l2(got_Y[1], refs[3]) <= FAST_EXPECTED[3]
+        assert oracle.rel_l2(got_Y[2], refs[2]) <= 2e-6
+        for t in ys + Ys:
+            t.fill_(float("nan"))
+        calls()                                           # the same calls issued eagerly
+        torch.cuda.synchronize()
+        for t, g in zip(ys + Ys, got_y + got_Y):
+            assert np.array_equal(t.cpu().numpy(), g)
