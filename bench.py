@@ -547,7 +547,21 @@ def main():
                 "weight_GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
                 "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                 "result_finite": bool(torch.isfinite(x).all())}
-            del layers, step
+            # the same token replayed from a captured HIP graph (the step records kernels only): the chain of dependent
+            # launches without the host's launch path
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                one_token()
+                with torch.cuda.graph(graph, stream=side):
+                    one_token()
+            torch.cuda.current_stream().wait_stream(side)
+            d, w = time_launches(torch, graph.replay, max(10, args.steps // 2), 5)
+            msg = sum(d) / len(d)
+            step_out[model]["ms_per_token_graph_replay"] = round(msg, 4)
+            step_out[model]["frac_hbm_peak_graph_replay"] = round(nbytes / (msg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            del graph, layers, step
         out["layer_step"] = step_out
 
     if not args.skip_two_level:
