@@ -784,6 +784,33 @@ def test_qgemv_seeded_sweep_of_shapes_around_the_kernel_boundaries(gpu, oracle):
         assert oracle.rel_l2(it[5].cpu().numpy(), ref) <= REL_L2_EXPECTED, case
 
 
+def test_qgemm_seeded_sweep_of_lone_call_shapes(gpu, oracle):
+    """Lone prefill calls at shapes drawn around what the dispatch makes special: M at and next to the streaming
+    kernel's limits (16, 32, 64), the producer / consumer kernels' m-blocks and a 300-row prefill; N at and next to tiles
+    and groups; K at and next to chunks and the depth from which a lone call splits K; both modes, both activation
+    types, an output whose row stride exceeds N (the extra columns must stay untouched)."""
+    torch, aq = gpu
+    rng = np.random.default_rng(2026)
+    for case in range(36):
+        N = int(rng.choice([1, 16, 17, 100, 128, 129, 300, 520, int(rng.integers(1, 600))]))
+        K = 32 * int(rng.choice([1, 7, 8, 9, 33, 64, 65, 96, 128, 200, int(rng.integers(1, 256))]))
+        M = int(rng.choice([1, 15, 16, 17, 33, 64, 65, 100, 129, 257, 300, 385, int(rng.integers(1, 400))]))
+        bits, kind = int(rng.integers(2, 5)), str(rng.choice(["bf16", "f16"]))
+        codes, scales = wl.draw_matrix(N, K, bits, 71, case)
+        X = wl.draw_activations(M, K, kind, 71, case)
+        packed = _pack(torch, aq, codes, scales, N, K, bits)
+        ref = oracle.qmatmul(codes, scales, N, K, bits, X, kind)
+        pad = int(rng.choice([0, 8, 24]))
+        for fast in (False, True):
+            big = torch.full((M, N + pad), float("nan"), dtype=torch.float32, device="cuda")
+            Y = big[:, :N]
+            aq.aq_qgemm(packed, N, K, bits, _dev(torch, X, kind), Y=Y, fast=fast)
+            got = Y.cpu().numpy()
+            assert np.isfinite(got).all(), (case, N, K, M, bits, kind, fast)
+            assert pad == 0 or torch.isnan(big[:, N:]).all(), (case, N, K, M, bits, kind, fast)
+            assert oracle.rel_l2(got, ref) <= (FAST_EXPECTED[bits] if fast else 3e-6), (case, N, K, M, bits, kind, fast)
+
+
 def test_entry_points_replayed_from_a_captured_graph(gpu, oracle):
     """The library launches kernels only (no memset nodes, no allocation, no synchronisation), so a caller may capture
     its calls in a HIP graph: a lone decode call, a listed decode launch, a lone prefill call that splits K (its
