@@ -135,6 +135,25 @@ int main()
         CHECK(aqc_qgemv_batch(plan, nullptr, nullptr) == AQ_ENULL);
         std::free(plan);
         CHECK(aqc_qgemm_workspace_size(300, 4096, 4096, 4) > aq_qgemm_workspace_size(300, 4096, 4096, 4));
+        // a list of prefill products over codebook blobs: the base plan image, then one table per task
+        std::vector<aqc_gemm_desc> gd(5);
+        for (int i = 0; i < 5; ++i) {
+            aq_gemm_desc& p = gd[i].product;
+            p.packed = dev(3 * i); p.X = dev(3 * i + 1); p.Y = (float*)dev(3 * i + 2);
+            p.N = 1 + 300 * i; p.K = 32 * (1 + 100 * i); p.M = 300; p.ldx = p.K + 8; p.ldy = p.N; p.bits = bits[i];
+            p.x_dtype = AQ_BF16;
+            gd[i].levels = tabs[i];
+        }
+        const size_t gbytes = aqc_qgemm_batch_plan_size(5);
+        CHECK(gbytes == aq_qgemm_batch_plan_size(5) + 5 * 64 && aqc_qgemm_batch_plan_size(0) == 0);
+        void* gplan = std::malloc(gbytes);
+        CHECK(aqc_qgemm_batch_plan(gd.data(), 5, 32, gplan, gbytes) == AQ_OK);
+        CHECK(aq_qgemm_batch_workspace_size(gplan) > 0);
+        CHECK(aqc_qgemm_batch_plan(gd.data(), 5, 32, gplan, gbytes - 1) == AQ_ESIZE);
+        CHECK(aqc_qgemm_batch_plan(gd.data(), 0, 32, gplan, gbytes) == AQ_EINVAL);
+        gd[2].levels = nullptr;
+        CHECK(aqc_qgemm_batch_plan(gd.data(), 5, 32, gplan, gbytes) == AQ_ENULL);
+        std::free(gplan);
         CHECK(aqc_qgemm(dev(0), 64, 512, 2, 32, gen2, dev(1), 40, 512, AQ_F16, (float*)dev(2), 64, dev(3), 16, nullptr) == AQ_ESIZE);
         CHECK(aqc_qgemv(dev(0), 16, 64, 2, 32, nullptr, dev(1), AQ_F16, (float*)dev(2), nullptr) == AQ_ENULL);
     }
