@@ -811,6 +811,38 @@ def test_qgemm_seeded_sweep_of_lone_call_shapes(gpu, oracle):
             assert oracle.rel_l2(got, ref) <= (FAST_EXPECTED[bits] if fast else 3e-6), (case, N, K, M, bits, kind, fast)
 
 
+def test_qgemm_seeded_sweep_of_lists_with_unlike_products(gpu, oracle):
+    """Listed prefill launches whose products differ in N, K, M and bit-width (a list's kernel is chosen from all of its
+    products: the streaming kernel only when every M fits it, the producer / consumer kernels only when every product
+    fills their m-tile slots, else the shared-role kernel): ten seeded lists, both modes, every output against the
+    oracle."""
+    torch, aq = gpu
+    rng = np.random.default_rng(2027)
+    for lst in range(10):
+        kind = str(rng.choice(["bf16", "f16"]))
+        same_m = bool(rng.integers(0, 2))
+        M0 = int(rng.choice([1, 16, 20, 64, 65, 130, 300, 385]))
+        tasks = []
+        for j in range(int(rng.integers(1, 7))):
+            N = int(rng.choice([1, 17, 128, 129, 300, int(rng.integers(1, 500))]))
+            K = 32 * int(rng.choice([1, 8, 9, 64, 65, 100, int(rng.integers(1, 160))]))
+            M = M0 if same_m else int(rng.choice([1, 16, 33, 64, 65, 130, 300]))
+            bits = int(rng.integers(2, 5))
+            codes, scales = wl.draw_matrix(N, K, bits, 73, lst, j)
+            X = wl.draw_activations(M, K, kind, 73, lst, j)
+            tasks.append((N, K, M, bits, _pack(torch, aq, codes, scales, N, K, bits), _dev(torch, X, kind),
+                          oracle.qmatmul(codes, scales, N, K, bits, X, kind)))
+        for fast in (False, True):
+            items = [(packed, N, K, bits, Xd, torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda"))
+                     for (N, K, M, bits, packed, Xd, _ref) in tasks]
+            aq.GemmBatch(items, fast=fast).run()
+            torch.cuda.synchronize()
+            for it, t in zip(items, tasks):
+                got = it[5].cpu().numpy()
+                assert np.isfinite(got).all(), (lst, t[:4], fast)
+                assert oracle.rel_l2(got, t[6]) <= (FAST_EXPECTED[t[3]] if fast else 3e-6), (lst, t[:4], fast)
+
+
 def test_entry_points_replayed_from_a_captured_graph(gpu, oracle):
     """The library launches kernels only (no memset nodes, no allocation, no synchronisation), so a caller may capture
     its calls in a HIP graph: a lone decode call, a listed decode launch, a lone prefill call that splits K (its
